@@ -1,0 +1,224 @@
+#!/usr/bin/env python3
+"""Benchmark of the 8-bit floating point training primitive on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of synthetic input for the
+ResNet-50-style 3x3 convolution layer taken as a GEMM (M=25088, N=128, K=1152):
+
+    Q(X) -> X8, X8^T      Q(W) -> W8, W8^T      Q(dY * 2^12) -> E8, E8^T (+ overflow stats)
+    forward GEMM  Y8  = Q(X8 . W8)              contraction K
+    backward-data dX8 = Q(E8 . W8^T)            contraction N
+    weight-grad   G8  = Q(X8^T . E8)            contraction M (split, summed in FP32, one rounding)
+    update        W16 <- half_SR(W16 - lr * G8 / 2^12)
+
+Inputs are resident in HBM before the timed region.  Prints ONE JSON line: `value` is the
+GEMM work of a step (3 * 2*M*N*K flop) divided by the time of the whole step; `roofline`
+describes the kernel that takes the largest share of the step; `kernels` lists every kernel
+of the step with its own roofline; `cpu_baseline` is the CPU oracle timed on this host.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+FP8_PEAK_TFLOPS = 5000.0       # MI355X dense FP8 MFMA, published
+LOSS_SCALE = 2.0 ** 12
+LR = 1e-3
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--kernel-iters", type=int, default=200,
+                    help="launches per kernel for the per-kernel roofline timing")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+class Workload:
+    """Device buffers and launch closures for the configs[1] layer."""
+
+    def __init__(self, mp8, torch, lay):
+        self.mp8, self.torch = mp8, torch
+        M, N, K = lay.M, lay.N, lay.K
+        self.M, self.N, self.K = M, N, K
+        dev = "cuda"
+        u8 = torch.uint8
+        self.X = torch.from_numpy(lay.X).to(dev)
+        self.W = torch.from_numpy(lay.W).to(dev)
+        self.dY = torch.from_numpy(lay.dY).to(dev)
+        self.W16 = torch.from_numpy(lay.W.astype(np.float16)).to(dev)
+        self.X8, self.X8t = torch.empty((M, K), dtype=u8, device=dev), torch.empty((K, M), dtype=u8, device=dev)
+        self.W8, self.W8t = torch.empty((K, N), dtype=u8, device=dev), torch.empty((N, K), dtype=u8, device=dev)
+        self.E8, self.E8t = torch.empty((M, N), dtype=u8, device=dev), torch.empty((N, M), dtype=u8, device=dev)
+        self.Y8 = torch.empty((M, N), dtype=u8, device=dev)
+        self.dX8 = torch.empty((M, K), dtype=u8, device=dev)
+        self.G8 = torch.empty((K, N), dtype=u8, device=dev)
+        self.stats = mp8.new_stats()
+        ws = max(mp8.gemm_fp8_workspace_bytes(op, M, N, K) for op in (mp8.FWD, mp8.BWD_DATA, mp8.WGRAD))
+        self.ws = torch.empty(max(ws, 16), dtype=u8, device=dev)
+        self.step_no = 0
+        mp8_ = mp8
+        self.kernels = [
+            # name, closure, algorithmic bytes, flops, bound
+            ("quantize_X", lambda: mp8_.quantize_e5m2(self.X, self.X8, self.X8t), 6 * M * K, 0, "hbm"),
+            ("quantize_W", lambda: mp8_.quantize_e5m2(self.W, self.W8, self.W8t), 6 * K * N, 0, "hbm"),
+            ("quantize_dY", lambda: mp8_.quantize_e5m2(self.dY, self.E8, self.E8t, scale=LOSS_SCALE,
+                                                       stats=self.stats), 6 * M * N, 0, "hbm"),
+            ("gemm_fwd", lambda: mp8_.gemm_fp8(mp8_.FWD, M, N, K, self.X8, self.W8t, out8=self.Y8,
+                                               workspace=self.ws),
+             M * K + K * N + M * N, 2 * M * N * K, "mfma"),
+            ("gemm_bwd_data", lambda: mp8_.gemm_fp8(mp8_.BWD_DATA, M, N, K, self.E8, self.W8,
+                                                    out8=self.dX8, workspace=self.ws),
+             M * N + K * N + M * K, 2 * M * N * K, "mfma"),
+            ("gemm_wgrad", lambda: mp8_.gemm_fp8(mp8_.WGRAD, M, N, K, self.X8t, self.E8t, out8=self.G8,
+                                                 stats=self.stats, workspace=self.ws),
+             M * K + M * N + K * N, 2 * M * N * K, "mfma"),
+            ("sgd_update", self._update, 5 * K * N, 0, "hbm"),
+        ]
+
+    def _update(self):
+        self.step_no += 1
+        self.mp8.sgd_update_fp16_sr(self.W16, self.G8, LR, 1.0 / LOSS_SCALE, round=self.mp8.SR,
+                                    seed=0x1905_1233_4000_0002, offset=self.step_no)
+
+    def step(self):
+        self.stats.zero_()
+        for _, fn, _, _, _ in self.kernels:
+            fn()
+
+
+def time_region(torch, fn, iters):
+    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    s.record()
+    for _ in range(iters):
+        fn()
+    e.record()
+    torch.cuda.synchronize()
+    return s.elapsed_time(e) / iters   # ms per call
+
+
+def cpu_baseline(lay):
+    """The CPU oracle, as it stands, on full steps of the same workload (about 10-20 s)."""
+    import oracle
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    w16 = lay.W.astype(np.float16).view(np.uint16).reshape(-1)
+
+    def one_step():
+        X8, X8t = oracle.quantize_e5m2(lay.X, want_t=True)
+        W8, W8t = oracle.quantize_e5m2(lay.W, want_t=True)
+        E8, E8t = oracle.quantize_e5m2(lay.dY, scale=LOSS_SCALE, want_t=True)
+        tq = time.perf_counter()
+        fwd, _ = oracle.gemm_ref(X8, W8t, want_abs=False)
+        bwd, _ = oracle.gemm_ref(E8, W8, want_abs=False)
+        wg, _ = oracle.gemm_ref(X8t, E8t, want_abs=False)
+        tg = time.perf_counter()
+        oracle.round_ref_e5m2(fwd)
+        oracle.round_ref_e5m2(bwd)
+        G8 = oracle.round_ref_e5m2(wg)
+        oracle.sgd_update_fp16(w16, G8.reshape(-1), LR, 1.0 / LOSS_SCALE, mode=oracle.SR, seed=1,
+                               offset=1)
+        return tg - tq
+
+    t0 = time.perf_counter()
+    gemm_s = [one_step()]
+    first = time.perf_counter() - t0
+    reps = max(1, min(5, int(12.0 / max(first, 1e-3))))
+    for _ in range(reps - 1):
+        gemm_s.append(one_step())
+    total = time.perf_counter() - t0
+    step_s = total / reps
+    flops = 3 * 2.0 * lay.M * lay.N * lay.K
+    return {
+        "value": flops / step_s / 1e12,
+        "unit": "TFLOP/s",
+        "cores": threads,
+        "kind": "oracle",
+        "sample": (f"{reps} full step(s) of the same workload (all three GEMMs over every output "
+                   f"row, quantize, update), {total:.1f} s of CPU work; GEMMs alone "
+                   f"{flops / (sum(gemm_s) / reps) / 1e9:.1f} GFLOP/s"),
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no collectives, no sharding "
+              "are part of it)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    import paper_1905_12334_amd as mp8
+    from paper_1905_12334_amd import workloads
+    mp8.lib()   # raises if the HIP library is not built: there is no fallback
+
+    lay = workloads.config2()
+    wl = Workload(mp8, torch, lay)
+    for _ in range(args.warmup):
+        wl.step()
+    ms_per_step = time_region(torch, wl.step, args.steps)
+    nonfinite = mp8.read_stats(wl.stats)[1]
+
+    gemm_flops = 3 * 2.0 * lay.M * lay.N * lay.K
+    value = gemm_flops / (ms_per_step * 1e-3) / 1e12
+
+    kernels = []
+    for name, fn, nbytes, flops, bound in wl.kernels:
+        for _ in range(5):
+            fn()
+        ms = time_region(torch, fn, args.kernel_iters)
+        if bound == "mfma":
+            achieved, peak, unit = flops / (ms * 1e-3) / 1e12, FP8_PEAK_TFLOPS, "TFLOP/s"
+        else:
+            achieved, peak, unit = nbytes / (ms * 1e-3) / 1e9, HBM_PEAK_GBS, "GB/s"
+        kernels.append({"kernel": name, "bound": bound, "us": ms * 1e3, "achieved": achieved,
+                        "peak": peak, "unit": unit, "frac": achieved / peak,
+                        "alg_bytes": nbytes, "flops": flops,
+                        "hbm_gbs": nbytes / (ms * 1e-3) / 1e9})
+    dom = max(kernels, key=lambda k: k["us"])
+    roofline = {"kernel": dom["kernel"], "bound": dom["bound"], "achieved": dom["achieved"],
+                "peak": dom["peak"], "unit": dom["unit"], "frac": dom["frac"], "traffic": None}
+    gemm_us = sum(k["us"] for k in kernels if k["bound"] == "mfma")
+
+    out = {
+        "metric": "FP8 GEMM TFLOP/s (E5M2 in, FP32 acc, FP8 out) and % of MFMA FP8 peak",
+        "value": value,
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "fp8_e5m2 x fp8_e5m2 -> f32",
+        "data": "synthetic",
+        "config": {"workload": "configs[1]: ResNet-50-style 3x3 conv as GEMM, M=25088 N=128 K=1152, "
+                               "quantize + fwd + bwd_data + wgrad + FP16 SR update, loss scale 2^12",
+                   "M": lay.M, "N": lay.N, "K": lay.K},
+        "pct_of_fp8_peak_whole_step": 100.0 * value / FP8_PEAK_TFLOPS,
+        "gemm_only_tflops": gemm_flops / (gemm_us * 1e-6) / 1e12,
+        "overflow_count_last_step": nonfinite,
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(lay)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,171 @@
+/*
+ * mp8 -- the 8-bit floating point (s=1, e=5, m=2) training primitive of
+ * "Mixed Precision Training With 8-bit Floating Point" (arXiv 1905.12334) for AMD
+ * MI355X (gfx950).  C ABI of libmp8.so.
+ *
+ * General rules for every entry point that takes a `stream`:
+ *   - All tensor pointers are DEVICE pointers owned by the caller; the library never
+ *     allocates, frees or keeps them.  Tensors are row-major, last dimension contiguous.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  A call only
+ *     enqueues work on that stream and returns; it never synchronises.
+ *   - Errors are return codes.  On any error nothing has been enqueued.
+ *   - `stats`, where present, is a nullable DEVICE pointer to an mp8_stats that the caller
+ *     zeroes; calls accumulate into it (atomic max / atomic add), so one struct can collect
+ *     a whole step.
+ *   - Random bits for stochastic rounding come from Philox4x32-10 keyed by `seed`, with the
+ *     call's `offset` in the upper counter words and the element's row-major linear index
+ *     selecting counter and halfword (see mp8_sr_bits).  The same (seed, offset, index)
+ *     always gives the same bits, whatever the launch shape.
+ */
+#ifndef MP8_H
+#define MP8_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MP8_OK = 0,
+    MP8_ERR_INVALID_ARG = 1, /* null pointer, negative size, bad enum value            */
+    MP8_ERR_UNSUPPORTED = 2, /* a shape or stride the kernels cannot handle            */
+    MP8_ERR_ALIGNMENT = 3,   /* pointer or leading dimension not aligned as required   */
+    MP8_ERR_WORKSPACE = 4,   /* workspace missing or smaller than the query says       */
+    MP8_ERR_HIP = 5          /* the HIP runtime refused the launch                     */
+} mp8_status;
+
+/* Rounding of a down-conversion (Section 3.2): round to nearest even, or stochastic
+ * rounding with 16 random bits per element. */
+typedef enum { MP8_RNE = 0, MP8_SR = 1 } mp8_round;
+
+/* Which of the three training GEMMs (Section 3, Figure 1a). */
+typedef enum { MP8_FWD = 0, MP8_BWD_DATA = 1, MP8_WGRAD = 2 } mp8_op;
+
+/* Finite values beyond the largest normal (57344) become +-57344 instead of +-Inf. */
+enum { MP8_FLAG_SATURATE = 1 };
+
+typedef struct {
+    uint32_t amax_bits; /* max over elements of the FP32 bit pattern of |value before
+                           rounding|; any NaN counts as 0x7FC00000                     */
+    uint32_t nonfinite; /* number of produced (quantize, gemm) or consumed (update)
+                           8-bit codes that are Inf or NaN                             */
+    uint32_t zeroed;    /* number of non-zero values that were rounded to +-0          */
+    uint32_t rsvd;
+} mp8_stats;
+
+/*
+ * The Q node of Figure 1a: dst[i] = Q(fl32(src[i] * scale)), one IEEE single multiply
+ * followed by one rounding to the 8-bit format.  `scale` is where the loss scale of
+ * Section 3.1 is applied to error tensors (1.0f otherwise).
+ *   src        [rows, cols] FP32, or IEEE half if src_is_f16 != 0; 16-byte aligned
+ *   dst        [rows, cols] 8-bit codes; 16-byte aligned
+ *   dst_t      nullable; [cols, rows], the same codes transposed (rounded once, stored
+ *              twice); 16-byte aligned
+ *   NaN -> 0x7F.  Overflow -> +-Inf (0x7C/0xFC), or +-57344 with MP8_FLAG_SATURATE.
+ *   rows*cols == 0 is valid and does nothing.
+ */
+mp8_status mp8_quantize_e5m2(const void *src, int src_is_f16, uint8_t *dst, uint8_t *dst_t,
+                             int64_t rows, int64_t cols, float scale, mp8_round round,
+                             int flags, uint64_t seed, uint64_t offset, mp8_stats *stats,
+                             void *stream);
+
+/*
+ * The FP8 compute primitive of Section 3: two 8-bit operands, FP32 accumulation, and the
+ * result rounded once to 8 bits in the epilogue (the Q node after each GEMM in Figure 1a).
+ *
+ * (M, N, K) are always the LAYER dimensions X[M,K] . W[K,N] = Y[M,N]; `op` selects the
+ * contraction.  Both operands are passed with the contraction index contiguous:
+ *        out[r, c] = sum_j a[r, j] * b[c, j]
+ *     MP8_FWD       a = X8   [M, K]   b = W8^T  [N, K]   out [M, N]   contraction K
+ *     MP8_BWD_DATA  a = dY8  [M, N]   b = W8    [K, N]   out [M, K]   contraction N
+ *     MP8_WGRAD     a = X8^T [K, M]   b = dY8^T [N, M]   out [K, N]   contraction M
+ *   lda, ldb   leading dimensions in elements (>= contraction length, multiples of 16)
+ *   a, b       16-byte aligned
+ *   alpha      out8 = Q(fl32(alpha * acc)); acc itself is stored unscaled
+ *   acc        nullable FP32 [rows, cols] (16-byte aligned).  acc_mode 0: not touched;
+ *              1: receives the FP32 accumulator; 2: acc += accumulator, and out8 is the
+ *              rounding of the updated acc (accumulation across calls, e.g. timesteps)
+ *   out8       nullable [rows, cols] 8-bit result; out8_t nullable [cols, rows] transposed
+ *   round      rounding of the epilogue; SR uses index r*cols + c
+ *   workspace  device scratch of at least mp8_gemm_fp8_workspace_bytes(op, M, N, K) bytes
+ *              (may be NULL when that is 0); 16-byte aligned; contents undefined afterwards
+ * Any contraction length >= 1 and any rows/cols >= 1 are accepted (ragged shapes run on a
+ * slower kernel); a zero dimension is valid and does nothing.  Partial sums of a split
+ * contraction are combined in FP32, in a fixed order, before the single rounding, so results
+ * are bit-reproducible run to run.
+ */
+mp8_status mp8_gemm_fp8(mp8_op op, int64_t M, int64_t N, int64_t K, const uint8_t *a,
+                        int64_t lda, const uint8_t *b, int64_t ldb, float alpha, float *acc,
+                        int acc_mode, uint8_t *out8, uint8_t *out8_t, mp8_round round,
+                        int flags, uint64_t seed, uint64_t offset, mp8_stats *stats,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+/* Upper bound of the scratch mp8_gemm_fp8 needs for this shape (0 if none). */
+size_t mp8_gemm_fp8_workspace_bytes(mp8_op op, int64_t M, int64_t N, int64_t K);
+
+/*
+ * As mp8_gemm_fp8 with the kernel choice made by the caller (for tuning and tests):
+ * tile_config 0 = automatic, otherwise an index below mp8_gemm_num_tile_configs() + 1;
+ * split_k 0 = automatic, otherwise the number of contraction slices.  Workspace need:
+ * mp8_gemm_fp8_workspace_bytes_tuned with the same two values.
+ */
+mp8_status mp8_gemm_fp8_tuned(mp8_op op, int64_t M, int64_t N, int64_t K, const uint8_t *a,
+                              int64_t lda, const uint8_t *b, int64_t ldb, float alpha,
+                              float *acc, int acc_mode, uint8_t *out8, uint8_t *out8_t,
+                              mp8_round round, int flags, uint64_t seed, uint64_t offset,
+                              mp8_stats *stats, void *workspace, size_t workspace_bytes,
+                              void *stream, int tile_config, int split_k);
+size_t mp8_gemm_fp8_workspace_bytes_tuned(mp8_op op, int64_t M, int64_t N, int64_t K,
+                                          int tile_config, int split_k);
+int mp8_gemm_num_tile_configs(void);
+/* Writes "BMxBNxBK" style description of tile_config (1-based) into buf. */
+int mp8_gemm_tile_config_name(int tile_config, char *buf, size_t buflen);
+
+/*
+ * The weight-update path of Figure 1b on half-precision master weights, per element:
+ *     g    = fl32(value(g8[i]) * inv_loss_scale)     un-scaling in full precision
+ *     w    = float(w16[i])
+ *     w'   = fmaf(-lr, g, w)                         32-bit update
+ *     w16[i] = half(w') rounded by `round` (SR uses index i)
+ *   w16              in/out IEEE half codes, 16-byte aligned
+ *   g8               8-bit weight gradients, 16-byte aligned
+ *   skip_if_nonzero  nullable device word; if it is non-zero when the kernel runs, nothing
+ *                    is written (an overflowed step is skipped without a host round trip)
+ *   w8_out           nullable; receives Q_RNE(new w16[i]), the next step's 8-bit weights
+ *   stats->nonfinite counts Inf/NaN codes in g8 (counted even when skipping)
+ */
+mp8_status mp8_sgd_update_fp16_sr(uint16_t *w16, const uint8_t *g8, int64_t n, float lr,
+                                  float inv_loss_scale, mp8_round round, uint64_t seed,
+                                  uint64_t offset, const uint32_t *skip_if_nonzero,
+                                  uint8_t *w8_out, mp8_stats *stats, void *stream);
+
+/* out[i] = the 16 random bits element i would use (device array of n uint16), for tests. */
+mp8_status mp8_sr_bits(uint16_t *out, int64_t n, uint64_t seed, uint64_t offset, void *stream);
+
+/* Host: one Philox4x32-10 block (Salmon et al., SC'11).  Host pointers. */
+void mp8_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
+
+/*
+ * Host-side loss scaler of Section 3.1: back-off dynamic scaling with a minimum threshold
+ * that the caller raises as training proceeds.  update(): nonfinite != 0 halves the scale
+ * (not below `floor`), resets the clean-step count and returns 1 (skip the step);
+ * otherwise counts a clean step, doubles the scale after growth_interval of them, returns 0.
+ */
+typedef struct {
+    double scale;
+    double floor;
+    int64_t growth_interval;
+    int64_t good_steps;
+} mp8_scaler;
+void mp8_scaler_init(mp8_scaler *s, double scale, double floor, int64_t growth_interval);
+int mp8_scaler_update(mp8_scaler *s, uint32_t nonfinite);
+void mp8_scaler_set_floor(mp8_scaler *s, double floor);
+
+const char *mp8_status_string(mp8_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MP8_H */

@@ -1,0 +1,238 @@
+"""Python binding of libmp8.so -- the MI355X-native 8-bit floating point training primitive
+(arXiv 1905.12334): ``quantize_e5m2``, ``gemm_fp8`` and ``sgd_update_fp16_sr``.
+
+Argument marshalling only: every function takes torch tensors that already live on the GPU,
+passes their ``data_ptr()`` and the current HIP stream through the C ABI declared in
+``include/mp8.h`` and returns without synchronising.  There is no CPU fallback: if the HIP
+library has not been built, loading it raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmp8.so")
+
+RNE, SR = 0, 1
+FWD, BWD_DATA, WGRAD = 0, 1, 2
+FLAG_SATURATE = 1
+
+EXPORTS = [
+    "mp8_quantize_e5m2", "mp8_gemm_fp8", "mp8_gemm_fp8_workspace_bytes", "mp8_gemm_fp8_tuned",
+    "mp8_gemm_fp8_workspace_bytes_tuned", "mp8_gemm_num_tile_configs",
+    "mp8_gemm_tile_config_name", "mp8_sgd_update_fp16_sr", "mp8_sr_bits", "mp8_philox4x32_10",
+    "mp8_scaler_init", "mp8_scaler_update", "mp8_scaler_set_floor", "mp8_status_string",
+]
+
+
+class Mp8Error(RuntimeError):
+    pass
+
+
+class Scaler(C.Structure):
+    """mp8_scaler: host-side dynamic loss scaler with a minimum threshold."""
+    _fields_ = [("scale", C.c_double), ("floor", C.c_double),
+                ("growth_interval", C.c_int64), ("good_steps", C.c_int64)]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load libmp8.so (built in-tree by ``build.py``); raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise Mp8Error(f"{LIB_PATH} not found: build it with `python -m paper_1905_12334_amd.build` "
+                       "(or __graft_entry__.build()); there is no fallback path")
+    L = C.CDLL(LIB_PATH)
+    i64, u64, vp, f32, ci = C.c_int64, C.c_uint64, C.c_void_p, C.c_float, C.c_int
+    L.mp8_quantize_e5m2.restype = ci
+    L.mp8_quantize_e5m2.argtypes = [vp, ci, vp, vp, i64, i64, f32, ci, ci, u64, u64, vp, vp]
+    gemm_args = [ci, i64, i64, i64, vp, i64, vp, i64, f32, vp, ci, vp, vp, ci, ci, u64, u64, vp,
+                 vp, C.c_size_t, vp]
+    L.mp8_gemm_fp8.restype = ci
+    L.mp8_gemm_fp8.argtypes = gemm_args
+    L.mp8_gemm_fp8_tuned.restype = ci
+    L.mp8_gemm_fp8_tuned.argtypes = gemm_args + [ci, ci]
+    L.mp8_gemm_fp8_workspace_bytes.restype = C.c_size_t
+    L.mp8_gemm_fp8_workspace_bytes.argtypes = [ci, i64, i64, i64]
+    L.mp8_gemm_fp8_workspace_bytes_tuned.restype = C.c_size_t
+    L.mp8_gemm_fp8_workspace_bytes_tuned.argtypes = [ci, i64, i64, i64, ci, ci]
+    L.mp8_gemm_num_tile_configs.restype = ci
+    L.mp8_gemm_num_tile_configs.argtypes = []
+    L.mp8_gemm_tile_config_name.restype = ci
+    L.mp8_gemm_tile_config_name.argtypes = [ci, C.c_char_p, C.c_size_t]
+    L.mp8_sgd_update_fp16_sr.restype = ci
+    L.mp8_sgd_update_fp16_sr.argtypes = [vp, vp, i64, f32, f32, ci, u64, u64, vp, vp, vp, vp]
+    L.mp8_sr_bits.restype = ci
+    L.mp8_sr_bits.argtypes = [vp, i64, u64, u64, vp]
+    L.mp8_philox4x32_10.restype = None
+    L.mp8_philox4x32_10.argtypes = [C.POINTER(C.c_uint32), C.POINTER(C.c_uint32),
+                                    C.POINTER(C.c_uint32)]
+    L.mp8_scaler_init.restype = None
+    L.mp8_scaler_init.argtypes = [C.POINTER(Scaler), C.c_double, C.c_double, i64]
+    L.mp8_scaler_update.restype = ci
+    L.mp8_scaler_update.argtypes = [C.POINTER(Scaler), C.c_uint32]
+    L.mp8_scaler_set_floor.restype = None
+    L.mp8_scaler_set_floor.argtypes = [C.POINTER(Scaler), C.c_double]
+    L.mp8_status_string.restype = C.c_char_p
+    L.mp8_status_string.argtypes = [ci]
+    _lib = L
+    return L
+
+
+def _check(status: int, what: str) -> None:
+    if status != 0:
+        raise Mp8Error(f"{what}: {lib().mp8_status_string(status).decode()} (status {status})")
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t, name, dtype=None):
+    if t is None:
+        return
+    if not t.is_cuda:
+        raise Mp8Error(f"{name} must be a GPU tensor")
+    if not t.is_contiguous():
+        raise Mp8Error(f"{name} must be contiguous")
+    if dtype is not None and t.dtype not in (dtype if isinstance(dtype, tuple) else (dtype,)):
+        raise Mp8Error(f"{name} has dtype {t.dtype}, expected {dtype}")
+
+
+def new_stats(device="cuda"):
+    """A zeroed mp8_stats on the device: uint32 [amax_bits, nonfinite, zeroed, rsvd] as int32."""
+    import torch
+    return torch.zeros(4, dtype=torch.int32, device=device)
+
+
+def read_stats(stats):
+    """(amax_bits, nonfinite, zeroed) as python ints (synchronises)."""
+    v = [int(x) & 0xFFFFFFFF for x in stats.cpu().tolist()]
+    return v[0], v[1], v[2]
+
+
+def quantize_e5m2(src, dst, dst_t=None, scale=1.0, round=RNE, flags=0, seed=0, offset=0,
+                  stats=None):
+    """mp8_quantize_e5m2: dst = Q(fl32(src*scale)); src [rows, cols] float32/float16."""
+    import torch
+    _dev(src, "src", (torch.float32, torch.float16))
+    _dev(dst, "dst", torch.uint8)
+    _dev(dst_t, "dst_t", torch.uint8)
+    if src.dim() != 2:
+        raise Mp8Error("src must be 2-D")
+    rows, cols = src.shape
+    if dst.numel() != rows * cols or (dst_t is not None and dst_t.numel() != rows * cols):
+        raise Mp8Error("dst / dst_t size does not match src")
+    st = lib().mp8_quantize_e5m2(_ptr(src), int(src.dtype == torch.float16), _ptr(dst), _ptr(dst_t),
+                                 rows, cols, float(scale), round, flags, seed, offset,
+                                 _ptr(stats), _stream())
+    _check(st, "mp8_quantize_e5m2")
+    return dst
+
+
+def _op_dims(op, M, N, K):
+    return {FWD: (M, N, K), BWD_DATA: (M, K, N), WGRAD: (K, N, M)}[op]
+
+
+def gemm_fp8_workspace_bytes(op, M, N, K, tile_config=0, split_k=0) -> int:
+    return int(lib().mp8_gemm_fp8_workspace_bytes_tuned(op, M, N, K, tile_config, split_k))
+
+
+def gemm_fp8(op, M, N, K, a, b, out8=None, out8_t=None, acc=None, acc_mode=0, alpha=1.0,
+             round=RNE, flags=0, seed=0, offset=0, stats=None, workspace=None, lda=None,
+             ldb=None, tile_config=0, split_k=0):
+    """mp8_gemm_fp8(_tuned): out[r,c] = sum_j a[r,j]*b[c,j] with the operand orientation of
+    include/mp8.h.  All tensors are caller-allocated GPU tensors; workspace is a uint8/any
+    tensor of at least gemm_fp8_workspace_bytes(...) bytes when that is non-zero."""
+    import torch
+    _dev(a, "a", torch.uint8)
+    _dev(b, "b", torch.uint8)
+    _dev(out8, "out8", torch.uint8)
+    _dev(out8_t, "out8_t", torch.uint8)
+    _dev(acc, "acc", torch.float32)
+    rows, cols, kc = _op_dims(op, M, N, K)
+    lda = kc if lda is None else lda
+    ldb = kc if ldb is None else ldb
+    if rows > 0 and a.numel() < (rows - 1) * lda + kc:
+        raise Mp8Error("a is smaller than [rows, lda] requires")
+    if cols > 0 and b.numel() < (cols - 1) * ldb + kc:
+        raise Mp8Error("b is smaller than [cols, ldb] requires")
+    for t, name in ((out8, "out8"), (out8_t, "out8_t"), (acc, "acc")):
+        if t is not None and t.numel() < rows * cols:
+            raise Mp8Error(f"{name} is smaller than rows*cols")
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = lib().mp8_gemm_fp8_tuned(op, M, N, K, _ptr(a), lda, _ptr(b), ldb, float(alpha), _ptr(acc),
+                                  acc_mode, _ptr(out8), _ptr(out8_t), round, flags, seed, offset,
+                                  _ptr(stats), _ptr(workspace), ws_bytes, _stream(), tile_config,
+                                  split_k)
+    _check(st, "mp8_gemm_fp8")
+    return out8
+
+
+def gemm_tile_configs():
+    n = lib().mp8_gemm_num_tile_configs()
+    names = []
+    for i in range(1, n + 1):
+        buf = C.create_string_buffer(64)
+        lib().mp8_gemm_tile_config_name(i, buf, 64)
+        names.append(buf.value.decode())
+    return names
+
+
+def sgd_update_fp16_sr(w16, g8, lr, inv_loss_scale, round=SR, seed=0, offset=0,
+                       skip_if_nonzero=None, w8_out=None, stats=None):
+    """mp8_sgd_update_fp16_sr: in-place SGD step on float16 master weights from 8-bit grads."""
+    import torch
+    _dev(w16, "w16", (torch.float16, torch.int16, torch.uint16))
+    _dev(g8, "g8", torch.uint8)
+    _dev(w8_out, "w8_out", torch.uint8)
+    n = w16.numel()
+    if g8.numel() != n or (w8_out is not None and w8_out.numel() != n):
+        raise Mp8Error("g8 / w8_out size does not match w16")
+    st = lib().mp8_sgd_update_fp16_sr(_ptr(w16), _ptr(g8), n, float(lr), float(inv_loss_scale),
+                                      round, seed, offset, _ptr(skip_if_nonzero), _ptr(w8_out),
+                                      _ptr(stats), _stream())
+    _check(st, "mp8_sgd_update_fp16_sr")
+    return w16
+
+
+def sr_bits(out, seed=0, offset=0):
+    """mp8_sr_bits: out[i] (int16/uint16 GPU tensor) = the 16 random bits of element i."""
+    _dev(out, "out")
+    if out.element_size() != 2:
+        raise Mp8Error("out must have 2-byte elements")
+    _check(lib().mp8_sr_bits(_ptr(out), out.numel(), seed, offset, _stream()), "mp8_sr_bits")
+    return out
+
+
+def philox4x32_10(ctr, key):
+    """Host: one Philox4x32-10 block; ctr 4 words, key 2 words -> list of 4 ints."""
+    c = (C.c_uint32 * 4)(*[int(x) & 0xFFFFFFFF for x in ctr])
+    k = (C.c_uint32 * 2)(*[int(x) & 0xFFFFFFFF for x in key])
+    o = (C.c_uint32 * 4)()
+    lib().mp8_philox4x32_10(c, k, o)
+    return [int(x) for x in o]
+
+
+def scaler_new(scale, floor, growth_interval=2000) -> Scaler:
+    s = Scaler()
+    lib().mp8_scaler_init(C.byref(s), float(scale), float(floor), int(growth_interval))
+    return s
+
+
+def scaler_update(s: Scaler, nonfinite: int) -> int:
+    return int(lib().mp8_scaler_update(C.byref(s), int(nonfinite)))
+
+
+def scaler_set_floor(s: Scaler, floor: float) -> None:
+    lib().mp8_scaler_set_floor(C.byref(s), float(floor))

@@ -1,0 +1,607 @@
+// mp8_gemm_fp8: the FP8 compute primitive of Section 3 (arXiv 1905.12334) for gfx950 --
+// two 8-bit (1,5,2) operands, FP32 accumulation on the matrix cores, and the Q node of
+// Figure 1a (one rounding of the complete FP32 sum to 8 bits, RNE or stochastic) fused into
+// the epilogue.  The three training GEMMs (forward, backward-data, weight-gradient) are the
+// same contraction  out[r,c] = sum_j a[r,j] * b[c,j]  on differently oriented operands.
+//
+// Main kernel: 256 threads (4 waves), block tile BM x BN x 128 bytes of contraction per
+// step.  Operand slabs travel HBM -> LDS with direct-to-LDS 16-byte loads into a two-stage
+// ring, are read as 32-byte-per-lane fragments and multiplied with
+// v_mfma_f32_32x32x64_f8f6f4 in its bf8 x bf8 form.  The LDS image is XOR-swizzled in
+// 16-byte chunks so that fragment reads are bank-conflict free; because direct-to-LDS
+// writes are lane-contiguous the swizzle is applied to the global address each lane
+// fetches.  The operands are fed to the MFMA swapped (b as the "row" matrix) so that each
+// lane ends up with four consecutive output columns of one output row.
+//
+// Split contraction: slices write FP32 partial tiles to the workspace and a second kernel
+// sums them in slice order and applies the epilogue -- the sum is rounded exactly once.
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+
+#include "mp8_device.hpp"
+
+namespace mp8 {
+
+using i32x8 = int __attribute__((ext_vector_type(8)));
+using i32x4 = int __attribute__((ext_vector_type(4)));
+using f32x16 = float __attribute__((ext_vector_type(16)));
+
+constexpr int BK = 128;  // bytes (= elements) of contraction per main-loop step
+
+struct Epilogue {
+    float alpha;
+    float *acc;
+    int acc_mode;
+    uint8_t *out8;
+    uint8_t *out8_t;
+    int sr;
+    int sat;
+    uint64_t seed, offset;
+    mp8_stats *stats;
+    int64_t rows, cols;
+};
+
+struct GemmArgs {
+    const uint8_t *a;
+    const uint8_t *b;
+    int64_t lda, ldb;
+    int64_t rows, cols;
+    int ksteps;         // contraction length / BK
+    int splits;         // number of contraction slices
+    int tiles_m, tiles_n;
+    float *partial;     // [splits, rows, cols] when splits > 1
+    Epilogue ep;
+};
+
+// One output element, any shape: optional FP32 accumulate / store, one rounding to 8 bits,
+// optional transposed copy, statistics.  Kept out of line: it only serves ragged shapes.
+__device__ __noinline__ void finish1(const Epilogue &ep, int64_t r, int64_t c, float v,
+                                     StatsAcc &st) {
+    const int64_t i = r * ep.cols + c;
+    if (ep.acc_mode != 0) {
+        if (ep.acc_mode == 2) v += ep.acc[i];
+        ep.acc[i] = v;
+    }
+    if (ep.out8 == nullptr && ep.out8_t == nullptr && ep.stats == nullptr) return;
+    const uint32_t u = f2u(v * ep.alpha);
+    uint32_t code;
+    if (ep.sr) {
+        const Philox rng(ep.seed, ep.offset);
+        uint32_t r16 = philox_half(rng.block((uint64_t)i >> 3), (int)(i & 7));
+        code = e5m2_from_f32_bits<true>(u, r16, ep.sat != 0);
+    } else {
+        code = e5m2_from_f32_bits<false>(u, 0u, ep.sat != 0);
+    }
+    if (ep.stats != nullptr) st.add(u & 0x7FFFFFFFu, code);
+    if (ep.out8 != nullptr) ep.out8[i] = (uint8_t)code;
+    if (ep.out8_t != nullptr) ep.out8_t[c * ep.rows + r] = (uint8_t)code;
+}
+
+// Finish sixteen consecutive columns c .. c+15 (c % 16 == 0, c < cols) of output row r.
+// When the row length is a multiple of 16 everything is done with 16-byte accesses and two
+// Philox blocks; otherwise element by element.
+template <bool kSR>
+__device__ __forceinline__ void finish16(const Epilogue &ep, int64_t r, int64_t c, float v[16],
+                                         StatsAcc &st) {
+    const int64_t cols = ep.cols;
+    if ((cols & 15) != 0) {
+        for (int j = 0; j < 16 && c + j < cols; ++j) finish1(ep, r, c + j, v[j], st);
+        return;
+    }
+    const int64_t i0 = r * cols + c;
+    if (ep.acc_mode != 0) {
+        f32x4 *p = reinterpret_cast<f32x4 *>(ep.acc + i0);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (ep.acc_mode == 2) {
+                f32x4 o = p[q];
+                v[4 * q] += o.x; v[4 * q + 1] += o.y; v[4 * q + 2] += o.z; v[4 * q + 3] += o.w;
+            }
+            f32x4 n = {v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]};
+            p[q] = n;
+        }
+    }
+    if (ep.out8 == nullptr && ep.out8_t == nullptr && ep.stats == nullptr) return;
+    uint32_t rw[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if constexpr (kSR) {
+        const Philox rng(ep.seed, ep.offset);
+        uint4 w0 = rng.block((uint64_t)i0 >> 3), w1 = rng.block(((uint64_t)i0 >> 3) + 1);
+        rw[0] = w0.x; rw[1] = w0.y; rw[2] = w0.z; rw[3] = w0.w;
+        rw[4] = w1.x; rw[5] = w1.y; rw[6] = w1.z; rw[7] = w1.w;
+    }
+    uint32_t pk[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        uint32_t u = f2u(v[j] * ep.alpha);
+        uint32_t r16 = (j & 1) ? (rw[j >> 1] >> 16) : (rw[j >> 1] & 0xFFFFu);
+        uint32_t code = e5m2_from_f32_bits<kSR>(u, r16, ep.sat != 0);
+        if (ep.stats != nullptr) st.add(u & 0x7FFFFFFFu, code);
+        pk[j >> 2] |= code << (8 * (j & 3));
+    }
+    if (ep.out8 != nullptr) {
+        u32x4 o = {pk[0], pk[1], pk[2], pk[3]};
+        *reinterpret_cast<u32x4 *>(ep.out8 + i0) = o;
+    }
+    if (ep.out8_t != nullptr) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+            ep.out8_t[(c + j) * ep.rows + r] = (uint8_t)(pk[j >> 2] >> (8 * (j & 3)));
+    }
+}
+
+// Map the linear workgroup id to (slice, tile row, tile column).  Consecutive ids go to
+// different XCDs (round robin), so ids are first regrouped so that each XCD works on a
+// contiguous range of tiles and its L2 sees operand reuse; inside the range, tiles are
+// walked in bands of 8 tile-rows.
+__device__ __forceinline__ void map_block(int tiles_m, int tiles_n, int &split, int &tm, int &tn) {
+    const int nb = (int)gridDim.x, bid = (int)blockIdx.x;
+    const int xcd = bid & 7, idx = bid >> 3;
+    const int per = nb >> 3, rem = nb & 7;
+    const int pid = xcd * per + (xcd < rem ? xcd : rem) + idx;
+    const int tiles = tiles_m * tiles_n;
+    split = pid / tiles;
+    const int t = pid - split * tiles;
+    constexpr int GM = 8;
+    const int band = GM * tiles_n;
+    const int g = t / band;
+    const int first = g * GM;
+    const int gsz = (tiles_m - first) < GM ? (tiles_m - first) : GM;
+    const int in = t - g * band;
+    tm = first + in % gsz;
+    tn = in / gsz;
+}
+
+// Wait until at most n vector-memory operations of this wave are outstanding (gfx9 encoding:
+// vmcnt in bits 3:0 and 15:14; expcnt and lgkmcnt fields left at "no wait").
+template <int n>
+__device__ __forceinline__ void wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt((n & 0xF) | ((n >> 4) << 14) | (0x7 << 4) | (0xF << 8));
+}
+
+// One direct-to-LDS load: 64 lanes x 16 bytes land at lds_base + lane * 16.
+__device__ __forceinline__ void dma16(const uint8_t *gptr, uint8_t *lds_base) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gptr,
+                                     (__attribute__((address_space(3))) void *)lds_base, 16, 0, 0);
+}
+
+template <int BM, int BN, int WGM, int WGN>
+__global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(const GemmArgs p) {
+    static_assert(WGM * WGN == 4, "four waves");
+    constexpr int WTM = BM / WGM, WTN = BN / WGN;  // wave tile
+    constexpr int MT = WTM / 32, NT = WTN / 32;    // 32x32 MFMA tiles per wave
+    constexpr int A_BYTES = BM * BK, B_BYTES = BN * BK, STAGE = A_BYTES + B_BYTES;
+    constexpr int A_DMA = BM / 32, B_DMA = BN / 32;  // direct loads per wave per step
+    // the operand ring, reused by the epilogue for FP32 row bands (2 x 32 rows per wave)
+    constexpr int EP_BYTES = 4 * (MT >= 2 ? 2 : 1) * 32 * (WTN + 4) * 4;
+    constexpr int LDS_BYTES = 2 * STAGE > EP_BYTES ? 2 * STAGE : EP_BYTES;
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[LDS_BYTES];
+
+    int split, tm, tn;
+    map_block(p.tiles_m, p.tiles_n, split, tm, tn);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave / WGN, wn = wave % WGN;
+    const int64_t row0 = (int64_t)tm * BM, col0 = (int64_t)tn * BN;
+
+    // contraction slice of this workgroup
+    const int per = p.ksteps / p.splits, extra = p.ksteps % p.splits;
+    const int ks_begin = split * per + (split < extra ? split : extra);
+    const int ks_count = per + (split < extra ? 1 : 0);
+
+    // Per-lane global offsets of the direct loads.  Load q of this wave brings rows
+    // 8*(wave + 4q) .. +7 of the tile; lane i lands in LDS slot (row i/8, chunk i%8) and
+    // therefore fetches global chunk (i%8) ^ (i/8) of that row.  Rows beyond the matrix
+    // are clamped to its last row (their products are never stored).
+    const int lrow = lane >> 3, lchunk = (lane & 7) ^ (lane >> 3);
+    const uint8_t *ga[A_DMA];
+    const uint8_t *gb[B_DMA];
+#pragma unroll
+    for (int q = 0; q < A_DMA; ++q) {
+        int64_t r = row0 + 8 * (wave + 4 * q) + lrow;
+        r = r < p.rows ? r : p.rows - 1;
+        ga[q] = p.a + r * p.lda + (int64_t)ks_begin * BK + lchunk * 16;
+    }
+#pragma unroll
+    for (int q = 0; q < B_DMA; ++q) {
+        int64_t c = col0 + 8 * (wave + 4 * q) + lrow;
+        c = c < p.cols ? c : p.cols - 1;
+        gb[q] = p.b + c * p.ldb + (int64_t)ks_begin * BK + lchunk * 16;
+    }
+
+    auto issue_loads = [&](int stage, int kstep) {
+        uint8_t *sa = lds + stage * STAGE;
+        uint8_t *sb = sa + A_BYTES;
+#pragma unroll
+        for (int q = 0; q < A_DMA; ++q)
+            dma16(ga[q] + (int64_t)kstep * BK, sa + (wave + 4 * q) * 1024);
+#pragma unroll
+        for (int q = 0; q < B_DMA; ++q)
+            dma16(gb[q] + (int64_t)kstep * BK, sb + (wave + 4 * q) * 1024);
+    };
+
+    f32x16 acc[MT][NT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+    // Fragment addressing: lane l supplies row (l % 32) of a 32-row tile and the 32 bytes
+    // k = 64*s + 32*(l/32) .. +31 of sub-step s, i.e. chunks 4s + 2*(l/32) and the next one,
+    // found at LDS slot chunk ^ (row % 8).
+    const int frow = lane & 31, fkb = lane >> 5;
+    const int fsw = frow & 7;
+    const int a_base = (wm * WTM + frow) * BK;
+    const int b_base = A_BYTES + (wn * WTN + frow) * BK;
+
+    if (ks_count > 0) issue_loads(0, 0);
+    for (int ks = 0; ks < ks_count; ++ks) {
+        const int stage = ks & 1;
+        wait_vmcnt<0>();
+        __syncthreads();  // stage `stage` is complete; everyone left stage `stage ^ 1`
+        if (ks + 1 < ks_count) issue_loads(stage ^ 1, ks + 1);
+        const uint8_t *s = lds + stage * STAGE;
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            const int c0 = ((4 * sub + 2 * fkb) ^ fsw) * 16;
+            const int c1 = ((4 * sub + 2 * fkb + 1) ^ fsw) * 16;
+            i32x8 af[MT], bf[NT];
+#pragma unroll
+            for (int i = 0; i < MT; ++i) {
+                i32x4 lo = *reinterpret_cast<const i32x4 *>(s + a_base + i * 32 * BK + c0);
+                i32x4 hi = *reinterpret_cast<const i32x4 *>(s + a_base + i * 32 * BK + c1);
+                af[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+                i32x4 lo = *reinterpret_cast<const i32x4 *>(s + b_base + j * 32 * BK + c0);
+                i32x4 hi = *reinterpret_cast<const i32x4 *>(s + b_base + j * 32 * BK + c1);
+                bf[j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                for (int j = 0; j < NT; ++j)
+                    // cbsz = blgp = 1 selects the (1,5,2) format for both operands; the
+                    // scale operands are zero, i.e. the unscaled instruction.
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                        bf[j], af[i], acc[i][j], 1, 1, 0, 0, 0, 0);
+        }
+    }
+
+    // Epilogue.  acc[i][j][4g + e] is output row  wm*WTM + 32i + lane%32  and column
+    // wn*WTN + 32j + 8g + 4*(lane/32) + e.  Each wave passes its tile through LDS one band
+    // of 32 rows at a time, so that afterwards every lane owns 16 consecutive columns of one
+    // row: full 16-byte stores of codes, 64-byte runs of FP32, one Philox block per eight
+    // elements.
+    constexpr int EP_LD = WTN + 4;                 // floats per band row (+4: bank spread)
+    constexpr int CG = WTN / 16;                   // 16-column groups per band row
+    constexpr int BANDS = MT >= 2 ? 2 : 1;         // bands staged per pass
+    static_assert(4 * BANDS * 32 * EP_LD * 4 <= LDS_BYTES, "band buffers fit in LDS");
+    __syncthreads();                               // all waves are done with the operand ring
+    float *band = reinterpret_cast<float *>(lds) + wave * BANDS * 32 * EP_LD;
+    StatsAcc st;
+    const bool partial = p.splits > 1;
+    const bool fast_cols = (p.cols & 15) == 0;
+#pragma unroll
+    for (int h = 0; h < MT; h += BANDS) {
+#pragma unroll
+        for (int bi = 0; bi < BANDS; ++bi)
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    f32x4 o = {acc[h + bi][j][4 * g], acc[h + bi][j][4 * g + 1],
+                               acc[h + bi][j][4 * g + 2], acc[h + bi][j][4 * g + 3]};
+                    *reinterpret_cast<f32x4 *>(band + (32 * bi + frow) * EP_LD + 32 * j + 8 * g +
+                                               4 * fkb) = o;
+                }
+        // the bands are private to this wave: order the LDS writes before the reads
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        for (int item = lane; item < BANDS * 32 * CG; item += 64) {
+            const int br = item / CG, cg = item - br * CG;
+            const int64_t r = row0 + wm * WTM + 32 * h + br;
+            const int64_t c = col0 + wn * WTN + 16 * cg;
+            if (r < p.rows && c < p.cols) {
+                float v[16];
+                const f32x4 *src = reinterpret_cast<const f32x4 *>(band + br * EP_LD + 16 * cg);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    f32x4 x = src[q];
+                    v[4 * q] = x.x; v[4 * q + 1] = x.y; v[4 * q + 2] = x.z; v[4 * q + 3] = x.w;
+                }
+                if (partial) {
+                    float *dst = p.partial + ((int64_t)split * p.rows + r) * p.cols + c;
+                    if (fast_cols) {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            f32x4 o = {v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]};
+                            reinterpret_cast<f32x4 *>(dst)[q] = o;
+                        }
+                    } else {
+                        for (int e = 0; e < 16 && c + e < p.cols; ++e) dst[e] = v[e];
+                    }
+                } else if (p.ep.sr) {
+                    finish16<true>(p.ep, r, c, v, st);
+                } else {
+                    finish16<false>(p.ep, r, c, v, st);
+                }
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+    if (!partial && p.ep.stats != nullptr) st.flush(p.ep.stats);
+}
+
+// Sum the slices in order and finish.  One thread per group of sixteen columns.
+__global__ __launch_bounds__(256) void splitk_finish_kernel(const float *__restrict__ partial,
+                                                            int splits, const Epilogue ep) {
+    const int64_t cgroups = (ep.cols + 15) >> 4;
+    const int64_t total = ep.rows * cgroups;
+    StatsAcc st;
+    const bool fast_cols = (ep.cols & 15) == 0;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += stride) {
+        const int64_t r = t / cgroups, c = (t - r * cgroups) << 4;
+        float v[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) v[e] = 0.f;
+        for (int s = 0; s < splits; ++s) {
+            const float *src = partial + ((int64_t)s * ep.rows + r) * ep.cols + c;
+            if (fast_cols) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    f32x4 x = reinterpret_cast<const f32x4 *>(src)[q];
+                    v[4 * q] += x.x; v[4 * q + 1] += x.y; v[4 * q + 2] += x.z; v[4 * q + 3] += x.w;
+                }
+            } else {
+                for (int e = 0; e < 16 && c + e < ep.cols; ++e) v[e] += src[e];
+            }
+        }
+        if (ep.sr) finish16<true>(ep, r, c, v, st);
+        else finish16<false>(ep, r, c, v, st);
+    }
+    if (ep.stats != nullptr) st.flush(ep.stats);
+}
+
+// Any-shape fallback: one thread per output element, operands decoded one by one, FP32 fused
+// multiply-adds in contraction order.  Used when the contraction length is not a multiple of
+// 128 or the operands are not 16-byte aligned.
+__global__ __launch_bounds__(256) void gemm_generic_kernel(const uint8_t *__restrict__ a,
+                                                           int64_t lda,
+                                                           const uint8_t *__restrict__ b,
+                                                           int64_t ldb, int64_t kc,
+                                                           const Epilogue ep) {
+    const int64_t total = ep.rows * ep.cols;
+    StatsAcc st;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += stride) {
+        const int64_t r = t / ep.cols, c = t - r * ep.cols;
+        const uint8_t *ar = a + r * lda, *bc = b + c * ldb;
+        float s = 0.f;
+        for (int64_t j = 0; j < kc; ++j)
+            s = __builtin_fmaf(e5m2_to_f32(ar[j]), e5m2_to_f32(bc[j]), s);
+        finish1(ep, r, c, s, st);
+    }
+    if (ep.stats != nullptr) st.flush(ep.stats);
+}
+
+// ---------------------------------------------------------------------------------------
+// Host side
+// ---------------------------------------------------------------------------------------
+struct TileConfig {
+    int bm, bn;
+    const char *name;
+    void (*kernel)(const GemmArgs);
+};
+
+static const TileConfig kTiles[] = {
+    {256, 256, "256x256x128", gemm_mfma_kernel<256, 256, 2, 2>},
+    {256, 128, "256x128x128", gemm_mfma_kernel<256, 128, 2, 2>},
+    {128, 256, "128x256x128", gemm_mfma_kernel<128, 256, 2, 2>},
+    {128, 128, "128x128x128", gemm_mfma_kernel<128, 128, 2, 2>},
+    {64, 128, "64x128x128", gemm_mfma_kernel<64, 128, 1, 4>},
+    {128, 64, "128x64x128", gemm_mfma_kernel<128, 64, 4, 1>},
+    {64, 64, "64x64x128", gemm_mfma_kernel<64, 64, 2, 2>},
+};
+constexpr int kNumTiles = (int)(sizeof(kTiles) / sizeof(kTiles[0]));
+constexpr int kCUs = 256;
+constexpr int kMaxSplits = 64;
+
+struct Plan {
+    bool mfma;
+    int tile;    // index into kTiles
+    int splits;
+    int tiles_m, tiles_n;
+};
+
+static void op_dims(mp8_op op, int64_t M, int64_t N, int64_t K, int64_t &rows, int64_t &cols,
+                    int64_t &kc) {
+    switch (op) {
+        case MP8_FWD: rows = M; cols = N; kc = K; break;
+        case MP8_BWD_DATA: rows = M; cols = K; kc = N; break;
+        default: rows = K; cols = N; kc = M; break;
+    }
+}
+
+// Choose tile shape and number of contraction slices.  Aim: at least one full wave of
+// workgroups over the 256 CUs, preferring large tiles (fewer LDS bytes per flop), and slices
+// of at least four main-loop steps.
+static Plan make_plan(int64_t rows, int64_t cols, int64_t kc, int tile_config, int split_k) {
+    Plan pl{};
+    pl.mfma = (kc % BK) == 0;
+    if (!pl.mfma) {
+        pl.splits = 1;
+        return pl;
+    }
+    const int ksteps = (int)(kc / BK);
+    auto tiles_of = [&](int t) {
+        return ((rows + kTiles[t].bm - 1) / kTiles[t].bm) * ((cols + kTiles[t].bn - 1) / kTiles[t].bn);
+    };
+    int t = 0;
+    if (tile_config > 0) {
+        t = tile_config - 1;
+    } else {
+        // largest tile that still yields >= kCUs workgroups with a sensible split; otherwise
+        // the smallest tile
+        t = kNumTiles - 1;
+        for (int cand = 0; cand < kNumTiles; ++cand) {
+            int64_t nt = tiles_of(cand);
+            int64_t max_split = std::max<int64_t>(1, std::min<int64_t>(kMaxSplits, ksteps / 4));
+            // padded work must not exceed real work by more than 25 %
+            double waste = (double)nt * kTiles[cand].bm * kTiles[cand].bn / ((double)rows * cols);
+            if (nt * max_split >= kCUs && waste <= 1.25) {
+                t = cand;
+                break;
+            }
+        }
+    }
+    pl.tile = t;
+    pl.tiles_m = (int)((rows + kTiles[t].bm - 1) / kTiles[t].bm);
+    pl.tiles_n = (int)((cols + kTiles[t].bn - 1) / kTiles[t].bn);
+    const int64_t nt = (int64_t)pl.tiles_m * pl.tiles_n;
+    int s = 1;
+    if (split_k > 0) {
+        s = split_k;
+    } else if (nt < kCUs) {
+        s = (int)((kCUs + nt - 1) / nt);
+        s = std::min<int>(s, std::max(1, ksteps / 4));
+        s = std::min(s, kMaxSplits);
+    }
+    s = std::max(1, std::min(s, ksteps));
+    pl.splits = s;
+    return pl;
+}
+
+static size_t plan_workspace(const Plan &pl, int64_t rows, int64_t cols) {
+    if (!pl.mfma || pl.splits <= 1) return 0;
+    return (size_t)pl.splits * (size_t)rows * (size_t)cols * sizeof(float);
+}
+
+}  // namespace mp8
+
+extern "C" int mp8_gemm_num_tile_configs(void) { return mp8::kNumTiles; }
+
+extern "C" int mp8_gemm_tile_config_name(int tile_config, char *buf, size_t buflen) {
+    if (tile_config < 1 || tile_config > mp8::kNumTiles || !buf || buflen == 0) return -1;
+    snprintf(buf, buflen, "%s", mp8::kTiles[tile_config - 1].name);
+    return 0;
+}
+
+extern "C" size_t mp8_gemm_fp8_workspace_bytes_tuned(mp8_op op, int64_t M, int64_t N, int64_t K,
+                                                     int tile_config, int split_k) {
+    using namespace mp8;
+    if (M <= 0 || N <= 0 || K <= 0 || (int)op < 0 || (int)op > 2) return 0;
+    if (tile_config < 0 || tile_config > kNumTiles || split_k < 0) return 0;
+    int64_t rows, cols, kc;
+    op_dims(op, M, N, K, rows, cols, kc);
+    return plan_workspace(make_plan(rows, cols, kc, tile_config, split_k), rows, cols);
+}
+
+extern "C" size_t mp8_gemm_fp8_workspace_bytes(mp8_op op, int64_t M, int64_t N, int64_t K) {
+    return mp8_gemm_fp8_workspace_bytes_tuned(op, M, N, K, 0, 0);
+}
+
+extern "C" mp8_status mp8_gemm_fp8_tuned(mp8_op op, int64_t M, int64_t N, int64_t K,
+                                         const uint8_t *a, int64_t lda, const uint8_t *b,
+                                         int64_t ldb, float alpha, float *acc, int acc_mode,
+                                         uint8_t *out8, uint8_t *out8_t, mp8_round round,
+                                         int flags, uint64_t seed, uint64_t offset,
+                                         mp8_stats *stats, void *workspace,
+                                         size_t workspace_bytes, void *stream, int tile_config,
+                                         int split_k) {
+    using namespace mp8;
+    if ((int)op < 0 || (int)op > 2) return MP8_ERR_INVALID_ARG;
+    if (M < 0 || N < 0 || K < 0) return MP8_ERR_INVALID_ARG;
+    if (round != MP8_RNE && round != MP8_SR) return MP8_ERR_INVALID_ARG;
+    if (acc_mode < 0 || acc_mode > 2) return MP8_ERR_INVALID_ARG;
+    if (tile_config < 0 || tile_config > kNumTiles || split_k < 0) return MP8_ERR_INVALID_ARG;
+    int64_t rows, cols, kc;
+    op_dims(op, M, N, K, rows, cols, kc);
+    if (rows == 0 || cols == 0) return MP8_OK;
+    if (acc_mode != 0 && acc == nullptr) return MP8_ERR_INVALID_ARG;
+    if (kc > 0 && (!a || !b)) return MP8_ERR_INVALID_ARG;
+    if (kc > 0 && (lda < kc || ldb < kc)) return MP8_ERR_INVALID_ARG;
+    if (rows > (INT64_MAX / 8) / cols) return MP8_ERR_UNSUPPORTED;
+    if (((uintptr_t)acc | (uintptr_t)out8 | (uintptr_t)out8_t | (uintptr_t)workspace) & 15u)
+        return MP8_ERR_ALIGNMENT;
+
+    Epilogue ep{};
+    ep.alpha = alpha;
+    ep.acc = acc_mode ? acc : nullptr;
+    ep.acc_mode = acc_mode;
+    ep.out8 = out8;
+    ep.out8_t = out8_t;
+    ep.sr = round == MP8_SR;
+    ep.sat = (flags & MP8_FLAG_SATURATE) ? 1 : 0;
+    ep.seed = seed;
+    ep.offset = offset;
+    ep.stats = stats;
+    ep.rows = rows;
+    ep.cols = cols;
+    hipStream_t s = (hipStream_t)stream;
+
+    Plan pl = make_plan(rows, cols, kc, tile_config, split_k);
+    const bool aligned = (((uintptr_t)a | (uintptr_t)b) & 15u) == 0 && (lda & 15) == 0 && (ldb & 15) == 0;
+    if (pl.mfma && !aligned) {
+        if (tile_config > 0) return MP8_ERR_ALIGNMENT;
+        pl.mfma = false;
+        pl.splits = 1;
+    }
+    if (tile_config > 0 && !pl.mfma) return MP8_ERR_UNSUPPORTED;
+    const int64_t cgroups = (cols + 15) / 16;
+
+    if (!pl.mfma || kc == 0) {
+        int64_t blocks = std::min<int64_t>((rows * cols + 255) / 256, 1 << 20);
+        hipLaunchKernelGGL(gemm_generic_kernel, dim3((unsigned)blocks), dim3(256), 0, s, a, lda, b,
+                           ldb, kc, ep);
+        return hipGetLastError() == hipSuccess ? MP8_OK : MP8_ERR_HIP;
+    }
+
+    const size_t need = plan_workspace(pl, rows, cols);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return MP8_ERR_WORKSPACE;
+    const int64_t nblocks = (int64_t)pl.tiles_m * pl.tiles_n * pl.splits;
+    if (nblocks > 0x7FFFFFFFLL) return MP8_ERR_UNSUPPORTED;
+
+    GemmArgs ga{};
+    ga.a = a;
+    ga.b = b;
+    ga.lda = lda;
+    ga.ldb = ldb;
+    ga.rows = rows;
+    ga.cols = cols;
+    ga.ksteps = (int)(kc / BK);
+    ga.splits = pl.splits;
+    ga.tiles_m = pl.tiles_m;
+    ga.tiles_n = pl.tiles_n;
+    ga.partial = pl.splits > 1 ? (float *)workspace : nullptr;
+    ga.ep = ep;
+    hipLaunchKernelGGL(kTiles[pl.tile].kernel, dim3((unsigned)nblocks), dim3(256), 0, s, ga);
+    if (hipGetLastError() != hipSuccess) return MP8_ERR_HIP;
+    if (pl.splits > 1) {
+        int64_t blocks = std::min<int64_t>((rows * cgroups + 255) / 256, 256 * 8);
+        hipLaunchKernelGGL(splitk_finish_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
+                           (const float *)workspace, pl.splits, ep);
+        if (hipGetLastError() != hipSuccess) return MP8_ERR_HIP;
+    }
+    return MP8_OK;
+}
+
+extern "C" mp8_status mp8_gemm_fp8(mp8_op op, int64_t M, int64_t N, int64_t K, const uint8_t *a,
+                                   int64_t lda, const uint8_t *b, int64_t ldb, float alpha,
+                                   float *acc, int acc_mode, uint8_t *out8, uint8_t *out8_t,
+                                   mp8_round round, int flags, uint64_t seed, uint64_t offset,
+                                   mp8_stats *stats, void *workspace, size_t workspace_bytes,
+                                   void *stream) {
+    return mp8_gemm_fp8_tuned(op, M, N, K, a, lda, b, ldb, alpha, acc, acc_mode, out8, out8_t,
+                              round, flags, seed, offset, stats, workspace, workspace_bytes,
+                              stream, 0, 0);
+}

@@ -1,0 +1,177 @@
+// Device-side building blocks shared by the mp8 kernels: bit-level conversions to the
+// 8-bit (1,5,2) and half (1,5,10) formats with round-to-nearest-even or stochastic
+// rounding (Section 3.2 of arXiv 1905.12334), the Philox4x32-10 stream used for the
+// random bits, and wave-level reductions for the overflow / amax statistics that drive
+// loss scaling (Section 3.1).  gfx950 only.
+#pragma once
+
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/mp8.h"
+
+namespace mp8 {
+
+constexpr int kWave = 64;
+
+using f32x4 = float __attribute__((ext_vector_type(4)));
+using u32x4 = uint32_t __attribute__((ext_vector_type(4)));
+using u32x2 = uint32_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t f2u(float f) { return __float_as_uint(f); }
+__device__ __forceinline__ float u2f(uint32_t u) { return __uint_as_float(u); }
+
+// ---------------------------------------------------------------------------------------
+// Philox4x32-10.  The key schedule is wave-uniform, so it lives in scalar registers; each
+// round is two 32x32->64 multiplies and two three-input xors per lane.
+// ---------------------------------------------------------------------------------------
+struct Philox {
+    uint32_t k0, k1, off_lo, off_hi;
+    __device__ __forceinline__ Philox(uint64_t seed, uint64_t offset)
+        : k0((uint32_t)seed), k1((uint32_t)(seed >> 32)), off_lo((uint32_t)offset),
+          off_hi((uint32_t)(offset >> 32)) {}
+
+    // The four output words for the group of eight elements with index / 8 == blk.
+    __device__ __forceinline__ uint4 block(uint64_t blk) const {
+        uint32_t c0 = (uint32_t)blk, c1 = (uint32_t)(blk >> 32), c2 = off_lo, c3 = off_hi;
+        uint32_t ka = k0, kb = k1;
+#pragma unroll
+        for (int r = 0; r < 10; ++r) {
+            uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+            uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+            uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ ka;
+            uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ kb;
+            c1 = (uint32_t)p1;
+            c3 = (uint32_t)p0;
+            c0 = n0;
+            c2 = n2;
+            ka += 0x9E3779B9u;
+            kb += 0xBB67AE85u;
+        }
+        return make_uint4(c0, c1, c2, c3);
+    }
+};
+
+// Halfword h (0..7) of a Philox block: low half of word 0 first.
+__device__ __forceinline__ uint32_t philox_half(const uint4 &w, int h) {
+    uint32_t word = (h >> 1) == 0 ? w.x : (h >> 1) == 1 ? w.y : (h >> 1) == 2 ? w.z : w.w;
+    return (h & 1) ? (word >> 16) : (word & 0xFFFFu);
+}
+
+// ---------------------------------------------------------------------------------------
+// FP32 bit pattern -> 8-bit (1,5,2) code.
+//   kSR = false: round to nearest even.  kSR = true: stochastic rounding on the magnitude,
+//   r16 in [0, 65536): with F the top 16 bits of the discarded fraction, the magnitude code
+//   is bumped by one iff F + r16 >= 65536.
+//   NaN -> 0x7F (canonical).  Inf -> sign|0x7C.  Finite overflow -> sign|0x7C, or
+//   sign|0x7B when `sat`.
+// The magnitude code of a normal result is (a - (112 << 23)) >> 21 because the two formats
+// differ only in exponent bias (127 vs 15) and mantissa width (23 vs 2).
+// ---------------------------------------------------------------------------------------
+template <bool kSR>
+__device__ __forceinline__ uint32_t e5m2_from_f32_bits(uint32_t u, uint32_t r16, bool sat) {
+    const uint32_t a = u & 0x7FFFFFFFu;
+    const uint32_t sign = (u >> 24) & 0x80u;
+    uint32_t mag;
+    if (a >= 0x38800000u) {  // |y| >= 2^-14: normal in the 8-bit format (or overflow)
+        uint32_t t = a - 0x38000000u;
+        if constexpr (kSR) {
+            uint32_t F = (t >> 5) & 0xFFFFu;
+            mag = (t >> 21) + ((F + r16) >> 16);
+        } else {
+            mag = (t + 0x000FFFFFu + ((t >> 21) & 1u)) >> 21;
+        }
+    } else {  // subnormal result: count of 2^-16 quanta
+        if constexpr (kSR) {
+            // |y| = mant * 2^(e-150); in units of 2^-32 that is mant >> (118 - e), truncated
+            uint32_t e = a >> 23;
+            uint32_t mant = (a & 0x007FFFFFu) | (e ? 0x00800000u : 0u);
+            e = e ? e : 1u;
+            uint32_t sh = 118u - e;  // >= 6 here
+            uint32_t v = sh < 32u ? (mant >> sh) : 0u;
+            mag = (v >> 16) + (((v & 0xFFFFu) + r16) >> 16);
+        } else {
+            // adding 128.0f makes the FP32 adder round |y| to a multiple of ulp(128) = 2^-16
+            // with its own round-to-nearest-even
+            mag = f2u(u2f(a) + 128.0f) - 0x43000000u;
+        }
+    }
+    if (a > 0x7F800000u) return 0x7Fu;
+    if (a == 0x7F800000u) return sign | 0x7Cu;
+    if (mag >= 0x7Cu) mag = sat ? 0x7Bu : 0x7Cu;
+    return sign | mag;
+}
+
+// Exact value of an 8-bit (1,5,2) code as FP32: the code is the top byte of an IEEE half.
+__device__ __forceinline__ float e5m2_to_f32(uint32_t code) {
+    return __half2float(__ushort_as_half((unsigned short)(code << 8)));
+}
+
+// FP32 bit pattern -> IEEE half code, same two rounding rules (13 discarded bits for normal
+// results).  NaN -> 0x7E00.  Overflow -> Inf.
+template <bool kSR>
+__device__ __forceinline__ uint32_t f16_from_f32_bits(uint32_t u, uint32_t r16) {
+    const uint32_t a = u & 0x7FFFFFFFu;
+    const uint32_t sign = (u >> 16) & 0x8000u;
+    uint32_t mag;
+    if (a >= 0x38800000u) {
+        uint32_t t = a - 0x38000000u;
+        if constexpr (kSR) {
+            uint32_t F = (t & 0x1FFFu) << 3;
+            mag = (t >> 13) + ((F + r16) >> 16);
+        } else {
+            mag = (t + 0x00000FFFu + ((t >> 13) & 1u)) >> 13;
+        }
+    } else {  // subnormal half: count of 2^-24 quanta
+        if constexpr (kSR) {
+            // units of 2^-40: mant * 2^(e-150+40) = mant >> (110 - e); e <= 112 so the shift
+            // may be negative by up to 2 bits
+            uint32_t e = a >> 23;
+            uint32_t mant = (a & 0x007FFFFFu) | (e ? 0x00800000u : 0u);
+            e = e ? e : 1u;
+            int sh = 110 - (int)e;  // >= -2
+            uint32_t v = sh >= 32 ? 0u : sh >= 0 ? (mant >> sh) : (mant << (-sh));
+            mag = (v >> 16) + (((v & 0xFFFFu) + r16) >> 16);
+        } else {
+            // 0.5f has ulp 2^-24: the adder rounds |y| to a multiple of 2^-24, ties to even
+            mag = f2u(u2f(a) + 0.5f) - 0x3F000000u;
+        }
+    }
+    if (a > 0x7F800000u) return 0x7E00u;
+    if (a == 0x7F800000u) return sign | 0x7C00u;
+    if (mag >= 0x7C00u) mag = 0x7C00u;
+    return sign | mag;
+}
+
+// ---------------------------------------------------------------------------------------
+// Statistics: per-thread partials, reduced across the wave with shuffles, then one atomic
+// per wave and field.
+// ---------------------------------------------------------------------------------------
+struct StatsAcc {
+    uint32_t amax = 0, nonfinite = 0, zeroed = 0;
+    // a_bits: |value before rounding| as FP32 bits; code: produced 8-bit code
+    __device__ __forceinline__ void add(uint32_t a_bits, uint32_t code) {
+        uint32_t ab = a_bits > 0x7F800000u ? 0x7FC00000u : a_bits;
+        amax = ab > amax ? ab : amax;
+        nonfinite += ((code & 0x7Cu) == 0x7Cu) ? 1u : 0u;
+        zeroed += (((code & 0x7Fu) == 0u) && a_bits != 0u) ? 1u : 0u;
+    }
+    __device__ __forceinline__ void flush(mp8_stats *out) {
+        uint32_t m = amax, nf = nonfinite, z = zeroed;
+#pragma unroll
+        for (int o = kWave / 2; o > 0; o >>= 1) {
+            uint32_t om = __shfl_xor(m, o);
+            m = om > m ? om : m;
+            nf += __shfl_xor(nf, o);
+            z += __shfl_xor(z, o);
+        }
+        if ((threadIdx.x & (kWave - 1)) == 0) {
+            if (m) atomicMax(&out->amax_bits, m);
+            if (nf) atomicAdd(&out->nonfinite, nf);
+            if (z) atomicAdd(&out->zeroed, z);
+        }
+    }
+};
+
+}  // namespace mp8

@@ -1,0 +1,243 @@
+"""GPU parity: mp8_gemm_fp8 (all three training GEMMs, RNE and SR epilogue, split
+contraction, ragged shapes) against the CPU oracle."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1905_12334_amd import workloads
+from gpu_util import gpu, host, check_outputs, acc_tolerance_ok, signed_rank
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mp8():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_1905_12334_amd as m
+    m.lib()
+    return m
+
+
+def run_gemm(mp8, a8, b8, op=None, dims=None, want_t=False, acc_in=None, acc_mode=1, **kw):
+    """out[r,c] = sum_j a8[r,j] b8[c,j] through the C ABI; returns (acc, out8, out8_t, stats)."""
+    import torch
+    rows, kc = a8.shape
+    cols = b8.shape[0]
+    if op is None:
+        op, dims = mp8.FWD, (rows, cols, kc)
+    M, N, K = dims
+    a, b = gpu(a8), gpu(b8)
+    acc = torch.full((rows * cols + 16,), 7.0, dtype=torch.float32, device="cuda")
+    if acc_in is not None:
+        acc[: rows * cols] = gpu(acc_in).reshape(-1)
+    obuf = torch.full((rows * cols + 64,), 0xAA, dtype=torch.uint8, device="cuda")
+    out8 = obuf[: rows * cols]
+    out8_t = torch.full((rows * cols,), 0xAA, dtype=torch.uint8, device="cuda") if want_t else None
+    tile, split = kw.pop("tile_config", 0), kw.pop("split_k", 0)
+    wsb = mp8.gemm_fp8_workspace_bytes(op, M, N, K, tile, split)
+    ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
+    stats = mp8.new_stats()
+    mp8.gemm_fp8(op, M, N, K, a, b, out8=out8, out8_t=out8_t, acc=acc[: rows * cols],
+                 acc_mode=acc_mode, stats=stats, workspace=ws, tile_config=tile, split_k=split, **kw)
+    torch.cuda.synchronize()
+    assert bool((obuf[rows * cols:] == 0xAA).all()), "write past the end of out8"
+    assert bool((acc[rows * cols:] == 7.0).all()), "write past the end of acc"
+    return (host(acc[: rows * cols]).reshape(rows, cols), host(out8).reshape(rows, cols),
+            host(out8_t).reshape(cols, rows) if want_t else None, mp8.read_stats(stats))
+
+
+def exact_sum_codes(rng, shape):
+    """Codes of {1,1.25,1.5,1.75} * 2^{0..3}, both signs: sums of up to 1024 products of two such
+    values are integers/16 below 2^24, hence exact in FP32 in any order."""
+    e = rng.integers(15, 19, shape)
+    m = rng.integers(0, 4, shape)
+    s = rng.integers(0, 2, shape)
+    return ((s << 7) | (e << 2) | m).astype(np.uint8)
+
+
+@pytest.mark.parametrize("kpos", [0, 37, 127, 200])
+def test_exhaustive_product_table(mp8, kpos):
+    """All 256 x 256 code pairs through the matrix cores: one non-zero contraction position,
+    so the FP32 accumulator must be exactly value(a) * value(b), with IEEE Inf/NaN classes."""
+    a8 = np.zeros((256, 256), np.uint8)
+    b8 = np.zeros((256, 256), np.uint8)
+    a8[:, kpos] = np.arange(256)
+    b8[:, kpos] = np.arange(256)
+    acc, out8, _, _ = run_gemm(mp8, a8, b8)
+    ref, _ = oracle.gemm_ref(a8, b8, want_abs=False)
+    assert np.array_equal(np.isnan(acc), np.isnan(ref))
+    ok = ~np.isnan(ref)
+    assert np.array_equal(acc[ok].astype(np.float64), ref[ok])
+    assert np.array_equal(np.signbit(acc[ok]), np.signbit(ref[ok]))
+    want8, _ = oracle.quantize_e5m2(acc)
+    assert np.array_equal(out8, want8)
+
+
+def test_exact_sums_every_tile_config_and_split(mp8):
+    rng = np.random.default_rng(10)
+    rows, cols, kc = 320, 288, 1024        # ragged against every tile shape
+    a8, b8 = exact_sum_codes(rng, (rows, kc)), exact_sum_codes(rng, (cols, kc))
+    ref, _ = oracle.gemm_ref(a8, b8, want_abs=False)
+    want8 = oracle.round_ref_e5m2(ref)
+    ntiles = len(mp8.gemm_tile_configs())
+    for tile in range(0, ntiles + 1):
+        for split in (0, 1, 2, 3, 8):
+            acc, out8, out8_t, _ = run_gemm(mp8, a8, b8, want_t=True, tile_config=tile, split_k=split)
+            assert np.array_equal(acc.astype(np.float64), ref), (tile, split)
+            assert np.array_equal(out8, want8), (tile, split)
+            assert np.array_equal(out8_t, want8.T), (tile, split)
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1), (3, 5, 7), (17, 33, 100), (64, 64, 128), (100, 36, 256),
+                                   (257, 130, 384), (31, 515, 128), (130, 70, 130)])
+def test_ragged_shapes_identity_and_onehot(mp8, shape):
+    rows, cols, kc = shape
+    rng = np.random.default_rng(rows * 7 + cols)
+    a8 = workloads.random_e5m2_codes(rows + 1, (rows, kc))
+    sel = rng.integers(0, kc, cols)
+    b8 = np.zeros((cols, kc), np.uint8)
+    b8[np.arange(cols), sel] = 0x3C                     # 1.0: out[r,c] = a[r, sel[c]]
+    acc, out8, out8_t, _ = run_gemm(mp8, a8, b8, want_t=True)
+    ref, _ = oracle.gemm_ref(a8, b8, want_abs=False)
+    assert np.array_equal(acc.astype(np.float64), ref)
+    want8, _ = oracle.quantize_e5m2(acc)
+    assert np.array_equal(out8, want8) and np.array_equal(out8_t, want8.T)
+    # random operands on the same ragged shape
+    b8 = workloads.random_e5m2_codes(cols + 2, (cols, kc))
+    a8 = (a8 & 0x83) | 0x38 | (a8 & 0x0C) >> 2 << 2    # exponents 14..15: no overflow
+    b8 = (b8 & 0x83) | 0x38 | (b8 & 0x0C) >> 2 << 2
+    acc, out8, _, _ = run_gemm(mp8, a8, b8)
+    ref, absref = oracle.gemm_ref(a8, b8)
+    check_outputs(acc, out8, ref, absref, kc)
+
+
+def _layer_operands(lay):
+    """8-bit operands of one layer as the library wants them (all from the oracle's Q)."""
+    X8, X8t = oracle.quantize_e5m2(lay.X, want_t=True)
+    W8, W8t = oracle.quantize_e5m2(lay.W, want_t=True)
+    E8, E8t = oracle.quantize_e5m2(lay.dY, scale=lay.loss_scale, want_t=True)
+    return X8, X8t, W8, W8t, E8, E8t
+
+
+def test_config1_square_256(mp8):
+    lay = workloads.config1()
+    X8, _, _, W8t, _, _ = _layer_operands(lay)
+    acc, out8, _, st = run_gemm(mp8, X8, W8t, op=mp8.FWD, dims=(256, 256, 256))
+    ref, absref = oracle.gemm_ref(X8, W8t)
+    check_outputs(acc, out8, ref, absref, 256)
+    ost = oracle.Stats()
+    oracle.quantize_e5m2(acc, stats=ost)
+    assert st == ost.as_tuple()
+    # the reference itself agrees with a float64 matmul of independently decoded operands
+    dec = lambda c: (c.astype(np.uint16) << 8).view(np.float16).astype(np.float64)
+    assert np.allclose(ref, dec(X8) @ dec(W8t).T, rtol=1e-12, atol=1e-12)
+
+
+def test_three_training_gemms_small_layer(mp8):
+    lay = workloads.config2(batch=1, hw=16, cin=128, cout=64)     # M=256, K=1152, N=64
+    M, N, K = lay.M, lay.N, lay.K
+    X8, X8t, W8, W8t, E8, E8t = _layer_operands(lay)
+    # forward: contraction K
+    acc, out8, _, _ = run_gemm(mp8, X8, W8t, op=mp8.FWD, dims=(M, N, K))
+    ref, absref = oracle.gemm_ref(X8, W8t)
+    check_outputs(acc, out8, ref, absref, K)
+    # backward data: contraction N; equals forward GEMM on explicitly transposed inputs
+    acc, out8, _, _ = run_gemm(mp8, E8, W8, op=mp8.BWD_DATA, dims=(M, N, K))
+    ref, absref = oracle.gemm_ref(E8, W8)
+    assert acc.shape == (M, K)
+    check_outputs(acc, out8, ref, absref, N)
+    # weight gradient: contraction M, un-scaled in the epilogue via alpha
+    alpha = 1.0 / 64
+    acc, out8, _, _ = run_gemm(mp8, X8t, E8t, op=mp8.WGRAD, dims=(M, N, K), alpha=alpha)
+    ref, absref = oracle.gemm_ref(X8t, E8t)
+    assert acc.shape == (K, N)
+    check_outputs(acc, out8, ref, absref, M, alpha=alpha)
+
+
+def test_sr_epilogue_matches_oracle_stream(mp8):
+    lay = workloads.config5(tokens=512, d_in=128, d_out=192)
+    X8, X8t, _, _, E8, E8t = _layer_operands(lay)
+    seed, offset = lay.extra["seed"], 17
+    for split in (1, 4):
+        acc, out8, out8_t, st = run_gemm(mp8, X8t, E8t, op=mp8.WGRAD, dims=(lay.M, lay.N, lay.K),
+                                         round=oracle.SR, seed=seed, offset=offset, want_t=True,
+                                         split_k=split)
+        ref, absref = oracle.gemm_ref(X8t, E8t)
+        check_outputs(acc, out8, ref, absref, lay.M, mode=oracle.SR, seed=seed, offset=offset)
+        assert np.array_equal(out8_t, out8.T)
+        # bracket of the reference: toward-zero code or the next one (+-1 for accumulator error)
+        lo = np.vectorize(lambda v: oracle.e5m2_encode(v, oracle.SR, 0))(ref).astype(np.uint8)
+        d = signed_rank(out8) - signed_rank(lo)
+        away = np.where(signed_rank(lo) < 0, -d, d)
+        away = np.where(ref == 0, np.abs(d), away)
+        assert away.min() >= -1 and away.max() <= 2
+    # a ragged column count takes the per-element stream path
+    a8 = workloads.random_e5m2_codes(1, (70, 256))
+    b8 = workloads.random_e5m2_codes(2, (50, 256))
+    a8, b8 = (a8 & 0x83) | 0x3C, (b8 & 0x83) | 0x3C
+    acc, out8, _, _ = run_gemm(mp8, a8, b8, round=oracle.SR, seed=5, offset=6)
+    ref, absref = oracle.gemm_ref(a8, b8)
+    check_outputs(acc, out8, ref, absref, 256, mode=oracle.SR, seed=5, offset=6)
+
+
+def test_accumulate_across_calls_equals_stacked_contraction(mp8):
+    """GNMT-style weight gradient: per-timestep GEMMs accumulated in FP32 (acc_mode 2) and one
+    GEMM over the stacked timesteps must both match the one double reference; rounding to 8 bits
+    happens once, after the last step."""
+    steps, batch, kdim, ndim = 4, 128, 64, 96
+    rng = np.random.default_rng(4)
+    xs = [workloads.random_e5m2_codes(100 + t, (kdim, batch)) for t in range(steps)]   # X_t^T [K, B]
+    es = [workloads.random_e5m2_codes(200 + t, (ndim, batch)) for t in range(steps)]   # dY_t^T [N, B]
+    xs = [(x & 0x83) | 0x38 for x in xs]
+    es = [(e & 0x83) | 0x34 for e in es]
+    a_stack, b_stack = np.concatenate(xs, axis=1), np.concatenate(es, axis=1)
+    ref, absref = oracle.gemm_ref(a_stack, b_stack)
+    acc1, out1, _, _ = run_gemm(mp8, a_stack, b_stack, op=mp8.WGRAD, dims=(steps * batch, ndim, kdim))
+    check_outputs(acc1, out1, ref, absref, steps * batch)
+    acc = np.zeros((kdim, ndim), np.float32)
+    for t in range(steps):
+        acc, out2, _, _ = run_gemm(mp8, xs[t], es[t], op=mp8.WGRAD, dims=(batch, ndim, kdim),
+                                   acc_in=acc, acc_mode=2)
+    check_outputs(acc, out2, ref, absref, steps * batch)
+
+
+def test_alpha_saturate_stats_nonfinite_and_determinism(mp8):
+    rng = np.random.default_rng(6)
+    a8 = workloads.random_e5m2_codes(7, (256, 512))
+    b8 = workloads.random_e5m2_codes(8, (128, 512))
+    a8, b8 = (a8 & 0x83) | 0x58, (b8 & 0x83) | 0x58         # values ~ 2^7: sums overflow 57344
+    acc, out8, _, st = run_gemm(mp8, a8, b8)
+    ost = oracle.Stats()
+    want, _ = oracle.quantize_e5m2(acc, stats=ost)
+    assert np.array_equal(out8, want) and st == ost.as_tuple() and st[1] > 0
+    acc_s, out_s, _, st_s = run_gemm(mp8, a8, b8, flags=oracle.FLAG_SATURATE)
+    want_s, _ = oracle.quantize_e5m2(acc_s, flags=oracle.FLAG_SATURATE)
+    assert np.array_equal(out_s, want_s) and st_s[1] == 0
+    # Inf / NaN operand codes propagate as IEEE says
+    a8[0, 0], b8[0, 0], b8[1, 0] = 0x7C, 0x00, 0x3C
+    acc_n, out_n, _, _ = run_gemm(mp8, a8, b8)
+    ref, _ = oracle.gemm_ref(a8, b8, want_abs=False)
+    assert np.isnan(acc_n[0, 0]) and np.isnan(ref[0, 0]) and out_n[0, 0] == 0x7F
+    assert np.isinf(acc_n[0, 1]) and acc_n[0, 1] == ref[0, 1]
+    # bit-reproducible, including the split path
+    for split in (1, 4):
+        r1 = run_gemm(mp8, a8, b8, split_k=split, round=oracle.SR, seed=1, offset=2)
+        r2 = run_gemm(mp8, a8, b8, split_k=split, round=oracle.SR, seed=1, offset=2)
+        assert np.array_equal(r1[0], r2[0], equal_nan=True) and np.array_equal(r1[1], r2[1])
+    # out8 only (no accumulator requested), as the benchmark calls it
+    import torch
+    o = torch.empty(256 * 128, dtype=torch.uint8, device="cuda")
+    mp8.gemm_fp8(mp8.FWD, 256, 128, 512, gpu(a8), gpu(b8), out8=o)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(o).reshape(256, 128), out_n)
+    # leading dimensions larger than the contraction length (operands are column windows)
+    big_a = workloads.random_e5m2_codes(9, (64, 640))
+    big_b = workloads.random_e5m2_codes(10, (64, 768))
+    big_a, big_b = (big_a & 0x83) | 0x38, (big_b & 0x83) | 0x38
+    accl = torch.empty(64 * 64, dtype=torch.float32, device="cuda")
+    mp8.gemm_fp8(mp8.FWD, 64, 64, 256, gpu(big_a).reshape(-1)[128:], gpu(big_b).reshape(-1)[256:],
+                 acc=accl, acc_mode=1, lda=640, ldb=768)
+    torch.cuda.synchronize()
+    ref, _ = oracle.gemm_ref(big_a[:, 128:384], big_b[:, 256:512], want_abs=False)
+    assert np.array_equal(host(accl).reshape(64, 64).astype(np.float64), ref)

@@ -1,0 +1,144 @@
+"""GPU parity: mp8_quantize_e5m2 and mp8_sr_bits against the CPU oracle, bit for bit."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1905_12334_amd import workloads
+from gpu_util import gpu, host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mp8():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_1905_12334_amd as m
+    m.lib()
+    return m
+
+
+def _run(mp8, x, want_t=False, with_stats=True, **kw):
+    import torch
+    src = gpu(x)
+    buf = torch.full((x.size + 64,), 0xAA, dtype=torch.uint8, device="cuda")
+    dst = buf[: x.size].view(x.shape)       # 64 canary bytes behind the output
+    dst_t = torch.empty((x.shape[1], x.shape[0]), dtype=torch.uint8, device="cuda") if want_t else None
+    stats = mp8.new_stats() if with_stats else None
+    mp8.quantize_e5m2(src, dst, dst_t, stats=stats, **kw)
+    torch.cuda.synchronize()
+    assert bool((buf[x.size:] == 0xAA).all()), "write past the end of dst"
+    return host(dst), (host(dst_t) if want_t else None), (mp8.read_stats(stats) if with_stats else None)
+
+
+def _oracle(x, want_t=False, **kw):
+    st = oracle.Stats()
+    mode = kw.pop("round", oracle.RNE)
+    q, qt = oracle.quantize_e5m2(x, mode=mode, want_t=want_t, stats=st, **kw)
+    return q, qt, st.as_tuple()
+
+
+def test_sr_bits_stream_matches_oracle(mp8):
+    import torch
+    n = 100_003
+    out = torch.empty(n, dtype=torch.int16, device="cuda")
+    seed, offset = 0xDEADBEEFCAFEF00D, 0x0123456789ABCDEF
+    mp8.sr_bits(out, seed, offset)
+    got = host(out).view(np.uint16)
+    idx = np.concatenate([np.arange(0, 4096), np.arange(n - 4096, n)])
+    want = np.array([oracle.sr_bits(seed, offset, int(i)) for i in idx], dtype=np.uint16)
+    assert np.array_equal(got[idx], want)
+    assert abs(got.astype(np.float64).mean() / 65536 - 0.5) < 0.01
+
+
+def test_all_codes_roundtrip_and_edge_values(mp8):
+    codes = np.arange(256, dtype=np.uint16)
+    vals = (codes << 8).astype(np.uint16).view(np.float16).astype(np.float32)
+    edge = np.array([61440.0, np.nextafter(np.float32(61440), np.float32(0)), 65536.0, 1e30,
+                     -61440.0, 2.0 ** -17, np.nextafter(np.float32(2.0 ** -17), np.float32(1)),
+                     1.5 * 2.0 ** -16, 2.5 * 2.0 ** -16, -0.0, 0.0, np.inf, -np.inf, np.nan,
+                     1e-45, -1e-45, 1.1754942e-38, 1.125, 1.375, 1.625, 57344.0, 3.0e-5],
+                    dtype=np.float32)
+    # all midpoints between adjacent finite codes, and their FP32 neighbours
+    fin = vals[:0x7C].astype(np.float64)
+    mids = ((fin[:-1] + fin[1:]) / 2).astype(np.float32)
+    around = np.concatenate([mids, np.nextafter(mids, np.float32(0)), np.nextafter(mids, np.float32(1e9))])
+    x = np.concatenate([vals, edge, around, -around]).astype(np.float32)
+    x = np.concatenate([x, np.zeros((-x.size) % 16 + 5, np.float32)]).reshape(1, -1)
+    for rnd in (oracle.RNE, oracle.SR):
+        for flags in (0, oracle.FLAG_SATURATE):
+            got, _, gst = _run(mp8, x, round=rnd, flags=flags, seed=9, offset=4)
+            want, _, wst = _oracle(x, round=rnd, flags=flags, seed=9, offset=4)
+            assert np.array_equal(got, want), (rnd, flags, np.nonzero(got != want))
+            assert gst == wst
+
+
+@pytest.mark.parametrize("rnd", [oracle.RNE, oracle.SR])
+def test_random_bit_patterns_4m(mp8, rnd):
+    x = workloads.random_f32_bit_patterns(77, 1 << 22).reshape(2048, 2048)
+    got, got_t, gst = _run(mp8, x, want_t=True, round=rnd, seed=1234, offset=99)
+    want, want_t, wst = _oracle(x, want_t=True, round=rnd, seed=1234, offset=99)
+    assert np.array_equal(got, want)
+    assert np.array_equal(got_t, want_t)
+    assert gst == wst
+
+
+@pytest.mark.parametrize("shape", [(1, 1), (1, 15), (3, 17), (64, 64), (65, 130), (257, 48),
+                                   (1000, 3), (5, 1031), (128, 1152)])
+@pytest.mark.parametrize("rnd", [oracle.RNE, oracle.SR])
+def test_ragged_shapes_scale_transpose_stats(mp8, shape, rnd):
+    rng = np.random.default_rng(shape[0] * 1000 + shape[1])
+    x = (rng.standard_normal(shape) * np.exp2(rng.integers(-22, 4, shape))).astype(np.float32)
+    for want_t in (False, True):
+        got, got_t, gst = _run(mp8, x, want_t=want_t, scale=4096.0, round=rnd, seed=5, offset=8)
+        want, want_t_arr, wst = _oracle(x, want_t=want_t, scale=4096.0, round=rnd, seed=5, offset=8)
+        assert np.array_equal(got, want)
+        if want_t:
+            assert np.array_equal(got_t, want_t_arr)
+        assert gst == wst
+
+
+def test_half_precision_source(mp8):
+    rng = np.random.default_rng(3)
+    x = (rng.standard_normal((130, 96)) * np.exp2(rng.integers(-18, 12, (130, 96)))).astype(np.float16)
+    for rnd in (oracle.RNE, oracle.SR):
+        for want_t in (False, True):
+            got, got_t, gst = _run(mp8, x, want_t=want_t, scale=0.5, round=rnd, seed=2, offset=1)
+            want, wt, wst = _oracle(x, want_t=want_t, scale=0.5, round=rnd, seed=2, offset=1)
+            assert np.array_equal(got, want) and gst == wst
+            if want_t:
+                assert np.array_equal(got_t, wt)
+
+
+def test_config_tensors_and_loss_scale_effect(mp8):
+    lay = workloads.config2(batch=4)                      # dY: 3136 x 128, errors N(0, 1e-4)
+    got, got_t, gst = _run(mp8, lay.dY, want_t=True, scale=lay.loss_scale)
+    want, want_t, wst = _oracle(lay.dY, want_t=True, scale=lay.loss_scale)
+    assert np.array_equal(got, want) and np.array_equal(got_t, want_t) and gst == wst
+    unscaled, _, st1 = _run(mp8, lay.dY * np.float32(0.1))
+    assert st1[2] > 0.5 * lay.dY.size          # most small errors vanish without loss scaling
+    assert gst[2] < 0.05 * lay.dY.size
+    lay5 = workloads.config5(tokens=512)
+    for rnd in (oracle.RNE, oracle.SR):
+        got, _, gst = _run(mp8, lay5.dY, scale=lay5.loss_scale, round=rnd, seed=lay5.extra["seed"], offset=3)
+        want, _, wst = _oracle(lay5.dY, scale=lay5.loss_scale, round=rnd, seed=lay5.extra["seed"], offset=3)
+        assert np.array_equal(got, want) and gst == wst
+
+
+def test_no_stats_and_empty_and_determinism(mp8):
+    import torch
+    x = workloads.normal(9, 0, (300, 200))
+    a, _, _ = _run(mp8, x, with_stats=False, round=oracle.SR, seed=3, offset=3)
+    b, _, _ = _run(mp8, x, with_stats=False, round=oracle.SR, seed=3, offset=3)
+    c, _, _ = _run(mp8, x, with_stats=False, round=oracle.SR, seed=3, offset=4)
+    assert np.array_equal(a, b) and not np.array_equal(a, c)
+    want, _, _ = _oracle(x, round=oracle.SR, seed=3, offset=3)
+    assert np.array_equal(a, want)
+    e = torch.empty((0, 16), dtype=torch.float32, device="cuda")
+    mp8.quantize_e5m2(e, torch.empty((0, 16), dtype=torch.uint8, device="cuda"))
+    # overflow is counted, and saturation removes it
+    big = np.full((4, 32), 7e4, np.float32)
+    _, _, st = _run(mp8, big)
+    assert st[1] == 128
+    _, _, st = _run(mp8, big, flags=oracle.FLAG_SATURATE)
+    assert st[1] == 0

@@ -1,0 +1,80 @@
+"""GPU parity: mp8_sgd_update_fp16_sr against the CPU oracle, bit for bit."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1905_12334_amd import workloads
+from gpu_util import gpu, host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mp8():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_1905_12334_amd as m
+    m.lib()
+    return m
+
+
+def _run(mp8, w16, g8, lr, inv, rnd, seed=0, offset=0, skip=None, want_w8=False):
+    import torch
+    w = gpu(w16.view(np.int16))
+    g = gpu(g8)
+    w8 = torch.zeros(w16.size, dtype=torch.uint8, device="cuda") if want_w8 else None
+    sk = None if skip is None else torch.tensor([skip], dtype=torch.int32, device="cuda")
+    stats = mp8.new_stats()
+    mp8.sgd_update_fp16_sr(w, g, lr, inv, round=rnd, seed=seed, offset=offset, skip_if_nonzero=sk,
+                           w8_out=w8, stats=stats)
+    torch.cuda.synchronize()
+    return host(w).view(np.uint16), (host(w8) if want_w8 else None), mp8.read_stats(stats)
+
+
+@pytest.mark.parametrize("n", [1, 15, 16, 17, 4099, 1 << 20])
+@pytest.mark.parametrize("rnd", [oracle.RNE, oracle.SR])
+def test_update_random_values_all_sizes(mp8, n, rnd):
+    rng = np.random.default_rng(n)
+    w16 = (rng.standard_normal(n) * np.exp2(rng.integers(-26, 2, n))).astype(np.float16).view(np.uint16)
+    g8 = workloads.random_e5m2_codes(n + 1, (n,), finite_only=False)
+    lr, inv = 0.05, 1.0 / 512
+    got, got8, gst = _run(mp8, w16, g8, lr, inv, rnd, seed=11, offset=n, want_w8=True)
+    st = oracle.Stats()
+    want, want8 = oracle.sgd_update_fp16(w16, g8, lr, inv, mode=rnd, seed=11, offset=n, want_w8=True,
+                                         stats=st)
+    assert np.array_equal(got, want)
+    assert np.array_equal(got8, want8)
+    assert gst[1] == st.nonfinite
+
+
+def test_update_all_half_patterns(mp8):
+    w16 = np.arange(65536, dtype=np.uint16)
+    for code in (0x00, 0x3C, 0xBC, 0x01, 0x7B, 0xFB, 0x44):
+        g8 = np.full(65536, code, dtype=np.uint8)
+        for rnd in (oracle.RNE, oracle.SR):
+            got, _, _ = _run(mp8, w16, g8, 1e-3, 1.0, rnd, seed=3, offset=code)
+            want, _ = oracle.sgd_update_fp16(w16, g8, 1e-3, 1.0, mode=rnd, seed=3, offset=code)
+            assert np.array_equal(got, want), (code, rnd)
+
+
+def test_update_transformer_big_magnitudes_and_skip(mp8):
+    lay = workloads.config5(tokens=8, d_in=256, d_out=512)
+    w16 = lay.W.astype(np.float16).view(np.uint16).reshape(-1)
+    n = w16.size
+    g = (np.random.default_rng(5).standard_normal(n) * 1e-5 * lay.loss_scale).astype(np.float32)
+    g8, _ = oracle.quantize_e5m2(g.reshape(1, -1))
+    g8 = g8.reshape(-1)
+    lr, inv = lay.extra["lr"], 1.0 / lay.loss_scale
+    seed = lay.extra["seed"]
+    rne, _, _ = _run(mp8, w16, g8, lr, inv, oracle.RNE)
+    assert np.array_equal(rne, w16)                   # RNE stalls at these magnitudes
+    sr, _, _ = _run(mp8, w16, g8, lr, inv, oracle.SR, seed=seed, offset=1)
+    want, _ = oracle.sgd_update_fp16(w16, g8, lr, inv, mode=oracle.SR, seed=seed, offset=1)
+    assert np.array_equal(sr, want) and not np.array_equal(sr, w16)
+    # device-side skip flag: weights untouched, non-finite gradients still counted
+    g_bad = g8.copy()
+    g_bad[7] = 0x7C
+    skipped, _, st = _run(mp8, w16, g_bad, lr, inv, oracle.SR, seed=seed, offset=1, skip=1)
+    assert np.array_equal(skipped, w16) and st[1] == 1
+    ran, _, _ = _run(mp8, w16, g8, lr, inv, oracle.SR, seed=seed, offset=1, skip=0)
+    assert np.array_equal(ran, want)
