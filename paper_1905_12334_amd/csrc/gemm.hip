@@ -67,16 +67,16 @@ __device__ __noinline__ void finish1(const Epilogue &ep, int64_t r, int64_t c, f
         ep.acc[i] = v;
     }
     if (ep.out8 == nullptr && ep.out8_t == nullptr && ep.stats == nullptr) return;
-    const uint32_t u = f2u(v * ep.alpha);
+    const float y = v * ep.alpha;
     uint32_t code;
     if (ep.sr) {
         const Philox rng(ep.seed, ep.offset);
         uint32_t r16 = philox_half(rng.block((uint64_t)i >> 3), (int)(i & 7));
-        code = e5m2_from_f32_bits<true>(u, r16, ep.sat != 0);
+        code = e5m2_from_f32_bits<true>(f2u(y), r16, ep.sat != 0);
     } else {
-        code = e5m2_from_f32_bits<false>(u, 0u, ep.sat != 0);
+        code = e5m2_from_f32_bits<false>(f2u(y), 0u, ep.sat != 0);
     }
-    if (ep.stats != nullptr) st.add(u & 0x7FFFFFFFu, code);
+    if (ep.stats != nullptr) st.add1(y, code);
     if (ep.out8 != nullptr) ep.out8[i] = (uint8_t)code;
     if (ep.out8_t != nullptr) ep.out8_t[c * ep.rows + r] = (uint8_t)code;
 }
@@ -113,14 +113,13 @@ __device__ __forceinline__ void finish16(const Epilogue &ep, int64_t r, int64_t 
         rw[0] = w0.x; rw[1] = w0.y; rw[2] = w0.z; rw[3] = w0.w;
         rw[4] = w1.x; rw[5] = w1.y; rw[6] = w1.z; rw[7] = w1.w;
     }
-    uint32_t pk[4] = {0, 0, 0, 0};
+    uint32_t pk[4];
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-        uint32_t u = f2u(v[j] * ep.alpha);
-        uint32_t r16 = (j & 1) ? (rw[j >> 1] >> 16) : (rw[j >> 1] & 0xFFFFu);
-        uint32_t code = e5m2_from_f32_bits<kSR>(u, r16, ep.sat != 0);
-        if (ep.stats != nullptr) st.add(u & 0x7FFFFFFFu, code);
-        pk[j >> 2] |= code << (8 * (j & 3));
+    for (int q = 0; q < 4; ++q) {
+        float y[4] = {v[4 * q] * ep.alpha, v[4 * q + 1] * ep.alpha, v[4 * q + 2] * ep.alpha,
+                      v[4 * q + 3] * ep.alpha};
+        pk[q] = e5m2_pack4<kSR>(y, rw[2 * q], rw[2 * q + 1], ep.sat != 0);
+        if (ep.stats != nullptr) st.add4(y, pk[q]);
     }
     if (ep.out8 != nullptr) {
         u32x4 o = {pk[0], pk[1], pk[2], pk[3]};

@@ -103,6 +103,43 @@ __device__ __forceinline__ uint32_t e5m2_from_f32_bits(uint32_t u, uint32_t r16,
     return sign | mag;
 }
 
+// ---------------------------------------------------------------------------------------
+// Hardware conversions.  v_cvt_pk_bf8_f32 (round to nearest even) and v_cvt_sr_bf8_f32 fed
+// with r16 << 16 (it adds the top 21 bits of its random operand to the 21 discarded mantissa
+// bits) produce exactly the codes of e5m2_from_f32_bits for every FP32 input that is not a
+// NaN -- including ties, subnormal results and overflow to Inf; this was checked over all
+// 2^32 inputs.  NaNs (the hardware keeps sign and payload bits) and the saturating mode go
+// through the bit-level routine.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ bool any_nan4(const float y[4]) {
+    return __builtin_isunordered(y[0], y[1]) | __builtin_isunordered(y[2], y[3]);
+}
+
+// Four values -> four codes packed little-endian.  r01 / r23 hold the 16 random bits of
+// elements (0: low half, 1: high half) and (2, 3); ignored for RNE.
+template <bool kSR>
+__device__ __forceinline__ uint32_t e5m2_pack4(const float y[4], uint32_t r01, uint32_t r23,
+                                               bool sat) {
+    if (sat || any_nan4(y)) {
+        const uint32_t r[4] = {r01 & 0xFFFFu, r01 >> 16, r23 & 0xFFFFu, r23 >> 16};
+        uint32_t w = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) w |= e5m2_from_f32_bits<kSR>(f2u(y[j]), r[j], sat) << (8 * j);
+        return w;
+    }
+    int w = 0;
+    if constexpr (kSR) {
+        w = __builtin_amdgcn_cvt_sr_bf8_f32(y[0], (int)(r01 << 16), w, 0);
+        w = __builtin_amdgcn_cvt_sr_bf8_f32(y[1], (int)(r01 & 0xFFFF0000u), w, 1);
+        w = __builtin_amdgcn_cvt_sr_bf8_f32(y[2], (int)(r23 << 16), w, 2);
+        w = __builtin_amdgcn_cvt_sr_bf8_f32(y[3], (int)(r23 & 0xFFFF0000u), w, 3);
+    } else {
+        w = __builtin_amdgcn_cvt_pk_bf8_f32(y[0], y[1], w, false);
+        w = __builtin_amdgcn_cvt_pk_bf8_f32(y[2], y[3], w, true);
+    }
+    return (uint32_t)w;
+}
+
 // Exact value of an 8-bit (1,5,2) code as FP32: the code is the top byte of an IEEE half.
 __device__ __forceinline__ float e5m2_to_f32(uint32_t code) {
     return __half2float(__ushort_as_half((unsigned short)(code << 8)));
@@ -149,16 +186,36 @@ __device__ __forceinline__ uint32_t f16_from_f32_bits(uint32_t u, uint32_t r16) 
 // per wave and field.
 // ---------------------------------------------------------------------------------------
 struct StatsAcc {
-    uint32_t amax = 0, nonfinite = 0, zeroed = 0;
-    // a_bits: |value before rounding| as FP32 bits; code: produced 8-bit code
-    __device__ __forceinline__ void add(uint32_t a_bits, uint32_t code) {
-        uint32_t ab = a_bits > 0x7F800000u ? 0x7FC00000u : a_bits;
-        amax = ab > amax ? ab : amax;
-        nonfinite += ((code & 0x7Cu) == 0x7Cu) ? 1u : 0u;
-        zeroed += (((code & 0x7Fu) == 0u) && a_bits != 0u) ? 1u : 0u;
+    float amax = 0.0f;      // max |y| over non-NaN values
+    uint32_t nan_seen = 0;  // any NaN among the values
+    uint32_t nonfinite = 0, zero_codes = 0, zero_inputs = 0;
+    // four values before rounding and their packed codes
+    __device__ __forceinline__ void add4(const float y[4], uint32_t packed) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            amax = __builtin_fmaxf(amax, __builtin_fabsf(y[j]));  // ignores NaN operands
+            zero_inputs += (y[j] == 0.0f) ? 1u : 0u;
+        }
+        nan_seen |= any_nan4(y) ? 1u : 0u;
+        // bytes whose exponent field is all ones: (c & 0x7C) + 4 reaches bit 7 only then
+        nonfinite += __builtin_popcount(((packed & 0x7C7C7C7Cu) + 0x04040404u) & 0x80808080u);
+        // bytes whose magnitude is zero
+        const uint32_t z = packed & 0x7F7F7F7Fu;
+        zero_codes += 4u - __builtin_popcount(((z + 0x7F7F7F7Fu) | z) & 0x80808080u);
     }
+    __device__ __forceinline__ void add1(float y, uint32_t code) {
+        if (y != y) nan_seen = 1u;
+        amax = __builtin_fmaxf(amax, __builtin_fabsf(y));
+        zero_inputs += (y == 0.0f) ? 1u : 0u;
+        nonfinite += ((code & 0x7Cu) == 0x7Cu) ? 1u : 0u;
+        zero_codes += ((code & 0x7Fu) == 0u) ? 1u : 0u;
+    }
+    // Reduce over the wave, then over the block's waves through LDS: one atomic per field
+    // and block.  Every thread of the block must call this (it contains a barrier).
     __device__ __forceinline__ void flush(mp8_stats *out) {
-        uint32_t m = amax, nf = nonfinite, z = zeroed;
+        __shared__ uint32_t part[3][16];
+        uint32_t m = nan_seen ? 0x7FC00000u : f2u(amax);
+        uint32_t nf = nonfinite, z = zero_codes - zero_inputs;
 #pragma unroll
         for (int o = kWave / 2; o > 0; o >>= 1) {
             uint32_t om = __shfl_xor(m, o);
@@ -166,7 +223,19 @@ struct StatsAcc {
             nf += __shfl_xor(nf, o);
             z += __shfl_xor(z, o);
         }
+        const int wave = threadIdx.x / kWave, nwaves = (blockDim.x + kWave - 1) / kWave;
         if ((threadIdx.x & (kWave - 1)) == 0) {
+            part[0][wave] = m;
+            part[1][wave] = nf;
+            part[2][wave] = z;
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            for (int w = 1; w < nwaves; ++w) {
+                m = part[0][w] > m ? part[0][w] : m;
+                nf += part[1][w];
+                z += part[2][w];
+            }
             if (m) atomicMax(&out->amax_bits, m);
             if (nf) atomicAdd(&out->nonfinite, nf);
             if (z) atomicAdd(&out->zeroed, z);

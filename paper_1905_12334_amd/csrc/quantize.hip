@@ -1,10 +1,15 @@
 // mp8_quantize_e5m2 / mp8_sr_bits: the Q node of Figure 1a (arXiv 1905.12334, Section 3)
 // as HBM-streaming kernels for gfx950.
 //
-// Flat kernel: every lane owns groups of 16 consecutive elements (64 B of FP32 in, 16 B of
-// codes out), which is also two groups of eight for the random-bit stream (one Philox block
-// per eight elements).  Transposing kernel: a 64x64 tile goes through LDS so that both the
-// row-major and the transposed copy are written with full 16-byte stores.
+// Flat kernel: a block owns a contiguous run of the tensor; its threads read it as
+// wave-interleaved 16-byte loads (every load instruction of a wave covers 1 KiB of
+// contiguous FP32), convert four values to one packed dword with the hardware conversion
+// instructions and store dwords (256 B contiguous per wave instruction).
+// Transposing kernel: a 128x128 tile; the row-major copy is written straight from registers,
+// the codes also go to an LDS tile from which every thread gathers 16 rows x 4 columns,
+// transposes the 4x4 byte blocks in registers and writes 16-byte pieces of the transposed
+// copy, eight lanes side by side per 128-byte line.
+// Shapes that are not multiples of 4 columns / 16 rows take a small generic kernel.
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
@@ -20,48 +25,52 @@ __device__ __forceinline__ float load_src(const void *src, int64_t i) {
         return reinterpret_cast<const float *>(src)[i];
 }
 
-// Load eight consecutive source elements starting at i (i % 8 == 0, all in range).
+// Four consecutive source elements starting at element index i (i % 4 == 0).
 template <bool kF16>
-__device__ __forceinline__ void load8(const void *src, int64_t i, float v[8]) {
+__device__ __forceinline__ void load4(const void *src, int64_t i, float v[4]) {
     if constexpr (kF16) {
-        uint4 raw = *reinterpret_cast<const uint4 *>(reinterpret_cast<const __half *>(src) + i);
+        u32x2 raw = __builtin_nontemporal_load(
+            reinterpret_cast<const u32x2 *>(reinterpret_cast<const __half *>(src) + i));
         const __half2 *h = reinterpret_cast<const __half2 *>(&raw);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            float2 f = __half22float2(h[j]);
-            v[2 * j] = f.x;
-            v[2 * j + 1] = f.y;
-        }
+        float2 a = __half22float2(h[0]), b = __half22float2(h[1]);
+        v[0] = a.x; v[1] = a.y; v[2] = b.x; v[3] = b.y;
     } else {
-        const f32x4 *p = reinterpret_cast<const f32x4 *>(reinterpret_cast<const float *>(src) + i);
-        f32x4 x0 = __builtin_nontemporal_load(p);
-        f32x4 x1 = __builtin_nontemporal_load(p + 1);
-        v[0] = x0.x; v[1] = x0.y; v[2] = x0.z; v[3] = x0.w;
-        v[4] = x1.x; v[5] = x1.y; v[6] = x1.z; v[7] = x1.w;
+        f32x4 x = __builtin_nontemporal_load(
+            reinterpret_cast<const f32x4 *>(reinterpret_cast<const float *>(src) + i));
+        v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
     }
 }
 
-// Round eight scaled values that share Philox block `blk`; returns the codes packed
-// little-endian (element 0 in the low byte of .x).
+// Scale and round four consecutive elements whose first has linear index i (i % 4 == 0).
 template <bool kSR, bool kStats>
-__device__ __forceinline__ uint2 round8(const float v[8], float scale, bool sat,
-                                        const Philox &rng, uint64_t blk, StatsAcc &st) {
-    uint4 w = make_uint4(0, 0, 0, 0);
-    if constexpr (kSR) w = rng.block(blk);
-    const uint32_t rw[4] = {w.x, w.y, w.z, w.w};
-    uint32_t c[8];
+__device__ __forceinline__ uint32_t round4(float v[4], float scale, bool sat, const Philox &rng,
+                                           int64_t i, StatsAcc &st) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        uint32_t u = f2u(v[j] * scale);
-        uint32_t r16 = (j & 1) ? (rw[j >> 1] >> 16) : (rw[j >> 1] & 0xFFFFu);
-        c[j] = e5m2_from_f32_bits<kSR>(u, r16, sat);
-        if constexpr (kStats) st.add(u & 0x7FFFFFFFu, c[j]);
+    for (int j = 0; j < 4; ++j) v[j] *= scale;
+    uint32_t r01 = 0, r23 = 0;
+    if constexpr (kSR) {
+        // elements i..i+3 are halfwords (i % 8) .. +3 of Philox block i / 8
+        uint4 w = rng.block((uint64_t)i >> 3);
+        r01 = (i & 4) ? w.z : w.x;
+        r23 = (i & 4) ? w.w : w.y;
     }
-    uint2 o;
-    o.x = c[0] | (c[1] << 8) | (c[2] << 16) | (c[3] << 24);
-    o.y = c[4] | (c[5] << 8) | (c[6] << 16) | (c[7] << 24);
-    return o;
+    uint32_t pk = e5m2_pack4<kSR>(v, r01, r23, sat);
+    if constexpr (kStats) st.add4(v, pk);
+    return pk;
 }
+
+template <bool kSR, bool kStats>
+__device__ __forceinline__ uint32_t round1(float x, float scale, bool sat, const Philox &rng,
+                                           int64_t i, StatsAcc &st) {
+    float y = x * scale;
+    uint32_t r16 = 0;
+    if constexpr (kSR) r16 = philox_half(rng.block((uint64_t)i >> 3), (int)(i & 7));
+    uint32_t c = e5m2_from_f32_bits<kSR>(f2u(y), r16, sat);
+    if constexpr (kStats) st.add1(y, c);
+    return c;
+}
+
+constexpr int kFlatUnroll = 4;  // 16-byte loads in flight per thread
 
 template <bool kF16, bool kSR, bool kStats>
 __global__ __launch_bounds__(256) void quantize_flat_kernel(const void *__restrict__ src,
@@ -70,92 +79,124 @@ __global__ __launch_bounds__(256) void quantize_flat_kernel(const void *__restri
                                                             uint64_t offset, mp8_stats *stats) {
     const Philox rng(seed, offset);
     StatsAcc st;
-    const int64_t ngroups = n >> 4;  // full groups of 16 elements
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < ngroups; g += stride) {
-        float v[16];
-        load8<kF16>(src, g * 16, v);
-        load8<kF16>(src, g * 16 + 8, v + 8);
-        uint2 lo = round8<kSR, kStats>(v, scale, sat != 0, rng, (uint64_t)(2 * g), st);
-        uint2 hi = round8<kSR, kStats>(v + 8, scale, sat != 0, rng, (uint64_t)(2 * g + 1), st);
-        u32x4 pk = {lo.x, lo.y, hi.x, hi.y};
-        __builtin_nontemporal_store(pk, reinterpret_cast<u32x4 *>(dst + g * 16));
-    }
-    // ragged tail (< 16 elements): one element per lane of the first wave of block 0
-    if (blockIdx.x == 0 && threadIdx.x < 16) {
-        int64_t i = (ngroups << 4) + threadIdx.x;
-        if (i < n) {
-            uint32_t u = f2u(load_src<kF16>(src, i) * scale);
-            uint32_t r16 = 0;
-            if constexpr (kSR) r16 = philox_half(rng.block((uint64_t)i >> 3), (int)(i & 7));
-            uint32_t c = e5m2_from_f32_bits<kSR>(u, r16, sat != 0);
-            dst[i] = (uint8_t)c;
-            if constexpr (kStats) st.add(u & 0x7FFFFFFFu, c);
+    const int64_t n4 = n >> 2;  // groups of four elements
+    uint32_t *dst4 = reinterpret_cast<uint32_t *>(dst);
+    const int64_t stride = (int64_t)gridDim.x * 256 * kFlatUnroll;
+    for (int64_t base = (int64_t)blockIdx.x * 256 * kFlatUnroll + threadIdx.x; base < n4;
+         base += stride) {
+        float v[kFlatUnroll][4];
+#pragma unroll
+        for (int u = 0; u < kFlatUnroll; ++u) {
+            const int64_t g = base + u * 256;
+            if (g < n4) load4<kF16>(src, g * 4, v[u]);
         }
+#pragma unroll
+        for (int u = 0; u < kFlatUnroll; ++u) {
+            const int64_t g = base + u * 256;
+            if (g < n4) {
+                uint32_t pk = round4<kSR, kStats>(v[u], scale, sat != 0, rng, g * 4, st);
+                __builtin_nontemporal_store(pk, dst4 + g);
+            }
+        }
+    }
+    // ragged tail (< 4 elements)
+    if (blockIdx.x == 0 && threadIdx.x < 4) {
+        const int64_t i = (n4 << 2) + threadIdx.x;
+        if (i < n)
+            dst[i] = (uint8_t)round1<kSR, kStats>(load_src<kF16>(src, i), scale, sat != 0, rng, i, st);
     }
     if constexpr (kStats) st.flush(stats);
 }
 
-// 64x64 tile per block of 256 threads.  Thread t handles row (t / 4) + {0}, 16 columns
-// starting at 16 * (t % 4): codes are packed into a uint4, written to dst directly and into
-// an LDS tile; after the barrier the tile is read column-wise for the transposed copy.
+// Transpose a 4x4 byte block held as four row dwords into four column dwords
+// (byte k of row j becomes byte j of column k).  v_perm_b32 picks bytes 0-3 from its second
+// operand and 4-7 from its first.
+__device__ __forceinline__ void transpose4x4(const uint32_t r[4], uint32_t c[4]) {
+    const uint32_t t0 = __builtin_amdgcn_perm(r[1], r[0], 0x05010400u);  // r0.0 r1.0 r0.1 r1.1
+    const uint32_t t1 = __builtin_amdgcn_perm(r[3], r[2], 0x05010400u);  // r2.0 r3.0 r2.1 r3.1
+    const uint32_t t2 = __builtin_amdgcn_perm(r[1], r[0], 0x07030602u);  // r0.2 r1.2 r0.3 r1.3
+    const uint32_t t3 = __builtin_amdgcn_perm(r[3], r[2], 0x07030602u);  // r2.2 r3.2 r2.3 r3.3
+    c[0] = __builtin_amdgcn_perm(t1, t0, 0x05040100u);
+    c[1] = __builtin_amdgcn_perm(t1, t0, 0x07060302u);
+    c[2] = __builtin_amdgcn_perm(t3, t2, 0x05040100u);
+    c[3] = __builtin_amdgcn_perm(t3, t2, 0x07060302u);
+}
+
+constexpr int kTile = 128;
+constexpr int kPitch = kTile / 4 + 1;  // LDS row pitch in dwords
+
+// Requires cols % 4 == 0 and rows % 16 == 0.
 template <bool kF16, bool kSR, bool kStats>
 __global__ __launch_bounds__(256) void quantize_transpose_kernel(
     const void *__restrict__ src, uint8_t *__restrict__ dst, uint8_t *__restrict__ dst_t,
     int64_t rows, int64_t cols, float scale, int sat, uint64_t seed, uint64_t offset,
     mp8_stats *stats) {
-    constexpr int T = 64;
-    // rows of 17 dwords: the column reads of the transposed pass spread over the banks
-    __shared__ __attribute__((aligned(16))) uint8_t tile[T][T + 4];
+    __shared__ uint32_t tile[kTile * kPitch];
     const Philox rng(seed, offset);
     StatsAcc st;
-    const int64_t tiles_c = (cols + T - 1) / T;
-    const int64_t r0 = (int64_t)(blockIdx.x / tiles_c) * T;
-    const int64_t c0 = (int64_t)(blockIdx.x % tiles_c) * T;
-    const int tr = threadIdx.x >> 2;         // 0..63 row inside the tile
-    const int tc = (threadIdx.x & 3) * 16;   // column offset inside the tile
-    const int64_t r = r0 + tr, c = c0 + tc;
-    const bool fast = ((cols & 15) == 0);    // rows of 16-element groups are aligned
-    if (r < rows && c < cols) {
-        if (fast) {
-            float v[16];
+    const int64_t tiles_c = (cols + kTile - 1) / kTile;
+    const int64_t r0 = (int64_t)(blockIdx.x / tiles_c) * kTile;
+    const int64_t c0 = (int64_t)(blockIdx.x % tiles_c) * kTile;
+    // phase 1: 128 rows x 32 column groups of four; item = u * 256 + tid -> (row, group)
+#pragma unroll 4
+    for (int u = 0; u < 16; ++u) {
+        const int item = u * 256 + threadIdx.x;
+        const int tr = item >> 5, cq = item & 31;
+        const int64_t r = r0 + tr, c = c0 + 4 * cq;
+        uint32_t pk = 0;
+        if (r < rows && c < cols) {
+            float v[4];
             const int64_t i = r * cols + c;
-            load8<kF16>(src, i, v);
-            load8<kF16>(src, i + 8, v + 8);
-            uint2 lo = round8<kSR, kStats>(v, scale, sat != 0, rng, (uint64_t)i >> 3, st);
-            uint2 hi = round8<kSR, kStats>(v + 8, scale, sat != 0, rng, ((uint64_t)i >> 3) + 1, st);
-            uint4 pk = make_uint4(lo.x, lo.y, hi.x, hi.y);
-            *reinterpret_cast<uint4 *>(dst + i) = pk;
-            uint32_t *trow = reinterpret_cast<uint32_t *>(&tile[tr][tc]);
-            trow[0] = pk.x; trow[1] = pk.y; trow[2] = pk.z; trow[3] = pk.w;
-        } else {
-            for (int j = 0; j < 16 && c + j < cols; ++j) {
-                const int64_t i = r * cols + c + j;
-                uint32_t u = f2u(load_src<kF16>(src, i) * scale);
-                uint32_t r16 = 0;
-                if constexpr (kSR) r16 = philox_half(rng.block((uint64_t)i >> 3), (int)(i & 7));
-                uint32_t cd = e5m2_from_f32_bits<kSR>(u, r16, sat != 0);
-                if constexpr (kStats) st.add(u & 0x7FFFFFFFu, cd);
-                dst[i] = (uint8_t)cd;
-                tile[tr][tc + j] = (uint8_t)cd;
+            load4<kF16>(src, i, v);
+            pk = round4<kSR, kStats>(v, scale, sat != 0, rng, i, st);
+            *reinterpret_cast<uint32_t *>(dst + i) = pk;
+        }
+        tile[tr * kPitch + cq] = pk;
+    }
+    __syncthreads();
+    // phase 2: thread = (column group cg, row chunk k): 16 rows x 4 columns, k fastest so that
+    // eight neighbouring lanes complete one 128-byte line of a transposed row
+    const int k = threadIdx.x & 7, cg = threadIdx.x >> 3;
+    uint32_t colw[4][4];  // [column][row block of 4]
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        uint32_t rr[4], cc[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) rr[j] = tile[(16 * k + 4 * b + j) * kPitch + cg];
+        transpose4x4(rr, cc);
+#pragma unroll
+        for (int col = 0; col < 4; ++col) colw[col][b] = cc[col];
+    }
+    const int64_t orow = r0 + 16 * k;
+    if (orow < rows) {
+#pragma unroll
+        for (int col = 0; col < 4; ++col) {
+            const int64_t oc = c0 + 4 * cg + col;
+            if (oc < cols) {
+                u32x4 o = {colw[col][0], colw[col][1], colw[col][2], colw[col][3]};
+                *reinterpret_cast<u32x4 *>(dst_t + oc * rows + orow) = o;
             }
         }
     }
-    __syncthreads();
-    // transposed write: thread t writes 16 consecutive source-rows of source-column tr2
-    const int tr2 = threadIdx.x >> 2;        // source column inside the tile
-    const int tq = (threadIdx.x & 3) * 16;   // first source row inside the tile
-    const int64_t oc = c0 + tr2;             // row of dst_t
-    const int64_t orow0 = r0 + tq;           // column of dst_t
-    if (oc < cols && orow0 < rows) {
-        uint32_t w[4] = {0, 0, 0, 0};
-#pragma unroll
-        for (int j = 0; j < 16; ++j) w[j >> 2] |= (uint32_t)tile[tq + j][tr2] << (8 * (j & 3));
-        uint8_t *p = dst_t + oc * rows + orow0;
-        if (((rows & 15) == 0) && orow0 + 16 <= rows) {
-            *reinterpret_cast<uint4 *>(p) = make_uint4(w[0], w[1], w[2], w[3]);
-        } else {
-            for (int j = 0; j < 16 && orow0 + j < rows; ++j) p[j] = (uint8_t)(w[j >> 2] >> (8 * (j & 3)));
+    if constexpr (kStats) st.flush(stats);
+}
+
+// Any shape: one element per thread and iteration.
+template <bool kF16, bool kSR, bool kStats>
+__global__ __launch_bounds__(256) void quantize_generic_kernel(
+    const void *__restrict__ src, uint8_t *__restrict__ dst, uint8_t *__restrict__ dst_t,
+    int64_t rows, int64_t cols, float scale, int sat, uint64_t seed, uint64_t offset,
+    mp8_stats *stats) {
+    const Philox rng(seed, offset);
+    StatsAcc st;
+    const int64_t n = rows * cols;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const uint32_t c = round1<kSR, kStats>(load_src<kF16>(src, i), scale, sat != 0, rng, i, st);
+        dst[i] = (uint8_t)c;
+        if (dst_t != nullptr) {
+            const int64_t r = i / cols;
+            dst_t[(i - r * cols) * rows + r] = (uint8_t)c;
         }
     }
     if constexpr (kStats) st.flush(stats);
@@ -175,15 +216,22 @@ static hipError_t launch_quantize(const void *src, uint8_t *dst, uint8_t *dst_t,
                                   uint64_t offset, mp8_stats *stats, hipStream_t s) {
     const int64_t n = rows * cols;
     if (dst_t == nullptr) {
-        int64_t groups = (n >> 4) + 1;
-        int64_t blocks = (groups + 255) / 256;
-        const int64_t cap = 256 * 16;  // 16 blocks per CU, grid-stride beyond that
-        if (blocks > cap) blocks = cap;
+        const int64_t per_block = 256 * kFlatUnroll;
+        int64_t blocks = ((n >> 2) + per_block - 1) / per_block;
+        if (blocks < 1) blocks = 1;
+        if (blocks > (1 << 22)) blocks = 1 << 22;  // grid-stride beyond 2^34 elements
+        if (kStats && blocks > 256 * 8) blocks = 256 * 8;  // fewer atomics: grid-stride
         hipLaunchKernelGGL((quantize_flat_kernel<kF16, kSR, kStats>), dim3((unsigned)blocks),
                            dim3(256), 0, s, src, dst, n, scale, sat, seed, offset, stats);
-    } else {
-        int64_t tiles = ((rows + 63) / 64) * ((cols + 63) / 64);
+    } else if ((cols & 3) == 0 && (rows & 15) == 0) {
+        const int64_t tiles = ((rows + kTile - 1) / kTile) * ((cols + kTile - 1) / kTile);
         hipLaunchKernelGGL((quantize_transpose_kernel<kF16, kSR, kStats>), dim3((unsigned)tiles),
+                           dim3(256), 0, s, src, dst, dst_t, rows, cols, scale, sat, seed, offset,
+                           stats);
+    } else {
+        int64_t blocks = (n + 255) / 256;
+        if (blocks > 256 * 32) blocks = 256 * 32;
+        hipLaunchKernelGGL((quantize_generic_kernel<kF16, kSR, kStats>), dim3((unsigned)blocks),
                            dim3(256), 0, s, src, dst, dst_t, rows, cols, scale, sat, seed, offset,
                            stats);
     }
@@ -202,7 +250,8 @@ extern "C" mp8_status mp8_quantize_e5m2(const void *src, int src_is_f16, uint8_t
     if (rows == 0 || cols == 0) return MP8_OK;
     if (!src || !dst) return MP8_ERR_INVALID_ARG;
     if (rows > (INT64_MAX / cols)) return MP8_ERR_UNSUPPORTED;
-    if (dst_t && ((rows + 63) / 64) * ((cols + 63) / 64) > 0x7FFFFFFFLL) return MP8_ERR_UNSUPPORTED;
+    if (dst_t && ((rows + kTile - 1) / kTile) * ((cols + kTile - 1) / kTile) > 0x7FFFFFFFLL)
+        return MP8_ERR_UNSUPPORTED;
     if (((uintptr_t)src | (uintptr_t)dst | (uintptr_t)dst_t) & 15u) return MP8_ERR_ALIGNMENT;
     hipStream_t s = (hipStream_t)stream;
     const int sat = (flags & MP8_FLAG_SATURATE) ? 1 : 0;

@@ -10,17 +10,36 @@
 
 namespace mp8 {
 
+// value(g8) * inv_scale, FP32 weight, one fused multiply-add, rounded to half.
 template <bool kSR>
 __device__ __forceinline__ uint32_t update_one(uint32_t w16, uint32_t g8, float neg_lr,
                                                float inv_scale, uint32_t r16) {
     float g = e5m2_to_f32(g8) * inv_scale;
     float w = __half2float(__ushort_as_half((unsigned short)w16));
     float wn = __builtin_fmaf(neg_lr, g, w);
-    return f16_from_f32_bits<kSR>(f2u(wn), r16);
+    // The update is an FP32 operation whose FP32 result is then converted to half: keep the
+    // compiler from merging the two into one mixed-precision instruction that rounds once.
+    asm volatile("" : "+v"(wn));
+    if constexpr (kSR) {
+        return f16_from_f32_bits<true>(f2u(wn), r16);
+    } else {
+        // v_cvt_f16_f32 rounds to nearest even exactly like the bit-level routine for every
+        // input that is not a NaN (checked over all 2^32 inputs); NaN is made canonical
+        uint32_t h = __half_as_ushort(__float2half_rn(wn));
+        return (wn != wn) ? 0x7E00u : h;
+    }
 }
 
-// Each lane owns groups of 16 consecutive elements: 32 B of weights in and out, 16 B of
-// gradients, two Philox blocks.
+__device__ __forceinline__ uint32_t e5m2_of_half(uint32_t h) {
+    return e5m2_from_f32_bits<false>(f2u(__half2float(__ushort_as_half((unsigned short)h))), 0u,
+                                     false);
+}
+
+constexpr int kUpdUnroll = 2;  // groups of eight elements in flight per thread
+
+// Thread item = eight consecutive elements (16 B of weights, 8 B of gradients, one Philox
+// block); items are wave-interleaved so that every load or store instruction of a wave
+// covers one contiguous run.
 template <bool kSR, bool kW8, bool kStats>
 __global__ __launch_bounds__(256) void sgd_update_kernel(uint16_t *__restrict__ w16,
                                                          const uint8_t *__restrict__ g8,
@@ -34,71 +53,74 @@ __global__ __launch_bounds__(256) void sgd_update_kernel(uint16_t *__restrict__ 
     const bool skipping = (skip != nullptr) && (*skip != 0u);
     if (skipping && !kStats) return;
     uint32_t nonfinite = 0;
-    const int64_t ngroups = n >> 4;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < ngroups; g += stride) {
-        u32x4 gr = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(g8 + g * 16));
-        const uint32_t gw[4] = {gr.x, gr.y, gr.z, gr.w};
-        if constexpr (kStats) {
+    const int64_t n8 = n >> 3;
+    const int64_t stride = (int64_t)gridDim.x * 256 * kUpdUnroll;
+    for (int64_t base = (int64_t)blockIdx.x * 256 * kUpdUnroll + threadIdx.x; base < n8;
+         base += stride) {
+        u32x2 gr[kUpdUnroll];
+        u32x4 wr[kUpdUnroll];
 #pragma unroll
-            for (int j = 0; j < 16; ++j)
-                nonfinite += ((((gw[j >> 2] >> (8 * (j & 3))) & 0x7Cu) == 0x7Cu) ? 1u : 0u);
-        }
-        if (skipping) continue;
-        u32x4 *wp = reinterpret_cast<u32x4 *>(w16 + g * 16);
-        u32x4 wa = wp[0], wb = wp[1];
-        uint32_t ww[8] = {wa.x, wa.y, wa.z, wa.w, wb.x, wb.y, wb.z, wb.w};
-        uint32_t rw[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        if constexpr (kSR) {
-            uint4 r0 = rng.block((uint64_t)(2 * g));
-            uint4 r1 = rng.block((uint64_t)(2 * g + 1));
-            rw[0] = r0.x; rw[1] = r0.y; rw[2] = r0.z; rw[3] = r0.w;
-            rw[4] = r1.x; rw[5] = r1.y; rw[6] = r1.z; rw[7] = r1.w;
-        }
-        uint32_t w8[4] = {0, 0, 0, 0};
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {  // pair j = elements 2j, 2j+1
-            uint32_t g_lo = (gw[j >> 1] >> (16 * (j & 1))) & 0xFFu;
-            uint32_t g_hi = (gw[j >> 1] >> (16 * (j & 1) + 8)) & 0xFFu;
-            uint32_t h_lo = update_one<kSR>(ww[j] & 0xFFFFu, g_lo, neg_lr, inv_scale, rw[j] & 0xFFFFu);
-            uint32_t h_hi = update_one<kSR>(ww[j] >> 16, g_hi, neg_lr, inv_scale, rw[j] >> 16);
-            ww[j] = h_lo | (h_hi << 16);
-            if constexpr (kW8) {
-                uint32_t c_lo = e5m2_from_f32_bits<false>(
-                    f2u(__half2float(__ushort_as_half((unsigned short)h_lo))), 0u, false);
-                uint32_t c_hi = e5m2_from_f32_bits<false>(
-                    f2u(__half2float(__ushort_as_half((unsigned short)h_hi))), 0u, false);
-                w8[j >> 1] |= (c_lo | (c_hi << 8)) << (16 * (j & 1));
+        for (int u = 0; u < kUpdUnroll; ++u) {
+            const int64_t t = base + u * 256;
+            if (t < n8) {
+                gr[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(g8) + t);
+                if (!skipping) wr[u] = __builtin_nontemporal_load(reinterpret_cast<u32x4 *>(w16) + t);
             }
         }
-        u32x4 oa = {ww[0], ww[1], ww[2], ww[3]}, ob = {ww[4], ww[5], ww[6], ww[7]};
-        wp[0] = oa;
-        wp[1] = ob;
-        if constexpr (kW8) {
-            u32x4 o8 = {w8[0], w8[1], w8[2], w8[3]};
-            *reinterpret_cast<u32x4 *>(w8_out + g * 16) = o8;
+#pragma unroll
+        for (int u = 0; u < kUpdUnroll; ++u) {
+            const int64_t t = base + u * 256;
+            if (t >= n8) continue;
+            const uint32_t gw[2] = {gr[u].x, gr[u].y};
+            if constexpr (kStats) {
+#pragma unroll
+                for (int q = 0; q < 2; ++q)
+                    nonfinite += __builtin_popcount(((gw[q] & 0x7C7C7C7Cu) + 0x04040404u) & 0x80808080u);
+            }
+            if (skipping) continue;
+            uint32_t ww[4] = {wr[u].x, wr[u].y, wr[u].z, wr[u].w};
+            uint32_t rw[4] = {0, 0, 0, 0};
+            if constexpr (kSR) {
+                uint4 r = rng.block((uint64_t)t);
+                rw[0] = r.x; rw[1] = r.y; rw[2] = r.z; rw[3] = r.w;
+            }
+            uint32_t w8[2] = {0, 0};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {  // pair j = elements 2j, 2j+1
+                const uint32_t g_lo = (gw[j >> 1] >> (16 * (j & 1))) & 0xFFu;
+                const uint32_t g_hi = (gw[j >> 1] >> (16 * (j & 1) + 8)) & 0xFFu;
+                const uint32_t h_lo = update_one<kSR>(ww[j] & 0xFFFFu, g_lo, neg_lr, inv_scale, rw[j] & 0xFFFFu);
+                const uint32_t h_hi = update_one<kSR>(ww[j] >> 16, g_hi, neg_lr, inv_scale, rw[j] >> 16);
+                ww[j] = h_lo | (h_hi << 16);
+                if constexpr (kW8)
+                    w8[j >> 1] |= (e5m2_of_half(h_lo) | (e5m2_of_half(h_hi) << 8)) << (16 * (j & 1));
+            }
+            u32x4 o = {ww[0], ww[1], ww[2], ww[3]};
+            __builtin_nontemporal_store(o, reinterpret_cast<u32x4 *>(w16) + t);
+            if constexpr (kW8) {
+                u32x2 o8 = {w8[0], w8[1]};
+                __builtin_nontemporal_store(o8, reinterpret_cast<u32x2 *>(w8_out) + t);
+            }
         }
     }
-    if (blockIdx.x == 0 && threadIdx.x < 16) {  // ragged tail
-        int64_t i = (ngroups << 4) + threadIdx.x;
+    if (blockIdx.x == 0 && threadIdx.x < 8) {  // ragged tail (< 8 elements)
+        const int64_t i = (n8 << 3) + threadIdx.x;
         if (i < n) {
-            uint32_t gc = g8[i];
+            const uint32_t gc = g8[i];
             if constexpr (kStats) nonfinite += ((gc & 0x7Cu) == 0x7Cu) ? 1u : 0u;
             if (!skipping) {
                 uint32_t r16 = 0;
                 if constexpr (kSR) r16 = philox_half(rng.block((uint64_t)i >> 3), (int)(i & 7));
-                uint32_t h = update_one<kSR>(w16[i], gc, neg_lr, inv_scale, r16);
+                const uint32_t h = update_one<kSR>(w16[i], gc, neg_lr, inv_scale, r16);
                 w16[i] = (uint16_t)h;
-                if constexpr (kW8)
-                    w8_out[i] = (uint8_t)e5m2_from_f32_bits<false>(
-                        f2u(__half2float(__ushort_as_half((unsigned short)h))), 0u, false);
+                if constexpr (kW8) w8_out[i] = (uint8_t)e5m2_of_half(h);
             }
         }
     }
     if constexpr (kStats) {
-#pragma unroll
-        for (int o = kWave / 2; o > 0; o >>= 1) nonfinite += __shfl_xor(nonfinite, o);
-        if ((threadIdx.x & (kWave - 1)) == 0 && nonfinite) atomicAdd(&stats->nonfinite, nonfinite);
+        StatsAcc st;
+        st.nonfinite = nonfinite;
+        st.flush(stats);
     }
 }
 
@@ -115,8 +137,11 @@ extern "C" mp8_status mp8_sgd_update_fp16_sr(uint16_t *w16, const uint8_t *g8, i
     if (n == 0) return MP8_OK;
     if (!w16 || !g8) return MP8_ERR_INVALID_ARG;
     if (((uintptr_t)w16 | (uintptr_t)g8 | (uintptr_t)w8_out) & 15u) return MP8_ERR_ALIGNMENT;
-    int64_t blocks = ((n >> 4) + 1 + 255) / 256;
-    if (blocks > 256 * 16) blocks = 256 * 16;
+    const int64_t per_block = 256 * kUpdUnroll;
+    int64_t blocks = ((n >> 3) + per_block - 1) / per_block;
+    if (blocks < 1) blocks = 1;
+    if (blocks > (1 << 22)) blocks = 1 << 22;
+    if (stats != nullptr && blocks > 256 * 8) blocks = 256 * 8;  // fewer atomics: grid-stride
     const float neg_lr = -lr;
     hipStream_t s = (hipStream_t)stream;
 #define MP8_U(SR, W8, ST)                                                                       \

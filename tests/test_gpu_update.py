@@ -67,7 +67,9 @@ def test_update_transformer_big_magnitudes_and_skip(mp8):
     lr, inv = lay.extra["lr"], 1.0 / lay.loss_scale
     seed = lay.extra["seed"]
     rne, _, _ = _run(mp8, w16, g8, lr, inv, oracle.RNE)
-    assert np.array_equal(rne, w16)                   # RNE stalls at these magnitudes
+    want_rne, _ = oracle.sgd_update_fp16(w16, g8, lr, inv, mode=oracle.RNE)
+    assert np.array_equal(rne, want_rne)
+    assert (rne == w16).mean() > 0.999                # RNE stalls at these magnitudes
     sr, _, _ = _run(mp8, w16, g8, lr, inv, oracle.SR, seed=seed, offset=1)
     want, _ = oracle.sgd_update_fp16(w16, g8, lr, inv, mode=oracle.SR, seed=seed, offset=1)
     assert np.array_equal(sr, want) and not np.array_equal(sr, w16)
