@@ -30,7 +30,7 @@ using i32x8 = int __attribute__((ext_vector_type(8)));
 using i32x4 = int __attribute__((ext_vector_type(4)));
 using f32x16 = float __attribute__((ext_vector_type(16)));
 
-constexpr int BK = 128;  // bytes (= elements) of contraction per main-loop step
+constexpr int BK = 128;  // bytes (= elements) of contraction per pipeline stage
 
 struct Epilogue {
     float alpha;
@@ -50,7 +50,7 @@ struct GemmArgs {
     const uint8_t *b;
     int64_t lda, ldb;
     int64_t rows, cols;
-    int ksteps;         // contraction length / BK
+    int ksteps;         // contraction length / BK (pipeline stages)
     int splits;         // number of contraction slices
     int tiles_m, tiles_n;
     float *partial;     // [splits, rows, cols] when splits > 1
@@ -154,71 +154,143 @@ __device__ __forceinline__ void map_block(int tiles_m, int tiles_n, int &split, 
     tn = in / gsz;
 }
 
-// Wait until at most n vector-memory operations of this wave are outstanding (gfx9 encoding:
-// vmcnt in bits 3:0 and 15:14; expcnt and lgkmcnt fields left at "no wait").
+// Wait until at most n vector-memory operations of this wave are outstanding and all of its
+// LDS operations have completed (gfx9 encoding: vmcnt in bits 3:0 and 15:14, lgkmcnt in
+// bits 11:8, expcnt left at "no wait").
 template <int n>
-__device__ __forceinline__ void wait_vmcnt() {
-    __builtin_amdgcn_s_waitcnt((n & 0xF) | ((n >> 4) << 14) | (0x7 << 4) | (0xF << 8));
+__device__ __forceinline__ void wait_vm_lds() {
+    static_assert(n >= 0 && n < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt((n & 0xF) | ((n >> 4) << 14) | (0x7 << 4) | (0x0 << 8));
 }
 
-// One direct-to-LDS load: 64 lanes x 16 bytes land at lds_base + lane * 16.
-__device__ __forceinline__ void dma16(const uint8_t *gptr, uint8_t *lds_base) {
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gptr,
-                                     (__attribute__((address_space(3))) void *)lds_base, 16, 0, 0);
+// One direct-to-LDS load: 64 lanes x 16 bytes land at LDS byte address lds_addr + lane * 16
+// (lds_addr is wave-uniform and travels in M0).  Written as inline assembly on purpose: the
+// compiler then neither knows nor tracks that this is a load into LDS, and would otherwise
+// put a wait for ALL outstanding loads in front of every later LDS read, which serialises
+// the prefetch ring.  Completion is tracked by hand with the vector-memory counter.
+__device__ __forceinline__ void dma16(const uint8_t *gbase, uint32_t lane_off, uint32_t lds_addr) {
+    // global address = wave-uniform base (SGPR pair) + per-lane 32-bit offset
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(lane_off), "s"(gbase), "s"(lds_addr)
+                 : "memory");
 }
 
-template <int BM, int BN, int WGM, int WGN>
-__global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(const GemmArgs p) {
+// Tell the compiler that a pointer is the same in every lane (keeps it in scalar registers).
+__device__ __forceinline__ const uint8_t *uniform_ptr(const uint8_t *p) {
+    const uint64_t v = (uint64_t)(uintptr_t)p;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return (const uint8_t *)(uintptr_t)(((uint64_t)hi << 32) | lo);
+}
+
+__device__ __forceinline__ uint32_t lds_address(const void *p) {
+    return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) uint8_t *)p;
+}
+
+// Main kernel.  256 threads = WGM x WGN waves, block tile BM x BN, NSTAGE-deep ring of
+// 128-byte-wide operand slabs in LDS (BK = 128: whole 128-byte lines travel from L2 to the
+// CU exactly once).  One slab = two MFMA sub-steps of 64.
+//
+// Pipeline of stage t, per wave (one barrier per stage, placed in its middle):
+//   sub-step 0:  read the fragments of (t, 1) into register set 1; multiply set 0 = (t, 0)
+//   middle:      wait for this wave's loads of stage t+1 and for its LDS reads; barrier --
+//                now stage t+1 is complete in LDS and nobody needs the buffer of stage t;
+//                issue the direct-to-LDS loads of stage t+NSTAGE into that buffer
+//   sub-step 1:  read the fragments of (t+1, 0) into set 0; multiply set 1 = (t, 1)
+// A load therefore has NSTAGE-1 stages of MFMA work to arrive, fragment reads are always one
+// sub-step ahead of their use, and the barrier is hidden behind queued MFMAs.
+//
+// LDS image of a slab: row r occupies 128 bytes, its 16-byte chunk c sits at slot
+// c ^ ((r >> 1) & 7).  The LDS serves a 16-byte-per-lane read sixteen lanes at a time over
+// its 64 banks (256 bytes = two rows); a fragment read has lanes 0..15 on rows r..r+15 with
+// the same chunk, and with this swizzle the sixteen pieces fall into sixteen different
+// 16-byte bank groups.  Direct-to-LDS writes are lane-contiguous, so the swizzle is applied
+// to the global address each lane fetches.
+template <int BM, int BN, int WGM, int WGN, int NSTAGE, int MINBLOCKS>
+__global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArgs p) {
     static_assert(WGM * WGN == 4, "four waves");
+    static_assert(NSTAGE >= 2, "ring depth");
     constexpr int WTM = BM / WGM, WTN = BN / WGN;  // wave tile
     constexpr int MT = WTM / 32, NT = WTN / 32;    // 32x32 MFMA tiles per wave
     constexpr int A_BYTES = BM * BK, B_BYTES = BN * BK, STAGE = A_BYTES + B_BYTES;
-    constexpr int A_DMA = BM / 32, B_DMA = BN / 32;  // direct loads per wave per step
+    constexpr int A_DMA = BM / 32, B_DMA = BN / 32;  // direct loads per wave per stage
+    constexpr int G = A_DMA + B_DMA;
+    static_assert(G * (NSTAGE - 2) < 64, "vmcnt range");
     // the operand ring, reused by the epilogue for FP32 row bands (2 x 32 rows per wave)
     constexpr int EP_BYTES = 4 * (MT >= 2 ? 2 : 1) * 32 * (WTN + 4) * 4;
-    constexpr int LDS_BYTES = 2 * STAGE > EP_BYTES ? 2 * STAGE : EP_BYTES;
+    constexpr int LDS_BYTES = NSTAGE * STAGE > EP_BYTES ? NSTAGE * STAGE : EP_BYTES;
     __shared__ __attribute__((aligned(1024))) uint8_t lds[LDS_BYTES];
 
     int split, tm, tn;
     map_block(p.tiles_m, p.tiles_n, split, tm, tn);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    split = __builtin_amdgcn_readfirstlane(split);
+    tm = __builtin_amdgcn_readfirstlane(tm);
+    tn = __builtin_amdgcn_readfirstlane(tn);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
     const int64_t row0 = (int64_t)tm * BM, col0 = (int64_t)tn * BN;
 
-    // contraction slice of this workgroup
+    // contraction slice of this workgroup, in stages of 128
     const int per = p.ksteps / p.splits, extra = p.ksteps % p.splits;
     const int ks_begin = split * per + (split < extra ? split : extra);
-    const int ks_count = per + (split < extra ? 1 : 0);
+    const int ks_count = __builtin_amdgcn_readfirstlane(per + (split < extra ? 1 : 0));
 
-    // Per-lane global offsets of the direct loads.  Load q of this wave brings rows
-    // 8*(wave + 4q) .. +7 of the tile; lane i lands in LDS slot (row i/8, chunk i%8) and
-    // therefore fetches global chunk (i%8) ^ (i/8) of that row.  Rows beyond the matrix
-    // are clamped to its last row (their products are never stored).
-    const int lrow = lane >> 3, lchunk = (lane & 7) ^ (lane >> 3);
-    const uint8_t *ga[A_DMA];
-    const uint8_t *gb[B_DMA];
+    // Direct loads.  Load q of this wave brings rows 8*(wave + 4q) .. +7 of the slab; lane i
+    // lands at (row i/8, slot i%8) and therefore fetches global chunk (i%8) ^ ((row >> 1) & 7)
+    // of that row; with row = 8*(wave + 4q) + i/8 that is ((4*wave + i/16) & 7).  Rows beyond
+    // the matrix are clamped to its last row (never stored).  Addresses are a wave-uniform
+    // base (tile origin + stage) plus a 32-bit lane offset.
+    const int lrow = lane >> 3, lchunk = (lane & 7) ^ ((4 * wave + (lane >> 4)) & 7);
+    const uint8_t *a_tile = uniform_ptr(p.a + row0 * p.lda + (int64_t)ks_begin * BK);
+    const uint8_t *b_tile = uniform_ptr(p.b + col0 * p.ldb + (int64_t)ks_begin * BK);
+    uint32_t oa[A_DMA], ob[B_DMA];
 #pragma unroll
     for (int q = 0; q < A_DMA; ++q) {
-        int64_t r = row0 + 8 * (wave + 4 * q) + lrow;
-        r = r < p.rows ? r : p.rows - 1;
-        ga[q] = p.a + r * p.lda + (int64_t)ks_begin * BK + lchunk * 16;
+        int64_t r = 8 * (wave + 4 * q) + lrow;
+        r = row0 + r < p.rows ? r : p.rows - 1 - row0;
+        oa[q] = (uint32_t)(r * p.lda) + lchunk * 16;
     }
 #pragma unroll
     for (int q = 0; q < B_DMA; ++q) {
-        int64_t c = col0 + 8 * (wave + 4 * q) + lrow;
-        c = c < p.cols ? c : p.cols - 1;
-        gb[q] = p.b + c * p.ldb + (int64_t)ks_begin * BK + lchunk * 16;
+        int64_t c = 8 * (wave + 4 * q) + lrow;
+        c = col0 + c < p.cols ? c : p.cols - 1 - col0;
+        ob[q] = (uint32_t)(c * p.ldb) + lchunk * 16;
     }
+    const uint32_t lds0 = lds_address(lds);
+    auto issue_loads = [&](int kstage) {
+        const uint32_t sa = lds0 + (kstage % NSTAGE) * STAGE + wave * 1024;
+        const uint32_t sb = sa + A_BYTES;
+        const uint8_t *ak = a_tile + (int64_t)kstage * BK;
+        const uint8_t *bk = b_tile + (int64_t)kstage * BK;
+#pragma unroll
+        for (int q = 0; q < A_DMA; ++q) dma16(ak, oa[q], sa + q * 4096);
+#pragma unroll
+        for (int q = 0; q < B_DMA; ++q) dma16(bk, ob[q], sb + q * 4096);
+    };
 
-    auto issue_loads = [&](int stage, int kstep) {
-        uint8_t *sa = lds + stage * STAGE;
-        uint8_t *sb = sa + A_BYTES;
+    // Fragments: lane l supplies row (l % 32) of a 32-row tile and, for sub-step s, the 32
+    // bytes k = 64*s + 32*(l/32) .. +31 of the slab, i.e. chunks 4s + 2*(l/32) and the next.
+    const int frow = lane & 31, fkb = lane >> 5;
+    const int fsw = (frow >> 1) & 7;
+    const int a_base = (wm * WTM + frow) * BK;
+    const int b_base = A_BYTES + (wn * WTN + frow) * BK;
+    auto read_frags = [&](int kstage, int sub, i32x8 (&af)[MT], i32x8 (&bf)[NT]) {
+        const uint8_t *s = lds + (kstage % NSTAGE) * STAGE;
+        const int c0 = ((4 * sub + 2 * fkb) ^ fsw) * 16, c1 = ((4 * sub + 2 * fkb + 1) ^ fsw) * 16;
 #pragma unroll
-        for (int q = 0; q < A_DMA; ++q)
-            dma16(ga[q] + (int64_t)kstep * BK, sa + (wave + 4 * q) * 1024);
+        for (int i = 0; i < MT; ++i) {
+            i32x4 lo = *reinterpret_cast<const i32x4 *>(s + a_base + i * 32 * BK + c0);
+            i32x4 hi = *reinterpret_cast<const i32x4 *>(s + a_base + i * 32 * BK + c1);
+            af[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        }
 #pragma unroll
-        for (int q = 0; q < B_DMA; ++q)
-            dma16(gb[q] + (int64_t)kstep * BK, sb + (wave + 4 * q) * 1024);
+        for (int j = 0; j < NT; ++j) {
+            i32x4 lo = *reinterpret_cast<const i32x4 *>(s + b_base + j * 32 * BK + c0);
+            i32x4 hi = *reinterpret_cast<const i32x4 *>(s + b_base + j * 32 * BK + c1);
+            bf[j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        }
     };
 
     f32x16 acc[MT][NT];
@@ -229,48 +301,70 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(const GemmArgs p) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-    // Fragment addressing: lane l supplies row (l % 32) of a 32-row tile and the 32 bytes
-    // k = 64*s + 32*(l/32) .. +31 of sub-step s, i.e. chunks 4s + 2*(l/32) and the next one,
-    // found at LDS slot chunk ^ (row % 8).
-    const int frow = lane & 31, fkb = lane >> 5;
-    const int fsw = frow & 7;
-    const int a_base = (wm * WTM + frow) * BK;
-    const int b_base = A_BYTES + (wn * WTN + frow) * BK;
+    // MFMAs [m0, m1) of a sub-step, numbered row-major over the wave's MT x NT tiles.
+    auto multiply = [&](const i32x8 (&af)[MT], const i32x8 (&bf)[NT], int m0, int m1) {
+#pragma unroll
+        for (int m = 0; m < MT * NT; ++m)
+            if (m >= m0 && m < m1)
+                // cbsz = blgp = 1 selects the (1,5,2) format for both operands; the scale
+                // operands are zero, i.e. the unscaled instruction.  b goes in as the "row"
+                // matrix so that a lane ends up with consecutive output columns.
+                acc[m / NT][m % NT] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                    bf[m % NT], af[m / NT], acc[m / NT][m % NT], 1, 1, 0, 0, 0, 0);
+    };
+    auto issue_one = [&](int kstage, int q) {  // load q (0 .. G-1) of a stage
+        const uint32_t sa = lds0 + (kstage % NSTAGE) * STAGE + wave * 1024;
+        if (q < A_DMA)
+            dma16(a_tile + (int64_t)kstage * BK, oa[q < A_DMA ? q : 0], sa + q * 4096);
+        else
+            dma16(b_tile + (int64_t)kstage * BK, ob[q >= A_DMA ? q - A_DMA : 0],
+                  sa + A_BYTES + (q - A_DMA) * 4096);
+    };
 
-    if (ks_count > 0) issue_loads(0, 0);
-    for (int ks = 0; ks < ks_count; ++ks) {
-        const int stage = ks & 1;
-        wait_vmcnt<0>();
-        __syncthreads();  // stage `stage` is complete; everyone left stage `stage ^ 1`
-        if (ks + 1 < ks_count) issue_loads(stage ^ 1, ks + 1);
-        const uint8_t *s = lds + stage * STAGE;
+    // Wait for this wave's loads of stage t+1 (and for its own LDS reads).  Loads complete in
+    // issue order; the groups still allowed in flight are the later stages already issued.
+    auto wait_stage = [&](int t) {
+        int later = ks_count - 2 - t;  // stages after t+1 that exist
+        later = later < NSTAGE - 2 ? later : NSTAGE - 2;
+        if (NSTAGE > 2 && later >= NSTAGE - 2) wait_vm_lds<G * (NSTAGE - 2)>();
+        else if (NSTAGE > 3 && later == NSTAGE - 3) wait_vm_lds<G * (NSTAGE > 3 ? NSTAGE - 3 : 0)>();
+        else wait_vm_lds<0>();
+    };
+
+    // MFMAs of sub-step 0 that are issued after the barrier, interleaved with the loads (two
+    // loads per MFMA) so that the matrix pipe stays fed while the wave issues them.
+    constexpr int NM = MT * NT;
+    constexpr int NPOST = (G / 2 < NM / 2) ? G / 2 : NM / 2;
+
+    i32x8 af0[MT], bf0[NT], af1[MT], bf1[NT];
+    // prologue: fill the ring, fetch the fragments of (0, 0)
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
-            const int c0 = ((4 * sub + 2 * fkb) ^ fsw) * 16;
-            const int c1 = ((4 * sub + 2 * fkb + 1) ^ fsw) * 16;
-            i32x8 af[MT], bf[NT];
+    for (int st = 0; st < NSTAGE; ++st)
+        if (st < ks_count) issue_loads(st);
+    wait_stage(-1);
+    __syncthreads();
+    read_frags(0, 0, af0, bf0);
+    for (int t = 0; t < ks_count; ++t) {
+        read_frags(t, 1, af1, bf1);
+        multiply(af0, bf0, 0, NM - NPOST);
+        __builtin_amdgcn_sched_barrier(0);
+        wait_stage(t);
+        __syncthreads();
+        const bool more = t + NSTAGE < ks_count;
 #pragma unroll
-            for (int i = 0; i < MT; ++i) {
-                i32x4 lo = *reinterpret_cast<const i32x4 *>(s + a_base + i * 32 * BK + c0);
-                i32x4 hi = *reinterpret_cast<const i32x4 *>(s + a_base + i * 32 * BK + c1);
-                af[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        for (int q = 0; q < G; ++q) {
+            if (more) issue_one(t + NSTAGE, q);
+            if ((q & 1) && (q >> 1) < NPOST) {
+                multiply(af0, bf0, NM - NPOST + (q >> 1), NM - NPOST + (q >> 1) + 1);
+                __builtin_amdgcn_sched_barrier(0);
             }
-#pragma unroll
-            for (int j = 0; j < NT; ++j) {
-                i32x4 lo = *reinterpret_cast<const i32x4 *>(s + b_base + j * 32 * BK + c0);
-                i32x4 hi = *reinterpret_cast<const i32x4 *>(s + b_base + j * 32 * BK + c1);
-                bf[j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            }
-#pragma unroll
-            for (int i = 0; i < MT; ++i)
-#pragma unroll
-                for (int j = 0; j < NT; ++j)
-                    // cbsz = blgp = 1 selects the (1,5,2) format for both operands; the
-                    // scale operands are zero, i.e. the unscaled instruction.
-                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                        bf[j], af[i], acc[i][j], 1, 1, 0, 0, 0, 0);
         }
+        if (G / 2 < NPOST) multiply(af0, bf0, NM - NPOST + G / 2, NM);
+        __builtin_amdgcn_sched_barrier(0);
+        if (t + 1 < ks_count) read_frags(t + 1, 0, af0, bf0);
+        multiply(af1, bf1, 0, NM);
     }
+    wait_vm_lds<0>();
 
     // Epilogue.  acc[i][j][4g + e] is output row  wm*WTM + 32i + lane%32  and column
     // wn*WTN + 32j + 8g + 4*(lane/32) + e.  Each wave passes its tile through LDS one band
@@ -403,13 +497,14 @@ struct TileConfig {
 };
 
 static const TileConfig kTiles[] = {
-    {256, 256, "256x256x128", gemm_mfma_kernel<256, 256, 2, 2>},
-    {256, 128, "256x128x128", gemm_mfma_kernel<256, 128, 2, 2>},
-    {128, 256, "128x256x128", gemm_mfma_kernel<128, 256, 2, 2>},
-    {128, 128, "128x128x128", gemm_mfma_kernel<128, 128, 2, 2>},
-    {64, 128, "64x128x128", gemm_mfma_kernel<64, 128, 1, 4>},
-    {128, 64, "128x64x128", gemm_mfma_kernel<128, 64, 4, 1>},
-    {64, 64, "64x64x128", gemm_mfma_kernel<64, 64, 2, 2>},
+    {256, 256, "256x256x128s2", gemm_mfma_kernel<256, 256, 2, 2, 2, 1>},
+    {256, 128, "256x128x128s3", gemm_mfma_kernel<256, 128, 2, 2, 3, 1>},
+    {128, 256, "128x256x128s3", gemm_mfma_kernel<128, 256, 2, 2, 3, 1>},
+    {128, 128, "128x128x128s2", gemm_mfma_kernel<128, 128, 2, 2, 2, 2>},
+    {128, 128, "128x128x128s4", gemm_mfma_kernel<128, 128, 2, 2, 4, 1>},
+    {64, 128, "64x128x128s3", gemm_mfma_kernel<64, 128, 1, 4, 3, 2>},
+    {128, 64, "128x64x128s3", gemm_mfma_kernel<128, 64, 4, 1, 3, 2>},
+    {64, 64, "64x64x128s4", gemm_mfma_kernel<64, 64, 2, 2, 4, 2>},
 };
 constexpr int kNumTiles = (int)(sizeof(kTiles) / sizeof(kTiles[0]));
 constexpr int kCUs = 256;
@@ -549,7 +644,9 @@ extern "C" mp8_status mp8_gemm_fp8_tuned(mp8_op op, int64_t M, int64_t N, int64_
     hipStream_t s = (hipStream_t)stream;
 
     Plan pl = make_plan(rows, cols, kc, tile_config, split_k);
-    const bool aligned = (((uintptr_t)a | (uintptr_t)b) & 15u) == 0 && (lda & 15) == 0 && (ldb & 15) == 0;
+    // the MFMA kernel wants 16-byte aligned rows and 32-bit offsets inside a 256-row tile
+    const bool aligned = (((uintptr_t)a | (uintptr_t)b) & 15u) == 0 && (lda & 15) == 0 &&
+                         (ldb & 15) == 0 && lda < (1 << 24) && ldb < (1 << 24);
     if (pl.mfma && !aligned) {
         if (tile_config > 0) return MP8_ERR_ALIGNMENT;
         pl.mfma = false;
