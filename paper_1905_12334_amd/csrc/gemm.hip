@@ -32,6 +32,14 @@ using f32x16 = float __attribute__((ext_vector_type(16)));
 
 constexpr int BK = 128;  // bytes (= elements) of contraction per pipeline stage
 
+#ifdef MP8_TRACE
+// Diagnostic build only: cycle stamps of block 0, [wave][stage][point].
+__device__ unsigned long long mp8_trace_buf[4][160][6];
+#define MP8_STAMP(pt) do { if (blockIdx.x == 0 && lane == 0 && t < 160) mp8_trace_buf[wave][t][pt] = __builtin_readcyclecounter(); } while (0)
+#else
+#define MP8_STAMP(pt) do { } while (0)
+#endif
+
 struct Epilogue {
     float alpha;
     float *acc;
@@ -272,25 +280,22 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
 
     // Fragments: lane l supplies row (l % 32) of a 32-row tile and, for sub-step s, the 32
     // bytes k = 64*s + 32*(l/32) .. +31 of the slab, i.e. chunks 4s + 2*(l/32) and the next.
+    // A fragment is fetched as two 16-byte LDS reads ("halves").  Fragment f of a sub-step is
+    // A tile f for f < MT and B tile f - MT otherwise.
     const int frow = lane & 31, fkb = lane >> 5;
     const int fsw = (frow >> 1) & 7;
     const int a_base = (wm * WTM + frow) * BK;
     const int b_base = A_BYTES + (wn * WTN + frow) * BK;
-    auto read_frags = [&](int kstage, int sub, i32x8 (&af)[MT], i32x8 (&bf)[NT]) {
+    constexpr int F = MT + NT;   // fragments per sub-step
+    constexpr int NM = MT * NT;  // MFMAs per sub-step
+    struct Frags {
+        i32x4 h[F][2];
+    };
+    auto read_half = [&](int kstage, int sub, int f, int half, Frags &fr) {
         const uint8_t *s = lds + (kstage % NSTAGE) * STAGE;
-        const int c0 = ((4 * sub + 2 * fkb) ^ fsw) * 16, c1 = ((4 * sub + 2 * fkb + 1) ^ fsw) * 16;
-#pragma unroll
-        for (int i = 0; i < MT; ++i) {
-            i32x4 lo = *reinterpret_cast<const i32x4 *>(s + a_base + i * 32 * BK + c0);
-            i32x4 hi = *reinterpret_cast<const i32x4 *>(s + a_base + i * 32 * BK + c1);
-            af[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        }
-#pragma unroll
-        for (int j = 0; j < NT; ++j) {
-            i32x4 lo = *reinterpret_cast<const i32x4 *>(s + b_base + j * 32 * BK + c0);
-            i32x4 hi = *reinterpret_cast<const i32x4 *>(s + b_base + j * 32 * BK + c1);
-            bf[j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        }
+        const int chunk = ((4 * sub + 2 * fkb + half) ^ fsw) * 16;
+        const int base = f < MT ? a_base + f * 32 * BK : b_base + (f - MT) * 32 * BK;
+        fr.h[f][half] = *reinterpret_cast<const i32x4 *>(s + base + chunk);
     };
 
     f32x16 acc[MT][NT];
@@ -301,16 +306,16 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-    // MFMAs [m0, m1) of a sub-step, numbered row-major over the wave's MT x NT tiles.
-    auto multiply = [&](const i32x8 (&af)[MT], const i32x8 (&bf)[NT], int m0, int m1) {
-#pragma unroll
-        for (int m = 0; m < MT * NT; ++m)
-            if (m >= m0 && m < m1)
-                // cbsz = blgp = 1 selects the (1,5,2) format for both operands; the scale
-                // operands are zero, i.e. the unscaled instruction.  b goes in as the "row"
-                // matrix so that a lane ends up with consecutive output columns.
-                acc[m / NT][m % NT] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                    bf[m % NT], af[m / NT], acc[m / NT][m % NT], 1, 1, 0, 0, 0, 0);
+    // MFMA m of a sub-step works on tile (m / NT, m % NT).
+    auto mfma = [&](const Frags &fr, int m) {
+        const int i = m / NT, j = m % NT;
+        const i32x8 av = __builtin_shufflevector(fr.h[i][0], fr.h[i][1], 0, 1, 2, 3, 4, 5, 6, 7);
+        const i32x8 bv =
+            __builtin_shufflevector(fr.h[MT + j][0], fr.h[MT + j][1], 0, 1, 2, 3, 4, 5, 6, 7);
+        // cbsz = blgp = 1 selects the (1,5,2) format for both operands; the scale operands are
+        // zero, i.e. the unscaled instruction.  b goes in as the "row" matrix so that a lane
+        // ends up with consecutive output columns.
+        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(bv, av, acc[i][j], 1, 1, 0, 0, 0, 0);
     };
     auto issue_one = [&](int kstage, int q) {  // load q (0 .. G-1) of a stage
         const uint32_t sa = lds0 + (kstage % NSTAGE) * STAGE + wave * 1024;
@@ -331,38 +336,80 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
         else wait_vm_lds<0>();
     };
 
-    // MFMAs of sub-step 0 that are issued after the barrier, interleaved with the loads (two
-    // loads per MFMA) so that the matrix pipe stays fed while the wave issues them.
-    constexpr int NM = MT * NT;
-    constexpr int NPOST = (G / 2 < NM / 2) ? G / 2 : NM / 2;
+    // The order in which the fragments of a sub-step are fetched: the order in which the
+    // MFMAs first need them (B0, A0, B1, ..., then the remaining A tiles).
+    auto frag_order = [&](int n) -> int {  // n-th fragment to fetch
+        if (n == 0) return MT;             // B0
+        if (n == 1) return 0;              // A0
+        if (n < NT + 1) return MT + n - 1; // B1 .. B(NT-1)
+        return n - NT;                     // A1 .. A(MT-1)
+    };
 
-    i32x8 af0[MT], bf0[NT], af1[MT], bf1[NT];
+    Frags f0, f1;
     // prologue: fill the ring, fetch the fragments of (0, 0)
 #pragma unroll
     for (int st = 0; st < NSTAGE; ++st)
         if (st < ks_count) issue_loads(st);
     wait_stage(-1);
     __syncthreads();
-    read_frags(0, 0, af0, bf0);
-    for (int t = 0; t < ks_count; ++t) {
-        read_frags(t, 1, af1, bf1);
-        multiply(af0, bf0, 0, NM - NPOST);
-        __builtin_amdgcn_sched_barrier(0);
-        wait_stage(t);
-        __syncthreads();
-        const bool more = t + NSTAGE < ks_count;
 #pragma unroll
-        for (int q = 0; q < G; ++q) {
-            if (more) issue_one(t + NSTAGE, q);
-            if ((q & 1) && (q >> 1) < NPOST) {
-                multiply(af0, bf0, NM - NPOST + (q >> 1), NM - NPOST + (q >> 1) + 1);
-                __builtin_amdgcn_sched_barrier(0);
+    for (int n = 0; n < 2 * F; ++n) read_half(0, 0, frag_order(n / 2), n & 1, f0);
+
+    // One stage = 2*NM "slots", one MFMA each, fenced so that the order below is the issue
+    // order.  Everything else a stage needs is spread over the slots so that it issues in the
+    // shadow of the running MFMA (one LDS read costs about a third, one direct load about
+    // two thirds of an MFMA's 64 cycles of issue time):
+    //   slots 0 .. NM/2-3      the 2F half-fragment reads of sub-step 1 (set f1), early enough
+    //                          to have returned when the barrier is reached
+    //   end of slot NM/2-1     wait + barrier: stage t+1 has landed everywhere, and nobody
+    //                          reads the buffer of stage t any more
+    //   slots NM/2 ...         the G direct loads of stage t+NSTAGE, one per slot
+    //   slots NM .. 2NM-1      the 2F half-fragment reads of (t+1, sub-step 0) (set f0),
+    //                          one per slot from the first slot after set f0's last use
+    constexpr int S_BAR = NM / 2 > 0 ? NM / 2 : 1;            // slots before the barrier
+    constexpr int S_RD = S_BAR > 2 ? S_BAR - 2 : 1;           // early slots that carry reads
+    constexpr int R0 = (2 * F + S_RD - 1) / S_RD;             // half reads per early slot
+    constexpr int R1 = (2 * F + NM - 1) / NM;                 // half reads per late slot
+    constexpr int D1 = (G + (2 * NM - S_BAR) - 1) / (2 * NM - S_BAR);  // loads per slot
+    for (int t = 0; t < ks_count; ++t) {
+        MP8_STAMP(0);
+        const bool more = t + NSTAGE < ks_count;
+        const bool next = t + 1 < ks_count;
+#pragma unroll
+        for (int k = 0; k < 2 * NM; ++k) {
+            if (k < NM) mfma(f0, k); else mfma(f1, k - NM);
+            if (k < S_RD) {
+#pragma unroll
+                for (int r = 0; r < R0; ++r) {
+                    const int n = k * R0 + r;
+                    if (n < 2 * F) read_half(t, 1, frag_order(n / 2), n & 1, f1);
+                }
             }
+            if (k == S_BAR - 1) {
+                __builtin_amdgcn_sched_barrier(0);
+                MP8_STAMP(1);
+                wait_stage(t);
+                MP8_STAMP(2);
+                __syncthreads();
+                MP8_STAMP(3);
+            }
+            if (k >= S_BAR) {
+#pragma unroll
+                for (int r = 0; r < D1; ++r) {
+                    const int q = (k - S_BAR) * D1 + r;
+                    if (q < G && more) issue_one(t + NSTAGE, q);
+                }
+            }
+            if (k >= NM) {
+#pragma unroll
+                for (int r = 0; r < R1; ++r) {
+                    const int n = (k - NM) * R1 + r;
+                    if (n < 2 * F && next) read_half(t + 1, 0, frag_order(n / 2), n & 1, f0);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
-        if (G / 2 < NPOST) multiply(af0, bf0, NM - NPOST + G / 2, NM);
-        __builtin_amdgcn_sched_barrier(0);
-        if (t + 1 < ks_count) read_frags(t + 1, 0, af0, bf0);
-        multiply(af1, bf1, 0, NM);
+        MP8_STAMP(5);
     }
     wait_vm_lds<0>();
 
@@ -701,3 +748,9 @@ extern "C" mp8_status mp8_gemm_fp8(mp8_op op, int64_t M, int64_t N, int64_t K, c
                               round, flags, seed, offset, stats, workspace, workspace_bytes,
                               stream, 0, 0);
 }
+
+#ifdef MP8_TRACE
+extern "C" int mp8_debug_read_trace(unsigned long long *host, size_t bytes) {
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(mp8::mp8_trace_buf), bytes);
+}
+#endif
