@@ -89,8 +89,11 @@ mp8_status mp8_quantize_e5m2(const void *src, int src_is_f16, uint8_t *dst, uint
  *              rounding of the updated acc (accumulation across calls, e.g. timesteps)
  *   out8       nullable [rows, cols] 8-bit result; out8_t nullable [cols, rows] transposed
  *   round      rounding of the epilogue; SR uses index r*cols + c
- *   workspace  device scratch of at least mp8_gemm_fp8_workspace_bytes(op, M, N, K) bytes
- *              (may be NULL when that is 0); 16-byte aligned; contents undefined afterwards
+ *   workspace  device scratch, 16-byte aligned, contents undefined afterwards.  It is needed
+ *              when the contraction is split (few output tiles, long contraction), for
+ *              acc_mode 2, for out8_t, and when cols is not a multiple of 16;
+ *              mp8_gemm_fp8_workspace_bytes(op, M, N, K) is enough in every case.  A call
+ *              that does not need it accepts NULL.
  * Any contraction length >= 1 and any rows/cols >= 1 are accepted (ragged shapes run on a
  * slower kernel); a zero dimension is valid and does nothing.  Partial sums of a split
  * contraction are combined in FP32, in a fixed order, before the single rounding, so results
@@ -102,7 +105,8 @@ mp8_status mp8_gemm_fp8(mp8_op op, int64_t M, int64_t N, int64_t K, const uint8_
                         int flags, uint64_t seed, uint64_t offset, mp8_stats *stats,
                         void *workspace, size_t workspace_bytes, void *stream);
 
-/* Upper bound of the scratch mp8_gemm_fp8 needs for this shape (0 if none). */
+/* Upper bound of the scratch mp8_gemm_fp8 can need for this shape, whatever the options
+ * (0 for shapes that take the generic kernel). */
 size_t mp8_gemm_fp8_workspace_bytes(mp8_op op, int64_t M, int64_t N, int64_t K);
 
 /*

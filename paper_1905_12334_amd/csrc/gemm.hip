@@ -34,10 +34,12 @@ constexpr int BK = 128;  // bytes (= elements) of contraction per pipeline stage
 
 #ifdef MP8_TRACE
 // Diagnostic build only: cycle stamps of block 0, [wave][stage][point].
-__device__ unsigned long long mp8_trace_buf[4][160][6];
-#define MP8_STAMP(pt) do { if (blockIdx.x == 0 && lane == 0 && t < 160) mp8_trace_buf[wave][t][pt] = __builtin_readcyclecounter(); } while (0)
+__device__ unsigned long long mp8_trace_buf[4][160][8];
+#define MP8_STAMP(pt) do { if (blockIdx.x == 0 && lane == 0 && t < 159) mp8_trace_buf[wave][t][pt] = __builtin_readcyclecounter(); } while (0)
+#define MP8_STAMP_PHASE(pt) do { if (blockIdx.x == 0 && (threadIdx.x & 63) == 0) mp8_trace_buf[threadIdx.x >> 6][159][pt] = __builtin_readcyclecounter(); } while (0)
 #else
 #define MP8_STAMP(pt) do { } while (0)
+#define MP8_STAMP_PHASE(pt) do { } while (0)
 #endif
 
 struct Epilogue {
@@ -66,9 +68,9 @@ struct GemmArgs {
 };
 
 // One output element, any shape: optional FP32 accumulate / store, one rounding to 8 bits,
-// optional transposed copy, statistics.  Kept out of line: it only serves ragged shapes.
-__device__ __noinline__ void finish1(const Epilogue &ep, int64_t r, int64_t c, float v,
-                                     StatsAcc &st) {
+// optional transposed copy, statistics.  Only the finishing kernels use it (ragged shapes).
+__device__ __forceinline__ void finish1(const Epilogue &ep, int64_t r, int64_t c, float v,
+                                        StatsAcc &st) {
     const int64_t i = r * ep.cols + c;
     if (ep.acc_mode != 0) {
         if (ep.acc_mode == 2) v += ep.acc[i];
@@ -89,18 +91,13 @@ __device__ __noinline__ void finish1(const Epilogue &ep, int64_t r, int64_t c, f
     if (ep.out8_t != nullptr) ep.out8_t[c * ep.rows + r] = (uint8_t)code;
 }
 
-// Finish sixteen consecutive columns c .. c+15 (c % 16 == 0, c < cols) of output row r.
-// When the row length is a multiple of 16 everything is done with 16-byte accesses and two
-// Philox blocks; otherwise element by element.
-template <bool kSR>
+// Finish sixteen consecutive columns c .. c+15 (c % 16 == 0) of output row r of an output
+// whose row length is a multiple of 16: 16-byte accesses, two Philox blocks, hardware
+// conversions.  Written to stay small: the rounding mode is a run-time flag and the rare
+// conversions are out of line.
 __device__ __forceinline__ void finish16(const Epilogue &ep, int64_t r, int64_t c, float v[16],
                                          StatsAcc &st) {
-    const int64_t cols = ep.cols;
-    if ((cols & 15) != 0) {
-        for (int j = 0; j < 16 && c + j < cols; ++j) finish1(ep, r, c + j, v[j], st);
-        return;
-    }
-    const int64_t i0 = r * cols + c;
+    const int64_t i0 = r * ep.cols + c;
     if (ep.acc_mode != 0) {
         f32x4 *p = reinterpret_cast<f32x4 *>(ep.acc + i0);
 #pragma unroll
@@ -115,7 +112,7 @@ __device__ __forceinline__ void finish16(const Epilogue &ep, int64_t r, int64_t 
     }
     if (ep.out8 == nullptr && ep.out8_t == nullptr && ep.stats == nullptr) return;
     uint32_t rw[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    if constexpr (kSR) {
+    if (ep.sr) {
         const Philox rng(ep.seed, ep.offset);
         uint4 w0 = rng.block((uint64_t)i0 >> 3), w1 = rng.block(((uint64_t)i0 >> 3) + 1);
         rw[0] = w0.x; rw[1] = w0.y; rw[2] = w0.z; rw[3] = w0.w;
@@ -126,7 +123,7 @@ __device__ __forceinline__ void finish16(const Epilogue &ep, int64_t r, int64_t 
     for (int q = 0; q < 4; ++q) {
         float y[4] = {v[4 * q] * ep.alpha, v[4 * q + 1] * ep.alpha, v[4 * q + 2] * ep.alpha,
                       v[4 * q + 3] * ep.alpha};
-        pk[q] = e5m2_pack4<kSR>(y, rw[2 * q], rw[2 * q + 1], ep.sat != 0);
+        pk[q] = e5m2_pack4_rt(y, rw[2 * q], rw[2 * q + 1], ep.sr != 0, ep.sat != 0);
         if (ep.stats != nullptr) st.add4(y, pk[q]);
     }
     if (ep.out8 != nullptr) {
@@ -134,9 +131,15 @@ __device__ __forceinline__ void finish16(const Epilogue &ep, int64_t r, int64_t 
         *reinterpret_cast<u32x4 *>(ep.out8 + i0) = o;
     }
     if (ep.out8_t != nullptr) {
-#pragma unroll
-        for (int j = 0; j < 16; ++j)
-            ep.out8_t[(c + j) * ep.rows + r] = (uint8_t)(pk[j >> 2] >> (8 * (j & 3)));
+        uint8_t *t = ep.out8_t + c * ep.rows + r;
+#pragma nounroll
+        for (int q = 0; q < 4; ++q) {
+            const uint32_t w = q == 0 ? pk[0] : q == 1 ? pk[1] : q == 2 ? pk[2] : pk[3];
+            t[(4 * q + 0) * ep.rows] = (uint8_t)w;
+            t[(4 * q + 1) * ep.rows] = (uint8_t)(w >> 8);
+            t[(4 * q + 2) * ep.rows] = (uint8_t)(w >> 16);
+            t[(4 * q + 3) * ep.rows] = (uint8_t)(w >> 24);
+        }
     }
 }
 
@@ -215,7 +218,15 @@ __device__ __forceinline__ uint32_t lds_address(const void *p) {
 // the same chunk, and with this swizzle the sixteen pieces fall into sixteen different
 // 16-byte bank groups.  Direct-to-LDS writes are lane-contiguous, so the swizzle is applied
 // to the global address each lane fetches.
-template <int BM, int BN, int WGM, int WGN, int NSTAGE, int MINBLOCKS>
+// EPI selects what happens to the finished FP32 tile (one kernel per variant keeps each
+// kernel's code, and with it the cold instruction-cache cost of every launch, small):
+//   EPI_PARTIAL  FP32 tile to the workspace (split contraction, or options the fused
+//                epilogue does not carry); the finishing kernel does the rest
+//   EPI_RNE      out8 = Q_RNE(alpha * acc), nothing else
+//   EPI_FULL     out8 with run-time rounding mode, saturation and statistics
+enum { EPI_PARTIAL = 0, EPI_RNE = 1, EPI_FULL = 2 };
+
+template <int BM, int BN, int WGM, int WGN, int NSTAGE, int MINBLOCKS, int EPI>
 __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArgs p) {
     static_assert(WGM * WGN == 4, "four waves");
     static_assert(NSTAGE >= 2, "ring depth");
@@ -230,6 +241,7 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     constexpr int LDS_BYTES = NSTAGE * STAGE > EP_BYTES ? NSTAGE * STAGE : EP_BYTES;
     __shared__ __attribute__((aligned(1024))) uint8_t lds[LDS_BYTES];
 
+    MP8_STAMP_PHASE(0);
     int split, tm, tn;
     map_block(p.tiles_m, p.tiles_n, split, tm, tn);
     split = __builtin_amdgcn_readfirstlane(split);
@@ -346,6 +358,7 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     };
 
     Frags f0, f1;
+    MP8_STAMP_PHASE(1);
     // prologue: fill the ring, fetch the fragments of (0, 0)
 #pragma unroll
     for (int st = 0; st < NSTAGE; ++st)
@@ -354,6 +367,7 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     __syncthreads();
 #pragma unroll
     for (int n = 0; n < 2 * F; ++n) read_half(0, 0, frag_order(n / 2), n & 1, f0);
+    MP8_STAMP_PHASE(2);
 
     // One stage = 2*NM "slots", one MFMA each, fenced so that the order below is the issue
     // order.  Everything else a stage needs is spread over the slots so that it issues in the
@@ -412,6 +426,7 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
         MP8_STAMP(5);
     }
     wait_vm_lds<0>();
+    MP8_STAMP_PHASE(3);
 
     // Epilogue.  acc[i][j][4g + e] is output row  wm*WTM + 32i + lane%32  and column
     // wn*WTN + 32j + 8g + 4*(lane/32) + e.  Each wave passes its tile through LDS one band
@@ -425,7 +440,6 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     __syncthreads();                               // all waves are done with the operand ring
     float *band = reinterpret_cast<float *>(lds) + wave * BANDS * 32 * EP_LD;
     StatsAcc st;
-    const bool partial = p.splits > 1;
     const bool fast_cols = (p.cols & 15) == 0;
 #pragma unroll
     for (int h = 0; h < MT; h += BANDS) {
@@ -444,6 +458,8 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        MP8_STAMP_PHASE(5);
+#pragma nounroll
         for (int item = lane; item < BANDS * 32 * CG; item += 64) {
             const int br = item / CG, cg = item - br * CG;
             const int64_t r = row0 + wm * WTM + 32 * h + br;
@@ -456,7 +472,7 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
                     f32x4 x = src[q];
                     v[4 * q] = x.x; v[4 * q + 1] = x.y; v[4 * q + 2] = x.z; v[4 * q + 3] = x.w;
                 }
-                if (partial) {
+                if constexpr (EPI == EPI_PARTIAL) {
                     float *dst = p.partial + ((int64_t)split * p.rows + r) * p.cols + c;
                     if (fast_cols) {
 #pragma unroll
@@ -465,20 +481,39 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
                             reinterpret_cast<f32x4 *>(dst)[q] = o;
                         }
                     } else {
-                        for (int e = 0; e < 16 && c + e < p.cols; ++e) dst[e] = v[e];
+#pragma nounroll
+                        for (int e = 0; e < 16; ++e) {
+                            float x = v[0];
+#pragma unroll
+                            for (int k = 1; k < 16; ++k) x = (e == k) ? v[k] : x;
+                            if (c + e < p.cols) dst[e] = x;
+                        }
                     }
-                } else if (p.ep.sr) {
-                    finish16<true>(p.ep, r, c, v, st);
+                } else if constexpr (EPI == EPI_RNE) {
+                    // the host sends only row lengths that are multiples of 16 here
+                    uint32_t pk[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        float y[4] = {v[4 * q] * p.ep.alpha, v[4 * q + 1] * p.ep.alpha,
+                                      v[4 * q + 2] * p.ep.alpha, v[4 * q + 3] * p.ep.alpha};
+                        pk[q] = e5m2_pack4<false>(y, 0u, 0u, false);
+                    }
+                    u32x4 o = {pk[0], pk[1], pk[2], pk[3]};
+                    *reinterpret_cast<u32x4 *>(p.ep.out8 + r * p.cols + c) = o;
                 } else {
-                    finish16<false>(p.ep, r, c, v, st);
+                    finish16(p.ep, r, c, v, st);
                 }
             }
         }
+        MP8_STAMP_PHASE(6);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
-    if (!partial && p.ep.stats != nullptr) st.flush(p.ep.stats);
+    if constexpr (EPI == EPI_FULL) {
+        if (p.ep.stats != nullptr) st.flush(p.ep.stats);
+    }
+    MP8_STAMP_PHASE(4);
 }
 
 // Sum the slices in order and finish.  One thread per group of sixteen columns.
@@ -506,8 +541,17 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const float *__restr
                 for (int e = 0; e < 16 && c + e < ep.cols; ++e) v[e] += src[e];
             }
         }
-        if (ep.sr) finish16<true>(ep, r, c, v, st);
-        else finish16<false>(ep, r, c, v, st);
+        if (fast_cols) {
+            finish16(ep, r, c, v, st);
+        } else {
+#pragma nounroll
+            for (int e = 0; e < 16; ++e) {
+                float x = v[0];  // select without indexing the register array dynamically
+#pragma unroll
+                for (int k = 1; k < 16; ++k) x = (e == k) ? v[k] : x;
+                if (c + e < ep.cols) finish1(ep, r, c + e, x, st);
+            }
+        }
     }
     if (ep.stats != nullptr) st.flush(ep.stats);
 }
@@ -540,19 +584,20 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const uint8_t *__rest
 struct TileConfig {
     int bm, bn;
     const char *name;
-    void (*kernel)(const GemmArgs);
+    void (*kernel[3])(const GemmArgs);  // indexed by EPI_*
 };
 
+#define MP8_TILE(BM, BN, WGM, WGN, NS, MB)                                   \
+    {BM, BN, #BM "x" #BN "x128s" #NS,                                         \
+     {gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_PARTIAL>,                \
+      gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_RNE>,                    \
+      gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_FULL>}}
 static const TileConfig kTiles[] = {
-    {256, 256, "256x256x128s2", gemm_mfma_kernel<256, 256, 2, 2, 2, 1>},
-    {256, 128, "256x128x128s3", gemm_mfma_kernel<256, 128, 2, 2, 3, 1>},
-    {128, 256, "128x256x128s3", gemm_mfma_kernel<128, 256, 2, 2, 3, 1>},
-    {128, 128, "128x128x128s2", gemm_mfma_kernel<128, 128, 2, 2, 2, 2>},
-    {128, 128, "128x128x128s4", gemm_mfma_kernel<128, 128, 2, 2, 4, 1>},
-    {64, 128, "64x128x128s3", gemm_mfma_kernel<64, 128, 1, 4, 3, 2>},
-    {128, 64, "128x64x128s3", gemm_mfma_kernel<128, 64, 4, 1, 3, 2>},
-    {64, 64, "64x64x128s4", gemm_mfma_kernel<64, 64, 2, 2, 4, 2>},
+    MP8_TILE(256, 256, 2, 2, 2, 1), MP8_TILE(256, 128, 2, 2, 3, 1), MP8_TILE(128, 256, 2, 2, 3, 1),
+    MP8_TILE(128, 128, 2, 2, 2, 2), MP8_TILE(128, 128, 2, 2, 4, 1), MP8_TILE(64, 128, 1, 4, 3, 2),
+    MP8_TILE(128, 64, 4, 1, 3, 2),  MP8_TILE(64, 64, 2, 2, 4, 2),
 };
+#undef MP8_TILE
 constexpr int kNumTiles = (int)(sizeof(kTiles) / sizeof(kTiles[0]));
 constexpr int kCUs = 256;
 constexpr int kMaxSplits = 64;
@@ -622,8 +667,12 @@ static Plan make_plan(int64_t rows, int64_t cols, int64_t kc, int tile_config, i
     return pl;
 }
 
+// Upper bound of the workspace: one FP32 tile set per contraction slice.  (The MFMA kernel
+// finishes its tiles itself only for an unsplit contraction, a row length that is a multiple
+// of 16 and no FP32 / transposed output; otherwise it writes FP32 tiles and the finishing
+// kernel takes over.)
 static size_t plan_workspace(const Plan &pl, int64_t rows, int64_t cols) {
-    if (!pl.mfma || pl.splits <= 1) return 0;
+    if (!pl.mfma) return 0;
     return (size_t)pl.splits * (size_t)rows * (size_t)cols * sizeof(float);
 }
 
@@ -709,8 +758,21 @@ extern "C" mp8_status mp8_gemm_fp8_tuned(mp8_op op, int64_t M, int64_t N, int64_
         return hipGetLastError() == hipSuccess ? MP8_OK : MP8_ERR_HIP;
     }
 
-    const size_t need = plan_workspace(pl, rows, cols);
-    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return MP8_ERR_WORKSPACE;
+    // Fused epilogue or two passes?
+    const bool two_pass = pl.splits > 1 || (cols & 15) != 0 || acc_mode != 0 || out8_t != nullptr;
+    float *partial = nullptr;
+    Epilogue fin = ep;  // what the finishing kernel applies
+    if (two_pass) {
+        if (pl.splits == 1 && acc_mode == 1) {
+            partial = acc;  // the tile goes straight into acc; the finishing kernel reads it there
+            fin.acc = nullptr;
+            fin.acc_mode = 0;
+        } else {
+            const size_t need = plan_workspace(pl, rows, cols);
+            if (workspace == nullptr || workspace_bytes < need) return MP8_ERR_WORKSPACE;
+            partial = (float *)workspace;
+        }
+    }
     const int64_t nblocks = (int64_t)pl.tiles_m * pl.tiles_n * pl.splits;
     if (nblocks > 0x7FFFFFFFLL) return MP8_ERR_UNSUPPORTED;
 
@@ -725,15 +787,22 @@ extern "C" mp8_status mp8_gemm_fp8_tuned(mp8_op op, int64_t M, int64_t N, int64_
     ga.splits = pl.splits;
     ga.tiles_m = pl.tiles_m;
     ga.tiles_n = pl.tiles_n;
-    ga.partial = pl.splits > 1 ? (float *)workspace : nullptr;
+    ga.partial = partial;
     ga.ep = ep;
-    hipLaunchKernelGGL(kTiles[pl.tile].kernel, dim3((unsigned)nblocks), dim3(256), 0, s, ga);
+    const int epi = two_pass ? EPI_PARTIAL
+                             : (ep.sr || ep.sat || ep.stats != nullptr || out8 == nullptr) ? EPI_FULL
+                                                                                            : EPI_RNE;
+    hipLaunchKernelGGL(kTiles[pl.tile].kernel[epi], dim3((unsigned)nblocks), dim3(256), 0, s, ga);
     if (hipGetLastError() != hipSuccess) return MP8_ERR_HIP;
-    if (pl.splits > 1) {
-        int64_t blocks = std::min<int64_t>((rows * cgroups + 255) / 256, 256 * 8);
-        hipLaunchKernelGGL(splitk_finish_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
-                           (const float *)workspace, pl.splits, ep);
-        if (hipGetLastError() != hipSuccess) return MP8_ERR_HIP;
+    if (two_pass) {
+        const bool only_acc = fin.acc_mode == 0 && fin.out8 == nullptr && fin.out8_t == nullptr &&
+                              fin.stats == nullptr;
+        if (!only_acc) {
+            int64_t blocks = std::min<int64_t>((rows * cgroups + 255) / 256, 256 * 8);
+            hipLaunchKernelGGL(splitk_finish_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
+                               (const float *)partial, pl.splits, fin);
+            if (hipGetLastError() != hipSuccess) return MP8_ERR_HIP;
+        }
     }
     return MP8_OK;
 }

@@ -115,20 +115,48 @@ __device__ __forceinline__ bool any_nan4(const float y[4]) {
     return __builtin_isunordered(y[0], y[1]) | __builtin_isunordered(y[2], y[3]);
 }
 
+// Bit-level conversion of four values (NaN inputs and the saturating mode).  Out of line on
+// purpose: it is rare, and keeping it out of the callers keeps their hot code small.
+static __device__ __noinline__ uint32_t e5m2_pack4_slow(float y0, float y1, float y2, float y3,
+                                                        uint32_t r01, uint32_t r23, bool sr,
+                                                        bool sat) {
+    const float y[4] = {y0, y1, y2, y3};
+    const uint32_t r[4] = {r01 & 0xFFFFu, r01 >> 16, r23 & 0xFFFFu, r23 >> 16};
+    uint32_t w = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t c = sr ? e5m2_from_f32_bits<true>(f2u(y[j]), r[j], sat)
+                              : e5m2_from_f32_bits<false>(f2u(y[j]), 0u, sat);
+        w |= c << (8 * j);
+    }
+    return w;
+}
+
 // Four values -> four codes packed little-endian.  r01 / r23 hold the 16 random bits of
 // elements (0: low half, 1: high half) and (2, 3); ignored for RNE.
 template <bool kSR>
 __device__ __forceinline__ uint32_t e5m2_pack4(const float y[4], uint32_t r01, uint32_t r23,
                                                bool sat) {
-    if (sat || any_nan4(y)) {
-        const uint32_t r[4] = {r01 & 0xFFFFu, r01 >> 16, r23 & 0xFFFFu, r23 >> 16};
-        uint32_t w = 0;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) w |= e5m2_from_f32_bits<kSR>(f2u(y[j]), r[j], sat) << (8 * j);
-        return w;
-    }
+    if (sat || any_nan4(y)) return e5m2_pack4_slow(y[0], y[1], y[2], y[3], r01, r23, kSR, sat);
     int w = 0;
     if constexpr (kSR) {
+        w = __builtin_amdgcn_cvt_sr_bf8_f32(y[0], (int)(r01 << 16), w, 0);
+        w = __builtin_amdgcn_cvt_sr_bf8_f32(y[1], (int)(r01 & 0xFFFF0000u), w, 1);
+        w = __builtin_amdgcn_cvt_sr_bf8_f32(y[2], (int)(r23 << 16), w, 2);
+        w = __builtin_amdgcn_cvt_sr_bf8_f32(y[3], (int)(r23 & 0xFFFF0000u), w, 3);
+    } else {
+        w = __builtin_amdgcn_cvt_pk_bf8_f32(y[0], y[1], w, false);
+        w = __builtin_amdgcn_cvt_pk_bf8_f32(y[2], y[3], w, true);
+    }
+    return (uint32_t)w;
+}
+
+// The same with the rounding mode chosen at run time.
+__device__ __forceinline__ uint32_t e5m2_pack4_rt(const float y[4], uint32_t r01, uint32_t r23,
+                                                  bool sr, bool sat) {
+    if (sat || any_nan4(y)) return e5m2_pack4_slow(y[0], y[1], y[2], y[3], r01, r23, sr, sat);
+    int w = 0;
+    if (sr) {
         w = __builtin_amdgcn_cvt_sr_bf8_f32(y[0], (int)(r01 << 16), w, 0);
         w = __builtin_amdgcn_cvt_sr_bf8_f32(y[1], (int)(r01 & 0xFFFF0000u), w, 1);
         w = __builtin_amdgcn_cvt_sr_bf8_f32(y[2], (int)(r23 << 16), w, 2);

@@ -43,8 +43,23 @@ def run_gemm(mp8, a8, b8, op=None, dims=None, want_t=False, acc_in=None, acc_mod
     torch.cuda.synchronize()
     assert bool((obuf[rows * cols:] == 0xAA).all()), "write past the end of out8"
     assert bool((acc[rows * cols:] == 7.0).all()), "write past the end of acc"
-    return (host(acc[: rows * cols]).reshape(rows, cols), host(out8).reshape(rows, cols),
-            host(out8_t).reshape(cols, rows) if want_t else None, mp8.read_stats(stats))
+    res = (host(acc[: rows * cols]).reshape(rows, cols), host(out8).reshape(rows, cols),
+           host(out8_t).reshape(cols, rows) if want_t else None, mp8.read_stats(stats))
+    if acc_mode == 1:
+        # the same call without FP32 / transposed outputs takes the fused epilogue (when the
+        # contraction is not split): its codes and statistics must be identical; once with
+        # statistics, once without (two different kernels)
+        for with_stats in (True, False):
+            o2 = torch.full((rows * cols + 64,), 0xAA, dtype=torch.uint8, device="cuda")
+            st2 = mp8.new_stats() if with_stats else None
+            mp8.gemm_fp8(op, M, N, K, a, b, out8=o2[: rows * cols], stats=st2, workspace=ws,
+                         tile_config=tile, split_k=split, **kw)
+            torch.cuda.synchronize()
+            assert bool((o2[rows * cols:] == 0xAA).all()), "fused: write past the end of out8"
+            assert np.array_equal(host(o2[: rows * cols]).reshape(rows, cols), res[1]), "fused out8 differs"
+            if with_stats:
+                assert mp8.read_stats(st2) == res[3], "fused statistics differ"
+    return res
 
 
 def exact_sum_codes(rng, shape):
