@@ -516,41 +516,78 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     MP8_STAMP_PHASE(4);
 }
 
-// Sum the slices in order and finish.  One thread per group of sixteen columns.
+// Finish four consecutive columns c .. c+3 (c % 4 == 0, row length a multiple of 4).
+__device__ __forceinline__ void finish4(const Epilogue &ep, int64_t r, int64_t c, float v[4],
+                                        StatsAcc &st) {
+    const int64_t i0 = r * ep.cols + c;
+    if (ep.acc_mode != 0) {
+        f32x4 *p = reinterpret_cast<f32x4 *>(ep.acc + i0);
+        if (ep.acc_mode == 2) {
+            f32x4 o = *p;
+            v[0] += o.x; v[1] += o.y; v[2] += o.z; v[3] += o.w;
+        }
+        f32x4 n = {v[0], v[1], v[2], v[3]};
+        *p = n;
+    }
+    if (ep.out8 == nullptr && ep.out8_t == nullptr && ep.stats == nullptr) return;
+    uint32_t r01 = 0, r23 = 0;
+    if (ep.sr) {
+        // elements i0..i0+3 are halfwords (i0 % 8) .. +3 of Philox block i0 / 8
+        const Philox rng(ep.seed, ep.offset);
+        uint4 w = rng.block((uint64_t)i0 >> 3);
+        r01 = (i0 & 4) ? w.z : w.x;
+        r23 = (i0 & 4) ? w.w : w.y;
+    }
+    float y[4] = {v[0] * ep.alpha, v[1] * ep.alpha, v[2] * ep.alpha, v[3] * ep.alpha};
+    const uint32_t pk = e5m2_pack4_rt(y, r01, r23, ep.sr != 0, ep.sat != 0);
+    if (ep.stats != nullptr) st.add4(y, pk);
+    if (ep.out8 != nullptr) *reinterpret_cast<uint32_t *>(ep.out8 + i0) = pk;
+    if (ep.out8_t != nullptr) {
+        uint8_t *t = ep.out8_t + c * ep.rows + r;
+        t[0] = (uint8_t)pk;
+        t[ep.rows] = (uint8_t)(pk >> 8);
+        t[2 * ep.rows] = (uint8_t)(pk >> 16);
+        t[3 * ep.rows] = (uint8_t)(pk >> 24);
+    }
+}
+
+// Sum the FP32 tiles of the contraction slices in slice order and finish: the complete sum is
+// rounded once.  One thread per four columns (per element when the row length is not a
+// multiple of four).
 __global__ __launch_bounds__(256) void splitk_finish_kernel(const float *__restrict__ partial,
                                                             int splits, const Epilogue ep) {
-    const int64_t cgroups = (ep.cols + 15) >> 4;
-    const int64_t total = ep.rows * cgroups;
     StatsAcc st;
-    const bool fast_cols = (ep.cols & 15) == 0;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += stride) {
-        const int64_t r = t / cgroups, c = (t - r * cgroups) << 4;
-        float v[16];
-#pragma unroll
-        for (int e = 0; e < 16; ++e) v[e] = 0.f;
-        for (int s = 0; s < splits; ++s) {
-            const float *src = partial + ((int64_t)s * ep.rows + r) * ep.cols + c;
-            if (fast_cols) {
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    f32x4 x = reinterpret_cast<const f32x4 *>(src)[q];
-                    v[4 * q] += x.x; v[4 * q + 1] += x.y; v[4 * q + 2] += x.z; v[4 * q + 3] += x.w;
-                }
-            } else {
-                for (int e = 0; e < 16 && c + e < ep.cols; ++e) v[e] += src[e];
+    const int64_t slice = ep.rows * ep.cols;
+    if ((ep.cols & 3) == 0) {
+        const int64_t total = slice >> 2;
+        for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += stride) {
+            const int64_t i0 = t << 2;
+            const int64_t r = i0 / ep.cols, c = i0 - r * ep.cols;
+            float v[4] = {0.f, 0.f, 0.f, 0.f};
+            int s = 0;
+            for (; s + 4 <= splits; s += 4) {  // four loads in flight, added in slice order
+                f32x4 x0 = *reinterpret_cast<const f32x4 *>(partial + (int64_t)s * slice + i0);
+                f32x4 x1 = *reinterpret_cast<const f32x4 *>(partial + (int64_t)(s + 1) * slice + i0);
+                f32x4 x2 = *reinterpret_cast<const f32x4 *>(partial + (int64_t)(s + 2) * slice + i0);
+                f32x4 x3 = *reinterpret_cast<const f32x4 *>(partial + (int64_t)(s + 3) * slice + i0);
+                v[0] += x0.x; v[1] += x0.y; v[2] += x0.z; v[3] += x0.w;
+                v[0] += x1.x; v[1] += x1.y; v[2] += x1.z; v[3] += x1.w;
+                v[0] += x2.x; v[1] += x2.y; v[2] += x2.z; v[3] += x2.w;
+                v[0] += x3.x; v[1] += x3.y; v[2] += x3.z; v[3] += x3.w;
             }
+            for (; s < splits; ++s) {
+                f32x4 x = *reinterpret_cast<const f32x4 *>(partial + (int64_t)s * slice + i0);
+                v[0] += x.x; v[1] += x.y; v[2] += x.z; v[3] += x.w;
+            }
+            finish4(ep, r, c, v, st);
         }
-        if (fast_cols) {
-            finish16(ep, r, c, v, st);
-        } else {
-#pragma nounroll
-            for (int e = 0; e < 16; ++e) {
-                float x = v[0];  // select without indexing the register array dynamically
-#pragma unroll
-                for (int k = 1; k < 16; ++k) x = (e == k) ? v[k] : x;
-                if (c + e < ep.cols) finish1(ep, r, c + e, x, st);
-            }
+    } else {
+        for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < slice; i += stride) {
+            float v = 0.f;
+            for (int s = 0; s < splits; ++s) v += partial[(int64_t)s * slice + i];
+            const int64_t r = i / ep.cols;
+            finish1(ep, r, i - r * ep.cols, v, st);
         }
     }
     if (ep.stats != nullptr) st.flush(ep.stats);
@@ -595,7 +632,8 @@ struct TileConfig {
 static const TileConfig kTiles[] = {
     MP8_TILE(256, 256, 2, 2, 2, 1), MP8_TILE(256, 128, 2, 2, 3, 1), MP8_TILE(128, 256, 2, 2, 3, 1),
     MP8_TILE(128, 128, 2, 2, 2, 2), MP8_TILE(128, 128, 2, 2, 4, 1), MP8_TILE(64, 128, 1, 4, 3, 2),
-    MP8_TILE(128, 64, 4, 1, 3, 2),  MP8_TILE(64, 64, 2, 2, 4, 2),
+    MP8_TILE(128, 64, 4, 1, 3, 2),  MP8_TILE(64, 64, 2, 2, 4, 2),   MP8_TILE(64, 128, 1, 4, 2, 3),
+    MP8_TILE(128, 64, 4, 1, 2, 3),  MP8_TILE(64, 64, 2, 2, 2, 4),
 };
 #undef MP8_TILE
 constexpr int kNumTiles = (int)(sizeof(kTiles) / sizeof(kTiles[0]));
@@ -618,37 +656,33 @@ static void op_dims(mp8_op op, int64_t M, int64_t N, int64_t K, int64_t &rows, i
     }
 }
 
-// Choose tile shape and number of contraction slices.  Aim: at least one full wave of
-// workgroups over the 256 CUs, preferring large tiles (fewer LDS bytes per flop), and slices
-// of at least four main-loop steps.
+// Choose tile shape and number of contraction slices.  Measured on MI355X: the 256x256 tile
+// is the only one that approaches the matrix-core peak (fewest LDS and L2 bytes per flop) but
+// needs enough tiles to fill whole rounds of 256 CUs; 128x128 serves mid-sized outputs (two
+// resident blocks per CU when the contraction is short, a deeper ring when it is long); small
+// outputs take 64x64 tiles and, if even those are too few, a split contraction -- kept to a
+// minimum because the second pass costs several microseconds.
+enum { T256x256 = 0, T128x128s2 = 3, T128x128s4 = 4, T64x64s2 = 10 };
 static Plan make_plan(int64_t rows, int64_t cols, int64_t kc, int tile_config, int split_k) {
     Plan pl{};
-    pl.mfma = (kc % BK) == 0;
+    pl.mfma = (kc % BK) == 0 && kc > 0;
     if (!pl.mfma) {
         pl.splits = 1;
         return pl;
     }
     const int ksteps = (int)(kc / BK);
-    auto tiles_of = [&](int t) {
+    auto count = [&](int t) {
         return ((rows + kTiles[t].bm - 1) / kTiles[t].bm) * ((cols + kTiles[t].bn - 1) / kTiles[t].bn);
     };
-    int t = 0;
+    int t;
     if (tile_config > 0) {
         t = tile_config - 1;
     } else {
-        // largest tile that still yields >= kCUs workgroups with a sensible split; otherwise
-        // the smallest tile
-        t = kNumTiles - 1;
-        for (int cand = 0; cand < kNumTiles; ++cand) {
-            int64_t nt = tiles_of(cand);
-            int64_t max_split = std::max<int64_t>(1, std::min<int64_t>(kMaxSplits, ksteps / 4));
-            // padded work must not exceed real work by more than 25 %
-            double waste = (double)nt * kTiles[cand].bm * kTiles[cand].bn / ((double)rows * cols);
-            if (nt * max_split >= kCUs && waste <= 1.25) {
-                t = cand;
-                break;
-            }
-        }
+        const int64_t n256 = count(T256x256), n128 = count(T128x128s2);
+        const double fill256 = (double)n256 / (double)(((n256 + kCUs - 1) / kCUs) * kCUs);
+        if (n256 >= 208 && fill256 >= 0.8) t = T256x256;
+        else if (n128 >= 192) t = (ksteps >= 64 && n128 <= 2 * kCUs) ? T128x128s4 : T128x128s2;
+        else t = T64x64s2;
     }
     pl.tile = t;
     pl.tiles_m = (int)((rows + kTiles[t].bm - 1) / kTiles[t].bm);
@@ -657,9 +691,9 @@ static Plan make_plan(int64_t rows, int64_t cols, int64_t kc, int tile_config, i
     int s = 1;
     if (split_k > 0) {
         s = split_k;
-    } else if (nt < kCUs) {
-        s = (int)((kCUs + nt - 1) / nt);
-        s = std::min<int>(s, std::max(1, ksteps / 4));
+    } else if (nt < kCUs / 2) {
+        s = (int)((384 + nt - 1) / nt);           // about one and a half blocks per CU
+        s = std::min(s, std::max(1, ksteps / 8));  // at least eight stages per slice
         s = std::min(s, kMaxSplits);
     }
     s = std::max(1, std::min(s, ksteps));
@@ -798,7 +832,8 @@ extern "C" mp8_status mp8_gemm_fp8_tuned(mp8_op op, int64_t M, int64_t N, int64_
         const bool only_acc = fin.acc_mode == 0 && fin.out8 == nullptr && fin.out8_t == nullptr &&
                               fin.stats == nullptr;
         if (!only_acc) {
-            int64_t blocks = std::min<int64_t>((rows * cgroups + 255) / 256, 256 * 8);
+            const int64_t items = (cols & 3) == 0 ? rows * cols / 4 : rows * cols;
+            int64_t blocks = std::min<int64_t>((items + 255) / 256, 256 * 16);
             hipLaunchKernelGGL(splitk_finish_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
                                (const float *)partial, pl.splits, fin);
             if (hipGetLastError() != hipSuccess) return MP8_ERR_HIP;
