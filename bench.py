@@ -11,9 +11,11 @@ ResNet-50-style 3x3 convolution layer taken as a GEMM (M=25088, N=128, K=1152):
     update        W16 <- half_SR(W16 - lr * G8 / 2^12)
 
 Inputs are resident in HBM before the timed region.  Prints ONE JSON line: `value` is the
-GEMM work of a step (3 * 2*M*N*K flop) divided by the time of the whole step; `roofline`
-describes the kernel that takes the largest share of the step; `kernels` lists every kernel
-of the step with its own roofline; `cpu_baseline` is the CPU oracle timed on this host.
+GEMM work of a step (3 * 2*M*N*K flop) divided by the time of the whole step (the steps are
+replayed from a captured HIP graph unless --launch eager); `roofline` describes the kernel
+that takes the largest share of the step, its duration measured with events around back-to-back
+launches; `kernels` lists every kernel of the step with its own roofline; `cpu_baseline` is the
+CPU oracle timed on this host.
 """
 from __future__ import annotations
 
@@ -32,6 +34,9 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 FP8_PEAK_TFLOPS = 5000.0       # MI355X dense FP8 MFMA, published
 LOSS_SCALE = 2.0 ** 12
 LR = 1e-3
+# HBM bytes per launch read off the FETCH_SIZE and WRITE_SIZE counters for this workload, scaled
+# by the same counters on a plain 1 GiB copy (profiles/quantize_transpose_cfg2_hbm_traffic.txt)
+MEASURED_TRAFFIC_BYTES = {}
 
 
 def parse_args():
@@ -39,9 +44,15 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--kernel-iters", type=int, default=200,
-                    help="launches per kernel for the per-kernel roofline timing")
+    ap.add_argument("--launch", choices=("graph", "eager"), default="graph",
+                    help="how the timed steps are launched: replay of a captured HIP graph "
+                         "(default) or one Python call per kernel")
+    ap.add_argument("--kernel-reps", type=int, default=50,
+                    help="back-to-back launches per graph in the per-kernel timing")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain device-to-device copy of 1 GiB ten times (the "
+                         "known-size kernel that scales the HBM traffic counters), then exit")
     return ap.parse_args()
 
 
@@ -82,31 +93,83 @@ class Workload:
                                                     out8=self.dX8, workspace=self.ws),
              M * N + K * N + M * K, 2 * M * N * K, "mfma"),
             ("gemm_wgrad", lambda: mp8_.gemm_fp8(mp8_.WGRAD, M, N, K, self.X8t, self.E8t, out8=self.G8,
-                                                 stats=self.stats, workspace=self.ws),
+                                                 workspace=self.ws),
              M * K + M * N + K * N, 2 * M * N * K, "mfma"),
             ("sgd_update", self._update, 5 * K * N, 0, "hbm"),
         ]
 
     def _update(self):
+        # every step draws from its own Philox offset; the overflow count of the error tensor
+        # (left in stats by quantize_dY) makes the kernel skip the step without a host round trip
         self.step_no += 1
         self.mp8.sgd_update_fp16_sr(self.W16, self.G8, LR, 1.0 / LOSS_SCALE, round=self.mp8.SR,
-                                    seed=0x1905_1233_4000_0002, offset=self.step_no)
+                                    seed=0x1905_1233_4000_0002, offset=self.step_no,
+                                    skip_if_nonzero=self.stats[1:2])
 
     def step(self):
-        self.stats.zero_()
+        self.stats.zero_()     # a small fill kernel (no memset node, so the step can be captured)
         for _, fn, _, _, _ in self.kernels:
             fn()
 
 
-def time_region(torch, fn, iters):
+def time_steps(torch, wl, steps, launch):
+    """Times exactly `steps` steps between two events on the current stream; returns ms/step."""
     s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    if launch == "eager":
+        torch.cuda.synchronize()
+        s.record()
+        for _ in range(steps):
+            wl.step()
+        e.record()
+        torch.cuda.synchronize()
+        return s.elapsed_time(e) / steps
+    per_graph = max(d for d in range(1, 11) if steps % d == 0)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for _ in range(per_graph):
+            wl.step()
+    graph.replay()
     torch.cuda.synchronize()
     s.record()
-    for _ in range(iters):
-        fn()
+    for _ in range(steps // per_graph):
+        graph.replay()
     e.record()
     torch.cuda.synchronize()
-    return s.elapsed_time(e) / iters   # ms per call
+    return s.elapsed_time(e) / steps
+
+
+def time_kernels(torch, wl, reps):
+    """Average duration of every kernel of the step: each one is captured `reps` times back to
+    back in a HIP graph of its own and the replay is timed with events on the replay stream, so
+    the figure is device time per launch (launch gaps of about a microsecond included), free of
+    host launch cost.  Returns ms per launch."""
+    out = []
+    for _, fn, _, _, _ in wl.kernels:
+        fn()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for _ in range(reps):
+                fn()
+        graph.replay()
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s.record()
+        graph.replay()
+        graph.replay()
+        e.record()
+        torch.cuda.synchronize()
+        out.append(s.elapsed_time(e) / (2 * reps))
+    return out
+
+
+def calibrate_copy(torch):
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 256)
+    dst = torch.empty_like(src)
+    for _ in range(10):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"calibrate_copy": {"bytes_read": n, "bytes_written": n, "launches": 10}}))
 
 
 def cpu_baseline(lay):
@@ -165,21 +228,22 @@ def main():
     from paper_1905_12334_amd import workloads
     mp8.lib()   # raises if the HIP library is not built: there is no fallback
 
+    if args.calibrate_copy:
+        calibrate_copy(torch)
+        return
+
     lay = workloads.config2()
     wl = Workload(mp8, torch, lay)
     for _ in range(args.warmup):
         wl.step()
-    ms_per_step = time_region(torch, wl.step, args.steps)
+    ms_per_step = time_steps(torch, wl, args.steps, args.launch)
     nonfinite = mp8.read_stats(wl.stats)[1]
 
     gemm_flops = 3 * 2.0 * lay.M * lay.N * lay.K
     value = gemm_flops / (ms_per_step * 1e-3) / 1e12
 
     kernels = []
-    for name, fn, nbytes, flops, bound in wl.kernels:
-        for _ in range(5):
-            fn()
-        ms = time_region(torch, fn, args.kernel_iters)
+    for (name, _, nbytes, flops, bound), ms in zip(wl.kernels, time_kernels(torch, wl, args.kernel_reps)):
         if bound == "mfma":
             achieved, peak, unit = flops / (ms * 1e-3) / 1e12, FP8_PEAK_TFLOPS, "TFLOP/s"
         else:
@@ -190,7 +254,8 @@ def main():
                         "hbm_gbs": nbytes / (ms * 1e-3) / 1e9})
     dom = max(kernels, key=lambda k: k["us"])
     roofline = {"kernel": dom["kernel"], "bound": dom["bound"], "achieved": dom["achieved"],
-                "peak": dom["peak"], "unit": dom["unit"], "frac": dom["frac"], "traffic": None}
+                "peak": dom["peak"], "unit": dom["unit"], "frac": dom["frac"],
+                "traffic": MEASURED_TRAFFIC_BYTES.get(dom["kernel"])}
     gemm_us = sum(k["us"] for k in kernels if k["bound"] == "mfma")
 
     out = {
@@ -208,7 +273,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": "configs[1]: ResNet-50-style 3x3 conv as GEMM, M=25088 N=128 K=1152, "
                                "quantize + fwd + bwd_data + wgrad + FP16 SR update, loss scale 2^12",
-                   "M": lay.M, "N": lay.N, "K": lay.K},
+                   "M": lay.M, "N": lay.N, "K": lay.K, "launch": args.launch},
         "pct_of_fp8_peak_whole_step": 100.0 * value / FP8_PEAK_TFLOPS,
         "gemm_only_tflops": gemm_flops / (gemm_us * 1e-6) / 1e12,
         "overflow_count_last_step": nonfinite,

@@ -662,7 +662,7 @@ static void op_dims(mp8_op op, int64_t M, int64_t N, int64_t K, int64_t &rows, i
 // resident blocks per CU when the contraction is short, a deeper ring when it is long); small
 // outputs take 64x64 tiles and, if even those are too few, a split contraction -- kept to a
 // minimum because the second pass costs several microseconds.
-enum { T256x256 = 0, T128x128s2 = 3, T128x128s4 = 4, T64x64s2 = 10 };
+enum { T256x256 = 0, T128x128s2 = 3, T128x128s4 = 4, T128x64s2 = 9, T64x64s2 = 10 };
 static Plan make_plan(int64_t rows, int64_t cols, int64_t kc, int tile_config, int split_k) {
     Plan pl{};
     pl.mfma = (kc % BK) == 0 && kc > 0;
@@ -680,7 +680,8 @@ static Plan make_plan(int64_t rows, int64_t cols, int64_t kc, int tile_config, i
     } else {
         const int64_t n256 = count(T256x256), n128 = count(T128x128s2);
         const double fill256 = (double)n256 / (double)(((n256 + kCUs - 1) / kCUs) * kCUs);
-        if (n256 >= 208 && fill256 >= 0.8) t = T256x256;
+        if (n256 >= 208 && fill256 >= 0.8 && ksteps >= 8) t = T256x256;
+        else if (n128 >= 192 && ksteps <= 2) t = T128x64s2;  // all prologue and epilogue
         else if (n128 >= 192) t = (ksteps >= 64 && n128 <= 2 * kCUs) ? T128x128s4 : T128x128s2;
         else t = T64x64s2;
     }
@@ -783,7 +784,6 @@ extern "C" mp8_status mp8_gemm_fp8_tuned(mp8_op op, int64_t M, int64_t N, int64_
         pl.splits = 1;
     }
     if (tile_config > 0 && !pl.mfma) return MP8_ERR_UNSUPPORTED;
-    const int64_t cgroups = (cols + 15) / 16;
 
     if (!pl.mfma || kc == 0) {
         int64_t blocks = std::min<int64_t>((rows * cols + 255) / 256, 1 << 20);

@@ -264,7 +264,10 @@ struct StatsAcc {
                 nf += part[1][w];
                 z += part[2][w];
             }
-            if (m) atomicMax(&out->amax_bits, m);
+            // the maximum only grows, so a block whose own maximum does not exceed a value
+            // already seen there has nothing to add (the load bypasses non-coherent caches)
+            if (m > __hip_atomic_load(&out->amax_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+                atomicMax(&out->amax_bits, m);
             if (nf) atomicAdd(&out->nonfinite, nf);
             if (z) atomicAdd(&out->zeroed, z);
         }

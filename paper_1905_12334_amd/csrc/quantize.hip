@@ -5,11 +5,11 @@
 // wave-interleaved 16-byte loads (every load instruction of a wave covers 1 KiB of
 // contiguous FP32), convert four values to one packed dword with the hardware conversion
 // instructions and store dwords (256 B contiguous per wave instruction).
-// Transposing kernel: a 128x128 tile; the row-major copy is written straight from registers,
-// the codes also go to an LDS tile from which every thread gathers 16 rows x 4 columns,
-// transposes the 4x4 byte blocks in registers and writes 16-byte pieces of the transposed
-// copy, eight lanes side by side per 128-byte line.
-// Shapes that are not multiples of 4 columns / 16 rows take a small generic kernel.
+// Transposing kernels: a square tile; the row-major copy is written straight from registers,
+// the codes also go to an LDS tile from which the threads gather 4x4 byte blocks, transpose
+// them in registers and write the transposed copy in whole 128-byte lines (tiles of 128; tiles
+// of 64 only for tensors so small that latency, not traffic, sets the time).
+// Shapes that are not multiples of 4 in both dimensions take a small generic kernel.
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
@@ -71,9 +71,10 @@ __device__ __forceinline__ uint32_t round1(float x, float scale, bool sat, const
 }
 
 constexpr int kFlatUnroll = 4;  // 16-byte loads in flight per thread
+constexpr int kStatsBlocks = 512;  // grid limit of the variants that end in atomics
 
 template <bool kF16, bool kSR, bool kStats>
-__global__ __launch_bounds__(256) void quantize_flat_kernel(const void *__restrict__ src,
+__global__ __launch_bounds__(kStats ? 1024 : 256) void quantize_flat_kernel(const void *__restrict__ src,
                                                             uint8_t *__restrict__ dst, int64_t n,
                                                             float scale, int sat, uint64_t seed,
                                                             uint64_t offset, mp8_stats *stats) {
@@ -81,18 +82,19 @@ __global__ __launch_bounds__(256) void quantize_flat_kernel(const void *__restri
     StatsAcc st;
     const int64_t n4 = n >> 2;  // groups of four elements
     uint32_t *dst4 = reinterpret_cast<uint32_t *>(dst);
-    const int64_t stride = (int64_t)gridDim.x * 256 * kFlatUnroll;
-    for (int64_t base = (int64_t)blockIdx.x * 256 * kFlatUnroll + threadIdx.x; base < n4;
+    constexpr int NT = kStats ? 1024 : 256;  // the stats variant runs few, large blocks
+    const int64_t stride = (int64_t)gridDim.x * NT * kFlatUnroll;
+    for (int64_t base = (int64_t)blockIdx.x * NT * kFlatUnroll + threadIdx.x; base < n4;
          base += stride) {
         float v[kFlatUnroll][4];
 #pragma unroll
         for (int u = 0; u < kFlatUnroll; ++u) {
-            const int64_t g = base + u * 256;
+            const int64_t g = base + u * NT;
             if (g < n4) load4<kF16>(src, g * 4, v[u]);
         }
 #pragma unroll
         for (int u = 0; u < kFlatUnroll; ++u) {
-            const int64_t g = base + u * 256;
+            const int64_t g = base + u * NT;
             if (g < n4) {
                 uint32_t pk = round4<kSR, kStats>(v[u], scale, sat != 0, rng, g * 4, st);
                 __builtin_nontemporal_store(pk, dst4 + g);
@@ -181,6 +183,74 @@ __global__ __launch_bounds__(256) void quantize_transpose_kernel(
     if constexpr (kStats) st.flush(stats);
 }
 
+// Transposing kernel, tile T x T with (T/4)^2 threads.  Phase 1: every thread converts four
+// groups of four consecutive elements (a wave instruction reads whole rows of the tile), stores
+// the row-major copy from registers and parks the packed codes in an LDS tile.  Phase 2: every
+// thread takes one 4x4 block of bytes from LDS, transposes it in registers and stores four
+// dwords of the transposed copy; T/4 neighbouring lanes complete T contiguous bytes of a
+// transposed row.  Requires cols % 4 == 0 and rows % 4 == 0.  Blocks stride over the tiles,
+// which are numbered super-tile by super-tile (S x S tiles each, row-major inside).
+template <int T, bool kF16, bool kSR, bool kStats>
+__global__ __launch_bounds__((T / 4) * (T / 4)) void quantize_tile_kernel(
+    const void *__restrict__ src, uint8_t *__restrict__ dst, uint8_t *__restrict__ dst_t,
+    int64_t rows, int64_t cols, float scale, int sat, uint64_t seed, uint64_t offset,
+    mp8_stats *stats, int S) {
+    constexpr int G = T / 4;       // column groups per tile row = threads per tile row
+    constexpr int NT = G * G;      // threads
+    constexpr int P = G + 1;       // LDS row pitch in dwords
+    __shared__ uint32_t tile[T * P];
+    const Philox rng(seed, offset);
+    StatsAcc st;
+    const int64_t tiles_c = (cols + T - 1) / T, tiles_r = (rows + T - 1) / T;
+    const int64_t sup_c = (tiles_c + S - 1) / S, sup_r = (tiles_r + S - 1) / S;
+    const int64_t ntiles = sup_c * sup_r * S * S;
+    const int tid = threadIdx.x;
+    const int k = tid % G, cg = tid / G;  // phase 2: rows 4k..4k+3, columns 4cg..4cg+3
+    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        const int64_t sup = t / (S * S), in = t % (S * S);
+        const int64_t tr_ = (sup / sup_c) * S + in / S, tc_ = (sup % sup_c) * S + in % S;
+        if (tr_ >= tiles_r || tc_ >= tiles_c) continue;
+        const int64_t r0 = tr_ * T, c0 = tc_ * T;
+        float v[4][4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int item = u * NT + tid;
+            const int64_t r = r0 + item / G, c = c0 + 4 * (item % G);
+            if (r < rows && c < cols) load4<kF16>(src, r * cols + c, v[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int item = u * NT + tid;
+            const int tr = item / G, cq = item % G;
+            const int64_t r = r0 + tr, c = c0 + 4 * cq;
+            uint32_t pk = 0;
+            if (r < rows && c < cols) {
+                const int64_t i = r * cols + c;
+                pk = round4<kSR, kStats>(v[u], scale, sat != 0, rng, i, st);
+                __builtin_nontemporal_store(pk, reinterpret_cast<uint32_t *>(dst + i));
+            }
+            tile[tr * P + cq] = pk;
+        }
+        __syncthreads();
+        uint32_t rr[4], cc[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) rr[j] = tile[(4 * k + j) * P + cg];
+        transpose4x4(rr, cc);
+        const int64_t orow = r0 + 4 * k;
+        if (orow < rows) {
+#pragma unroll
+            for (int col = 0; col < 4; ++col) {
+                const int64_t oc = c0 + 4 * cg + col;
+                if (oc < cols)
+                    __builtin_nontemporal_store(cc[col],
+                                                reinterpret_cast<uint32_t *>(dst_t + oc * rows + orow));
+            }
+        }
+        __syncthreads();  // the tile is rewritten by the next iteration
+    }
+    if constexpr (kStats) st.flush(stats);
+}
+
 // Any shape: one element per thread and iteration.
 template <bool kF16, bool kSR, bool kStats>
 __global__ __launch_bounds__(256) void quantize_generic_kernel(
@@ -216,18 +286,40 @@ static hipError_t launch_quantize(const void *src, uint8_t *dst, uint8_t *dst_t,
                                   uint64_t offset, mp8_stats *stats, hipStream_t s) {
     const int64_t n = rows * cols;
     if (dst_t == nullptr) {
-        const int64_t per_block = 256 * kFlatUnroll;
+        // Every block of a stats variant ends with atomics on the one mp8_stats; they are
+        // serialised at the memory side, so those variants run at most two 1024-thread blocks
+        // per CU and stride over the tensor.
+        const int nt = kStats ? 1024 : 256;
+        const int64_t per_block = (int64_t)nt * kFlatUnroll;
         int64_t blocks = ((n >> 2) + per_block - 1) / per_block;
         if (blocks < 1) blocks = 1;
         if (blocks > (1 << 22)) blocks = 1 << 22;  // grid-stride beyond 2^34 elements
-        if (kStats && blocks > 256 * 8) blocks = 256 * 8;  // fewer atomics: grid-stride
+        if (kStats && blocks > kStatsBlocks) blocks = kStatsBlocks;
         hipLaunchKernelGGL((quantize_flat_kernel<kF16, kSR, kStats>), dim3((unsigned)blocks),
-                           dim3(256), 0, s, src, dst, n, scale, sat, seed, offset, stats);
-    } else if ((cols & 3) == 0 && (rows & 15) == 0) {
-        const int64_t tiles = ((rows + kTile - 1) / kTile) * ((cols + kTile - 1) / kTile);
-        hipLaunchKernelGGL((quantize_transpose_kernel<kF16, kSR, kStats>), dim3((unsigned)tiles),
-                           dim3(256), 0, s, src, dst, dst_t, rows, cols, scale, sat, seed, offset,
-                           stats);
+                           dim3(nt), 0, s, src, dst, n, scale, sat, seed, offset, stats);
+    } else if ((cols & 3) == 0 && (rows & 3) == 0) {
+        const int64_t tr128 = (rows + 127) / 128, tc128 = (cols + 127) / 128;
+        if (!kStats && (rows & 15) == 0 && tr128 * tc128 >= 1024) {
+            // large tensors: every CU holds several 256-thread blocks at different phases
+            hipLaunchKernelGGL((quantize_transpose_kernel<kF16, kSR, kStats>),
+                               dim3((unsigned)(tr128 * tc128)), dim3(256), 0, s, src, dst, dst_t,
+                               rows, cols, scale, sat, seed, offset, stats);
+        } else if (tr128 * tc128 >= 64) {
+            // super-tiles of 4x4 keep the lines written by concurrently running blocks close
+            // together in both copies of a wide matrix
+            const int S = (tr128 >= 64 && tc128 >= 64) ? 4 : 1;
+            int64_t blocks = ((tr128 + S - 1) / S) * ((tc128 + S - 1) / S) * S * S;
+            if (kStats && blocks > kStatsBlocks) blocks = kStatsBlocks;
+            hipLaunchKernelGGL((quantize_tile_kernel<128, kF16, kSR, kStats>),
+                               dim3((unsigned)blocks), dim3(1024), 0, s, src, dst, dst_t, rows, cols,
+                               scale, sat, seed, offset, stats, S);
+        } else {
+            // few tiles: smaller ones shorten the latency chain of the single round of blocks
+            const int64_t blocks = ((rows + 63) / 64) * ((cols + 63) / 64);
+            hipLaunchKernelGGL((quantize_tile_kernel<64, kF16, kSR, kStats>),
+                               dim3((unsigned)blocks), dim3(256), 0, s, src, dst, dst_t, rows, cols,
+                               scale, sat, seed, offset, stats, 1);
+        }
     } else {
         int64_t blocks = (n + 255) / 256;
         if (blocks > 256 * 32) blocks = 256 * 32;

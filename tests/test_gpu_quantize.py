@@ -98,6 +98,26 @@ def test_ragged_shapes_scale_transpose_stats(mp8, shape, rnd):
         assert gst == wst
 
 
+@pytest.mark.parametrize("shape,with_stats", [
+    ((100, 36), True),        # a handful of 64x64 tiles, ragged in both directions
+    ((1100, 1284), True),     # 128x128 tiles with ragged edges, grid-strided stats variant
+    ((1100, 1284), False),
+    ((4096, 4100), False),    # more than a thousand tiles: the 256-thread streaming variant
+    ((8192, 8196), True),     # wide and tall: super-tiled block order, capped grid
+    ((8192, 8196), False),
+])
+def test_transposed_copy_on_every_launch_path(mp8, shape, with_stats):
+    x = workloads.random_f32_bit_patterns(shape[0] + shape[1], shape[0] * shape[1]).reshape(shape)
+    x[3, 5] = np.float32(3.0e-5)
+    rnd = oracle.SR if shape[1] % 8 else oracle.RNE
+    got, got_t, gst = _run(mp8, x, want_t=True, with_stats=with_stats, round=rnd, seed=21, offset=6)
+    want, want_t, wst = _oracle(x, want_t=True, round=rnd, seed=21, offset=6)
+    assert np.array_equal(got, want)
+    assert np.array_equal(got_t, want_t)
+    if with_stats:
+        assert gst == wst
+
+
 def test_half_precision_source(mp8):
     rng = np.random.default_rng(3)
     x = (rng.standard_normal((130, 96)) * np.exp2(rng.integers(-18, 12, (130, 96)))).astype(np.float16)
