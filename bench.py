@@ -14,7 +14,8 @@ Inputs are resident in HBM before the timed region.  Prints ONE JSON line: `valu
 GEMM work of a step (3 * 2*M*N*K flop) divided by the time of the whole step (the steps are
 replayed from a captured HIP graph unless --launch eager); `roofline` describes the kernel
 that takes the largest share of the step, its duration measured with events around back-to-back
-launches; `kernels` lists every kernel of the step with its own roofline; `cpu_baseline` is the
+launches; `kernels` lists every kernel of the step with its own roofline; `all_configs` is a kernel-level table over the GEMM shapes
+of all five configurations and the streaming kernels at 2^28 elements; `cpu_baseline` is the
 CPU oracle timed on this host.
 """
 from __future__ import annotations
@@ -35,8 +36,13 @@ FP8_PEAK_TFLOPS = 5000.0       # MI355X dense FP8 MFMA, published
 LOSS_SCALE = 2.0 ** 12
 LR = 1e-3
 # HBM bytes per launch read off the FETCH_SIZE and WRITE_SIZE counters for this workload, scaled
-# by the same counters on a plain 1 GiB copy (profiles/quantize_transpose_cfg2_hbm_traffic.txt)
-MEASURED_TRAFFIC_BYTES = {}
+# by what the same counters read on a plain 1 GiB copy (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000);
+# the runs and their raw figures are in profiles/bench_step_cfg2_hbm_traffic.txt
+MEASURED_TRAFFIC_BYTES = {
+    "quantize_X": 173475021, "quantize_W": 980000, "quantize_dY": 19410000,
+    "gemm_fwd": 33370000, "gemm_bwd_data": 34280000, "gemm_wgrad": 51660000,
+    "sgd_update": 850000,
+}
 
 
 def parse_args():
@@ -50,6 +56,8 @@ def parse_args():
     ap.add_argument("--kernel-reps", type=int, default=50,
                     help="back-to-back launches per graph in the per-kernel timing")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-all-configs", action="store_true",
+                    help="skip the kernel-level table over the GEMM shapes of all configurations")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device-to-device copy of 1 GiB ten times (the "
                          "known-size kernel that scales the HBM traffic counters), then exit")
@@ -162,6 +170,84 @@ def time_kernels(torch, wl, reps):
     return out
 
 
+def graph_time_us(torch, fn, reps=20):
+    """Device time per call of fn, from a captured graph of `reps` back-to-back calls."""
+    fn()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for _ in range(reps):
+            fn()
+    graph.replay()
+    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    s.record()
+    graph.replay()
+    graph.replay()
+    e.record()
+    torch.cuda.synchronize()
+    return s.elapsed_time(e) / (2 * reps) * 1e3
+
+
+def all_configs_report(mp8, torch):
+    """Kernel-level throughput on the GEMM shapes of every workload configuration (plus two large
+    shapes that show what the main loop reaches when nothing else binds) and on the streaming
+    kernels at a size far beyond the caches.  Operand values are random finite codes; parity on
+    these shapes is the business of the tests, not of this table."""
+    dev = "cuda"
+    rows = []
+    gemms = [("configs[0] fwd", mp8.FWD, 256, 256, 256, mp8.RNE),
+             ("configs[1] fwd", mp8.FWD, 25088, 128, 1152, mp8.RNE),
+             ("configs[1] bwd_data", mp8.BWD_DATA, 25088, 128, 1152, mp8.RNE),
+             ("configs[1] wgrad", mp8.WGRAD, 25088, 128, 1152, mp8.RNE),
+             ("configs[2] ffn1 fwd", mp8.FWD, 4096, 2048, 512, mp8.RNE),
+             ("configs[2] ffn1 bwd_data", mp8.BWD_DATA, 4096, 2048, 512, mp8.RNE),
+             ("configs[2] ffn1 wgrad", mp8.WGRAD, 4096, 2048, 512, mp8.RNE),
+             ("configs[2] ffn2 fwd", mp8.FWD, 4096, 512, 2048, mp8.RNE),
+             ("configs[2] ffn2 bwd_data", mp8.BWD_DATA, 4096, 512, 2048, mp8.RNE),
+             ("configs[2] ffn2 wgrad", mp8.WGRAD, 4096, 512, 2048, mp8.RNE),
+             ("configs[3] fwd (one timestep)", mp8.FWD, 128, 4096, 2048, mp8.RNE),
+             ("configs[3] bwd_data (one timestep)", mp8.BWD_DATA, 128, 4096, 2048, mp8.RNE),
+             ("configs[3] wgrad (50 timesteps stacked)", mp8.WGRAD, 6400, 4096, 2048, mp8.RNE),
+             ("configs[4] wgrad, SR epilogue", mp8.WGRAD, 16384, 4096, 1024, mp8.SR),
+             ("large 4096x4096x16384 fwd", mp8.FWD, 4096, 4096, 16384, mp8.RNE),
+             ("large 8192^3 fwd", mp8.FWD, 8192, 8192, 8192, mp8.RNE)]
+    for name, op, M, N, K, rnd in gemms:
+        r, c, kc = {mp8.FWD: (M, N, K), mp8.BWD_DATA: (M, K, N), mp8.WGRAD: (K, N, M)}[op]
+        a = (torch.randint(0, 256, (r, kc), dtype=torch.uint8, device=dev) & 0x83) | 0x38
+        b = (torch.randint(0, 256, (c, kc), dtype=torch.uint8, device=dev) & 0x83) | 0x38
+        out = torch.empty((r, c), dtype=torch.uint8, device=dev)
+        ws = torch.empty(max(mp8.gemm_fp8_workspace_bytes(op, M, N, K), 16), dtype=torch.uint8, device=dev)
+        us = graph_time_us(torch, lambda: mp8.gemm_fp8(op, M, N, K, a, b, out8=out, round=rnd, seed=5,
+                                                       offset=1, workspace=ws))
+        flops, nbytes = 2.0 * M * N * K, r * kc + c * kc + r * c
+        rows.append({"kernel": "gemm_fp8", "case": name, "us": us, "tflops": flops / us / 1e6,
+                     "frac_mfma_peak": flops / us / 1e6 / FP8_PEAK_TFLOPS,
+                     "alg_gbs": nbytes / us / 1e3, "flop_per_byte": flops / nbytes})
+        del a, b, out, ws
+    n = 1 << 28
+    src = torch.empty((1 << 14, 1 << 14), dtype=torch.float32, device=dev).normal_()
+    d8 = torch.empty((1 << 14, 1 << 14), dtype=torch.uint8, device=dev)
+    for rnd, rn in ((mp8.RNE, "RNE"), (mp8.SR, "SR")):
+        us = graph_time_us(torch, lambda: mp8.quantize_e5m2(src, d8, round=rnd, seed=1, offset=2), 5)
+        rows.append({"kernel": "quantize_e5m2", "case": f"2^28 elements, {rn}", "us": us,
+                     "alg_gbs": 5.0 * n / us / 1e3, "frac_hbm_peak": 5.0 * n / us / 1e3 / HBM_PEAK_GBS})
+    w16 = torch.empty(n, dtype=torch.float16, device=dev).normal_(0, 0.02)
+    g8 = d8.view(-1)
+    for rnd, rn in ((mp8.RNE, "RNE"), (mp8.SR, "SR")):
+        us = graph_time_us(torch, lambda: mp8.sgd_update_fp16_sr(w16, g8, LR, 1.0 / LOSS_SCALE, round=rnd,
+                                                                 seed=1, offset=3), 5)
+        rows.append({"kernel": "sgd_update_fp16_sr", "case": f"2^28 elements, {rn}", "us": us,
+                     "alg_gbs": 5.0 * n / us / 1e3, "frac_hbm_peak": 5.0 * n / us / 1e3 / HBM_PEAK_GBS})
+    del src, d8, w16
+    x = torch.empty((100352, 1152), dtype=torch.float32, device=dev).normal_()
+    q, qt = torch.empty((100352, 1152), dtype=torch.uint8, device=dev), torch.empty((1152, 100352), dtype=torch.uint8, device=dev)
+    us = graph_time_us(torch, lambda: mp8.quantize_e5m2(x, q, qt), 5)
+    rows.append({"kernel": "quantize_e5m2", "case": "with transposed copy, 100352x1152 (4x configs[1] X), RNE",
+                 "us": us, "alg_gbs": 6.0 * x.numel() / us / 1e3,
+                 "frac_hbm_peak": 6.0 * x.numel() / us / 1e3 / HBM_PEAK_GBS})
+    return rows
+
+
 def calibrate_copy(torch):
     n = 1 << 30
     src = torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 256)
@@ -197,7 +283,7 @@ def cpu_baseline(lay):
     t0 = time.perf_counter()
     gemm_s = [one_step()]
     first = time.perf_counter() - t0
-    reps = max(1, min(5, int(12.0 / max(first, 1e-3))))
+    reps = max(1, min(25, int(15.0 / max(first, 1e-3))))
     for _ in range(reps - 1):
         gemm_s.append(one_step())
     total = time.perf_counter() - t0
@@ -251,7 +337,8 @@ def main():
         kernels.append({"kernel": name, "bound": bound, "us": ms * 1e3, "achieved": achieved,
                         "peak": peak, "unit": unit, "frac": achieved / peak,
                         "alg_bytes": nbytes, "flops": flops,
-                        "hbm_gbs": nbytes / (ms * 1e-3) / 1e9})
+                        "hbm_gbs": nbytes / (ms * 1e-3) / 1e9,
+                        "traffic": MEASURED_TRAFFIC_BYTES.get(name)})
     dom = max(kernels, key=lambda k: k["us"])
     roofline = {"kernel": dom["kernel"], "bound": dom["bound"], "achieved": dom["achieved"],
                 "peak": dom["peak"], "unit": dom["unit"], "frac": dom["frac"],
@@ -280,6 +367,13 @@ def main():
         "roofline": roofline,
         "kernels": kernels,
     }
+    if not args.no_all_configs:
+        del wl
+        torch.cuda.empty_cache()
+        try:
+            out["all_configs"] = all_configs_report(mp8, torch)
+        except Exception as exc:  # the table is extra evidence; the line above it stands on its own
+            out["all_configs"] = {"error": repr(exc)}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(lay)
     print(json.dumps(out))
