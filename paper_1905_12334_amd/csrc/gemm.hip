@@ -4,17 +4,22 @@
 // the epilogue.  The three training GEMMs (forward, backward-data, weight-gradient) are the
 // same contraction  out[r,c] = sum_j a[r,j] * b[c,j]  on differently oriented operands.
 //
-// Main kernel: 256 threads (4 waves), block tile BM x BN x 128 bytes of contraction per
-// step.  Operand slabs travel HBM -> LDS with direct-to-LDS 16-byte loads into a two-stage
-// ring, are read as 32-byte-per-lane fragments and multiplied with
-// v_mfma_f32_32x32x64_f8f6f4 in its bf8 x bf8 form.  The LDS image is XOR-swizzled in
-// 16-byte chunks so that fragment reads are bank-conflict free; because direct-to-LDS
-// writes are lane-contiguous the swizzle is applied to the global address each lane
-// fetches.  The operands are fed to the MFMA swapped (b as the "row" matrix) so that each
-// lane ends up with four consecutive output columns of one output row.
+// Main kernel: 256 threads (4 waves), block tile BM x BN, 128 bytes of contraction per
+// pipeline stage.  Operand slabs travel HBM -> LDS with direct-to-LDS 16-byte loads into a
+// ring of 2-4 stages (issued from inline asm with hand-tracked wait counts), are read as
+// 32-byte-per-lane fragments into double-buffered registers and multiplied with
+// v_mfma_f32_32x32x64_f8f6f4 in its bf8 x bf8 form.  The main loop is slot-scheduled: one
+// MFMA per slot, with the LDS reads and direct loads of the next half-stage spread in its
+// shadow.  The LDS image is XOR-swizzled in 16-byte chunks so that fragment reads are
+// bank-conflict free; because direct-to-LDS writes are lane-contiguous the swizzle is applied
+// to the global address each lane fetches.  The operands are fed to the MFMA swapped (b as
+// the "row" matrix) so that each lane ends up with consecutive output columns of one row.
+// The kernel is instantiated per epilogue variant (FP32 partial tile, RNE only, everything) to
+// keep each instance's code small.
 //
-// Split contraction: slices write FP32 partial tiles to the workspace and a second kernel
-// sums them in slice order and applies the epilogue -- the sum is rounded exactly once.
+// Split contraction, FP32 / transposed outputs, ragged column counts: the main kernel writes
+// FP32 tiles and a second kernel sums the slices in order and applies the epilogue -- the sum
+// is rounded exactly once.
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
