@@ -390,6 +390,21 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     constexpr int R0 = (2 * F + S_RD - 1) / S_RD;             // half reads per early slot
     constexpr int R1 = (2 * F + NM - 1) / NM;                 // half reads per late slot
     constexpr int D1 = (G + (2 * NM - S_BAR) - 1) / (2 * NM - S_BAR);  // loads per slot
+    // Mid-sized tiles with a three-stage ring split the barrier in two (measured +7-11 % there,
+    // nothing on the 256x256 tile): the first (end of slot S_BAR-1) only says that nobody reads
+    // the buffer of stage t any more, so the loads of stage t+NSTAGE can start; the wait for
+    // stage t+1 to land moves to the end of slot NM-1, right before its first fragment read,
+    // which gives the loads half a stage more to arrive.  By then N_ISS loads of stage
+    // t+NSTAGE are already in flight behind the ones waited for.
+    constexpr bool SPLIT_BAR = NM >= 8 && NSTAGE == 3;
+    constexpr int N_ISS = (NM - S_BAR) * D1 < G ? (NM - S_BAR) * D1 : G;
+    static_assert(!SPLIT_BAR || G * (NSTAGE - 2) + N_ISS < 64, "vmcnt range");
+    auto wait_stage_late = [&](int t, bool more_) {
+        const int later = ks_count - 2 - t;  // stages after t+1 that exist
+        if (more_) wait_vm_lds<SPLIT_BAR ? G * (NSTAGE - 2) + N_ISS : 0>();
+        else if (NSTAGE > 2 && later >= NSTAGE - 2) wait_vm_lds<G * (NSTAGE - 2)>();
+        else wait_vm_lds<0>();
+    };
     for (int t = 0; t < ks_count; ++t) {
         MP8_STAMP(0);
         const bool more = t + NSTAGE < ks_count;
@@ -407,7 +422,8 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
             if (k == S_BAR - 1) {
                 __builtin_amdgcn_sched_barrier(0);
                 MP8_STAMP(1);
-                wait_stage(t);
+                if constexpr (SPLIT_BAR) wait_vm_lds<63>();  // own LDS reads only
+                else wait_stage(t);
                 MP8_STAMP(2);
                 __syncthreads();
                 MP8_STAMP(3);
@@ -425,6 +441,11 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
                     const int n = (k - NM) * R1 + r;
                     if (n < 2 * F && next) read_half(t + 1, 0, frag_order(n / 2), n & 1, f0);
                 }
+            }
+            if (SPLIT_BAR && k == NM - 1) {  // after this slot's loads: N_ISS are in flight
+                __builtin_amdgcn_sched_barrier(0);
+                wait_stage_late(t, more);
+                __syncthreads();
             }
             __builtin_amdgcn_sched_barrier(0);
         }

@@ -13,6 +13,8 @@
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "mp8_device.hpp"
 
 namespace mp8 {
@@ -127,9 +129,110 @@ __device__ __forceinline__ void transpose4x4(const uint32_t r[4], uint32_t c[4])
 constexpr int kTile = 128;
 constexpr int kPitch = kTile / 4 + 1;  // LDS row pitch in dwords
 
-// Requires cols % 4 == 0 and rows % 16 == 0.
+// Streaming transposing kernel for large tensors: 128x128 tiles, 256 threads, and every block
+// walks over several tiles (tile = blockIdx.x + i * gridDim.x).  The sixteen 16-byte loads of
+// a thread's share of the NEXT tile are issued before the block turns to the transposed
+// stores of the current one, so reads, row-major stores and transposed stores overlap inside
+// a block instead of running in lock-step phases across the whole chip.  Phase 1: convert,
+// store the row-major copy from registers, park the codes in one of two LDS tiles (pitch 33
+// dwords).  Phase 2: every thread gathers 16 rows x 4 columns, transposes 4x4 byte blocks in
+// registers and writes 16-byte pieces of the transposed copy, eight lanes side by side per
+// 128-byte line.  Requires cols % 4 == 0 and rows % 16 == 0.
 template <bool kF16, bool kSR, bool kStats>
-__global__ __launch_bounds__(256) void quantize_transpose_kernel(
+__global__ __launch_bounds__(256, 2) void quantize_transpose_kernel(
+    const void *__restrict__ src, uint8_t *__restrict__ dst, uint8_t *__restrict__ dst_t,
+    int64_t rows, int64_t cols, float scale, int sat, uint64_t seed, uint64_t offset,
+    mp8_stats *stats) {
+    __shared__ uint32_t tiles[2][kTile * kPitch];
+    const Philox rng(seed, offset);
+    StatsAcc st;
+    const int64_t tiles_c = (cols + kTile - 1) / kTile;
+    const int64_t ntiles = ((rows + kTile - 1) / kTile) * tiles_c;
+    const int tid = threadIdx.x;
+    const int cq = tid & 31, tr0 = tid >> 5;   // phase 1: column group, first row (then +8)
+    const int k = tid & 7, cg = tid >> 3;      // phase 2: row chunk of 16, column group
+    float v[16][4];
+    // Tiles that lie completely inside the tensor take code without any per-element guard:
+    // with guards the compiler can no longer count outstanding loads and stores and falls
+    // back to waiting for everything before each use, which serialises the stores.
+    auto is_full = [&](int64_t t) {
+        return (t / tiles_c + 1) * kTile <= rows && (t % tiles_c + 1) * kTile <= cols;
+    };
+    auto load_tile = [&](int64_t t, auto guard) {
+        const int64_t r0 = (t / tiles_c) * kTile, c = (t % tiles_c) * kTile + 4 * cq;
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int64_t r = r0 + tr0 + 8 * u;
+            if (!decltype(guard)::value || (r < rows && c < cols)) load4<kF16>(src, r * cols + c, v[u]);
+        }
+    };
+    auto phase1 = [&](int64_t t, uint32_t *tile, auto guard) {
+        const int64_t r0 = (t / tiles_c) * kTile, c = (t % tiles_c) * kTile + 4 * cq;
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int tr = tr0 + 8 * u;
+            const int64_t r = r0 + tr;
+            uint32_t pk = 0;
+            if (!decltype(guard)::value || (r < rows && c < cols)) {
+                const int64_t i = r * cols + c;
+                pk = round4<kSR, kStats>(v[u], scale, sat != 0, rng, i, st);
+                __builtin_nontemporal_store(pk, reinterpret_cast<uint32_t *>(dst + i));
+            }
+            tile[tr * kPitch + cq] = pk;
+        }
+    };
+    auto phase2 = [&](int64_t t, const uint32_t *tile, auto guard) {
+        const int64_t r0 = (t / tiles_c) * kTile, c0 = (t % tiles_c) * kTile;
+        uint32_t colw[4][4];  // [column][row block of 4]
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            uint32_t rr[4], cc[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) rr[j] = tile[(16 * k + 4 * b + j) * kPitch + cg];
+            transpose4x4(rr, cc);
+#pragma unroll
+            for (int col = 0; col < 4; ++col) colw[col][b] = cc[col];
+        }
+        const int64_t orow = r0 + 16 * k;
+        if (!decltype(guard)::value || orow < rows) {
+#pragma unroll
+            for (int col = 0; col < 4; ++col) {
+                const int64_t oc = c0 + 4 * cg + col;
+                if (!decltype(guard)::value || oc < cols) {
+                    u32x4 o = {colw[col][0], colw[col][1], colw[col][2], colw[col][3]};
+                    __builtin_nontemporal_store(o, reinterpret_cast<u32x4 *>(dst_t + oc * rows + orow));
+                }
+            }
+        }
+    };
+    using Guarded = std::true_type;
+    using Plain = std::false_type;
+    int64_t t = blockIdx.x;
+    if (t < ntiles) {
+        if (is_full(t)) load_tile(t, Plain{}); else load_tile(t, Guarded{});
+    }
+    for (int buf = 0; t < ntiles; t += gridDim.x, buf ^= 1) {
+        uint32_t *tile = tiles[buf];
+        const bool full = is_full(t);
+        if (full) phase1(t, tile, Plain{}); else phase1(t, tile, Guarded{});
+        const int64_t tn = t + gridDim.x;
+        if (tn < ntiles) {
+            if (is_full(tn)) load_tile(tn, Plain{}); else load_tile(tn, Guarded{});
+        }
+        // LDS-only synchronisation (the prefetch just issued must stay in flight); one barrier
+        // per tile is enough: the other LDS tile was last read before the previous barrier
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        if (full) phase2(t, tile, Plain{}); else phase2(t, tile, Guarded{});
+    }
+    if constexpr (kStats) st.flush(stats);
+}
+
+// One tile per block (no tile loop): with thousands of tiles many blocks per CU are resident at
+// different phases and this simple form streams best.  Same tile layout and phases as the
+// kernel above.  Requires cols % 4 == 0 and rows % 16 == 0; not used with statistics (one
+// atomic per field and block would be too many).
+template <bool kF16, bool kSR, bool kStats>
+__global__ __launch_bounds__(256) void quantize_transpose_oneshot_kernel(
     const void *__restrict__ src, uint8_t *__restrict__ dst, uint8_t *__restrict__ dst_t,
     int64_t rows, int64_t cols, float scale, int sat, uint64_t seed, uint64_t offset,
     mp8_stats *stats) {
@@ -299,15 +402,26 @@ static hipError_t launch_quantize(const void *src, uint8_t *dst, uint8_t *dst_t,
                            dim3(nt), 0, s, src, dst, n, scale, sat, seed, offset, stats);
     } else if ((cols & 3) == 0 && (rows & 3) == 0) {
         const int64_t tr128 = (rows + 127) / 128, tc128 = (cols + 127) / 128;
-        if (!kStats && (rows & 15) == 0 && tr128 * tc128 >= 1024) {
-            // large tensors: every CU holds several 256-thread blocks at different phases
+        const int64_t nt = tr128 * tc128;
+        const bool wide = tr128 >= 64 && tc128 >= 64;
+        if (!kStats && !wide && (rows & 15) == 0 && nt >= 6144) {
+            // several rounds of blocks: plain one-tile blocks, many per CU
+            hipLaunchKernelGGL((quantize_transpose_oneshot_kernel<kF16, kSR, kStats>),
+                               dim3((unsigned)nt), dim3(256), 0, s, src, dst, dst_t, rows, cols,
+                               scale, sat, seed, offset, stats);
+        } else if (!wide && (rows & 15) == 0 && nt >= 1024) {
+            // a few tiles per CU: about two persistent blocks per CU, the same number of tiles
+            // each, prefetching across tiles
+            const int64_t per = (nt + 511) / 512;
+            const int64_t blocks = (nt + per - 1) / per;
             hipLaunchKernelGGL((quantize_transpose_kernel<kF16, kSR, kStats>),
-                               dim3((unsigned)(tr128 * tc128)), dim3(256), 0, s, src, dst, dst_t,
-                               rows, cols, scale, sat, seed, offset, stats);
-        } else if (tr128 * tc128 >= 64) {
-            // super-tiles of 4x4 keep the lines written by concurrently running blocks close
-            // together in both copies of a wide matrix
-            const int S = (tr128 >= 64 && tc128 >= 64) ? 4 : 1;
+                               dim3((unsigned)blocks), dim3(256), 0, s, src, dst, dst_t, rows, cols,
+                               scale, sat, seed, offset, stats);
+        } else if (nt >= 64) {
+            // 1024-thread blocks, all loads of a tile in flight; for a matrix that is wide in
+            // both directions, super-tiles of 4x4 keep the lines written by concurrently
+            // running blocks close together in both copies
+            const int S = wide ? 4 : 1;
             int64_t blocks = ((tr128 + S - 1) / S) * ((tc128 + S - 1) / S) * S * S;
             if (kStats && blocks > kStatsBlocks) blocks = kStatsBlocks;
             hipLaunchKernelGGL((quantize_tile_kernel<128, kF16, kSR, kStats>),

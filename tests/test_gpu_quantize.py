@@ -102,7 +102,9 @@ def test_ragged_shapes_scale_transpose_stats(mp8, shape, rnd):
     ((100, 36), True),        # a handful of 64x64 tiles, ragged in both directions
     ((1100, 1284), True),     # 128x128 tiles with ragged edges, grid-strided stats variant
     ((1100, 1284), False),
-    ((4096, 4100), False),    # more than a thousand tiles: the 256-thread streaming variant
+    ((4096, 4100), False),    # about a thousand tiles: persistent blocks prefetching across tiles
+    ((4096, 4100), True),
+    ((16384, 6148), False),   # several rounds of tiles, narrow: one tile per block
     ((8192, 8196), True),     # wide and tall: super-tiled block order, capped grid
     ((8192, 8196), False),
 ])
