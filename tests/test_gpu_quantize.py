@@ -120,6 +120,44 @@ def test_transposed_copy_on_every_launch_path(mp8, shape, with_stats):
         assert gst == wst
 
 
+@pytest.mark.parametrize("quarter", [0, 1, 2, 3])
+def test_every_fp32_bit_pattern_rne(mp8, quarter):
+    """All 2^32 FP32 inputs (a quarter per case, 2^26 at a time), nearest-even rounding with
+    statistics: the hardware conversion path, its NaN detour and the counters against the oracle."""
+    import torch
+    n = 1 << 26
+    dst = torch.empty((1 << 13, 1 << 13), dtype=torch.uint8, device="cuda")
+    for chunk in range(16 * quarter, 16 * quarter + 16):
+        x = np.arange(chunk * n, (chunk + 1) * n, dtype=np.uint64).astype(np.uint32).view(np.float32)
+        x = x.reshape(1 << 13, 1 << 13)
+        st = mp8.new_stats()
+        mp8.quantize_e5m2(gpu(x), dst, stats=st)
+        torch.cuda.synchronize()
+        ost = oracle.Stats()
+        want, _ = oracle.quantize_e5m2(x, stats=ost)
+        assert np.array_equal(host(dst), want), f"chunk {chunk}"
+        assert mp8.read_stats(st) == ost.as_tuple(), f"chunk {chunk}"
+
+
+def test_every_16th_fp32_bit_pattern_sr_and_saturating(mp8):
+    """2^28 FP32 inputs spread over the whole range with stochastic rounding (Philox bits by
+    element index), and the same inputs with nearest-even rounding in the saturating mode."""
+    import torch
+    n = 1 << 26
+    dst = torch.empty((1 << 13, 1 << 13), dtype=torch.uint8, device="cuda")
+    for chunk in range(4):
+        x = ((np.arange(chunk * n, (chunk + 1) * n, dtype=np.uint64) * 16 + 5) & 0xFFFFFFFF)
+        x = x.astype(np.uint32).view(np.float32).reshape(1 << 13, 1 << 13)
+        xd = gpu(x)
+        for kw in (dict(round=oracle.SR, seed=0xABCDEF + chunk, offset=chunk),
+                   dict(round=oracle.RNE, flags=oracle.FLAG_SATURATE)):
+            mp8.quantize_e5m2(xd, dst, **kw)
+            torch.cuda.synchronize()
+            want, _ = oracle.quantize_e5m2(x, mode=kw.get("round"), flags=kw.get("flags", 0),
+                                           seed=kw.get("seed", 0), offset=kw.get("offset", 0))
+            assert np.array_equal(host(dst), want), (chunk, kw)
+
+
 def test_half_precision_source(mp8):
     rng = np.random.default_rng(3)
     x = (rng.standard_normal((130, 96)) * np.exp2(rng.integers(-18, 12, (130, 96)))).astype(np.float16)

@@ -57,6 +57,22 @@ def test_update_all_half_patterns(mp8):
             assert np.array_equal(got, want), (code, rnd)
 
 
+@pytest.mark.parametrize("lr,inv", [(1e-3, 1.0 / 4096), (0.25, 1.0), (7.0, 1.0 / 3)])
+def test_update_every_weight_and_gradient_code_pair(mp8, lr, inv):
+    """All 65536 half-precision weights x all 256 gradient codes (2^24 pairs), both rounding
+    modes, with the 8-bit copy of the new weights."""
+    w16 = np.tile(np.arange(65536, dtype=np.uint16), 256)
+    g8 = np.repeat(np.arange(256, dtype=np.uint8), 65536)
+    for rnd in (oracle.RNE, oracle.SR):
+        got, got8, gst = _run(mp8, w16, g8, lr, inv, rnd, seed=99, offset=5, want_w8=True)
+        st = oracle.Stats()
+        want, want8 = oracle.sgd_update_fp16(w16, g8, lr, inv, mode=rnd, seed=99, offset=5,
+                                             want_w8=True, stats=st)
+        assert np.array_equal(got, want), (lr, rnd)
+        assert np.array_equal(got8, want8), (lr, rnd)
+        assert gst[1] == st.nonfinite == 8 * 65536
+
+
 def test_update_transformer_big_magnitudes_and_skip(mp8):
     lay = workloads.config5(tokens=8, d_in=256, d_out=512)
     w16 = lay.W.astype(np.float16).view(np.uint16).reshape(-1)
