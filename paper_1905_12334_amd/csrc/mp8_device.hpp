@@ -108,14 +108,14 @@ __device__ __forceinline__ uint32_t e5m2_from_f32_bits(uint32_t u, uint32_t r16,
 // with r16 << 16 (it adds the top 21 bits of its random operand to the 21 discarded mantissa
 // bits) produce exactly the codes of e5m2_from_f32_bits for every FP32 input that is not a
 // NaN -- including ties, subnormal results and overflow to Inf; this was checked over all
-// 2^32 inputs.  NaNs (the hardware keeps sign and payload bits) and the saturating mode go
-// through the bit-level routine.
+// 2^32 inputs.  NaNs (the hardware keeps sign and payload bits) go through the bit-level
+// routine.
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ bool any_nan4(const float y[4]) {
     return __builtin_isunordered(y[0], y[1]) | __builtin_isunordered(y[2], y[3]);
 }
 
-// Bit-level conversion of four values (NaN inputs and the saturating mode).  Out of line on
+// Bit-level conversion of four values (groups that contain a NaN).  Out of line on
 // purpose: it is rare, and keeping it out of the callers keeps their hot code small.
 static __device__ __noinline__ uint32_t e5m2_pack4_slow(float y0, float y1, float y2, float y3,
                                                         uint32_t r01, uint32_t r23, bool sr,
@@ -132,21 +132,35 @@ static __device__ __noinline__ uint32_t e5m2_pack4_slow(float y0, float y1, floa
     return w;
 }
 
+// Saturating mode on the hardware path: every finite value beyond the largest normal ends at
+// +-57344 under either rounding rule (nearest-even: (57344, 61440) rounds down, the rest would
+// overflow; stochastic: the bracket is [57344, 65536) and its upper end would overflow), so
+// such values are replaced by +-57344 before the conversion.  Infinities stay infinities.
+__device__ __forceinline__ float saturate_finite(float y) {
+    const float a = __builtin_fabsf(y);
+    return (a > 57344.0f && a < __builtin_inff()) ? __builtin_copysignf(57344.0f, y) : y;
+}
+
 // Four values -> four codes packed little-endian.  r01 / r23 hold the 16 random bits of
 // elements (0: low half, 1: high half) and (2, 3); ignored for RNE.
 template <bool kSR>
 __device__ __forceinline__ uint32_t e5m2_pack4(const float y[4], uint32_t r01, uint32_t r23,
                                                bool sat) {
-    if (sat || any_nan4(y)) return e5m2_pack4_slow(y[0], y[1], y[2], y[3], r01, r23, kSR, sat);
+    if (any_nan4(y)) return e5m2_pack4_slow(y[0], y[1], y[2], y[3], r01, r23, kSR, sat);
+    float z[4] = {y[0], y[1], y[2], y[3]};
+    if (sat) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) z[j] = saturate_finite(z[j]);
+    }
     int w = 0;
     if constexpr (kSR) {
-        w = __builtin_amdgcn_cvt_sr_bf8_f32(y[0], (int)(r01 << 16), w, 0);
-        w = __builtin_amdgcn_cvt_sr_bf8_f32(y[1], (int)(r01 & 0xFFFF0000u), w, 1);
-        w = __builtin_amdgcn_cvt_sr_bf8_f32(y[2], (int)(r23 << 16), w, 2);
-        w = __builtin_amdgcn_cvt_sr_bf8_f32(y[3], (int)(r23 & 0xFFFF0000u), w, 3);
+        w = __builtin_amdgcn_cvt_sr_bf8_f32(z[0], (int)(r01 << 16), w, 0);
+        w = __builtin_amdgcn_cvt_sr_bf8_f32(z[1], (int)(r01 & 0xFFFF0000u), w, 1);
+        w = __builtin_amdgcn_cvt_sr_bf8_f32(z[2], (int)(r23 << 16), w, 2);
+        w = __builtin_amdgcn_cvt_sr_bf8_f32(z[3], (int)(r23 & 0xFFFF0000u), w, 3);
     } else {
-        w = __builtin_amdgcn_cvt_pk_bf8_f32(y[0], y[1], w, false);
-        w = __builtin_amdgcn_cvt_pk_bf8_f32(y[2], y[3], w, true);
+        w = __builtin_amdgcn_cvt_pk_bf8_f32(z[0], z[1], w, false);
+        w = __builtin_amdgcn_cvt_pk_bf8_f32(z[2], z[3], w, true);
     }
     return (uint32_t)w;
 }
@@ -154,16 +168,21 @@ __device__ __forceinline__ uint32_t e5m2_pack4(const float y[4], uint32_t r01, u
 // The same with the rounding mode chosen at run time.
 __device__ __forceinline__ uint32_t e5m2_pack4_rt(const float y[4], uint32_t r01, uint32_t r23,
                                                   bool sr, bool sat) {
-    if (sat || any_nan4(y)) return e5m2_pack4_slow(y[0], y[1], y[2], y[3], r01, r23, sr, sat);
+    if (any_nan4(y)) return e5m2_pack4_slow(y[0], y[1], y[2], y[3], r01, r23, sr, sat);
+    float z[4] = {y[0], y[1], y[2], y[3]};
+    if (sat) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) z[j] = saturate_finite(z[j]);
+    }
     int w = 0;
     if (sr) {
-        w = __builtin_amdgcn_cvt_sr_bf8_f32(y[0], (int)(r01 << 16), w, 0);
-        w = __builtin_amdgcn_cvt_sr_bf8_f32(y[1], (int)(r01 & 0xFFFF0000u), w, 1);
-        w = __builtin_amdgcn_cvt_sr_bf8_f32(y[2], (int)(r23 << 16), w, 2);
-        w = __builtin_amdgcn_cvt_sr_bf8_f32(y[3], (int)(r23 & 0xFFFF0000u), w, 3);
+        w = __builtin_amdgcn_cvt_sr_bf8_f32(z[0], (int)(r01 << 16), w, 0);
+        w = __builtin_amdgcn_cvt_sr_bf8_f32(z[1], (int)(r01 & 0xFFFF0000u), w, 1);
+        w = __builtin_amdgcn_cvt_sr_bf8_f32(z[2], (int)(r23 << 16), w, 2);
+        w = __builtin_amdgcn_cvt_sr_bf8_f32(z[3], (int)(r23 & 0xFFFF0000u), w, 3);
     } else {
-        w = __builtin_amdgcn_cvt_pk_bf8_f32(y[0], y[1], w, false);
-        w = __builtin_amdgcn_cvt_pk_bf8_f32(y[2], y[3], w, true);
+        w = __builtin_amdgcn_cvt_pk_bf8_f32(z[0], z[1], w, false);
+        w = __builtin_amdgcn_cvt_pk_bf8_f32(z[2], z[3], w, true);
     }
     return (uint32_t)w;
 }

@@ -141,7 +141,7 @@ def test_every_fp32_bit_pattern_rne(mp8, quarter):
 
 def test_every_16th_fp32_bit_pattern_sr_and_saturating(mp8):
     """2^28 FP32 inputs spread over the whole range with stochastic rounding (Philox bits by
-    element index), and the same inputs with nearest-even rounding in the saturating mode."""
+    element index), and the same inputs in the saturating mode under both rounding rules."""
     import torch
     n = 1 << 26
     dst = torch.empty((1 << 13, 1 << 13), dtype=torch.uint8, device="cuda")
@@ -150,7 +150,8 @@ def test_every_16th_fp32_bit_pattern_sr_and_saturating(mp8):
         x = x.astype(np.uint32).view(np.float32).reshape(1 << 13, 1 << 13)
         xd = gpu(x)
         for kw in (dict(round=oracle.SR, seed=0xABCDEF + chunk, offset=chunk),
-                   dict(round=oracle.RNE, flags=oracle.FLAG_SATURATE)):
+                   dict(round=oracle.RNE, flags=oracle.FLAG_SATURATE),
+                   dict(round=oracle.SR, flags=oracle.FLAG_SATURATE, seed=77, offset=chunk)):
             mp8.quantize_e5m2(xd, dst, **kw)
             torch.cuda.synchronize()
             want, _ = oracle.quantize_e5m2(x, mode=kw.get("round"), flags=kw.get("flags", 0),
