@@ -43,8 +43,15 @@ typedef enum { MP8_RNE = 0, MP8_SR = 1 } mp8_round;
 /* Which of the three training GEMMs (Section 3, Figure 1a). */
 typedef enum { MP8_FWD = 0, MP8_BWD_DATA = 1, MP8_WGRAD = 2 } mp8_op;
 
-/* Finite values beyond the largest normal (57344) become +-57344 instead of +-Inf. */
-enum { MP8_FLAG_SATURATE = 1 };
+enum {
+    /* Finite values beyond the largest normal (57344) become +-57344 instead of +-Inf. */
+    MP8_FLAG_SATURATE = 1,
+    /* mp8_gemm_fp8 only: both operands are stored with the contraction index as the slow one,
+     * a [kc, rows] and b [kc, cols], i.e. out[r, c] = sum_j a[j, r] * b[j, c].  For the weight
+     * gradient that is X8 [M, K] and dY8 [M, N] as the Q node writes them, so no transposed
+     * copies are needed. */
+    MP8_FLAG_CONTRACTION_MAJOR = 2
+};
 
 typedef struct {
     uint32_t amax_bits; /* max over elements of the FP32 bit pattern of |value before
@@ -81,7 +88,8 @@ mp8_status mp8_quantize_e5m2(const void *src, int src_is_f16, uint8_t *dst, uint
  *     MP8_FWD       a = X8   [M, K]   b = W8^T  [N, K]   out [M, N]   contraction K
  *     MP8_BWD_DATA  a = dY8  [M, N]   b = W8    [K, N]   out [M, K]   contraction N
  *     MP8_WGRAD     a = X8^T [K, M]   b = dY8^T [N, M]   out [K, N]   contraction M
- *   lda, ldb   leading dimensions in elements (>= contraction length, multiples of 16)
+ *   lda, ldb   leading dimensions in elements (>= contraction length, multiples of 16; with
+ *              MP8_FLAG_CONTRACTION_MAJOR: >= rows resp. cols of the output)
  *   a, b       16-byte aligned
  *   alpha      out8 = Q(fl32(alpha * acc)); acc itself is stored unscaled
  *   acc        nullable FP32 [rows, cols] (16-byte aligned).  acc_mode 0: not touched;

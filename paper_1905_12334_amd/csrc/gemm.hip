@@ -33,19 +33,44 @@ namespace mp8 {
 
 using i32x8 = int __attribute__((ext_vector_type(8)));
 using i32x4 = int __attribute__((ext_vector_type(4)));
+using i32x2 = int __attribute__((ext_vector_type(2)));
 using f32x16 = float __attribute__((ext_vector_type(16)));
 
 constexpr int BK = 128;  // bytes (= elements) of contraction per pipeline stage
 
 #ifdef MP8_TRACE
-// Diagnostic build only: cycle stamps of block 0, [wave][stage][point].
+// Diagnostic build only: cycle stamps of one block, [wave][stage][point].
+#ifndef MP8_TRACE_BLOCK
+#define MP8_TRACE_BLOCK 0
+#endif
 __device__ unsigned long long mp8_trace_buf[4][160][8];
-#define MP8_STAMP(pt) do { if (blockIdx.x == 0 && lane == 0 && t < 159) mp8_trace_buf[wave][t][pt] = __builtin_readcyclecounter(); } while (0)
-#define MP8_STAMP_PHASE(pt) do { if (blockIdx.x == 0 && (threadIdx.x & 63) == 0) mp8_trace_buf[threadIdx.x >> 6][159][pt] = __builtin_readcyclecounter(); } while (0)
+#define MP8_STAMP(pt) do { if (blockIdx.x == MP8_TRACE_BLOCK && lane == 0 && t < 159) mp8_trace_buf[wave][t][pt] = __builtin_readcyclecounter(); } while (0)
+#define MP8_STAMP_PHASE(pt) do { if (blockIdx.x == MP8_TRACE_BLOCK && (threadIdx.x & 63) == 0) mp8_trace_buf[threadIdx.x >> 6][159][pt] = __builtin_readcyclecounter(); } while (0)
 #else
 #define MP8_STAMP(pt) do { } while (0)
 #define MP8_STAMP_PHASE(pt) do { } while (0)
 #endif
+
+// Division of a 31-bit number by a fixed divisor with a precomputed reciprocal:
+// m = floor(2^32 / d) (all ones for d = 1) makes mulhi(x, m) the quotient or one less.
+struct FastDiv {
+    uint32_t d, m;
+};
+static inline FastDiv make_fastdiv(uint32_t d) {
+    FastDiv f;
+    f.d = d;
+    f.m = d <= 1 ? 0xFFFFFFFFu : (uint32_t)((1ull << 32) / d);
+    return f;
+}
+__device__ __forceinline__ uint32_t fastdiv(uint32_t x, const FastDiv &f, uint32_t &rem) {
+    uint32_t q = __umulhi(x, f.m);
+    rem = x - q * f.d;
+    if (rem >= f.d) {
+        ++q;
+        rem -= f.d;
+    }
+    return q;
+}
 
 struct Epilogue {
     float alpha;
@@ -68,6 +93,12 @@ struct GemmArgs {
     int ksteps;         // contraction length / BK (pipeline stages)
     int splits;         // number of contraction slices
     int tiles_m, tiles_n;
+    // host-side precomputation for the workgroup -> (slice, tile) map, so that the kernel's
+    // start-up does no integer division
+    FastDiv div_tiles;  // by tiles_m * tiles_n
+    FastDiv div_band;   // by 8 * tiles_n
+    FastDiv div_tail;   // by the height of the last band of tile rows (tiles_m % 8, or 8)
+    int ks_per, ks_extra;  // ksteps / splits and ksteps % splits
     float *partial;     // [splits, rows, cols] when splits > 1
     Epilogue ep;
 };
@@ -152,22 +183,24 @@ __device__ __forceinline__ void finish16(const Epilogue &ep, int64_t r, int64_t 
 // different XCDs (round robin), so ids are first regrouped so that each XCD works on a
 // contiguous range of tiles and its L2 sees operand reuse; inside the range, tiles are
 // walked in bands of 8 tile-rows.
-__device__ __forceinline__ void map_block(int tiles_m, int tiles_n, int &split, int &tm, int &tn) {
-    const int nb = (int)gridDim.x, bid = (int)blockIdx.x;
-    const int xcd = bid & 7, idx = bid >> 3;
-    const int per = nb >> 3, rem = nb & 7;
-    const int pid = xcd * per + (xcd < rem ? xcd : rem) + idx;
-    const int tiles = tiles_m * tiles_n;
-    split = pid / tiles;
-    const int t = pid - split * tiles;
-    constexpr int GM = 8;
-    const int band = GM * tiles_n;
-    const int g = t / band;
-    const int first = g * GM;
-    const int gsz = (tiles_m - first) < GM ? (tiles_m - first) : GM;
-    const int in = t - g * band;
-    tm = first + in % gsz;
-    tn = in / gsz;
+__device__ __forceinline__ void map_block(const GemmArgs &p, int &split, int &tm, int &tn) {
+    const uint32_t nb = gridDim.x, bid = blockIdx.x;
+    const uint32_t xcd = bid & 7, idx = bid >> 3;
+    const uint32_t per = nb >> 3, rem = nb & 7;
+    const uint32_t pid = xcd * per + (xcd < rem ? xcd : rem) + idx;
+    uint32_t t, in;
+    split = (int)fastdiv(pid, p.div_tiles, t);
+    constexpr uint32_t GM = 8;
+    const uint32_t g = fastdiv(t, p.div_band, in);
+    const uint32_t first = g * GM;
+    if ((uint32_t)p.tiles_m - first >= GM) {
+        tm = (int)(first + (in & (GM - 1)));
+        tn = (int)(in >> 3);
+    } else {
+        uint32_t r;
+        tn = (int)fastdiv(in, p.div_tail, r);
+        tm = (int)(first + r);
+    }
 }
 
 // Wait until at most n vector-memory operations of this wave are outstanding and all of its
@@ -231,8 +264,9 @@ __device__ __forceinline__ uint32_t lds_address(const void *p) {
 //   EPI_FULL     out8 with run-time rounding mode, saturation and statistics
 enum { EPI_PARTIAL = 0, EPI_RNE = 1, EPI_FULL = 2 };
 
-template <int BM, int BN, int WGM, int WGN, int NSTAGE, int MINBLOCKS, int EPI>
+template <int BM, int BN, int WGM, int WGN, int NSTAGE, int MINBLOCKS, int EPI, bool TN = false>
 __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArgs p) {
+    static_assert(!TN || (BM % 128 == 0 && BN % 128 == 0), "contraction-major operands: 128-row panels");
     static_assert(WGM * WGN == 4, "four waves");
     static_assert(NSTAGE >= 2, "ring depth");
     constexpr int WTM = BM / WGM, WTN = BN / WGN;  // wave tile
@@ -248,7 +282,7 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
 
     MP8_STAMP_PHASE(0);
     int split, tm, tn;
-    map_block(p.tiles_m, p.tiles_n, split, tm, tn);
+    map_block(p, split, tm, tn);
     split = __builtin_amdgcn_readfirstlane(split);
     tm = __builtin_amdgcn_readfirstlane(tm);
     tn = __builtin_amdgcn_readfirstlane(tn);
@@ -258,7 +292,7 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     const int64_t row0 = (int64_t)tm * BM, col0 = (int64_t)tn * BN;
 
     // contraction slice of this workgroup, in stages of 128
-    const int per = p.ksteps / p.splits, extra = p.ksteps % p.splits;
+    const int per = p.ks_per, extra = p.ks_extra;
     const int ks_begin = split * per + (split < extra ? split : extra);
     const int ks_count = __builtin_amdgcn_readfirstlane(per + (split < extra ? 1 : 0));
 
@@ -267,28 +301,51 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     // of that row; with row = 8*(wave + 4q) + i/8 that is ((4*wave + i/16) & 7).  Rows beyond
     // the matrix are clamped to its last row (never stored).  Addresses are a wave-uniform
     // base (tile origin + stage) plus a 32-bit lane offset.
+    //
+    // Contraction-major operands (TN: a is [kc, rows], b is [kc, cols]) use the same LDS
+    // geometry with the roles swapped: a slab is cut into panels of 128 tile rows, each panel
+    // is 128 contraction rows of 128 bytes, chunk c of contraction row k sits in slot
+    // c ^ ((k >> 1) & 7).  Chunks that would start beyond the matrix are clamped to its last
+    // 16 rows (never stored).
     const int lrow = lane >> 3, lchunk = (lane & 7) ^ ((4 * wave + (lane >> 4)) & 7);
-    const uint8_t *a_tile = uniform_ptr(p.a + row0 * p.lda + (int64_t)ks_begin * BK);
-    const uint8_t *b_tile = uniform_ptr(p.b + col0 * p.ldb + (int64_t)ks_begin * BK);
+    const int64_t a_kstep = TN ? (int64_t)BK * p.lda : BK, b_kstep = TN ? (int64_t)BK * p.ldb : BK;
+    const uint8_t *a_tile =
+        uniform_ptr(TN ? p.a + (int64_t)ks_begin * a_kstep + row0 : p.a + row0 * p.lda + (int64_t)ks_begin * BK);
+    const uint8_t *b_tile =
+        uniform_ptr(TN ? p.b + (int64_t)ks_begin * b_kstep + col0 : p.b + col0 * p.ldb + (int64_t)ks_begin * BK);
     uint32_t oa[A_DMA], ob[B_DMA];
 #pragma unroll
     for (int q = 0; q < A_DMA; ++q) {
-        int64_t r = 8 * (wave + 4 * q) + lrow;
-        r = row0 + r < p.rows ? r : p.rows - 1 - row0;
-        oa[q] = (uint32_t)(r * p.lda) + lchunk * 16;
+        if constexpr (TN) {
+            const int64_t krow = 8 * (wave + 4 * (q & 3)) + lrow;
+            int64_t m = 128 * (q >> 2) + 16 * lchunk;
+            m = row0 + m + 16 <= p.rows ? m : p.rows - 16 - row0;
+            oa[q] = (uint32_t)(krow * p.lda + m);
+        } else {
+            int64_t r = 8 * (wave + 4 * q) + lrow;
+            r = row0 + r < p.rows ? r : p.rows - 1 - row0;
+            oa[q] = (uint32_t)(r * p.lda) + lchunk * 16;
+        }
     }
 #pragma unroll
     for (int q = 0; q < B_DMA; ++q) {
-        int64_t c = 8 * (wave + 4 * q) + lrow;
-        c = col0 + c < p.cols ? c : p.cols - 1 - col0;
-        ob[q] = (uint32_t)(c * p.ldb) + lchunk * 16;
+        if constexpr (TN) {
+            const int64_t krow = 8 * (wave + 4 * (q & 3)) + lrow;
+            int64_t m = 128 * (q >> 2) + 16 * lchunk;
+            m = col0 + m + 16 <= p.cols ? m : p.cols - 16 - col0;
+            ob[q] = (uint32_t)(krow * p.ldb + m);
+        } else {
+            int64_t c = 8 * (wave + 4 * q) + lrow;
+            c = col0 + c < p.cols ? c : p.cols - 1 - col0;
+            ob[q] = (uint32_t)(c * p.ldb) + lchunk * 16;
+        }
     }
     const uint32_t lds0 = lds_address(lds);
     auto issue_loads = [&](int kstage) {
         const uint32_t sa = lds0 + (kstage % NSTAGE) * STAGE + wave * 1024;
         const uint32_t sb = sa + A_BYTES;
-        const uint8_t *ak = a_tile + (int64_t)kstage * BK;
-        const uint8_t *bk = b_tile + (int64_t)kstage * BK;
+        const uint8_t *ak = a_tile + (int64_t)kstage * a_kstep;
+        const uint8_t *bk = b_tile + (int64_t)kstage * b_kstep;
 #pragma unroll
         for (int q = 0; q < A_DMA; ++q) dma16(ak, oa[q], sa + q * 4096);
 #pragma unroll
@@ -310,9 +367,30 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     };
     auto read_half = [&](int kstage, int sub, int f, int half, Frags &fr) {
         const uint8_t *s = lds + (kstage % NSTAGE) * STAGE;
-        const int chunk = ((4 * sub + 2 * fkb + half) ^ fsw) * 16;
-        const int base = f < MT ? a_base + f * 32 * BK : b_base + (f - MT) * 32 * BK;
-        fr.h[f][half] = *reinterpret_cast<const i32x4 *>(s + base + chunk);
+        if constexpr (TN) {
+            // Transposing LDS reads: the 16 lanes of a group each name 8 bytes ("row" t of a
+            // 16x8 block), and lane l of the group receives, as byte b, byte l%8 of row
+            // 2b + l/8.  With row t = contraction index k0 + t/2, tile rows m0 + 8*(t%2) .. +7,
+            // lane l ends up with contraction indices k0 .. k0+7 of tile row m0 + l.  Four such
+            // reads make the 32 bytes a lane feeds to one MFMA.
+            const int t = lane & 15;
+            const int m = (f < MT ? wm * WTM + f * 32 : wn * WTN + (f - MT) * 32) + (frow & 16);
+            const int obase = (f < MT ? 0 : A_BYTES) + (m >> 7) * 16384;
+            const int mc = (m & 127) >> 4;
+            i32x2 part[2];
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const int k = 64 * sub + 32 * fkb + 8 * (2 * half + e) + (t >> 1);
+                const int off = obase + k * 128 + ((mc ^ ((k >> 1) & 7)) << 4) + 8 * (t & 1);
+                part[e] = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
+                    (__attribute__((address_space(3))) i32x2 *)(s + off));
+            }
+            fr.h[f][half] = i32x4{part[0].x, part[0].y, part[1].x, part[1].y};
+        } else {
+            const int chunk = ((4 * sub + 2 * fkb + half) ^ fsw) * 16;
+            const int base = f < MT ? a_base + f * 32 * BK : b_base + (f - MT) * 32 * BK;
+            fr.h[f][half] = *reinterpret_cast<const i32x4 *>(s + base + chunk);
+        }
     };
 
     f32x16 acc[MT][NT];
@@ -337,9 +415,9 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     auto issue_one = [&](int kstage, int q) {  // load q (0 .. G-1) of a stage
         const uint32_t sa = lds0 + (kstage % NSTAGE) * STAGE + wave * 1024;
         if (q < A_DMA)
-            dma16(a_tile + (int64_t)kstage * BK, oa[q < A_DMA ? q : 0], sa + q * 4096);
+            dma16(a_tile + (int64_t)kstage * a_kstep, oa[q < A_DMA ? q : 0], sa + q * 4096);
         else
-            dma16(b_tile + (int64_t)kstage * BK, ob[q >= A_DMA ? q - A_DMA : 0],
+            dma16(b_tile + (int64_t)kstage * b_kstep, ob[q >= A_DMA ? q - A_DMA : 0],
                   sa + A_BYTES + (q - A_DMA) * 4096);
     };
 
@@ -485,7 +563,9 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         MP8_STAMP_PHASE(5);
-#pragma nounroll
+        // the RNE-only variant is small enough to unroll: the LDS reads of several items then
+        // overlap instead of each item paying the full LDS latency
+#pragma unroll(EPI == EPI_RNE ? 4 : 1)
         for (int item = lane; item < BANDS * 32 * CG; item += 64) {
             const int br = item / CG, cg = item - br * CG;
             const int64_t r = row0 + wm * WTM + 32 * h + br;
@@ -625,17 +705,19 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const float *__restr
 __global__ __launch_bounds__(256) void gemm_generic_kernel(const uint8_t *__restrict__ a,
                                                            int64_t lda,
                                                            const uint8_t *__restrict__ b,
-                                                           int64_t ldb, int64_t kc,
+                                                           int64_t ldb, int64_t kc, int tn,
                                                            const Epilogue ep) {
     const int64_t total = ep.rows * ep.cols;
     StatsAcc st;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += stride) {
         const int64_t r = t / ep.cols, c = t - r * ep.cols;
-        const uint8_t *ar = a + r * lda, *bc = b + c * ldb;
+        // element (r, j) of a: a[r * lda + j], or a[j * lda + r] for contraction-major operands
+        const uint8_t *ar = tn ? a + r : a + r * lda, *bc = tn ? b + c : b + c * ldb;
+        const int64_t sa = tn ? lda : 1, sb = tn ? ldb : 1;
         float s = 0.f;
         for (int64_t j = 0; j < kc; ++j)
-            s = __builtin_fmaf(e5m2_to_f32(ar[j]), e5m2_to_f32(bc[j]), s);
+            s = __builtin_fmaf(e5m2_to_f32(ar[j * sa]), e5m2_to_f32(bc[j * sb]), s);
         finish1(ep, r, c, s, st);
     }
     if (ep.stats != nullptr) st.flush(ep.stats);
@@ -647,21 +729,30 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const uint8_t *__rest
 struct TileConfig {
     int bm, bn;
     const char *name;
-    void (*kernel[3])(const GemmArgs);  // indexed by EPI_*
+    void (*kernel[3])(const GemmArgs);     // indexed by EPI_*
+    void (*kernel_tn[3])(const GemmArgs);  // contraction-major operands; null if not built
 };
 
 #define MP8_TILE(BM, BN, WGM, WGN, NS, MB)                                   \
     {BM, BN, #BM "x" #BN "x128s" #NS,                                         \
      {gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_PARTIAL>,                \
       gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_RNE>,                    \
-      gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_FULL>}}
+      gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_FULL>},                  \
+     {nullptr, nullptr, nullptr}}
+#define MP8_TILE_TN(BM, BN, WGM, WGN, NS, MB)                                \
+    {BM, BN, #BM "x" #BN "x128s" #NS,                                         \
+     {gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_PARTIAL>,                \
+      gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_RNE>,                    \
+      gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_FULL>},                  \
+     {gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_PARTIAL, true>,          \
+      gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_RNE, true>,              \
+      gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_FULL, true>}}
 static const TileConfig kTiles[] = {
-    MP8_TILE(256, 256, 2, 2, 2, 1), MP8_TILE(256, 128, 2, 2, 3, 1), MP8_TILE(128, 256, 2, 2, 3, 1),
-    MP8_TILE(128, 128, 2, 2, 2, 2), MP8_TILE(128, 128, 2, 2, 4, 1), MP8_TILE(64, 128, 1, 4, 3, 2),
+    MP8_TILE_TN(256, 256, 2, 2, 2, 1), MP8_TILE(256, 128, 2, 2, 3, 1), MP8_TILE(128, 256, 2, 2, 3, 1),
+    MP8_TILE_TN(128, 128, 2, 2, 2, 2), MP8_TILE_TN(128, 128, 2, 2, 4, 1), MP8_TILE(64, 128, 1, 4, 3, 2),
     MP8_TILE(128, 64, 4, 1, 3, 2),  MP8_TILE(64, 64, 2, 2, 4, 2),   MP8_TILE(64, 128, 1, 4, 2, 3),
     MP8_TILE(128, 64, 4, 1, 2, 3),  MP8_TILE(64, 64, 2, 2, 2, 4),
 };
-#undef MP8_TILE
 constexpr int kNumTiles = (int)(sizeof(kTiles) / sizeof(kTiles[0]));
 constexpr int kCUs = 256;
 constexpr int kMaxSplits = 64;
@@ -689,9 +780,13 @@ static void op_dims(mp8_op op, int64_t M, int64_t N, int64_t K, int64_t &rows, i
 // outputs take 64x64 tiles and, if even those are too few, a split contraction -- kept to a
 // minimum because the second pass costs several microseconds.
 enum { T256x256 = 0, T128x128s2 = 3, T128x128s4 = 4, T128x64s2 = 9, T64x64s2 = 10 };
-static Plan make_plan(int64_t rows, int64_t cols, int64_t kc, int tile_config, int split_k) {
+static Plan make_plan(int64_t rows, int64_t cols, int64_t kc, int tile_config, int split_k,
+                      bool tn = false) {
     Plan pl{};
     pl.mfma = (kc % BK) == 0 && kc > 0;
+    // contraction-major operands are fetched in 16-row chunks, by the tiles built for them
+    if (tn && ((rows & 15) != 0 || (cols & 15) != 0)) pl.mfma = false;
+    if (tn && tile_config > 0 && kTiles[tile_config - 1].kernel_tn[0] == nullptr) pl.mfma = false;
     if (!pl.mfma) {
         pl.splits = 1;
         return pl;
@@ -707,6 +802,7 @@ static Plan make_plan(int64_t rows, int64_t cols, int64_t kc, int tile_config, i
         const int64_t n256 = count(T256x256), n128 = count(T128x128s2);
         const double fill256 = (double)n256 / (double)(((n256 + kCUs - 1) / kCUs) * kCUs);
         if (n256 >= 208 && fill256 >= 0.8 && ksteps >= 8) t = T256x256;
+        else if (tn) t = ksteps >= 64 ? T128x128s4 : T128x128s2;
         else if (n128 >= 192 && ksteps <= 2) t = T128x64s2;  // all prologue and epilogue
         else if (n128 >= 192) t = (ksteps >= 64 && n128 <= 2 * kCUs) ? T128x128s4 : T128x128s2;
         else t = T64x64s2;
@@ -754,7 +850,9 @@ extern "C" size_t mp8_gemm_fp8_workspace_bytes_tuned(mp8_op op, int64_t M, int64
     if (tile_config < 0 || tile_config > kNumTiles || split_k < 0) return 0;
     int64_t rows, cols, kc;
     op_dims(op, M, N, K, rows, cols, kc);
-    return plan_workspace(make_plan(rows, cols, kc, tile_config, split_k), rows, cols);
+    // enough for either operand layout
+    return std::max(plan_workspace(make_plan(rows, cols, kc, tile_config, split_k, false), rows, cols),
+                    plan_workspace(make_plan(rows, cols, kc, tile_config, split_k, true), rows, cols));
 }
 
 extern "C" size_t mp8_gemm_fp8_workspace_bytes(mp8_op op, int64_t M, int64_t N, int64_t K) {
@@ -780,7 +878,8 @@ extern "C" mp8_status mp8_gemm_fp8_tuned(mp8_op op, int64_t M, int64_t N, int64_
     if (rows == 0 || cols == 0) return MP8_OK;
     if (acc_mode != 0 && acc == nullptr) return MP8_ERR_INVALID_ARG;
     if (kc > 0 && (!a || !b)) return MP8_ERR_INVALID_ARG;
-    if (kc > 0 && (lda < kc || ldb < kc)) return MP8_ERR_INVALID_ARG;
+    const bool tn = (flags & MP8_FLAG_CONTRACTION_MAJOR) != 0;
+    if (kc > 0 && (tn ? (lda < rows || ldb < cols) : (lda < kc || ldb < kc))) return MP8_ERR_INVALID_ARG;
     if (rows > (INT64_MAX / 8) / cols) return MP8_ERR_UNSUPPORTED;
     if (((uintptr_t)acc | (uintptr_t)out8 | (uintptr_t)out8_t | (uintptr_t)workspace) & 15u)
         return MP8_ERR_ALIGNMENT;
@@ -800,7 +899,7 @@ extern "C" mp8_status mp8_gemm_fp8_tuned(mp8_op op, int64_t M, int64_t N, int64_
     ep.cols = cols;
     hipStream_t s = (hipStream_t)stream;
 
-    Plan pl = make_plan(rows, cols, kc, tile_config, split_k);
+    Plan pl = make_plan(rows, cols, kc, tile_config, split_k, tn);
     // the MFMA kernel wants 16-byte aligned rows and 32-bit offsets inside a 256-row tile
     const bool aligned = (((uintptr_t)a | (uintptr_t)b) & 15u) == 0 && (lda & 15) == 0 &&
                          (ldb & 15) == 0 && lda < (1 << 24) && ldb < (1 << 24);
@@ -814,7 +913,7 @@ extern "C" mp8_status mp8_gemm_fp8_tuned(mp8_op op, int64_t M, int64_t N, int64_
     if (!pl.mfma || kc == 0) {
         int64_t blocks = std::min<int64_t>((rows * cols + 255) / 256, 1 << 20);
         hipLaunchKernelGGL(gemm_generic_kernel, dim3((unsigned)blocks), dim3(256), 0, s, a, lda, b,
-                           ldb, kc, ep);
+                           ldb, kc, tn ? 1 : 0, ep);
         return hipGetLastError() == hipSuccess ? MP8_OK : MP8_ERR_HIP;
     }
 
@@ -847,12 +946,18 @@ extern "C" mp8_status mp8_gemm_fp8_tuned(mp8_op op, int64_t M, int64_t N, int64_
     ga.splits = pl.splits;
     ga.tiles_m = pl.tiles_m;
     ga.tiles_n = pl.tiles_n;
+    ga.div_tiles = make_fastdiv((uint32_t)(pl.tiles_m * pl.tiles_n));
+    ga.div_band = make_fastdiv((uint32_t)(8 * pl.tiles_n));
+    ga.div_tail = make_fastdiv((uint32_t)((pl.tiles_m & 7) ? (pl.tiles_m & 7) : 8));
+    ga.ks_per = ga.ksteps / pl.splits;
+    ga.ks_extra = ga.ksteps % pl.splits;
     ga.partial = partial;
     ga.ep = ep;
     const int epi = two_pass ? EPI_PARTIAL
                              : (ep.sr || ep.sat || ep.stats != nullptr || out8 == nullptr) ? EPI_FULL
                                                                                             : EPI_RNE;
-    hipLaunchKernelGGL(kTiles[pl.tile].kernel[epi], dim3((unsigned)nblocks), dim3(256), 0, s, ga);
+    hipLaunchKernelGGL(tn ? kTiles[pl.tile].kernel_tn[epi] : kTiles[pl.tile].kernel[epi],
+                       dim3((unsigned)nblocks), dim3(256), 0, s, ga);
     if (hipGetLastError() != hipSuccess) return MP8_ERR_HIP;
     if (two_pass) {
         const bool only_acc = fin.acc_mode == 0 && fin.out8 == nullptr && fin.out8_t == nullptr &&

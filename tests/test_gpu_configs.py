@@ -53,10 +53,12 @@ def quantize_both(mp8, x, scale=1.0, with_stats=False, **kw):
 
 
 def gemm_checked(mp8, op, dims, a_dev, b_dev, a8, b8, nsample=40, alpha=1.0, mode=oracle.RNE,
-                 seed=0, offset=0, acc_in=None, acc_mode=1):
+                 seed=0, offset=0, acc_in=None, acc_mode=1, flags=0):
     """One GEMM as the benchmark calls it (8-bit output only, automatic plan), and again with the
     FP32 accumulator exposed; both must give the same codes; the accumulator is checked against
-    the double reference on sampled rows.  Returns (acc, out8) as host arrays."""
+    the double reference on sampled rows.  a8 / b8 are the host operands in the plain layout
+    ([rows, kc] and [cols, kc]); with the contraction-major flag the device tensors are their
+    transposes.  Returns (acc as device tensor, out8 as host array)."""
     import torch
     M, N, K = dims
     rows, kc = a8.shape
@@ -67,7 +69,7 @@ def gemm_checked(mp8, op, dims, a_dev, b_dev, a8, b8, nsample=40, alpha=1.0, mod
     acc = torch.zeros((rows, cols), dtype=torch.float32, device="cuda")
     if acc_in is not None:
         acc.copy_(acc_in)
-    kw = dict(alpha=alpha, round=mode, seed=seed, offset=offset, workspace=ws)
+    kw = dict(alpha=alpha, round=mode, seed=seed, offset=offset, workspace=ws, flags=flags)
     if acc_mode == 1:
         mp8.gemm_fp8(op, M, N, K, a_dev, b_dev, out8=out_a, **kw)
     mp8.gemm_fp8(op, M, N, K, a_dev, b_dev, out8=out_b, acc=acc, acc_mode=acc_mode, **kw)
@@ -98,6 +100,10 @@ def test_config2_resnet_conv_layer_full_step(mp8):
     gemm_checked(mp8, mp8.FWD, (M, N, K), X8d, W8td, X8, W8t)
     gemm_checked(mp8, mp8.BWD_DATA, (M, N, K), E8d, W8d, E8, W8)
     _, G8 = gemm_checked(mp8, mp8.WGRAD, (M, N, K), X8td, E8td, X8t, E8t, nsample=96)
+    # the same weight gradient straight from the row-major X8 and E8 (what the benchmark runs)
+    _, G8b = gemm_checked(mp8, mp8.WGRAD, (M, N, K), X8d, E8d, X8t, E8t, nsample=96,
+                          flags=mp8.FLAG_CONTRACTION_MAJOR)
+    assert np.abs(G8.astype(np.int32) - G8b.astype(np.int32)).max() <= 1   # different slicing only
     w16 = lay.W.astype(np.float16).view(np.uint16).reshape(-1)
     wd = gpu(w16.view(np.int16))
     mp8.sgd_update_fp16_sr(wd, gpu(G8.reshape(-1)), 1e-3, 1.0 / lay.loss_scale, round=mp8.SR,
@@ -190,6 +196,8 @@ def test_config5_transformer_big_wgrad_sr_and_update(mp8):
     assert est[1] == 0
     _, G8 = gemm_checked(mp8, mp8.WGRAD, (M, N, K), X8td, E8td, X8t, E8t, nsample=20,
                          mode=oracle.SR, seed=seed, offset=11)
+    gemm_checked(mp8, mp8.WGRAD, (M, N, K), X8d, E8d, X8t, E8t, nsample=20, mode=oracle.SR,
+                 seed=seed, offset=11, flags=mp8.FLAG_CONTRACTION_MAJOR)
     w16 = lay.W.astype(np.float16).view(np.uint16).reshape(-1)
     for rnd in (oracle.SR, oracle.RNE):
         wd = gpu(w16.view(np.int16))

@@ -256,3 +256,82 @@ def test_alpha_saturate_stats_nonfinite_and_determinism(mp8):
     torch.cuda.synchronize()
     ref, _ = oracle.gemm_ref(big_a[:, 128:384], big_b[:, 256:512], want_abs=False)
     assert np.array_equal(host(accl).reshape(64, 64).astype(np.float64), ref)
+
+
+def run_gemm_tn(mp8, a_km, b_km, **kw):
+    """out[r,c] = sum_j a_km[j,r] b_km[j,c] with contraction-major operands; returns (acc, out8)."""
+    import torch
+    kc, rows = a_km.shape
+    cols = b_km.shape[1]
+    tile, split = kw.pop("tile_config", 0), kw.pop("split_k", 0)
+    ws = torch.empty(max(mp8.gemm_fp8_workspace_bytes(mp8.FWD, rows, cols, kc, tile, split), 16),
+                     dtype=torch.uint8, device="cuda")
+    acc = torch.full((rows * cols + 16,), 7.0, dtype=torch.float32, device="cuda")
+    obuf = torch.full((rows * cols + 64,), 0xAA, dtype=torch.uint8, device="cuda")
+    flags = kw.pop("flags", 0) | mp8.FLAG_CONTRACTION_MAJOR
+    mp8.gemm_fp8(mp8.FWD, rows, cols, kc, gpu(a_km), gpu(b_km), out8=obuf[: rows * cols],
+                 acc=acc[: rows * cols], acc_mode=1, workspace=ws, flags=flags, tile_config=tile,
+                 split_k=split, **kw)
+    o2 = torch.full((rows * cols + 64,), 0xAA, dtype=torch.uint8, device="cuda")
+    mp8.gemm_fp8(mp8.FWD, rows, cols, kc, gpu(a_km), gpu(b_km), out8=o2[: rows * cols], workspace=ws,
+                 flags=flags, tile_config=tile, split_k=split, **kw)
+    torch.cuda.synchronize()
+    assert bool((obuf[rows * cols:] == 0xAA).all()) and bool((o2[rows * cols:] == 0xAA).all())
+    assert bool((acc[rows * cols:] == 7.0).all())
+    out8 = host(obuf[: rows * cols]).reshape(rows, cols)
+    assert np.array_equal(host(o2[: rows * cols]).reshape(rows, cols), out8), "fused out8 differs"
+    return host(acc[: rows * cols]).reshape(rows, cols), out8
+
+
+def test_contraction_major_operands_exact_sums_every_capable_tile(mp8):
+    """Operands stored [contraction, rows]: the kernel's transposing LDS reads must deliver the
+    same sums as the plain layout; exact-sum codes make any mix-up of indices visible."""
+    rng = np.random.default_rng(21)
+    rows, cols, kc = 320, 288, 1024                   # ragged against 128- and 256-row tiles
+    a_km, b_km = exact_sum_codes(rng, (kc, rows)), exact_sum_codes(rng, (kc, cols))
+    ref, _ = oracle.gemm_ref(np.ascontiguousarray(a_km.T), np.ascontiguousarray(b_km.T), want_abs=False)
+    want8 = oracle.round_ref_e5m2(ref)
+    names = mp8.gemm_tile_configs()
+    tried = 0
+    for tile in range(0, len(names) + 1):
+        for split in (0, 1, 3):
+            try:
+                acc, out8 = run_gemm_tn(mp8, a_km, b_km, tile_config=tile, split_k=split)
+            except mp8.Mp8Error:
+                assert tile > 0              # a tile shape without contraction-major kernels
+                continue
+            tried += 1
+            assert np.array_equal(acc.astype(np.float64), ref), (tile, split)
+            assert np.array_equal(out8, want8), (tile, split)
+    assert tried >= 9
+
+
+@pytest.mark.parametrize("shape", [(128, 128, 128), (144, 16, 256), (400, 272, 384), (70, 50, 256),
+                                   (64, 64, 100)])
+def test_contraction_major_operands_random(mp8, shape):
+    rows, cols, kc = shape                            # the last two take the any-shape kernel
+    a_km = (workloads.random_e5m2_codes(rows, (kc, rows)) & 0x83) | 0x38
+    b_km = (workloads.random_e5m2_codes(cols + 7, (kc, cols)) & 0x83) | 0x38
+    acc, out8 = run_gemm_tn(mp8, a_km, b_km, round=oracle.SR, seed=4, offset=9)
+    ref, absref = oracle.gemm_ref(np.ascontiguousarray(a_km.T), np.ascontiguousarray(b_km.T))
+    check_outputs(acc, out8, ref, absref, kc, mode=oracle.SR, seed=4, offset=9)
+
+
+def test_weight_gradient_from_row_major_activations_and_errors(mp8):
+    """The weight gradient straight from X8 [M, K] and dY8 [M, N] as the Q node writes them
+    equals the one computed from the transposed copies."""
+    import torch
+    lay = workloads.config2(batch=2, hw=16, cin=128, cout=128)       # M=512, K=1152, N=128
+    X8, X8t, _, _, E8, E8t = _layer_operands(lay)
+    M, N, K = lay.M, lay.N, lay.K
+    acc_t, out_t, _, _ = run_gemm(mp8, X8t, E8t, op=mp8.WGRAD, dims=(M, N, K))
+    ws = torch.empty(max(mp8.gemm_fp8_workspace_bytes(mp8.WGRAD, M, N, K), 16), dtype=torch.uint8, device="cuda")
+    acc = torch.zeros((K, N), dtype=torch.float32, device="cuda")
+    out = torch.zeros((K, N), dtype=torch.uint8, device="cuda")
+    mp8.gemm_fp8(mp8.WGRAD, M, N, K, gpu(X8), gpu(E8), out8=out, acc=acc, acc_mode=1, workspace=ws,
+                 flags=mp8.FLAG_CONTRACTION_MAJOR)
+    torch.cuda.synchronize()
+    ref, absref = oracle.gemm_ref(X8t, E8t)
+    check_outputs(host(acc), host(out), ref, absref, M)
+    # both layouts feed the matrix cores the same products in the same order
+    assert np.array_equal(host(acc), acc_t) and np.array_equal(host(out), out_t)
