@@ -4,12 +4,15 @@
 One "step" is one pass of the whole hot path over one batch of synthetic input for the
 ResNet-50-style 3x3 convolution layer taken as a GEMM (M=25088, N=128, K=1152):
 
-    Q(X) -> X8            Q(W) -> W8, W8^T      Q(dY * 2^12) -> E8 (+ overflow stats)
+    Q(X) -> X8                                  Q(dY * 2^12) -> E8 (+ overflow stats)
     forward GEMM  Y8  = Q(X8 . W8)              contraction K
     backward-data dX8 = Q(E8 . W8^T)            contraction N
-    weight-grad   G8  = Q(X8^T . E8)            contraction M, read straight from the row-major
-                                                X8 and E8 (split, summed in FP32, one rounding)
-    update        W16 <- half_SR(W16 - lr * G8 / 2^12)
+    weight-grad   G8  = Q(X8^T . E8)            contraction M (split, summed in FP32, one rounding)
+    update        W16 <- half_SR(W16 - lr * G8 / 2^12),  W8 <- Q(W16) for the next step
+
+Every tensor exists once, row-major, as its producer wrote it: the GEMMs read X8 [M,K],
+E8 [M,N] and W8 [K,N] in whichever orientation they need (contraction-major operands go
+through transposing LDS reads), and the Q node on the weights is part of the update kernel.
 
 Inputs are resident in HBM before the timed region.  Prints ONE JSON line: `value` is the
 GEMM work of a step (3 * 2*M*N*K flop) divided by the time of the whole step (the steps are
@@ -75,7 +78,7 @@ class Workload:
         self.dY = torch.from_numpy(lay.dY).to(dev)
         self.W16 = torch.from_numpy(lay.W.astype(np.float16)).to(dev)
         self.X8 = torch.empty((M, K), dtype=u8, device=dev)
-        self.W8, self.W8t = torch.empty((K, N), dtype=u8, device=dev), torch.empty((N, K), dtype=u8, device=dev)
+        self.W8 = torch.empty((K, N), dtype=u8, device=dev)
         self.E8 = torch.empty((M, N), dtype=u8, device=dev)
         self.Y8 = torch.empty((M, N), dtype=u8, device=dev)
         self.dX8 = torch.empty((M, K), dtype=u8, device=dev)
@@ -85,34 +88,36 @@ class Workload:
         self.ws = torch.empty(max(ws, 16), dtype=u8, device=dev)
         self.step_no = 0
         mp8_ = mp8
-        tn = mp8_.FLAG_CONTRACTION_MAJOR
+        # Every GEMM reads the row-major tensors as their producers wrote them; no transposed
+        # copy of anything exists.  The 8-bit weights of a step are written by the previous
+        # step's update (its w8_out), i.e. the Q node on the weights is fused into the update.
         self.kernels = [
             # name, closure, algorithmic bytes, flops, bound
             ("quantize_X", lambda: mp8_.quantize_e5m2(self.X, self.X8), 5 * M * K, 0, "hbm"),
-            ("quantize_W", lambda: mp8_.quantize_e5m2(self.W, self.W8, self.W8t), 6 * K * N, 0, "hbm"),
             ("quantize_dY", lambda: mp8_.quantize_e5m2(self.dY, self.E8, scale=LOSS_SCALE,
                                                        stats=self.stats), 5 * M * N, 0, "hbm"),
-            ("gemm_fwd", lambda: mp8_.gemm_fp8(mp8_.FWD, M, N, K, self.X8, self.W8t, out8=self.Y8,
-                                               workspace=self.ws),
+            ("gemm_fwd", lambda: mp8_.gemm_fp8(mp8_.FWD, M, N, K, self.X8, self.W8, out8=self.Y8,
+                                               workspace=self.ws, flags=mp8_.FLAG_B_CONTRACTION_MAJOR),
              M * K + K * N + M * N, 2 * M * N * K, "mfma"),
             ("gemm_bwd_data", lambda: mp8_.gemm_fp8(mp8_.BWD_DATA, M, N, K, self.E8, self.W8,
                                                     out8=self.dX8, workspace=self.ws),
              M * N + K * N + M * K, 2 * M * N * K, "mfma"),
-            # the weight gradient reads X8 [M,K] and E8 [M,N] as the Q node wrote them
-            # (contraction index slow): no transposed copies of the two large tensors exist
             ("gemm_wgrad", lambda: mp8_.gemm_fp8(mp8_.WGRAD, M, N, K, self.X8, self.E8, out8=self.G8,
-                                                 workspace=self.ws, flags=tn),
+                                                 workspace=self.ws, flags=mp8_.FLAG_CONTRACTION_MAJOR),
              M * K + M * N + K * N, 2 * M * N * K, "mfma"),
-            ("sgd_update", self._update, 5 * K * N, 0, "hbm"),
+            ("sgd_update", self._update, 6 * K * N, 0, "hbm"),
         ]
+        # the weights of the first step: Q(W16), outside the timed region
+        mp8_.quantize_e5m2(self.W16.view(K, N), self.W8)
 
     def _update(self):
         # every step draws from its own Philox offset; the overflow count of the error tensor
-        # (left in stats by quantize_dY) makes the kernel skip the step without a host round trip
+        # (left in stats by quantize_dY) makes the kernel skip the step without a host round
+        # trip; the new master weights are also written as the next step's 8-bit weights
         self.step_no += 1
         self.mp8.sgd_update_fp16_sr(self.W16, self.G8, LR, 1.0 / LOSS_SCALE, round=self.mp8.SR,
                                     seed=0x1905_1233_4000_0002, offset=self.step_no,
-                                    skip_if_nonzero=self.stats[1:2])
+                                    skip_if_nonzero=self.stats[1:2], w8_out=self.W8)
 
     def step(self):
         self.stats.zero_()     # a small fill kernel (no memset node, so the step can be captured)
@@ -359,7 +364,7 @@ def main():
         "dtype": "fp8_e5m2 x fp8_e5m2 -> f32",
         "data": "synthetic",
         "config": {"workload": "configs[1]: ResNet-50-style 3x3 conv as GEMM, M=25088 N=128 K=1152, "
-                               "quantize + fwd + bwd_data + wgrad + FP16 SR update, loss scale 2^12",
+                               "quantize X and dY + fwd + bwd_data + wgrad + FP16 SR update emitting the next 8-bit weights, loss scale 2^12",
                    "M": lay.M, "N": lay.N, "K": lay.K, "launch": args.launch},
         "pct_of_fp8_peak_whole_step": 100.0 * value / FP8_PEAK_TFLOPS,
         "gemm_only_tflops": gemm_flops / (gemm_us * 1e-6) / 1e12,

@@ -46,11 +46,14 @@ typedef enum { MP8_FWD = 0, MP8_BWD_DATA = 1, MP8_WGRAD = 2 } mp8_op;
 enum {
     /* Finite values beyond the largest normal (57344) become +-57344 instead of +-Inf. */
     MP8_FLAG_SATURATE = 1,
-    /* mp8_gemm_fp8 only: both operands are stored with the contraction index as the slow one,
-     * a [kc, rows] and b [kc, cols], i.e. out[r, c] = sum_j a[j, r] * b[j, c].  For the weight
-     * gradient that is X8 [M, K] and dY8 [M, N] as the Q node writes them, so no transposed
-     * copies are needed. */
-    MP8_FLAG_CONTRACTION_MAJOR = 2
+    /* mp8_gemm_fp8 only: an operand is stored with the contraction index as the slow one:
+     * a as [kc, rows] (out[r, c] = sum_j a[j, r] * ...), b as [kc, cols].  With both flags the
+     * weight gradient reads X8 [M, K] and dY8 [M, N] as the Q node writes them; with the b flag
+     * alone the forward GEMM reads W8 [K, N]: no transposed copy of any tensor is needed.
+     * (a alone is not supported.) */
+    MP8_FLAG_A_CONTRACTION_MAJOR = 2,
+    MP8_FLAG_B_CONTRACTION_MAJOR = 4,
+    MP8_FLAG_CONTRACTION_MAJOR = 6
 };
 
 typedef struct {
@@ -89,7 +92,7 @@ mp8_status mp8_quantize_e5m2(const void *src, int src_is_f16, uint8_t *dst, uint
  *     MP8_BWD_DATA  a = dY8  [M, N]   b = W8    [K, N]   out [M, K]   contraction N
  *     MP8_WGRAD     a = X8^T [K, M]   b = dY8^T [N, M]   out [K, N]   contraction M
  *   lda, ldb   leading dimensions in elements (>= contraction length, multiples of 16; with
- *              MP8_FLAG_CONTRACTION_MAJOR: >= rows resp. cols of the output)
+ *              a contraction-major flag: >= rows resp. cols of the output)
  *   a, b       16-byte aligned
  *   alpha      out8 = Q(fl32(alpha * acc)); acc itself is stored unscaled
  *   acc        nullable FP32 [rows, cols] (16-byte aligned).  acc_mode 0: not touched;

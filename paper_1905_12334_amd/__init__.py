@@ -17,7 +17,9 @@ LIB_PATH = os.path.join(_HERE, "libmp8.so")
 RNE, SR = 0, 1
 FWD, BWD_DATA, WGRAD = 0, 1, 2
 FLAG_SATURATE = 1
-FLAG_CONTRACTION_MAJOR = 2
+FLAG_A_CONTRACTION_MAJOR = 2
+FLAG_B_CONTRACTION_MAJOR = 4
+FLAG_CONTRACTION_MAJOR = 6
 
 EXPORTS = [
     "mp8_quantize_e5m2", "mp8_gemm_fp8", "mp8_gemm_fp8_workspace_bytes", "mp8_gemm_fp8_tuned",
@@ -162,18 +164,17 @@ def gemm_fp8(op, M, N, K, a, b, out8=None, out8_t=None, acc=None, acc_mode=0, al
     _dev(out8_t, "out8_t", torch.uint8)
     _dev(acc, "acc", torch.float32)
     rows, cols, kc = _op_dims(op, M, N, K)
-    if flags & FLAG_CONTRACTION_MAJOR:      # a [kc, rows], b [kc, cols]
-        lda = rows if lda is None else lda
-        ldb = cols if ldb is None else ldb
-        if kc > 0 and (a.numel() < (kc - 1) * lda + rows or b.numel() < (kc - 1) * ldb + cols):
-            raise Mp8Error("a / b are smaller than [kc, lda] / [kc, ldb] require")
-    else:
-        lda = kc if lda is None else lda
-        ldb = kc if ldb is None else ldb
-        if rows > 0 and a.numel() < (rows - 1) * lda + kc:
-            raise Mp8Error("a is smaller than [rows, lda] requires")
-        if cols > 0 and b.numel() < (cols - 1) * ldb + kc:
-            raise Mp8Error("b is smaller than [cols, ldb] requires")
+    a_km, b_km = bool(flags & FLAG_A_CONTRACTION_MAJOR), bool(flags & FLAG_B_CONTRACTION_MAJOR)
+    if lda is None:
+        lda = rows if a_km else kc
+    if ldb is None:
+        ldb = cols if b_km else kc
+    need_a = ((kc - 1) * lda + rows if a_km else (rows - 1) * lda + kc) if rows > 0 and kc > 0 else 0
+    need_b = ((kc - 1) * ldb + cols if b_km else (cols - 1) * ldb + kc) if cols > 0 and kc > 0 else 0
+    if a.numel() < need_a:
+        raise Mp8Error("a is smaller than its shape and leading dimension require")
+    if b.numel() < need_b:
+        raise Mp8Error("b is smaller than its shape and leading dimension require")
     for t, name in ((out8, "out8"), (out8_t, "out8_t"), (acc, "acc")):
         if t is not None and t.numel() < rows * cols:
             raise Mp8Error(f"{name} is smaller than rows*cols")

@@ -264,9 +264,11 @@ __device__ __forceinline__ uint32_t lds_address(const void *p) {
 //   EPI_FULL     out8 with run-time rounding mode, saturation and statistics
 enum { EPI_PARTIAL = 0, EPI_RNE = 1, EPI_FULL = 2 };
 
-template <int BM, int BN, int WGM, int WGN, int NSTAGE, int MINBLOCKS, int EPI, bool TN = false>
+template <int BM, int BN, int WGM, int WGN, int NSTAGE, int MINBLOCKS, int EPI, bool ATN = false,
+          bool BTN = false>
 __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArgs p) {
-    static_assert(!TN || (BM % 128 == 0 && BN % 128 == 0), "contraction-major operands: 128-row panels");
+    static_assert((!ATN || BM % 128 == 0) && (!BTN || BN % 128 == 0),
+                  "contraction-major operands: 128-row panels");
     static_assert(WGM * WGN == 4, "four waves");
     static_assert(NSTAGE >= 2, "ring depth");
     constexpr int WTM = BM / WGM, WTN = BN / WGN;  // wave tile
@@ -302,21 +304,21 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     // the matrix are clamped to its last row (never stored).  Addresses are a wave-uniform
     // base (tile origin + stage) plus a 32-bit lane offset.
     //
-    // Contraction-major operands (TN: a is [kc, rows], b is [kc, cols]) use the same LDS
+    // Contraction-major operands (ATN: a is [kc, rows]; BTN: b is [kc, cols]) use the same LDS
     // geometry with the roles swapped: a slab is cut into panels of 128 tile rows, each panel
     // is 128 contraction rows of 128 bytes, chunk c of contraction row k sits in slot
     // c ^ ((k >> 1) & 7).  Chunks that would start beyond the matrix are clamped to its last
     // 16 rows (never stored).
     const int lrow = lane >> 3, lchunk = (lane & 7) ^ ((4 * wave + (lane >> 4)) & 7);
-    const int64_t a_kstep = TN ? (int64_t)BK * p.lda : BK, b_kstep = TN ? (int64_t)BK * p.ldb : BK;
+    const int64_t a_kstep = ATN ? (int64_t)BK * p.lda : BK, b_kstep = BTN ? (int64_t)BK * p.ldb : BK;
     const uint8_t *a_tile =
-        uniform_ptr(TN ? p.a + (int64_t)ks_begin * a_kstep + row0 : p.a + row0 * p.lda + (int64_t)ks_begin * BK);
+        uniform_ptr(ATN ? p.a + (int64_t)ks_begin * a_kstep + row0 : p.a + row0 * p.lda + (int64_t)ks_begin * BK);
     const uint8_t *b_tile =
-        uniform_ptr(TN ? p.b + (int64_t)ks_begin * b_kstep + col0 : p.b + col0 * p.ldb + (int64_t)ks_begin * BK);
+        uniform_ptr(BTN ? p.b + (int64_t)ks_begin * b_kstep + col0 : p.b + col0 * p.ldb + (int64_t)ks_begin * BK);
     uint32_t oa[A_DMA], ob[B_DMA];
 #pragma unroll
     for (int q = 0; q < A_DMA; ++q) {
-        if constexpr (TN) {
+        if constexpr (ATN) {
             const int64_t krow = 8 * (wave + 4 * (q & 3)) + lrow;
             int64_t m = 128 * (q >> 2) + 16 * lchunk;
             m = row0 + m + 16 <= p.rows ? m : p.rows - 16 - row0;
@@ -329,7 +331,7 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     }
 #pragma unroll
     for (int q = 0; q < B_DMA; ++q) {
-        if constexpr (TN) {
+        if constexpr (BTN) {
             const int64_t krow = 8 * (wave + 4 * (q & 3)) + lrow;
             int64_t m = 128 * (q >> 2) + 16 * lchunk;
             m = col0 + m + 16 <= p.cols ? m : p.cols - 16 - col0;
@@ -367,7 +369,7 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     };
     auto read_half = [&](int kstage, int sub, int f, int half, Frags &fr) {
         const uint8_t *s = lds + (kstage % NSTAGE) * STAGE;
-        if constexpr (TN) {
+        if ((f < MT && ATN) || (f >= MT && BTN)) {
             // Transposing LDS reads: the 16 lanes of a group each name 8 bytes ("row" t of a
             // 16x8 block), and lane l of the group receives, as byte b, byte l%8 of row
             // 2b + l/8.  With row t = contraction index k0 + t/2, tile rows m0 + 8*(t%2) .. +7,
@@ -712,9 +714,10 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const uint8_t *__rest
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += stride) {
         const int64_t r = t / ep.cols, c = t - r * ep.cols;
-        // element (r, j) of a: a[r * lda + j], or a[j * lda + r] for contraction-major operands
-        const uint8_t *ar = tn ? a + r : a + r * lda, *bc = tn ? b + c : b + c * ldb;
-        const int64_t sa = tn ? lda : 1, sb = tn ? ldb : 1;
+        // element (r, j) of a: a[r * lda + j], or a[j * lda + r] when a is contraction-major
+        // (bit 0 of tn; bit 1 likewise for b)
+        const uint8_t *ar = (tn & 1) ? a + r : a + r * lda, *bc = (tn & 2) ? b + c : b + c * ldb;
+        const int64_t sa = (tn & 1) ? lda : 1, sb = (tn & 2) ? ldb : 1;
         float s = 0.f;
         for (int64_t j = 0; j < kc; ++j)
             s = __builtin_fmaf(e5m2_to_f32(ar[j * sa]), e5m2_to_f32(bc[j * sb]), s);
@@ -730,7 +733,8 @@ struct TileConfig {
     int bm, bn;
     const char *name;
     void (*kernel[3])(const GemmArgs);     // indexed by EPI_*
-    void (*kernel_tn[3])(const GemmArgs);  // contraction-major operands; null if not built
+    void (*kernel_tn[3])(const GemmArgs);  // both operands contraction-major; null if not built
+    void (*kernel_bt[3])(const GemmArgs);  // only b contraction-major; null if not built
 };
 
 #define MP8_TILE(BM, BN, WGM, WGN, NS, MB)                                   \
@@ -738,15 +742,18 @@ struct TileConfig {
      {gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_PARTIAL>,                \
       gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_RNE>,                    \
       gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_FULL>},                  \
-     {nullptr, nullptr, nullptr}}
+     {nullptr, nullptr, nullptr}, {nullptr, nullptr, nullptr}}
 #define MP8_TILE_TN(BM, BN, WGM, WGN, NS, MB)                                \
     {BM, BN, #BM "x" #BN "x128s" #NS,                                         \
      {gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_PARTIAL>,                \
       gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_RNE>,                    \
       gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_FULL>},                  \
-     {gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_PARTIAL, true>,          \
-      gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_RNE, true>,              \
-      gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_FULL, true>}}
+     {gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_PARTIAL, true, true>,    \
+      gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_RNE, true, true>,        \
+      gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_FULL, true, true>},      \
+     {gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_PARTIAL, false, true>,   \
+      gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_RNE, false, true>,       \
+      gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_FULL, false, true>}}
 static const TileConfig kTiles[] = {
     MP8_TILE_TN(256, 256, 2, 2, 2, 1), MP8_TILE(256, 128, 2, 2, 3, 1), MP8_TILE(128, 256, 2, 2, 3, 1),
     MP8_TILE_TN(128, 128, 2, 2, 2, 2), MP8_TILE_TN(128, 128, 2, 2, 4, 1), MP8_TILE(64, 128, 1, 4, 3, 2),
@@ -781,12 +788,16 @@ static void op_dims(mp8_op op, int64_t M, int64_t N, int64_t K, int64_t &rows, i
 // minimum because the second pass costs several microseconds.
 enum { T256x256 = 0, T128x128s2 = 3, T128x128s4 = 4, T128x64s2 = 9, T64x64s2 = 10 };
 static Plan make_plan(int64_t rows, int64_t cols, int64_t kc, int tile_config, int split_k,
-                      bool tn = false) {
+                      int layout = 0) {  // bit 0: a contraction-major, bit 1: b
     Plan pl{};
     pl.mfma = (kc % BK) == 0 && kc > 0;
     // contraction-major operands are fetched in 16-row chunks, by the tiles built for them
-    if (tn && ((rows & 15) != 0 || (cols & 15) != 0)) pl.mfma = false;
-    if (tn && tile_config > 0 && kTiles[tile_config - 1].kernel_tn[0] == nullptr) pl.mfma = false;
+    if ((layout & 1) && (rows & 15) != 0) pl.mfma = false;
+    if ((layout & 2) && (cols & 15) != 0) pl.mfma = false;
+    if (layout != 0 && tile_config > 0 &&
+        (layout == 3 ? kTiles[tile_config - 1].kernel_tn[0] : kTiles[tile_config - 1].kernel_bt[0]) == nullptr)
+        pl.mfma = false;
+    const bool tn = layout != 0;
     if (!pl.mfma) {
         pl.splits = 1;
         return pl;
@@ -850,9 +861,11 @@ extern "C" size_t mp8_gemm_fp8_workspace_bytes_tuned(mp8_op op, int64_t M, int64
     if (tile_config < 0 || tile_config > kNumTiles || split_k < 0) return 0;
     int64_t rows, cols, kc;
     op_dims(op, M, N, K, rows, cols, kc);
-    // enough for either operand layout
-    return std::max(plan_workspace(make_plan(rows, cols, kc, tile_config, split_k, false), rows, cols),
-                    plan_workspace(make_plan(rows, cols, kc, tile_config, split_k, true), rows, cols));
+    // enough for every operand layout
+    size_t need = 0;
+    for (int layout : {0, 2, 3})
+        need = std::max(need, plan_workspace(make_plan(rows, cols, kc, tile_config, split_k, layout), rows, cols));
+    return need;
 }
 
 extern "C" size_t mp8_gemm_fp8_workspace_bytes(mp8_op op, int64_t M, int64_t N, int64_t K) {
@@ -878,8 +891,10 @@ extern "C" mp8_status mp8_gemm_fp8_tuned(mp8_op op, int64_t M, int64_t N, int64_
     if (rows == 0 || cols == 0) return MP8_OK;
     if (acc_mode != 0 && acc == nullptr) return MP8_ERR_INVALID_ARG;
     if (kc > 0 && (!a || !b)) return MP8_ERR_INVALID_ARG;
-    const bool tn = (flags & MP8_FLAG_CONTRACTION_MAJOR) != 0;
-    if (kc > 0 && (tn ? (lda < rows || ldb < cols) : (lda < kc || ldb < kc))) return MP8_ERR_INVALID_ARG;
+    const bool atn = (flags & MP8_FLAG_A_CONTRACTION_MAJOR) != 0;
+    const bool btn = (flags & MP8_FLAG_B_CONTRACTION_MAJOR) != 0;
+    if (atn && !btn) return MP8_ERR_UNSUPPORTED;  // no kernel is built for this combination
+    if (kc > 0 && (lda < (atn ? rows : kc) || ldb < (btn ? cols : kc))) return MP8_ERR_INVALID_ARG;
     if (rows > (INT64_MAX / 8) / cols) return MP8_ERR_UNSUPPORTED;
     if (((uintptr_t)acc | (uintptr_t)out8 | (uintptr_t)out8_t | (uintptr_t)workspace) & 15u)
         return MP8_ERR_ALIGNMENT;
@@ -899,7 +914,7 @@ extern "C" mp8_status mp8_gemm_fp8_tuned(mp8_op op, int64_t M, int64_t N, int64_
     ep.cols = cols;
     hipStream_t s = (hipStream_t)stream;
 
-    Plan pl = make_plan(rows, cols, kc, tile_config, split_k, tn);
+    Plan pl = make_plan(rows, cols, kc, tile_config, split_k, (atn ? 1 : 0) | (btn ? 2 : 0));
     // the MFMA kernel wants 16-byte aligned rows and 32-bit offsets inside a 256-row tile
     const bool aligned = (((uintptr_t)a | (uintptr_t)b) & 15u) == 0 && (lda & 15) == 0 &&
                          (ldb & 15) == 0 && lda < (1 << 24) && ldb < (1 << 24);
@@ -913,7 +928,7 @@ extern "C" mp8_status mp8_gemm_fp8_tuned(mp8_op op, int64_t M, int64_t N, int64_
     if (!pl.mfma || kc == 0) {
         int64_t blocks = std::min<int64_t>((rows * cols + 255) / 256, 1 << 20);
         hipLaunchKernelGGL(gemm_generic_kernel, dim3((unsigned)blocks), dim3(256), 0, s, a, lda, b,
-                           ldb, kc, tn ? 1 : 0, ep);
+                           ldb, kc, (atn ? 1 : 0) | (btn ? 2 : 0), ep);
         return hipGetLastError() == hipSuccess ? MP8_OK : MP8_ERR_HIP;
     }
 
@@ -956,7 +971,8 @@ extern "C" mp8_status mp8_gemm_fp8_tuned(mp8_op op, int64_t M, int64_t N, int64_
     const int epi = two_pass ? EPI_PARTIAL
                              : (ep.sr || ep.sat || ep.stats != nullptr || out8 == nullptr) ? EPI_FULL
                                                                                             : EPI_RNE;
-    hipLaunchKernelGGL(tn ? kTiles[pl.tile].kernel_tn[epi] : kTiles[pl.tile].kernel[epi],
+    hipLaunchKernelGGL(atn ? kTiles[pl.tile].kernel_tn[epi]
+                           : btn ? kTiles[pl.tile].kernel_bt[epi] : kTiles[pl.tile].kernel[epi],
                        dim3((unsigned)nblocks), dim3(256), 0, s, ga);
     if (hipGetLastError() != hipSuccess) return MP8_ERR_HIP;
     if (two_pass) {

@@ -335,3 +335,30 @@ def test_weight_gradient_from_row_major_activations_and_errors(mp8):
     check_outputs(host(acc), host(out), ref, absref, M)
     # both layouts feed the matrix cores the same products in the same order
     assert np.array_equal(host(acc), acc_t) and np.array_equal(host(out), out_t)
+
+
+def test_forward_from_row_major_weights(mp8):
+    """The forward GEMM reading W8 [K, N] (b contraction-major) gives exactly what it gives from
+    the transposed copy W8^T [N, K]; ragged row count, exact and random operands."""
+    import torch
+    lay = workloads.config2(batch=1, hw=17, cin=128, cout=128)        # M=289, K=1152, N=128
+    X8, _, W8, W8t, _, _ = _layer_operands(lay)
+    M, N, K = lay.M, lay.N, lay.K
+    acc_t, out_t, _, _ = run_gemm(mp8, X8, W8t, op=mp8.FWD, dims=(M, N, K))
+    for split in (0, 3):
+        ws = torch.empty(max(mp8.gemm_fp8_workspace_bytes(mp8.FWD, M, N, K, 0, split), 16),
+                         dtype=torch.uint8, device="cuda")
+        acc = torch.zeros((M, N), dtype=torch.float32, device="cuda")
+        out = torch.zeros((M, N), dtype=torch.uint8, device="cuda")
+        mp8.gemm_fp8(mp8.FWD, M, N, K, gpu(X8), gpu(W8), out8=out, acc=acc, acc_mode=1, workspace=ws,
+                     flags=mp8.FLAG_B_CONTRACTION_MAJOR, split_k=split)
+        torch.cuda.synchronize()
+        ref, absref = oracle.gemm_ref(X8, W8t)
+        check_outputs(host(acc), host(out), ref, absref, K)
+        if split == 0:
+            assert np.array_equal(host(out), out_t)
+    # only a contraction-major: no kernel is built for it, and the call says so
+    with pytest.raises(mp8.Mp8Error):
+        mp8.gemm_fp8(mp8.FWD, 128, 128, 128, gpu(X8[:128, :128].copy()), gpu(W8t[:, :128].copy()),
+                     out8=torch.zeros((128, 128), dtype=torch.uint8, device="cuda"),
+                     flags=mp8.FLAG_A_CONTRACTION_MAJOR)
