@@ -72,6 +72,9 @@ def lib():
         L.orc_gemm_ref.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int64,
                                    C.c_int64, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p,
                                    C.c_void_p]
+        for fn in (L.orc_conv3x3_fwd_ref, L.orc_conv3x3_bwd_data_ref, L.orc_conv3x3_wgrad_ref):
+            fn.restype = None
+            fn.argtypes = [C.c_void_p, C.c_void_p] + [C.c_int64] * 5 + [C.c_void_p, C.c_void_p]
         L.orc_gemm_exact.restype = C.c_int64
         L.orc_gemm_exact.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int64,
                                      C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]
@@ -173,6 +176,36 @@ def gemm_ref(a, b, row_idx=None, want_abs=True):
     absref = np.empty((nrows, cols), dtype=np.float64) if want_abs else None
     lib().orc_gemm_ref(_p(a), a.strides[0], _p(b), b.strides[0], rows, cols, kc, _p(idx),
                        nrows if idx is not None else 0, _p(ref), _p(absref))
+    return ref, absref
+
+
+def conv3x3_ref(op, a, b, want_abs=True):
+    """Double-precision 3x3 convolution (stride 1, zero padding 1, channels last) on E5M2 codes.
+
+    op 'fwd':      a = x [B,H,W,Ci], b = w [3,3,Ci,Co]   -> y  [B,H,W,Co]
+    op 'bwd_data': a = e [B,H,W,Co], b = w [3,3,Ci,Co]   -> dx [B,H,W,Ci]
+    op 'wgrad':    a = x [B,H,W,Ci], b = e [B,H,W,Co]    -> dw [3,3,Ci,Co]
+    Returns (ref, absref or None)."""
+    a = _carr(a, np.uint8)
+    b = _carr(b, np.uint8)
+    if op == "fwd":
+        B, H, W, Ci = a.shape
+        Co = b.shape[3]
+        shape, fn = (B, H, W, Co), lib().orc_conv3x3_fwd_ref
+        assert b.shape == (3, 3, Ci, Co)
+    elif op == "bwd_data":
+        B, H, W, Co = a.shape
+        Ci = b.shape[2]
+        shape, fn = (B, H, W, Ci), lib().orc_conv3x3_bwd_data_ref
+        assert b.shape == (3, 3, Ci, Co)
+    else:
+        B, H, W, Ci = a.shape
+        Co = b.shape[3]
+        shape, fn = (3, 3, Ci, Co), lib().orc_conv3x3_wgrad_ref
+        assert b.shape == (B, H, W, Co)
+    ref = np.empty(shape, dtype=np.float64)
+    absref = np.empty(shape, dtype=np.float64) if want_abs else None
+    fn(_p(a), _p(b), B, H, W, Ci, Co, _p(ref), _p(absref))
     return ref, absref
 
 

@@ -312,6 +312,125 @@ void orc_gemm_ref(const uint8_t *a, int64_t lda, const uint8_t *b, int64_t ldb,
     }
 }
 
+/* ------------------------------------------------------------------------- */
+/* 3x3 convolution reference (Section 3: "all convolution and GEMM kernels";   */
+/* Section 4: the ResNet layers)                                               */
+/* ------------------------------------------------------------------------- */
+
+/*
+ * The paper applies the 8-bit primitive to convolutions as it does to GEMMs but
+ * does not restate the operation; the reading taken is the one of the residual
+ * networks it trains: stride 1, zero padding 1, cross-correlation (no kernel
+ * flip), activations stored [B, H, W, C] (channel fastest), weights
+ * [3, 3, Cin, Cout].  All three functions decode the codes exactly, sum in double
+ * in the index order written below, and also return the sum of absolute products.
+ *
+ *   forward        y[b,h,w,co]    = sum_{r,s,ci} x[b,h+r-1,w+s-1,ci] * wt[r,s,ci,co]
+ *   backward data  dx[b,h,w,ci]   = sum_{r,s,co} e[b,h-r+1,w-s+1,co] * wt[r,s,ci,co]
+ *   weight grad    dw[r,s,ci,co]  = sum_{b,h,w}  x[b,h+r-1,w+s-1,ci] * e[b,h,w,co]
+ * with every out-of-range pixel read as zero.  Backward data and weight gradient
+ * are the derivatives of sum(y * e) with respect to x and wt.
+ */
+static void conv_tables(double *table)
+{
+    int c;
+    for (c = 0; c < 256; ++c)
+        table[c] = orc_e5m2_decode((uint8_t)c);
+}
+
+void orc_conv3x3_fwd_ref(const uint8_t *x, const uint8_t *wt, int64_t B, int64_t H, int64_t W,
+                         int64_t Ci, int64_t Co, double *ref, double *absref)
+{
+    double table[256];
+    int64_t pix;
+    conv_tables(table);
+#pragma omp parallel for schedule(dynamic, 16)
+    for (pix = 0; pix < B * H * W; ++pix) {
+        int64_t b = pix / (H * W), h = (pix / W) % H, w = pix % W, co;
+        for (co = 0; co < Co; ++co) {
+            double s = 0.0, sa = 0.0;
+            int r, t;
+            for (r = 0; r < 3; ++r)
+                for (t = 0; t < 3; ++t) {
+                    int64_t hh = h + r - 1, ww = w + t - 1, ci;
+                    if (hh < 0 || hh >= H || ww < 0 || ww >= W)
+                        continue;
+                    for (ci = 0; ci < Ci; ++ci) {
+                        double p = table[x[((b * H + hh) * W + ww) * Ci + ci]] *
+                                   table[wt[((r * 3 + t) * Ci + ci) * Co + co]];
+                        s += p;
+                        sa += fabs(p);
+                    }
+                }
+            ref[pix * Co + co] = s;
+            if (absref)
+                absref[pix * Co + co] = sa;
+        }
+    }
+}
+
+void orc_conv3x3_bwd_data_ref(const uint8_t *e, const uint8_t *wt, int64_t B, int64_t H,
+                              int64_t W, int64_t Ci, int64_t Co, double *ref, double *absref)
+{
+    double table[256];
+    int64_t pix;
+    conv_tables(table);
+#pragma omp parallel for schedule(dynamic, 16)
+    for (pix = 0; pix < B * H * W; ++pix) {
+        int64_t b = pix / (H * W), h = (pix / W) % H, w = pix % W, ci;
+        for (ci = 0; ci < Ci; ++ci) {
+            double s = 0.0, sa = 0.0;
+            int r, t;
+            for (r = 0; r < 3; ++r)
+                for (t = 0; t < 3; ++t) {
+                    int64_t hh = h - r + 1, ww = w - t + 1, co;
+                    if (hh < 0 || hh >= H || ww < 0 || ww >= W)
+                        continue;
+                    for (co = 0; co < Co; ++co) {
+                        double p = table[e[((b * H + hh) * W + ww) * Co + co]] *
+                                   table[wt[((r * 3 + t) * Ci + ci) * Co + co]];
+                        s += p;
+                        sa += fabs(p);
+                    }
+                }
+            ref[pix * Ci + ci] = s;
+            if (absref)
+                absref[pix * Ci + ci] = sa;
+        }
+    }
+}
+
+void orc_conv3x3_wgrad_ref(const uint8_t *x, const uint8_t *e, int64_t B, int64_t H, int64_t W,
+                           int64_t Ci, int64_t Co, double *ref, double *absref)
+{
+    double table[256];
+    int64_t row;
+    conv_tables(table);
+#pragma omp parallel for schedule(dynamic, 4)
+    for (row = 0; row < 9 * Ci; ++row) {
+        int64_t tap = row / Ci, ci = row % Ci, r = tap / 3, t = tap % 3, co;
+        for (co = 0; co < Co; ++co) {
+            double s = 0.0, sa = 0.0;
+            int64_t b, h, w;
+            for (b = 0; b < B; ++b)
+                for (h = 0; h < H; ++h)
+                    for (w = 0; w < W; ++w) {
+                        int64_t hh = h + r - 1, ww = w + t - 1;
+                        double p;
+                        if (hh < 0 || hh >= H || ww < 0 || ww >= W)
+                            continue;
+                        p = table[x[((b * H + hh) * W + ww) * Ci + ci]] *
+                            table[e[((b * H + h) * W + w) * Co + co]];
+                        s += p;
+                        sa += fabs(p);
+                    }
+            ref[row * Co + co] = s;
+            if (absref)
+                absref[row * Co + co] = sa;
+        }
+    }
+}
+
 /*
  * Exact dot products for small cases.  Every finite E5M2 value is an integer
  * multiple of 2^-16 below 2^32 in those units, so each product is an integer
