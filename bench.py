@@ -13,6 +13,8 @@ ResNet-50-style 3x3 convolution layer taken as a GEMM (M=25088, N=128, K=1152):
 Every tensor exists once, row-major, as its producer wrote it: the GEMMs read X8 [M,K],
 E8 [M,N] and W8 [K,N] in whichever orientation they need (contraction-major operands go
 through transposing LDS reads), and the Q node on the weights is part of the update kernel.
+`conv_step` reports the same layer run as the 3x3 convolution it stands for (implicit GEMM on
+zero-padded channels-last tensors, nothing lowered): same useful flops, a ninth of the bytes.
 
 Inputs are resident in HBM before the timed region.  Prints ONE JSON line: `value` is the
 GEMM work of a step (3 * 2*M*N*K flop) divided by the time of the whole step (the steps are
@@ -59,6 +61,8 @@ def parse_args():
     ap.add_argument("--kernel-reps", type=int, default=50,
                     help="back-to-back launches per graph in the per-kernel timing")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-conv-step", action="store_true",
+                    help="skip the implicit-GEMM convolution form of the same layer")
     ap.add_argument("--no-all-configs", action="store_true",
                     help="skip the kernel-level table over the GEMM shapes of all configurations")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -126,6 +130,82 @@ class Workload:
         self.stats.zero_()     # a small fill kernel (no memset node, so the step can be captured)
         for _, fn, _, _, _ in self.kernels:
             fn()
+
+
+class ConvWorkload:
+    """The same layer as the 3x3 convolution it stands for (batch 32, 28x28, 128 -> 128 channels),
+    run as an implicit GEMM: activations and errors live channels-last on the zero-padded pixel
+    grid ([28800, 128] instead of the lowered [25088, 1152]); a filter tap is a row shift of the
+    operand, so nothing is lowered and nothing is transposed."""
+
+    def __init__(self, mp8, torch, lay):
+        self.mp8, self.torch = mp8, torch
+        B, H, W, C = 32, 28, 28, 128
+        self.dims = (B, H, W, C, C)
+        dev, u8 = "cuda", torch.uint8
+        P = mp8.conv_prows(B, H, W)
+        n = B * (H + 2) * (W + 2)
+        from paper_1905_12334_amd import workloads
+
+        def padded(x):      # [B,H,W,C] host FP32 -> [P, C] device FP32 with zero padding
+            xp = np.zeros((B, H + 2, W + 2, C), np.float32)
+            xp[:, 1:-1, 1:-1] = x
+            out = torch.zeros((P, C), dtype=torch.float32, device=dev)
+            out[:n] = torch.from_numpy(xp.reshape(-1, C)).to(dev)
+            return out
+        self.X = padded(workloads.relu_normal(2, 10, (B, H, W, C)))
+        self.dY = padded(workloads.normal(2, 12, (B, H, W, C), 1e-4))
+        w = workloads.normal(2, 11, (3, 3, C, C), float(np.sqrt(2.0 / (9 * C))))
+        self.W16 = torch.from_numpy(w.astype(np.float16).reshape(-1)).to(dev)
+        self.X8, self.E8 = mp8.conv_buffer(P, C, W), mp8.conv_buffer(P, C, W)
+        self.W8 = torch.empty((9 * C, C), dtype=u8, device=dev)
+        self.Y8 = torch.empty((P, C), dtype=u8, device=dev)
+        self.dX8 = torch.empty((P, C), dtype=u8, device=dev)
+        self.G8 = torch.empty((9 * C, C), dtype=u8, device=dev)
+        self.stats = mp8.new_stats()
+        ws = max(mp8.conv3x3_fp8_workspace_bytes(op, *self.dims) for op in (mp8.FWD, mp8.BWD_DATA, mp8.WGRAD))
+        self.ws = torch.empty(max(ws, 16), dtype=u8, device=dev)
+        self.step_no = 0
+        flops = 2 * B * H * W * 9 * C * C
+        conv = lambda op, a, b, out: mp8.conv3x3_fp8(op, *self.dims, a, b, out8=out, workspace=self.ws)
+        self.kernels = [
+            ("quantize_X", lambda: mp8.quantize_e5m2(self.X, self.X8), 5 * P * C, 0, "hbm"),
+            ("quantize_dY", lambda: mp8.quantize_e5m2(self.dY, self.E8, scale=LOSS_SCALE, stats=self.stats),
+             5 * P * C, 0, "hbm"),
+            ("conv_fwd", lambda: conv(mp8.FWD, self.X8, self.W8, self.Y8), 2 * P * C + 9 * C * C, flops, "mfma"),
+            ("conv_bwd_data", lambda: conv(mp8.BWD_DATA, self.E8, self.W8, self.dX8),
+             2 * P * C + 9 * C * C, flops, "mfma"),
+            ("conv_wgrad", lambda: conv(mp8.WGRAD, self.X8, self.E8, self.G8), 2 * P * C + 9 * C * C, flops,
+             "mfma"),
+            ("sgd_update", self._update, 6 * 9 * C * C, 0, "hbm"),
+        ]
+        mp8.quantize_e5m2(self.W16.view(9 * C, C), self.W8)
+
+    def _update(self):
+        self.step_no += 1
+        self.mp8.sgd_update_fp16_sr(self.W16, self.G8, LR, 1.0 / LOSS_SCALE, round=self.mp8.SR,
+                                    seed=0x1905_1233_4000_0003, offset=self.step_no,
+                                    skip_if_nonzero=self.stats[1:2], w8_out=self.W8)
+
+    def step(self):
+        self.stats.zero_()
+        for _, fn, _, _, _ in self.kernels:
+            fn()
+
+
+def kernel_table(kernels, times_ms, traffic=None):
+    out = []
+    for (name, _, nbytes, flops, bound), ms in zip(kernels, times_ms):
+        if bound == "mfma":
+            achieved, peak, unit = flops / (ms * 1e-3) / 1e12, FP8_PEAK_TFLOPS, "TFLOP/s"
+        else:
+            achieved, peak, unit = nbytes / (ms * 1e-3) / 1e9, HBM_PEAK_GBS, "GB/s"
+        out.append({"kernel": name, "bound": bound, "us": ms * 1e3, "achieved": achieved,
+                    "peak": peak, "unit": unit, "frac": achieved / peak,
+                    "alg_bytes": nbytes, "flops": flops,
+                    "hbm_gbs": nbytes / (ms * 1e-3) / 1e9,
+                    "traffic": (traffic or {}).get(name)})
+    return out
 
 
 def time_steps(torch, wl, steps, launch):
@@ -336,17 +416,7 @@ def main():
     gemm_flops = 3 * 2.0 * lay.M * lay.N * lay.K
     value = gemm_flops / (ms_per_step * 1e-3) / 1e12
 
-    kernels = []
-    for (name, _, nbytes, flops, bound), ms in zip(wl.kernels, time_kernels(torch, wl, args.kernel_reps)):
-        if bound == "mfma":
-            achieved, peak, unit = flops / (ms * 1e-3) / 1e12, FP8_PEAK_TFLOPS, "TFLOP/s"
-        else:
-            achieved, peak, unit = nbytes / (ms * 1e-3) / 1e9, HBM_PEAK_GBS, "GB/s"
-        kernels.append({"kernel": name, "bound": bound, "us": ms * 1e3, "achieved": achieved,
-                        "peak": peak, "unit": unit, "frac": achieved / peak,
-                        "alg_bytes": nbytes, "flops": flops,
-                        "hbm_gbs": nbytes / (ms * 1e-3) / 1e9,
-                        "traffic": MEASURED_TRAFFIC_BYTES.get(name)})
+    kernels = kernel_table(wl.kernels, time_kernels(torch, wl, args.kernel_reps), MEASURED_TRAFFIC_BYTES)
     dom = max(kernels, key=lambda k: k["us"])
     roofline = {"kernel": dom["kernel"], "bound": dom["bound"], "achieved": dom["achieved"],
                 "peak": dom["peak"], "unit": dom["unit"], "frac": dom["frac"],
@@ -375,9 +445,30 @@ def main():
         "roofline": roofline,
         "kernels": kernels,
     }
+    del wl
+    torch.cuda.empty_cache()
+    if not args.no_conv_step:
+        # the same layer without the lowering: 3x3 convolution as an implicit GEMM
+        try:
+            cw = ConvWorkload(mp8, torch, lay)
+            for _ in range(args.warmup):
+                cw.step()
+            conv_ms = time_steps(torch, cw, args.steps, args.launch)
+            out["conv_step"] = {
+                "workload": "the configs[1] layer as an implicit-GEMM 3x3 convolution on zero-padded "
+                            "channels-last tensors (no lowered operand): quantize X and dY, conv "
+                            "fwd + bwd_data + wgrad, FP16 SR update emitting the next 8-bit weights",
+                "ms_per_step": conv_ms,
+                "value": gemm_flops / (conv_ms * 1e-3) / 1e12,
+                "unit": "TFLOP/s (useful flops of the unpadded layer, 3 * 2*M*N*K)",
+                "overflow_count_last_step": mp8.read_stats(cw.stats)[1],
+                "kernels": kernel_table(cw.kernels, time_kernels(torch, cw, args.kernel_reps)),
+            }
+            del cw
+            torch.cuda.empty_cache()
+        except Exception as exc:
+            out["conv_step"] = {"error": repr(exc)}
     if not args.no_all_configs:
-        del wl
-        torch.cuda.empty_cache()
         try:
             out["all_configs"] = all_configs_report(mp8, torch)
         except Exception as exc:  # the table is extra evidence; the line above it stands on its own

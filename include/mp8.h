@@ -139,6 +139,36 @@ int mp8_gemm_num_tile_configs(void);
 int mp8_gemm_tile_config_name(int tile_config, char *buf, size_t buflen);
 
 /*
+ * The same primitive for a 3x3 convolution (stride 1, zero padding 1; Section 3 applies the
+ * 8-bit format to "all convolution and GEMM kernels", Section 4 trains residual networks), as
+ * an implicit GEMM: no lowered (im2col) copy of the activations exists.
+ *
+ * Activations and errors are channels-last on the ZERO-PADDED pixel grid: a tensor with C
+ * channels is [prows, C] with prows >= B*(H+2)*(W+2); row (b*(H+2) + y)*(W+2) + x holds pixel
+ * (y-1, x-1) of image b, rows with y in {0, H+1} or x in {0, W+1} and rows beyond the last
+ * image are padding and hold zero codes.  The operand `a` (read at shifted pixel positions)
+ * must in addition be readable for W+3 rows before its first and after its last row, and
+ * those guard rows must hold finite codes (they only ever meet padding).  Weights are
+ * w8 [3, 3, Cin, Cout].
+ *     MP8_FWD       a = x8 [prows, Cin]   b = w8                out  y8  [prows, Cout]
+ *     MP8_BWD_DATA  a = e8 [prows, Cout]  b = w8                out  dx8 [prows, Cin]
+ *     MP8_WGRAD     a = x8 [prows, Cin]   b = e8 [prows, Cout]  out  dw8 [3, 3, Cin, Cout]
+ * Padding rows of y8 / dx8 are written as zero codes (so an output can be the next input) and
+ * do not enter the statistics; acc, if requested, has the shape of out and its padding rows are
+ * unspecified.  SR uses the row-major index of the output matrix.  Cin and Cout must be
+ * multiples of 128, and prows a multiple of 128 for MP8_WGRAD (MP8_ERR_UNSUPPORTED otherwise).
+ * Everything else (alpha, acc_mode, round, flags = MP8_FLAG_SATURATE or 0, stats, workspace)
+ * as for mp8_gemm_fp8.
+ */
+mp8_status mp8_conv3x3_fp8(mp8_op op, int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                           int64_t prows, const uint8_t *a, const uint8_t *b, float alpha,
+                           float *acc, int acc_mode, uint8_t *out8, mp8_round round, int flags,
+                           uint64_t seed, uint64_t offset, mp8_stats *stats, void *workspace,
+                           size_t workspace_bytes, void *stream);
+size_t mp8_conv3x3_fp8_workspace_bytes(mp8_op op, int64_t B, int64_t H, int64_t W, int64_t Cin,
+                                       int64_t Cout, int64_t prows);
+
+/*
  * The weight-update path of Figure 1b on half-precision master weights, per element:
  *     g    = fl32(value(g8[i]) * inv_loss_scale)     un-scaling in full precision
  *     w    = float(w16[i])

@@ -26,6 +26,7 @@ EXPORTS = [
     "mp8_gemm_fp8_workspace_bytes_tuned", "mp8_gemm_num_tile_configs",
     "mp8_gemm_tile_config_name", "mp8_sgd_update_fp16_sr", "mp8_sr_bits", "mp8_philox4x32_10",
     "mp8_scaler_init", "mp8_scaler_update", "mp8_scaler_set_floor", "mp8_status_string",
+    "mp8_conv3x3_fp8", "mp8_conv3x3_fp8_workspace_bytes",
 ]
 
 
@@ -81,6 +82,11 @@ def lib() -> C.CDLL:
     L.mp8_scaler_update.argtypes = [C.POINTER(Scaler), C.c_uint32]
     L.mp8_scaler_set_floor.restype = None
     L.mp8_scaler_set_floor.argtypes = [C.POINTER(Scaler), C.c_double]
+    L.mp8_conv3x3_fp8.restype = ci
+    L.mp8_conv3x3_fp8.argtypes = [ci, i64, i64, i64, i64, i64, i64, vp, vp, f32, vp, ci, vp, ci, ci,
+                                  u64, u64, vp, vp, C.c_size_t, vp]
+    L.mp8_conv3x3_fp8_workspace_bytes.restype = C.c_size_t
+    L.mp8_conv3x3_fp8_workspace_bytes.argtypes = [ci, i64, i64, i64, i64, i64, i64]
     L.mp8_status_string.restype = C.c_char_p
     L.mp8_status_string.argtypes = [ci]
     _lib = L
@@ -184,6 +190,60 @@ def gemm_fp8(op, M, N, K, a, b, out8=None, out8_t=None, acc=None, acc_mode=0, al
                                   _ptr(stats), _ptr(workspace), ws_bytes, _stream(), tile_config,
                                   split_k)
     _check(st, "mp8_gemm_fp8")
+    return out8
+
+
+def conv_prows(B, H, W) -> int:
+    """Rows of a padded channels-last tensor: B*(H+2)*(W+2) rounded up to a multiple of 128."""
+    return -(-(B * (H + 2) * (W + 2)) // 128) * 128
+
+
+def conv_buffer(prows, channels, W, dtype=None, device="cuda"):
+    """A zeroed [prows, channels] tensor for mp8_conv3x3_fp8 with the W+3 guard rows it wants
+    readable before and after (the returned view starts behind the leading guard)."""
+    import torch
+    guard = (W + 3) * channels
+    store = torch.zeros(prows * channels + 2 * guard, dtype=dtype or torch.uint8, device=device)
+    return store[guard:guard + prows * channels].view(prows, channels)
+
+
+def _has_guard(t, guard_elems):
+    after = t.untyped_storage().nbytes() // t.element_size() - (t.storage_offset() + t.numel())
+    return t.storage_offset() >= guard_elems and after >= guard_elems
+
+
+def conv3x3_fp8_workspace_bytes(op, B, H, W, Cin, Cout, prows=None) -> int:
+    prows = conv_prows(B, H, W) if prows is None else prows
+    return int(lib().mp8_conv3x3_fp8_workspace_bytes(op, B, H, W, Cin, Cout, prows))
+
+
+def conv3x3_fp8(op, B, H, W, Cin, Cout, a, b, out8=None, acc=None, acc_mode=0, alpha=1.0, round=RNE,
+                flags=0, seed=0, offset=0, stats=None, workspace=None, prows=None):
+    """mp8_conv3x3_fp8 on padded channels-last tensors (see include/mp8.h): a / b are
+    [prows, C] views with guard rows around them (conv_buffer), weights are [3, 3, Cin, Cout]."""
+    import torch
+    prows = conv_prows(B, H, W) if prows is None else prows
+    _dev(a, "a", torch.uint8)
+    _dev(b, "b", torch.uint8)
+    _dev(out8, "out8", torch.uint8)
+    _dev(acc, "acc", torch.float32)
+    ca = Cout if op == BWD_DATA else Cin
+    shapes = {FWD: (prows * Cin, 9 * Cin * Cout, prows * Cout),
+              BWD_DATA: (prows * Cout, 9 * Cin * Cout, prows * Cin),
+              WGRAD: (prows * Cin, prows * Cout, 9 * Cin * Cout)}[op]
+    if a.numel() != shapes[0] or b.numel() != shapes[1]:
+        raise Mp8Error("a / b do not have the sizes the operation implies")
+    for t, name in ((out8, "out8"), (acc, "acc")):
+        if t is not None and t.numel() < shapes[2]:
+            raise Mp8Error(f"{name} is smaller than the output")
+    if not _has_guard(a, (W + 3) * ca):
+        raise Mp8Error("the padded tensor `a` needs W+3 readable guard rows before and after "
+                       "(allocate it with conv_buffer)")
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = lib().mp8_conv3x3_fp8(op, B, H, W, Cin, Cout, prows, _ptr(a), _ptr(b), float(alpha), _ptr(acc),
+                               acc_mode, _ptr(out8), round, flags, seed, offset, _ptr(stats),
+                               _ptr(workspace), ws_bytes, _stream())
+    _check(st, "mp8_conv3x3_fp8")
     return out8
 
 

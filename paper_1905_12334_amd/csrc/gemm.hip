@@ -83,6 +83,30 @@ struct Epilogue {
     uint64_t seed, offset;
     mp8_stats *stats;
     int64_t rows, cols;
+    // Convolution outputs live on the zero-padded pixel grid (rows = padded pixels): rows that
+    // are padding receive zero codes and stay out of the statistics.  mask = 0: no masking.
+    int mask;
+    int hh;              // H + 2
+    int64_t valid_rows;  // B * (H+2) * (W+2); rows beyond are padding as well
+    FastDiv div_img;     // by (H+2) * (W+2)
+    FastDiv div_w2;      // by W + 2
+};
+
+// Is output row r a padding pixel of the convolution grid?
+__device__ __forceinline__ bool conv_padding_row(const Epilogue &ep, int64_t r) {
+    if (r >= ep.valid_rows) return true;
+    uint32_t rem, x;
+    fastdiv((uint32_t)r, ep.div_img, rem);
+    const uint32_t y = fastdiv(rem, ep.div_w2, x);
+    return y == 0 || y == (uint32_t)ep.hh - 1 || x == 0 || x == ep.div_w2.d - 1;
+}
+
+// What a convolution adds to the operand addressing (conv = 0: plain GEMM).
+struct ConvArgs {
+    int w2;               // W + 2: a tap (r, s) shifts the pixel row by (r-1)*w2 + (s-1)
+    FastDiv div_cpb;      // by the number of 128-byte stages per tap (channels / 128)
+    int64_t b_tap_stride; // backward data: bytes between the weight slabs of two taps
+    FastDiv div_ci;       // weight gradient: by Cin (tile row -> tap, first channel)
 };
 
 struct GemmArgs {
@@ -100,6 +124,7 @@ struct GemmArgs {
     FastDiv div_tail;   // by the height of the last band of tile rows (tiles_m % 8, or 8)
     int ks_per, ks_extra;  // ksteps / splits and ksteps % splits
     float *partial;     // [splits, rows, cols] when splits > 1
+    ConvArgs cv;
     Epilogue ep;
 };
 
@@ -113,6 +138,11 @@ __device__ __forceinline__ void finish1(const Epilogue &ep, int64_t r, int64_t c
         ep.acc[i] = v;
     }
     if (ep.out8 == nullptr && ep.out8_t == nullptr && ep.stats == nullptr) return;
+    if (ep.mask && conv_padding_row(ep, r)) {
+        if (ep.out8 != nullptr) ep.out8[i] = 0;
+        if (ep.out8_t != nullptr) ep.out8_t[c * ep.rows + r] = 0;
+        return;
+    }
     const float y = v * ep.alpha;
     uint32_t code;
     if (ep.sr) {
@@ -147,6 +177,7 @@ __device__ __forceinline__ void finish16(const Epilogue &ep, int64_t r, int64_t 
         }
     }
     if (ep.out8 == nullptr && ep.out8_t == nullptr && ep.stats == nullptr) return;
+    const bool padding = ep.mask && conv_padding_row(ep, r);
     uint32_t rw[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     if (ep.sr) {
         const Philox rng(ep.seed, ep.offset);
@@ -160,7 +191,8 @@ __device__ __forceinline__ void finish16(const Epilogue &ep, int64_t r, int64_t 
         float y[4] = {v[4 * q] * ep.alpha, v[4 * q + 1] * ep.alpha, v[4 * q + 2] * ep.alpha,
                       v[4 * q + 3] * ep.alpha};
         pk[q] = e5m2_pack4_rt(y, rw[2 * q], rw[2 * q + 1], ep.sr != 0, ep.sat != 0);
-        if (ep.stats != nullptr) st.add4(y, pk[q]);
+        if (padding) pk[q] = 0;
+        else if (ep.stats != nullptr) st.add4(y, pk[q]);
     }
     if (ep.out8 != nullptr) {
         u32x4 o = {pk[0], pk[1], pk[2], pk[3]};
@@ -264,9 +296,17 @@ __device__ __forceinline__ uint32_t lds_address(const void *p) {
 //   EPI_FULL     out8 with run-time rounding mode, saturation and statistics
 enum { EPI_PARTIAL = 0, EPI_RNE = 1, EPI_FULL = 2 };
 
+// CONV: 0 plain GEMM; 1 / 2 / 3 forward / backward-data / weight-gradient 3x3 convolution on
+// zero-padded channels-last tensors, where a tap of the filter is a shift of the pixel row:
+//   1  a[r, (tap, ci)] = x[r + shift(tap), ci]      a plain, b = w [9 Cin, Cout] contraction-major
+//   2  a[r, (tap, co)] = e[r - shift(tap), co]      a plain, b[ci, (tap, co)] = w[tap][ci][co]
+//   3  a[(tap, ci), r] = x[r + shift(tap), ci]      both contraction-major, tap fixed per tile row
+// so only the base address of a stage (1, 2) or of a tile (3) differs from the plain GEMM.
 template <int BM, int BN, int WGM, int WGN, int NSTAGE, int MINBLOCKS, int EPI, bool ATN = false,
-          bool BTN = false>
+          bool BTN = false, int CONV = 0>
 __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArgs p) {
+    static_assert(CONV == 0 || (CONV == 1 && !ATN && BTN) || (CONV == 2 && !ATN && !BTN) ||
+                      (CONV == 3 && ATN && BTN), "operand layouts of the convolution forms");
     static_assert((!ATN || BM % 128 == 0) && (!BTN || BN % 128 == 0),
                   "contraction-major operands: 128-row panels");
     static_assert(WGM * WGN == 4, "four waves");
@@ -311,10 +351,44 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     // 16 rows (never stored).
     const int lrow = lane >> 3, lchunk = (lane & 7) ^ ((4 * wave + (lane >> 4)) & 7);
     const int64_t a_kstep = ATN ? (int64_t)BK * p.lda : BK, b_kstep = BTN ? (int64_t)BK * p.ldb : BK;
-    const uint8_t *a_tile =
-        uniform_ptr(ATN ? p.a + (int64_t)ks_begin * a_kstep + row0 : p.a + row0 * p.lda + (int64_t)ks_begin * BK);
-    const uint8_t *b_tile =
-        uniform_ptr(BTN ? p.b + (int64_t)ks_begin * b_kstep + col0 : p.b + col0 * p.ldb + (int64_t)ks_begin * BK);
+    auto tap_shift = [&](uint32_t tap) {  // pixel-row shift of filter tap (r, s) = (tap / 3, tap % 3)
+        const int r = (int)((tap * 11u) >> 5);
+        return (r - 1) * p.cv.w2 + ((int)tap - 3 * r - 1);
+    };
+    const uint8_t *a_origin, *b_origin;
+    if constexpr (CONV == 1 || CONV == 2) {
+        a_origin = p.a + row0 * p.lda;  // the stage's tap and channel part are added per stage
+    } else if constexpr (CONV == 3) {
+        uint32_t ci0;
+        const uint32_t tap = fastdiv((uint32_t)row0, p.cv.div_ci, ci0);
+        a_origin = p.a + (int64_t)tap_shift(tap) * p.lda + ci0 + (int64_t)ks_begin * a_kstep;
+    } else {
+        a_origin = ATN ? p.a + (int64_t)ks_begin * a_kstep + row0 : p.a + row0 * p.lda + (int64_t)ks_begin * BK;
+    }
+    if constexpr (CONV == 2) b_origin = p.b + col0 * p.ldb;
+    else b_origin = BTN ? p.b + (int64_t)ks_begin * b_kstep + col0 : p.b + col0 * p.ldb + (int64_t)ks_begin * BK;
+    const uint8_t *a_tile = uniform_ptr(a_origin);
+    const uint8_t *b_tile = uniform_ptr(b_origin);
+    // base addresses of stage `kstage` of this workgroup's slice
+    auto a_stage = [&](int kstage) -> const uint8_t * {
+        if constexpr (CONV == 1 || CONV == 2) {
+            uint32_t part;
+            const uint32_t tap = fastdiv((uint32_t)(ks_begin + kstage), p.cv.div_cpb, part);
+            const int sh = CONV == 1 ? tap_shift(tap) : -tap_shift(tap);
+            return a_tile + (int64_t)sh * p.lda + part * BK;
+        } else {
+            return a_tile + (int64_t)kstage * a_kstep;
+        }
+    };
+    auto b_stage = [&](int kstage) -> const uint8_t * {
+        if constexpr (CONV == 2) {
+            uint32_t part;
+            const uint32_t tap = fastdiv((uint32_t)(ks_begin + kstage), p.cv.div_cpb, part);
+            return b_tile + (int64_t)tap * p.cv.b_tap_stride + part * BK;
+        } else {
+            return b_tile + (int64_t)kstage * b_kstep;
+        }
+    };
     uint32_t oa[A_DMA], ob[B_DMA];
 #pragma unroll
     for (int q = 0; q < A_DMA; ++q) {
@@ -346,8 +420,8 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     auto issue_loads = [&](int kstage) {
         const uint32_t sa = lds0 + (kstage % NSTAGE) * STAGE + wave * 1024;
         const uint32_t sb = sa + A_BYTES;
-        const uint8_t *ak = a_tile + (int64_t)kstage * a_kstep;
-        const uint8_t *bk = b_tile + (int64_t)kstage * b_kstep;
+        const uint8_t *ak = a_stage(kstage);
+        const uint8_t *bk = b_stage(kstage);
 #pragma unroll
         for (int q = 0; q < A_DMA; ++q) dma16(ak, oa[q], sa + q * 4096);
 #pragma unroll
@@ -417,9 +491,9 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     auto issue_one = [&](int kstage, int q) {  // load q (0 .. G-1) of a stage
         const uint32_t sa = lds0 + (kstage % NSTAGE) * STAGE + wave * 1024;
         if (q < A_DMA)
-            dma16(a_tile + (int64_t)kstage * a_kstep, oa[q < A_DMA ? q : 0], sa + q * 4096);
+            dma16(a_stage(kstage), oa[q < A_DMA ? q : 0], sa + q * 4096);
         else
-            dma16(b_tile + (int64_t)kstage * b_kstep, ob[q >= A_DMA ? q - A_DMA : 0],
+            dma16(b_stage(kstage), ob[q >= A_DMA ? q - A_DMA : 0],
                   sa + A_BYTES + (q - A_DMA) * 4096);
     };
 
@@ -606,6 +680,7 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
                                       v[4 * q + 2] * p.ep.alpha, v[4 * q + 3] * p.ep.alpha};
                         pk[q] = e5m2_pack4<false>(y, 0u, 0u, false);
                     }
+                    if (p.ep.mask && conv_padding_row(p.ep, r)) pk[0] = pk[1] = pk[2] = pk[3] = 0;
                     u32x4 o = {pk[0], pk[1], pk[2], pk[3]};
                     *reinterpret_cast<u32x4 *>(p.ep.out8 + r * p.cols + c) = o;
                 } else {
@@ -647,8 +722,9 @@ __device__ __forceinline__ void finish4(const Epilogue &ep, int64_t r, int64_t c
         r23 = (i0 & 4) ? w.w : w.y;
     }
     float y[4] = {v[0] * ep.alpha, v[1] * ep.alpha, v[2] * ep.alpha, v[3] * ep.alpha};
-    const uint32_t pk = e5m2_pack4_rt(y, r01, r23, ep.sr != 0, ep.sat != 0);
-    if (ep.stats != nullptr) st.add4(y, pk);
+    uint32_t pk = e5m2_pack4_rt(y, r01, r23, ep.sr != 0, ep.sat != 0);
+    if (ep.mask && conv_padding_row(ep, r)) pk = 0;
+    else if (ep.stats != nullptr) st.add4(y, pk);
     if (ep.out8 != nullptr) *reinterpret_cast<uint32_t *>(ep.out8 + i0) = pk;
     if (ep.out8_t != nullptr) {
         uint8_t *t = ep.out8_t + c * ep.rows + r;
@@ -735,6 +811,7 @@ struct TileConfig {
     void (*kernel[3])(const GemmArgs);     // indexed by EPI_*
     void (*kernel_tn[3])(const GemmArgs);  // both operands contraction-major; null if not built
     void (*kernel_bt[3])(const GemmArgs);  // only b contraction-major; null if not built
+    void (*kernel_conv[3][3])(const GemmArgs);  // [mp8_op][EPI_*] 3x3 convolution; null if not built
 };
 
 #define MP8_TILE(BM, BN, WGM, WGN, NS, MB)                                   \
@@ -742,7 +819,8 @@ struct TileConfig {
      {gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_PARTIAL>,                \
       gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_RNE>,                    \
       gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_FULL>},                  \
-     {nullptr, nullptr, nullptr}, {nullptr, nullptr, nullptr}}
+     {nullptr, nullptr, nullptr}, {nullptr, nullptr, nullptr},                \
+     {{nullptr, nullptr, nullptr}, {nullptr, nullptr, nullptr}, {nullptr, nullptr, nullptr}}}
 #define MP8_TILE_TN(BM, BN, WGM, WGN, NS, MB)                                \
     {BM, BN, #BM "x" #BN "x128s" #NS,                                         \
      {gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_PARTIAL>,                \
@@ -753,7 +831,16 @@ struct TileConfig {
       gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_FULL, true, true>},      \
      {gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_PARTIAL, false, true>,   \
       gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_RNE, false, true>,       \
-      gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_FULL, false, true>}}
+      gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_FULL, false, true>},      \
+     {{gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_PARTIAL, false, true, 1>, \
+       gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_RNE, false, true, 1>,     \
+       gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_FULL, false, true, 1>},   \
+      {gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_PARTIAL, false, false, 2>, \
+       gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_RNE, false, false, 2>,    \
+       gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_FULL, false, false, 2>},  \
+      {gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_PARTIAL, true, true, 3>,  \
+       gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_RNE, true, true, 3>,      \
+       gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_FULL, true, true, 3>}}}
 static const TileConfig kTiles[] = {
     MP8_TILE_TN(256, 256, 2, 2, 2, 1), MP8_TILE(256, 128, 2, 2, 3, 1), MP8_TILE(128, 256, 2, 2, 3, 1),
     MP8_TILE_TN(128, 128, 2, 2, 2, 2), MP8_TILE_TN(128, 128, 2, 2, 4, 1), MP8_TILE(64, 128, 1, 4, 3, 2),
@@ -826,7 +913,9 @@ static Plan make_plan(int64_t rows, int64_t cols, int64_t kc, int tile_config, i
     if (split_k > 0) {
         s = split_k;
     } else if (nt < kCUs / 2) {
-        s = (int)((384 + nt - 1) / nt);           // about one and a half blocks per CU
+        // about one and a half blocks per CU; fewer for the 128-row tiles of contraction-major
+        // operands, whose FP32 partial tiles are four times as large
+        s = (int)(((tn ? 160 : 384) + nt - 1) / nt);
         s = std::min(s, std::max(1, ksteps / 8));  // at least eight stages per slice
         s = std::min(s, kMaxSplits);
     }
@@ -871,6 +960,70 @@ extern "C" size_t mp8_gemm_fp8_workspace_bytes_tuned(mp8_op op, int64_t M, int64
 extern "C" size_t mp8_gemm_fp8_workspace_bytes(mp8_op op, int64_t M, int64_t N, int64_t K) {
     return mp8_gemm_fp8_workspace_bytes_tuned(op, M, N, K, 0, 0);
 }
+
+namespace mp8 {
+
+// Launch the MFMA kernel chosen by `pick` (indexed by EPI_*) for plan `pl`, and the finishing
+// kernel when the epilogue cannot be fused.  `ga` carries the operands; its tiling, slicing and
+// epilogue fields are filled in here.
+static mp8_status launch_mfma(GemmArgs ga, const Epilogue &ep, const Plan &pl, int64_t kc,
+                              void (*const pick[3])(const GemmArgs), void *workspace,
+                              size_t workspace_bytes, hipStream_t s) {
+    const int64_t rows = ep.rows, cols = ep.cols;
+    const int acc_mode = ep.acc_mode;
+    float *acc = ep.acc;
+    uint8_t *out8 = ep.out8, *out8_t = ep.out8_t;
+    // Fused epilogue or two passes?
+    const bool two_pass = pl.splits > 1 || (cols & 15) != 0 || acc_mode != 0 || out8_t != nullptr;
+    float *partial = nullptr;
+    Epilogue fin = ep;  // what the finishing kernel applies
+    if (two_pass) {
+        if (pl.splits == 1 && acc_mode == 1) {
+            partial = acc;  // the tile goes straight into acc; the finishing kernel reads it there
+            fin.acc = nullptr;
+            fin.acc_mode = 0;
+        } else {
+            const size_t need = plan_workspace(pl, rows, cols);
+            if (workspace == nullptr || workspace_bytes < need) return MP8_ERR_WORKSPACE;
+            partial = (float *)workspace;
+        }
+    }
+    const int64_t nblocks = (int64_t)pl.tiles_m * pl.tiles_n * pl.splits;
+    if (nblocks > 0x7FFFFFFFLL) return MP8_ERR_UNSUPPORTED;
+
+    ga.rows = rows;
+    ga.cols = cols;
+    ga.ksteps = (int)(kc / BK);
+    ga.splits = pl.splits;
+    ga.tiles_m = pl.tiles_m;
+    ga.tiles_n = pl.tiles_n;
+    ga.div_tiles = make_fastdiv((uint32_t)(pl.tiles_m * pl.tiles_n));
+    ga.div_band = make_fastdiv((uint32_t)(8 * pl.tiles_n));
+    ga.div_tail = make_fastdiv((uint32_t)((pl.tiles_m & 7) ? (pl.tiles_m & 7) : 8));
+    ga.ks_per = ga.ksteps / pl.splits;
+    ga.ks_extra = ga.ksteps % pl.splits;
+    ga.partial = partial;
+    ga.ep = ep;
+    const int epi = two_pass ? EPI_PARTIAL
+                             : (ep.sr || ep.sat || ep.stats != nullptr || out8 == nullptr) ? EPI_FULL
+                                                                                            : EPI_RNE;
+    hipLaunchKernelGGL(pick[epi], dim3((unsigned)nblocks), dim3(256), 0, s, ga);
+    if (hipGetLastError() != hipSuccess) return MP8_ERR_HIP;
+    if (two_pass) {
+        const bool only_acc = fin.acc_mode == 0 && fin.out8 == nullptr && fin.out8_t == nullptr &&
+                              fin.stats == nullptr;
+        if (!only_acc) {
+            const int64_t items = (cols & 3) == 0 ? rows * cols / 4 : rows * cols;
+            int64_t blocks = std::min<int64_t>((items + 255) / 256, 256 * 16);
+            hipLaunchKernelGGL(splitk_finish_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
+                               (const float *)partial, pl.splits, fin);
+            if (hipGetLastError() != hipSuccess) return MP8_ERR_HIP;
+        }
+    }
+    return MP8_OK;
+}
+
+}  // namespace mp8
 
 extern "C" mp8_status mp8_gemm_fp8_tuned(mp8_op op, int64_t M, int64_t N, int64_t K,
                                          const uint8_t *a, int64_t lda, const uint8_t *b,
@@ -932,61 +1085,14 @@ extern "C" mp8_status mp8_gemm_fp8_tuned(mp8_op op, int64_t M, int64_t N, int64_
         return hipGetLastError() == hipSuccess ? MP8_OK : MP8_ERR_HIP;
     }
 
-    // Fused epilogue or two passes?
-    const bool two_pass = pl.splits > 1 || (cols & 15) != 0 || acc_mode != 0 || out8_t != nullptr;
-    float *partial = nullptr;
-    Epilogue fin = ep;  // what the finishing kernel applies
-    if (two_pass) {
-        if (pl.splits == 1 && acc_mode == 1) {
-            partial = acc;  // the tile goes straight into acc; the finishing kernel reads it there
-            fin.acc = nullptr;
-            fin.acc_mode = 0;
-        } else {
-            const size_t need = plan_workspace(pl, rows, cols);
-            if (workspace == nullptr || workspace_bytes < need) return MP8_ERR_WORKSPACE;
-            partial = (float *)workspace;
-        }
-    }
-    const int64_t nblocks = (int64_t)pl.tiles_m * pl.tiles_n * pl.splits;
-    if (nblocks > 0x7FFFFFFFLL) return MP8_ERR_UNSUPPORTED;
-
     GemmArgs ga{};
     ga.a = a;
     ga.b = b;
     ga.lda = lda;
     ga.ldb = ldb;
-    ga.rows = rows;
-    ga.cols = cols;
-    ga.ksteps = (int)(kc / BK);
-    ga.splits = pl.splits;
-    ga.tiles_m = pl.tiles_m;
-    ga.tiles_n = pl.tiles_n;
-    ga.div_tiles = make_fastdiv((uint32_t)(pl.tiles_m * pl.tiles_n));
-    ga.div_band = make_fastdiv((uint32_t)(8 * pl.tiles_n));
-    ga.div_tail = make_fastdiv((uint32_t)((pl.tiles_m & 7) ? (pl.tiles_m & 7) : 8));
-    ga.ks_per = ga.ksteps / pl.splits;
-    ga.ks_extra = ga.ksteps % pl.splits;
-    ga.partial = partial;
-    ga.ep = ep;
-    const int epi = two_pass ? EPI_PARTIAL
-                             : (ep.sr || ep.sat || ep.stats != nullptr || out8 == nullptr) ? EPI_FULL
-                                                                                            : EPI_RNE;
-    hipLaunchKernelGGL(atn ? kTiles[pl.tile].kernel_tn[epi]
-                           : btn ? kTiles[pl.tile].kernel_bt[epi] : kTiles[pl.tile].kernel[epi],
-                       dim3((unsigned)nblocks), dim3(256), 0, s, ga);
-    if (hipGetLastError() != hipSuccess) return MP8_ERR_HIP;
-    if (two_pass) {
-        const bool only_acc = fin.acc_mode == 0 && fin.out8 == nullptr && fin.out8_t == nullptr &&
-                              fin.stats == nullptr;
-        if (!only_acc) {
-            const int64_t items = (cols & 3) == 0 ? rows * cols / 4 : rows * cols;
-            int64_t blocks = std::min<int64_t>((items + 255) / 256, 256 * 16);
-            hipLaunchKernelGGL(splitk_finish_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
-                               (const float *)partial, pl.splits, fin);
-            if (hipGetLastError() != hipSuccess) return MP8_ERR_HIP;
-        }
-    }
-    return MP8_OK;
+    const TileConfig &tc = kTiles[pl.tile];
+    return launch_mfma(ga, ep, pl, kc, atn ? tc.kernel_tn : btn ? tc.kernel_bt : tc.kernel, workspace,
+                       workspace_bytes, s);
 }
 
 extern "C" mp8_status mp8_gemm_fp8(mp8_op op, int64_t M, int64_t N, int64_t K, const uint8_t *a,
@@ -998,6 +1104,102 @@ extern "C" mp8_status mp8_gemm_fp8(mp8_op op, int64_t M, int64_t N, int64_t K, c
     return mp8_gemm_fp8_tuned(op, M, N, K, a, lda, b, ldb, alpha, acc, acc_mode, out8, out8_t,
                               round, flags, seed, offset, stats, workspace, workspace_bytes,
                               stream, 0, 0);
+}
+
+// ---------------------------------------------------------------------------------------
+// 3x3 convolution as an implicit GEMM on zero-padded channels-last tensors
+// ---------------------------------------------------------------------------------------
+namespace mp8 {
+
+struct ConvDims {
+    int64_t rows, cols, kc;  // of the implicit GEMM
+    int64_t lda, ldb;
+};
+
+static bool conv_dims(mp8_op op, int64_t prows, int64_t Ci, int64_t Co, ConvDims &d) {
+    switch (op) {
+        case MP8_FWD: d = {prows, Co, 9 * Ci, Ci, Co}; return true;
+        case MP8_BWD_DATA: d = {prows, Ci, 9 * Co, Co, Co}; return true;
+        case MP8_WGRAD: d = {9 * Ci, Co, prows, Ci, Co}; return true;
+    }
+    return false;
+}
+
+static Plan conv_plan(mp8_op op, const ConvDims &d, int64_t Ci) {
+    // the tile shapes built for contraction-major operands are the ones built for convolutions
+    Plan pl = make_plan(d.rows, d.cols, d.kc, 0, 0, 3);
+    // a tile row of the weight gradient must not straddle two taps
+    if (pl.mfma && op == MP8_WGRAD && (Ci % kTiles[pl.tile].bm) != 0)
+        pl = make_plan(d.rows, d.cols, d.kc, T128x128s2 + 1, 0, 3);
+    return pl;
+}
+
+}  // namespace mp8
+
+extern "C" size_t mp8_conv3x3_fp8_workspace_bytes(mp8_op op, int64_t B, int64_t H, int64_t W,
+                                                  int64_t Ci, int64_t Co, int64_t prows) {
+    using namespace mp8;
+    ConvDims d;
+    if (B <= 0 || H <= 0 || W <= 0 || Ci <= 0 || Co <= 0 || prows <= 0) return 0;
+    if (!conv_dims(op, prows, Ci, Co, d)) return 0;
+    return plan_workspace(conv_plan(op, d, Ci), d.rows, d.cols);
+}
+
+extern "C" mp8_status mp8_conv3x3_fp8(mp8_op op, int64_t B, int64_t H, int64_t W, int64_t Ci,
+                                      int64_t Co, int64_t prows, const uint8_t *a,
+                                      const uint8_t *b, float alpha, float *acc, int acc_mode,
+                                      uint8_t *out8, mp8_round round, int flags, uint64_t seed,
+                                      uint64_t offset, mp8_stats *stats, void *workspace,
+                                      size_t workspace_bytes, void *stream) {
+    using namespace mp8;
+    ConvDims d;
+    if (B < 0 || H < 0 || W < 0 || Ci < 0 || Co < 0 || prows < 0) return MP8_ERR_INVALID_ARG;
+    if (!conv_dims(op, prows, Ci, Co, d)) return MP8_ERR_INVALID_ARG;
+    if (round != MP8_RNE && round != MP8_SR) return MP8_ERR_INVALID_ARG;
+    if (acc_mode < 0 || acc_mode > 2) return MP8_ERR_INVALID_ARG;
+    if (flags & ~MP8_FLAG_SATURATE) return MP8_ERR_INVALID_ARG;
+    if (B == 0 || H == 0 || W == 0 || Ci == 0 || Co == 0) return MP8_OK;
+    const int64_t img = (H + 2) * (W + 2);
+    if (B > (int64_t)0x7FFFFFFF / img || prows < B * img || prows > 0x7FFFFFFF) return MP8_ERR_INVALID_ARG;
+    if (!a || !b || (acc_mode != 0 && !acc)) return MP8_ERR_INVALID_ARG;
+    // whole 128-byte stages per tap, whole tiles per tap of the weight gradient
+    if ((Ci & 127) != 0 || (Co & 127) != 0 || Ci >= (1 << 20) || Co >= (1 << 20)) return MP8_ERR_UNSUPPORTED;
+    if (op == MP8_WGRAD && (prows & 127) != 0) return MP8_ERR_UNSUPPORTED;
+    if (((uintptr_t)a | (uintptr_t)b | (uintptr_t)acc | (uintptr_t)out8 | (uintptr_t)workspace) & 15u)
+        return MP8_ERR_ALIGNMENT;
+    const Plan pl = conv_plan(op, d, Ci);
+    if (!pl.mfma) return MP8_ERR_UNSUPPORTED;
+
+    Epilogue ep{};
+    ep.alpha = alpha;
+    ep.acc = acc_mode ? acc : nullptr;
+    ep.acc_mode = acc_mode;
+    ep.out8 = out8;
+    ep.sr = round == MP8_SR;
+    ep.sat = (flags & MP8_FLAG_SATURATE) ? 1 : 0;
+    ep.seed = seed;
+    ep.offset = offset;
+    ep.stats = stats;
+    ep.rows = d.rows;
+    ep.cols = d.cols;
+    if (op != MP8_WGRAD) {
+        ep.mask = 1;
+        ep.hh = (int)(H + 2);
+        ep.valid_rows = B * img;
+        ep.div_img = make_fastdiv((uint32_t)img);
+        ep.div_w2 = make_fastdiv((uint32_t)(W + 2));
+    }
+    GemmArgs ga{};
+    ga.a = a;
+    ga.b = b;
+    ga.lda = d.lda;
+    ga.ldb = d.ldb;
+    ga.cv.w2 = (int)(W + 2);
+    ga.cv.div_cpb = make_fastdiv((uint32_t)((op == MP8_BWD_DATA ? Co : Ci) / 128));
+    ga.cv.b_tap_stride = Ci * Co;
+    ga.cv.div_ci = make_fastdiv((uint32_t)Ci);
+    return launch_mfma(ga, ep, pl, d.kc, kTiles[pl.tile].kernel_conv[(int)op], workspace, workspace_bytes,
+                       (hipStream_t)stream);
 }
 
 #ifdef MP8_TRACE
