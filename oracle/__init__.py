@@ -84,6 +84,10 @@ def lib():
         L.orc_sgd_update_fp16.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_float, C.c_float,
                                           C.c_int, C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p,
                                           C.c_void_p]
+        L.orc_sgd_momentum_fp16.restype = None
+        L.orc_sgd_momentum_fp16.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_float,
+                                            C.c_float, C.c_float, C.c_float, C.c_int, C.c_uint64,
+                                            C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]
         L.orc_scaler_update.restype = C.c_int
         L.orc_scaler_update.argtypes = [C.POINTER(Scaler), C.c_uint32]
         L.orc_scaler_set_floor.restype = None
@@ -243,6 +247,22 @@ def sgd_update_fp16(w16, g8, lr, inv_loss_scale, mode=SR, seed=0, offset=0, skip
                               offset, _p(sk), _p(w8),
                               C.byref(stats) if stats is not None else None)
     return w, w8
+
+
+def sgd_momentum_fp16(w16, vel, g8, lr, inv_loss_scale, momentum, weight_decay=0.0, mode=SR, seed=0,
+                      offset=0, skip=None, want_w8=False, stats: Stats | None = None):
+    """Momentum SGD with L2 regularisation on half master weights and an FP32 velocity.
+    Returns (new_w16, new_vel, w8 or None); inputs are not modified."""
+    w = np.array(w16, dtype=np.uint16, copy=True).reshape(-1)
+    v = np.array(vel, dtype=np.float32, copy=True).reshape(-1)
+    g = _carr(g8, np.uint8).reshape(-1)
+    assert w.size == g.size == v.size
+    w8 = np.zeros(w.size, dtype=np.uint8) if want_w8 else None
+    sk = None if skip is None else np.array([skip], dtype=np.uint32)
+    lib().orc_sgd_momentum_fp16(_p(w), _p(v), _p(g), w.size, float(lr), float(inv_loss_scale),
+                                float(momentum), float(weight_decay), mode, seed, offset, _p(sk),
+                                _p(w8), C.byref(stats) if stats is not None else None)
+    return w, v, w8
 
 
 def scaler_new(scale, floor, growth_interval) -> Scaler:

@@ -524,6 +524,52 @@ void orc_sgd_update_fp16(uint16_t *w16, const uint8_t *g8, int64_t n, float lr,
     }
 }
 
+/*
+ * The same path with the momentum optimizer that Figure 1b draws between the
+ * un-scaled gradient and the master weights, and the L2 regularisation term of
+ * Eq. 1 (loss + lambda * sum w^2, whose gradient 2 * lambda * w enters as
+ * weight_decay * w):
+ *   g   = fl32(value(g8) * inv_loss_scale)
+ *   w   = value(w16) as FP32
+ *   g   = fmaf(weight_decay, w, g)              regularisation gradient
+ *   v'  = fmaf(momentum, v, g)                  velocity, kept in FP32
+ *   w'  = fmaf(-lr, v', w)
+ *   w16 = half(w') rounded by `mode`
+ * The paper does not give the precision of the velocity; FP32 is the reading
+ * taken (every operation of this path is "a 32-bit operation").  With
+ * momentum = 0 and weight_decay = 0 this is orc_sgd_update_fp16 exactly.
+ */
+void orc_sgd_momentum_fp16(uint16_t *w16, float *vel, const uint8_t *g8, int64_t n, float lr,
+                           float inv_loss_scale, float momentum, float weight_decay, int mode,
+                           uint64_t seed, uint64_t offset, const uint32_t *skip,
+                           uint8_t *w8_out, orc_stats *stats)
+{
+    int64_t i;
+    uint32_t nonfinite = 0u;
+#pragma omp parallel for reduction(+ : nonfinite)
+    for (i = 0; i < n; ++i)
+        if ((g8[i] & 0x7Cu) == 0x7Cu)
+            nonfinite++;
+    if (stats)
+        stats->nonfinite += nonfinite;
+    if (skip && *skip != 0u)
+        return;
+#pragma omp parallel for
+    for (i = 0; i < n; ++i) {
+        volatile float g0 = (float)orc_e5m2_decode(g8[i]) * inv_loss_scale;
+        float w = (float)orc_fp16_decode(w16[i]);
+        float g = fmaf(weight_decay, w, g0);
+        float v = fmaf(momentum, vel[i], g);
+        float wn = fmaf(-lr, v, w);
+        uint32_t r16 = (mode == ORC_SR) ? orc_sr_bits(seed, offset, (uint64_t)i) : 0u;
+        uint16_t h = orc_fp16_encode((double)wn, mode, r16);
+        vel[i] = v;
+        w16[i] = h;
+        if (w8_out)
+            w8_out[i] = orc_e5m2_encode(orc_fp16_decode(h), ORC_RNE, 0u, 0);
+    }
+}
+
 /* ------------------------------------------------------------------------- */
 /* Loss scaler (Section 3.1)                                                  */
 /* ------------------------------------------------------------------------- */

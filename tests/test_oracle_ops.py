@@ -262,3 +262,65 @@ def test_overflow_injection_drives_scaler():
     oracle.quantize_e5m2(e, scale=lay.loss_scale, stats=st)
     s = oracle.scaler_new(2.0 ** 12, 2.0 ** 10, 2000)
     assert st.nonfinite == 1 and oracle.scaler_update(s, st.nonfinite) == 1 and s.scale == 2.0 ** 11
+
+
+# --- momentum optimizer on the master weights (Figure 1b, Eq. 1) ------------------------------
+
+def test_momentum_update_reduces_to_plain_update_and_closed_forms():
+    rng = np.random.default_rng(5)
+    n = 4096
+    w16 = (rng.standard_normal(n) * 0.05).astype(np.float16).view(np.uint16)
+    g8 = workloads.random_e5m2_codes(6, (n,), finite_only=False)
+    vel = np.zeros(n, np.float32)
+    # momentum 0, no decay: the plain update, bit for bit, under both rounding modes
+    for mode in (oracle.RNE, oracle.SR):
+        a, _ = oracle.sgd_update_fp16(w16, g8, 0.01, 1 / 256.0, mode=mode, seed=3, offset=4)
+        b, v, _ = oracle.sgd_momentum_fp16(w16, vel, g8, 0.01, 1 / 256.0, 0.0, 0.0, mode=mode, seed=3, offset=4)
+        assert np.array_equal(a, b)
+        gf = ((g8.astype(np.uint16) << 8).view(np.float16).astype(np.float32) * np.float32(1 / 256.0))
+        assert np.array_equal(v, gf, equal_nan=True)                       # velocity = gradient
+    # constant gradient 1.0, momentum 1/2: v_t = 2 - 2^(1-t) exactly; lr = 2^-6 keeps every
+    # weight on the half-precision grid, so t steps from w = 1 give 1 - 2^-6 * sum_{k<=t} v_k exactly
+    w = np.array([0x3C00], np.uint16)                                       # 1.0
+    v = np.zeros(1, np.float32)
+    g = np.array([0x3C], np.uint8)
+    want_w = 1.0
+    for t in range(1, 6):
+        w, v, _ = oracle.sgd_momentum_fp16(w, v, g, 2.0 ** -6, 1.0, 0.5, 0.0, mode=oracle.RNE)
+        assert v[0] == 2.0 - 2.0 ** (1 - t)
+        want_w -= 2.0 ** -6 * v[0]
+        assert oracle.fp16_decode(int(w[0])) == want_w
+    # regularisation alone: zero gradient, decay d, lr: w' = w - lr*d*w = w * (1 - lr*d)
+    w = np.array([0x4000], np.uint16)                                       # 2.0
+    w2, v2, _ = oracle.sgd_momentum_fp16(w, np.zeros(1, np.float32), np.zeros(1, np.uint8), 0.25, 1.0, 0.0,
+                                         0.5, mode=oracle.RNE)
+    assert v2[0] == 1.0 and oracle.fp16_decode(int(w2[0])) == 2.0 * (1 - 0.25 * 0.5)
+    # the skip flag leaves weights and velocity untouched, non-finite gradient codes are counted
+    st = oracle.Stats()
+    g_bad = np.array([0x7C, 0x3C, 0xFF], np.uint8)
+    w3 = np.array([0x3C00, 0x3C00, 0x3C00], np.uint16)
+    w4, v4, _ = oracle.sgd_momentum_fp16(w3, np.ones(3, np.float32), g_bad, 0.1, 1.0, 0.9, 0.0, skip=1, stats=st)
+    assert np.array_equal(w4, w3) and np.array_equal(v4, np.ones(3, np.float32)) and st.nonfinite == 2
+
+
+def test_momentum_update_against_float32_numpy():
+    """numpy float32 arithmetic with the fused multiply-adds written as exact double products
+    (a double holds the product of two floats exactly) rounded once to float32."""
+    rng = np.random.default_rng(8)
+    n = 20000
+    w16 = (rng.standard_normal(n) * 0.1).astype(np.float16).view(np.uint16)
+    g8 = workloads.random_e5m2_codes(9, (n,))
+    vel = (rng.standard_normal(n) * 0.01).astype(np.float32)
+    lr, inv, mu, wd = np.float32(0.05), np.float32(1 / 1024.0), np.float32(0.9), np.float32(1e-4)
+    got_w, got_v, _ = oracle.sgd_momentum_fp16(w16, vel, g8, lr, inv, mu, wd, mode=oracle.RNE)
+    fma = lambda a, b, c: (a.astype(np.float64) * b.astype(np.float64) + c.astype(np.float64)).astype(np.float32)
+    w = w16.view(np.float16).astype(np.float32)
+    g0 = ((g8.astype(np.uint16) << 8).view(np.float16).astype(np.float32) * inv).astype(np.float32)
+    g = fma(np.full(n, wd), w, g0)
+    v = fma(np.full(n, mu), vel, g)
+    wn = fma(np.full(n, -lr), v, w)
+    # the double-then-float rounding of the emulation differs from a true fused operation only on
+    # rare double-rounding ties: allow a handful of last-bit differences in the velocity
+    assert np.mean(got_v.view(np.uint32) != v.view(np.uint32)) < 1e-3
+    same = got_v.view(np.uint32) == v.view(np.uint32)
+    assert np.array_equal(got_w[same], wn.astype(np.float16).view(np.uint16)[same])
