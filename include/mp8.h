@@ -186,6 +186,21 @@ mp8_status mp8_sgd_update_fp16_sr(uint16_t *w16, const uint8_t *g8, int64_t n, f
                                   uint64_t offset, const uint32_t *skip_if_nonzero,
                                   uint8_t *w8_out, mp8_stats *stats, void *stream);
 
+/*
+ * The same path with the momentum optimizer of Figure 1b and the L2 regularisation term of
+ * Eq. 1 (its gradient enters as weight_decay * w), per element:
+ *     g  = fmaf(weight_decay, w, fl32(value(g8[i]) * inv_loss_scale))
+ *     v' = fmaf(momentum, velocity[i], g)        velocity is FP32, in/out, 16-byte aligned
+ *     w' = fmaf(-lr, v', w);   w16[i] = half(w') rounded by `round`
+ * With momentum = weight_decay = 0 the weights equal those of mp8_sgd_update_fp16_sr.  Other
+ * arguments as there; a skipped step leaves the velocity untouched too.
+ */
+mp8_status mp8_sgd_momentum_fp16_sr(uint16_t *w16, float *velocity, const uint8_t *g8, int64_t n,
+                                    float lr, float inv_loss_scale, float momentum,
+                                    float weight_decay, mp8_round round, uint64_t seed,
+                                    uint64_t offset, const uint32_t *skip_if_nonzero,
+                                    uint8_t *w8_out, mp8_stats *stats, void *stream);
+
 /* out[i] = the 16 random bits element i would use (device array of n uint16), for tests. */
 mp8_status mp8_sr_bits(uint16_t *out, int64_t n, uint64_t seed, uint64_t offset, void *stream);
 

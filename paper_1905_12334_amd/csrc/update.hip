@@ -30,6 +30,26 @@ __device__ __forceinline__ uint32_t update_one(uint32_t w16, uint32_t g8, float 
     }
 }
 
+// The same with the momentum optimizer and the L2 regularisation gradient in front of the
+// weight step; the velocity stays in FP32.  Every operation is rounded on its own (FP32).
+template <bool kSR>
+__device__ __forceinline__ uint32_t momentum_one(uint32_t w16, uint32_t g8, float &vel, float neg_lr,
+                                                 float inv_scale, float mu, float wd, uint32_t r16) {
+    float g = e5m2_to_f32(g8) * inv_scale;
+    const float w = __half2float(__ushort_as_half((unsigned short)w16));
+    g = __builtin_fmaf(wd, w, g);
+    const float v = __builtin_fmaf(mu, vel, g);
+    float wn = __builtin_fmaf(neg_lr, v, w);
+    asm volatile("" : "+v"(wn));  // keep the conversion a separate, second rounding
+    vel = v;
+    if constexpr (kSR) {
+        return f16_from_f32_bits<true>(f2u(wn), r16);
+    } else {
+        uint32_t h = __half_as_ushort(__float2half_rn(wn));
+        return (wn != wn) ? 0x7E00u : h;
+    }
+}
+
 __device__ __forceinline__ uint32_t e5m2_of_half(uint32_t h) {
     return e5m2_from_f32_bits<false>(f2u(__half2float(__ushort_as_half((unsigned short)h))), 0u,
                                      false);
@@ -124,7 +144,117 @@ __global__ __launch_bounds__(256) void sgd_update_kernel(uint16_t *__restrict__ 
     }
 }
 
+// Momentum variant: the same item shape (eight elements) plus 32 bytes of velocity read and
+// written per item; 13 bytes of traffic per element (+1 with the 8-bit copy).
+template <bool kSR, bool kW8>
+__global__ __launch_bounds__(256) void sgd_momentum_kernel(uint16_t *__restrict__ w16,
+                                                           float *__restrict__ vel,
+                                                           const uint8_t *__restrict__ g8, int64_t n,
+                                                           float neg_lr, float inv_scale, float mu,
+                                                           float wd, uint64_t seed, uint64_t offset,
+                                                           const uint32_t *__restrict__ skip,
+                                                           uint8_t *__restrict__ w8_out,
+                                                           mp8_stats *stats) {
+    const Philox rng(seed, offset);
+    const bool skipping = (skip != nullptr) && (*skip != 0u);
+    if (skipping && stats == nullptr) return;
+    uint32_t nonfinite = 0;
+    const int64_t n8 = n >> 3;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < n8; t += stride) {
+        const u32x2 gr = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(g8) + t);
+        const uint32_t gw[2] = {gr.x, gr.y};
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+            nonfinite += __builtin_popcount(((gw[q] & 0x7C7C7C7Cu) + 0x04040404u) & 0x80808080u);
+        if (skipping) continue;
+        const u32x4 wr = __builtin_nontemporal_load(reinterpret_cast<u32x4 *>(w16) + t);
+        f32x4 v0 = __builtin_nontemporal_load(reinterpret_cast<f32x4 *>(vel) + 2 * t);
+        f32x4 v1 = __builtin_nontemporal_load(reinterpret_cast<f32x4 *>(vel) + 2 * t + 1);
+        float vv[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+        uint32_t ww[4] = {wr.x, wr.y, wr.z, wr.w};
+        uint32_t rw[4] = {0, 0, 0, 0};
+        if constexpr (kSR) {
+            uint4 r = rng.block((uint64_t)t);
+            rw[0] = r.x; rw[1] = r.y; rw[2] = r.z; rw[3] = r.w;
+        }
+        uint32_t w8[2] = {0, 0};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {  // pair j = elements 2j, 2j+1
+            const uint32_t g_lo = (gw[j >> 1] >> (16 * (j & 1))) & 0xFFu;
+            const uint32_t g_hi = (gw[j >> 1] >> (16 * (j & 1) + 8)) & 0xFFu;
+            const uint32_t h_lo = momentum_one<kSR>(ww[j] & 0xFFFFu, g_lo, vv[2 * j], neg_lr, inv_scale, mu,
+                                                    wd, rw[j] & 0xFFFFu);
+            const uint32_t h_hi = momentum_one<kSR>(ww[j] >> 16, g_hi, vv[2 * j + 1], neg_lr, inv_scale, mu,
+                                                    wd, rw[j] >> 16);
+            ww[j] = h_lo | (h_hi << 16);
+            if constexpr (kW8)
+                w8[j >> 1] |= (e5m2_of_half(h_lo) | (e5m2_of_half(h_hi) << 8)) << (16 * (j & 1));
+        }
+        u32x4 o = {ww[0], ww[1], ww[2], ww[3]};
+        __builtin_nontemporal_store(o, reinterpret_cast<u32x4 *>(w16) + t);
+        v0 = f32x4{vv[0], vv[1], vv[2], vv[3]};
+        v1 = f32x4{vv[4], vv[5], vv[6], vv[7]};
+        __builtin_nontemporal_store(v0, reinterpret_cast<f32x4 *>(vel) + 2 * t);
+        __builtin_nontemporal_store(v1, reinterpret_cast<f32x4 *>(vel) + 2 * t + 1);
+        if constexpr (kW8) {
+            u32x2 o8 = {w8[0], w8[1]};
+            __builtin_nontemporal_store(o8, reinterpret_cast<u32x2 *>(w8_out) + t);
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x < 8) {  // ragged tail (< 8 elements)
+        const int64_t i = (n8 << 3) + threadIdx.x;
+        if (i < n) {
+            const uint32_t gc = g8[i];
+            nonfinite += ((gc & 0x7Cu) == 0x7Cu) ? 1u : 0u;
+            if (!skipping) {
+                uint32_t r16 = 0;
+                if constexpr (kSR) r16 = philox_half(rng.block((uint64_t)i >> 3), (int)(i & 7));
+                float v = vel[i];
+                const uint32_t h = momentum_one<kSR>(w16[i], gc, v, neg_lr, inv_scale, mu, wd, r16);
+                vel[i] = v;
+                w16[i] = (uint16_t)h;
+                if constexpr (kW8) w8_out[i] = (uint8_t)e5m2_of_half(h);
+            }
+        }
+    }
+    if (stats != nullptr) {
+        StatsAcc st;
+        st.nonfinite = nonfinite;
+        st.flush(stats);
+    }
+}
+
 }  // namespace mp8
+
+extern "C" mp8_status mp8_sgd_momentum_fp16_sr(uint16_t *w16, float *velocity, const uint8_t *g8,
+                                               int64_t n, float lr, float inv_loss_scale,
+                                               float momentum, float weight_decay, mp8_round round,
+                                               uint64_t seed, uint64_t offset,
+                                               const uint32_t *skip_if_nonzero, uint8_t *w8_out,
+                                               mp8_stats *stats, void *stream) {
+    using namespace mp8;
+    if (n < 0) return MP8_ERR_INVALID_ARG;
+    if (round != MP8_RNE && round != MP8_SR) return MP8_ERR_INVALID_ARG;
+    if (n == 0) return MP8_OK;
+    if (!w16 || !g8 || !velocity) return MP8_ERR_INVALID_ARG;
+    if (((uintptr_t)w16 | (uintptr_t)g8 | (uintptr_t)w8_out | (uintptr_t)velocity) & 15u)
+        return MP8_ERR_ALIGNMENT;
+    int64_t blocks = ((n >> 3) + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    if (blocks > (stats != nullptr ? 2048 : (1 << 22))) blocks = stats != nullptr ? 2048 : (1 << 22);
+    hipStream_t s = (hipStream_t)stream;
+    const float neg_lr = -lr;
+#define MP8_M(SR, W8)                                                                             \
+    hipLaunchKernelGGL((sgd_momentum_kernel<SR, W8>), dim3((unsigned)blocks), dim3(256), 0, s, w16, \
+                       velocity, g8, n, neg_lr, inv_loss_scale, momentum, weight_decay, seed,      \
+                       offset, skip_if_nonzero, w8_out, stats)
+    const bool sr = round == MP8_SR, w8 = w8_out != nullptr;
+    if (sr) { if (w8) MP8_M(true, true); else MP8_M(true, false); }
+    else    { if (w8) MP8_M(false, true); else MP8_M(false, false); }
+#undef MP8_M
+    return hipGetLastError() == hipSuccess ? MP8_OK : MP8_ERR_HIP;
+}
 
 extern "C" mp8_status mp8_sgd_update_fp16_sr(uint16_t *w16, const uint8_t *g8, int64_t n,
                                              float lr, float inv_loss_scale, mp8_round round,

@@ -96,3 +96,54 @@ def test_update_transformer_big_magnitudes_and_skip(mp8):
     assert np.array_equal(skipped, w16) and st[1] == 1
     ran, _, _ = _run(mp8, w16, g8, lr, inv, oracle.SR, seed=seed, offset=1, skip=0)
     assert np.array_equal(ran, want)
+
+
+@pytest.mark.parametrize("n", [1, 7, 4099, 1 << 20])
+@pytest.mark.parametrize("rnd", [oracle.RNE, oracle.SR])
+def test_momentum_update_matches_oracle_over_several_steps(mp8, n, rnd):
+    """Momentum SGD with L2 regularisation: weights, FP32 velocity and the 8-bit weight copy
+    bit-exact against the oracle over three chained steps."""
+    import torch
+    rng = np.random.default_rng(n + rnd)
+    w16 = (rng.standard_normal(n) * np.exp2(rng.integers(-20, 1, n))).astype(np.float16).view(np.uint16)
+    vel = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    lr, inv, mu, wd = 0.05, 1.0 / 1024, 0.9, 1e-4
+    wd_dev, vd = gpu(w16.view(np.int16)), gpu(vel)
+    w8d = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    ow, ov = w16, vel
+    for step in range(3):
+        g8 = workloads.random_e5m2_codes(100 * step + n % 97, (n,), finite_only=(step != 1))
+        st = mp8.new_stats()
+        mp8.sgd_momentum_fp16_sr(wd_dev, vd, gpu(g8), lr, inv, mu, wd, round=rnd, seed=5, offset=step,
+                                 w8_out=w8d, stats=st)
+        torch.cuda.synchronize()
+        ost = oracle.Stats()
+        ow, ov, o8 = oracle.sgd_momentum_fp16(ow, ov, g8, lr, inv, mu, wd, mode=rnd, seed=5, offset=step,
+                                              want_w8=True, stats=ost)
+        assert np.array_equal(host(wd_dev).view(np.uint16), ow), step
+        gv = host(vd)                      # bit-exact except for the payload of NaNs
+        ok = ~np.isnan(ov)
+        assert np.array_equal(np.isnan(gv), ~ok) and np.array_equal(gv[ok].view(np.uint32), ov[ok].view(np.uint32)), step
+        assert np.array_equal(host(w8d), o8), step
+        assert mp8.read_stats(st)[1] == ost.nonfinite
+
+
+def test_momentum_update_skip_and_reduction_to_plain_update(mp8):
+    import torch
+    n = 50000
+    rng = np.random.default_rng(12)
+    w16 = (rng.standard_normal(n) * 0.02).astype(np.float16).view(np.uint16)
+    g8 = workloads.random_e5m2_codes(13, (n,))
+    a = gpu(w16.view(np.int16))
+    b = gpu(w16.view(np.int16))
+    v = torch.zeros(n, dtype=torch.float32, device="cuda")
+    mp8.sgd_update_fp16_sr(a, gpu(g8), 1e-2, 1 / 64.0, round=mp8.SR, seed=1, offset=2)
+    mp8.sgd_momentum_fp16_sr(b, v, gpu(g8), 1e-2, 1 / 64.0, 0.0, 0.0, round=mp8.SR, seed=1, offset=2)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+    # a skipped step touches neither weights nor velocity
+    flag = torch.ones(1, dtype=torch.int32, device="cuda")
+    v0, b0 = v.clone(), b.clone()
+    mp8.sgd_momentum_fp16_sr(b, v, gpu(g8), 1e-2, 1 / 64.0, 0.9, 0.0, skip_if_nonzero=flag)
+    torch.cuda.synchronize()
+    assert torch.equal(b, b0) and torch.equal(v, v0)
