@@ -307,8 +307,8 @@ template <int BM, int BN, int WGM, int WGN, int NSTAGE, int MINBLOCKS, int EPI, 
 __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArgs p) {
     static_assert(CONV == 0 || (CONV == 1 && !ATN && BTN) || (CONV == 2 && !ATN && !BTN) ||
                       (CONV == 3 && ATN && BTN), "operand layouts of the convolution forms");
-    static_assert((!ATN || BM % 128 == 0) && (!BTN || BN % 128 == 0),
-                  "contraction-major operands: 128-row panels");
+    static_assert((!ATN || BM % 128 == 0 || BM == 64) && (!BTN || BN % 128 == 0 || BN == 64),
+                  "contraction-major operands: panels of 128 (or one of 64) tile rows");
     static_assert(WGM * WGN == 4, "four waves");
     static_assert(NSTAGE >= 2, "ring depth");
     constexpr int WTM = BM / WGM, WTN = BN / WGN;  // wave tile
@@ -349,7 +349,11 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     // is 128 contraction rows of 128 bytes, chunk c of contraction row k sits in slot
     // c ^ ((k >> 1) & 7).  Chunks that would start beyond the matrix are clamped to its last
     // 16 rows (never stored).
+    // A tile of only 64 rows is one panel of 128 contraction rows of 64 bytes: a direct load
+    // then covers 16 contraction rows, lane i lands at (row i/4, slot i%4), and chunk c of
+    // contraction row k sits in slot c ^ ((k >> 2) & 3).
     const int lrow = lane >> 3, lchunk = (lane & 7) ^ ((4 * wave + (lane >> 4)) & 7);
+    const int lrow64 = lane >> 2, lchunk64 = (lane & 3) ^ ((lane >> 4) & 3);
     const int64_t a_kstep = ATN ? (int64_t)BK * p.lda : BK, b_kstep = BTN ? (int64_t)BK * p.ldb : BK;
     auto tap_shift = [&](uint32_t tap) {  // pixel-row shift of filter tap (r, s) = (tap / 3, tap % 3)
         const int r = (int)((tap * 11u) >> 5);
@@ -393,8 +397,8 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
 #pragma unroll
     for (int q = 0; q < A_DMA; ++q) {
         if constexpr (ATN) {
-            const int64_t krow = 8 * (wave + 4 * (q & 3)) + lrow;
-            int64_t m = 128 * (q >> 2) + 16 * lchunk;
+            const int64_t krow = BM == 64 ? 16 * (wave + 4 * q) + lrow64 : 8 * (wave + 4 * (q & 3)) + lrow;
+            int64_t m = BM == 64 ? 16 * lchunk64 : 128 * (q >> 2) + 16 * lchunk;
             m = row0 + m + 16 <= p.rows ? m : p.rows - 16 - row0;
             oa[q] = (uint32_t)(krow * p.lda + m);
         } else {
@@ -406,8 +410,8 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
 #pragma unroll
     for (int q = 0; q < B_DMA; ++q) {
         if constexpr (BTN) {
-            const int64_t krow = 8 * (wave + 4 * (q & 3)) + lrow;
-            int64_t m = 128 * (q >> 2) + 16 * lchunk;
+            const int64_t krow = BN == 64 ? 16 * (wave + 4 * q) + lrow64 : 8 * (wave + 4 * (q & 3)) + lrow;
+            int64_t m = BN == 64 ? 16 * lchunk64 : 128 * (q >> 2) + 16 * lchunk;
             m = col0 + m + 16 <= p.cols ? m : p.cols - 16 - col0;
             ob[q] = (uint32_t)(krow * p.ldb + m);
         } else {
@@ -451,13 +455,15 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
             // reads make the 32 bytes a lane feeds to one MFMA.
             const int t = lane & 15;
             const int m = (f < MT ? wm * WTM + f * 32 : wn * WTN + (f - MT) * 32) + (frow & 16);
-            const int obase = (f < MT ? 0 : A_BYTES) + (m >> 7) * 16384;
-            const int mc = (m & 127) >> 4;
+            const bool narrow = f < MT ? BM == 64 : BN == 64;  // one panel of 64-byte rows
+            const int obase = (f < MT ? 0 : A_BYTES) + (narrow ? 0 : (m >> 7) * 16384);
+            const int mc = narrow ? (m & 63) >> 4 : (m & 127) >> 4;
             i32x2 part[2];
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
                 const int k = 64 * sub + 32 * fkb + 8 * (2 * half + e) + (t >> 1);
-                const int off = obase + k * 128 + ((mc ^ ((k >> 1) & 7)) << 4) + 8 * (t & 1);
+                const int off = obase + (narrow ? k * 64 + ((mc ^ ((k >> 2) & 3)) << 4)
+                                                : k * 128 + ((mc ^ ((k >> 1) & 7)) << 4)) + 8 * (t & 1);
                 part[e] = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
                     (__attribute__((address_space(3))) i32x2 *)(s + off));
             }
@@ -844,8 +850,8 @@ struct TileConfig {
 static const TileConfig kTiles[] = {
     MP8_TILE_TN(256, 256, 2, 2, 2, 1), MP8_TILE(256, 128, 2, 2, 3, 1), MP8_TILE(128, 256, 2, 2, 3, 1),
     MP8_TILE_TN(128, 128, 2, 2, 2, 2), MP8_TILE_TN(128, 128, 2, 2, 4, 1), MP8_TILE(64, 128, 1, 4, 3, 2),
-    MP8_TILE(128, 64, 4, 1, 3, 2),  MP8_TILE(64, 64, 2, 2, 4, 2),   MP8_TILE(64, 128, 1, 4, 2, 3),
-    MP8_TILE(128, 64, 4, 1, 2, 3),  MP8_TILE(64, 64, 2, 2, 2, 4),
+    MP8_TILE(128, 64, 4, 1, 3, 2),  MP8_TILE_TN(64, 64, 2, 2, 4, 2), MP8_TILE(64, 128, 1, 4, 2, 3),
+    MP8_TILE(128, 64, 4, 1, 2, 3),  MP8_TILE_TN(64, 64, 2, 2, 2, 4),
 };
 constexpr int kNumTiles = (int)(sizeof(kTiles) / sizeof(kTiles[0]));
 constexpr int kCUs = 256;
@@ -900,6 +906,7 @@ static Plan make_plan(int64_t rows, int64_t cols, int64_t kc, int tile_config, i
         const int64_t n256 = count(T256x256), n128 = count(T128x128s2);
         const double fill256 = (double)n256 / (double)(((n256 + kCUs - 1) / kCUs) * kCUs);
         if (n256 >= 208 && fill256 >= 0.8 && ksteps >= 8) t = T256x256;
+        else if (tn && (n128 < 16 || (n128 < 192 && ksteps <= 64))) t = T64x64s2;
         else if (tn) t = ksteps >= 64 ? T128x128s4 : T128x128s2;
         else if (n128 >= 192 && ksteps <= 2) t = T128x64s2;  // all prologue and epilogue
         else if (n128 >= 192) t = (ksteps >= 64 && n128 <= 2 * kCUs) ? T128x128s4 : T128x128s2;
@@ -913,9 +920,11 @@ static Plan make_plan(int64_t rows, int64_t cols, int64_t kc, int tile_config, i
     if (split_k > 0) {
         s = split_k;
     } else if (nt < kCUs / 2) {
-        // about one and a half blocks per CU; fewer for the 128-row tiles of contraction-major
-        // operands, whose FP32 partial tiles are four times as large
-        s = (int)(((tn ? 160 : 384) + nt - 1) / nt);
+        // about one and a half blocks per CU; two for the smallest tiles; fewer for the 128-row
+        // tiles of contraction-major operands, whose FP32 partial tiles are four times as large
+        const int target = kTiles[t].bm * kTiles[t].bn <= 64 * 64 ? 512 : tn ? 160 : 384;
+        s = std::max(1, (int)(target / nt));        // never more blocks than the target: the
+                                                    // CUs that got one more would set the time
         s = std::min(s, std::max(1, ksteps / 8));  // at least eight stages per slice
         s = std::min(s, kMaxSplits);
     }
@@ -1130,6 +1139,10 @@ static Plan conv_plan(mp8_op op, const ConvDims &d, int64_t Ci) {
     Plan pl = make_plan(d.rows, d.cols, d.kc, 0, 0, 3);
     // a tile row of the weight gradient must not straddle two taps
     if (pl.mfma && op == MP8_WGRAD && (Ci % kTiles[pl.tile].bm) != 0)
+        pl = make_plan(d.rows, d.cols, d.kc, T128x128s2 + 1, 0, 3);
+    // forward and backward data have one tile row per 128 pixels and few tile columns: the
+    // 128-row tile keeps the re-reads of the weights low
+    if (pl.mfma && op != MP8_WGRAD && kTiles[pl.tile].bm < 128)
         pl = make_plan(d.rows, d.cols, d.kc, T128x128s2 + 1, 0, 3);
     return pl;
 }
