@@ -261,15 +261,16 @@ struct StatsAcc {
     // and block.  Every thread of the block must call this (it contains a barrier).
     __device__ __forceinline__ void flush(mp8_stats *out) {
         __shared__ uint32_t part[3][16];
+        // The running maximum at the destination, fetched early so that its latency hides
+        // behind the reductions: the maximum only grows, so a block whose own maximum does not
+        // exceed a value already seen there has nothing to add (the load bypasses non-coherent
+        // caches; an older value only makes the test more conservative).
+        uint32_t seen = 0;
+        if (threadIdx.x == 0)
+            seen = __hip_atomic_load(&out->amax_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         uint32_t m = nan_seen ? 0x7FC00000u : f2u(amax);
         uint32_t nf = nonfinite, z = zero_codes - zero_inputs;
-#pragma unroll
-        for (int o = kWave / 2; o > 0; o >>= 1) {
-            uint32_t om = __shfl_xor(m, o);
-            m = om > m ? om : m;
-            nf += __shfl_xor(nf, o);
-            z += __shfl_xor(z, o);
-        }
+        reduce_wave(m, nf, z);
         const int wave = threadIdx.x / kWave, nwaves = (blockDim.x + kWave - 1) / kWave;
         if ((threadIdx.x & (kWave - 1)) == 0) {
             part[0][wave] = m;
@@ -277,19 +278,49 @@ struct StatsAcc {
             part[2][wave] = z;
         }
         __syncthreads();
-        if (threadIdx.x == 0) {
-            for (int w = 1; w < nwaves; ++w) {
-                m = part[0][w] > m ? part[0][w] : m;
-                nf += part[1][w];
-                z += part[2][w];
+        if (wave == 0) {  // the first wave combines the (at most 16) wave results
+            const int l = threadIdx.x;
+            m = l < nwaves ? part[0][l] : 0u;
+            nf = l < nwaves ? part[1][l] : 0u;
+            z = l < nwaves ? part[2][l] : 0u;
+            reduce_wave(m, nf, z);
+            if (l == 0) {
+                if (m > seen) atomicMax(&out->amax_bits, m);
+                if (nf) atomicAdd(&out->nonfinite, nf);
+                if (z) atomicAdd(&out->zeroed, z);
             }
-            // the maximum only grows, so a block whose own maximum does not exceed a value
-            // already seen there has nothing to add (the load bypasses non-coherent caches)
-            if (m > __hip_atomic_load(&out->amax_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
-                atomicMax(&out->amax_bits, m);
-            if (nf) atomicAdd(&out->nonfinite, nf);
-            if (z) atomicAdd(&out->zeroed, z);
         }
+    }
+
+    // Maximum of m and sums of nf and z over the 64 lanes, left in every lane.  Four
+    // data-parallel-primitive steps combine the 16 lanes of a row (neighbour, pair, mirrored
+    // half row, mirrored row); the four row results are then read as scalars.
+    static __device__ __forceinline__ void reduce_wave(uint32_t &m, uint32_t &nf, uint32_t &z) {
+#define MP8_DPP_STEP(ctrl)                                                                    \
+    {                                                                                         \
+        const uint32_t om = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)m, ctrl, 0xF, 0xF, true);   \
+        const uint32_t onf = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)nf, ctrl, 0xF, 0xF, true); \
+        const uint32_t oz = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)z, ctrl, 0xF, 0xF, true);   \
+        m = om > m ? om : m;                                                                  \
+        nf += onf;                                                                            \
+        z += oz;                                                                              \
+    }
+        MP8_DPP_STEP(0xB1)   // quad_perm [1,0,3,2]
+        MP8_DPP_STEP(0x4E)   // quad_perm [2,3,0,1]
+        MP8_DPP_STEP(0x141)  // row_half_mirror
+        MP8_DPP_STEP(0x140)  // row_mirror
+#undef MP8_DPP_STEP
+        uint32_t rm = 0, rnf = 0, rz = 0;
+#pragma unroll
+        for (int row = 0; row < 4; ++row) {
+            const uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)m, 16 * row);
+            rm = a > rm ? a : rm;
+            rnf += (uint32_t)__builtin_amdgcn_readlane((int)nf, 16 * row);
+            rz += (uint32_t)__builtin_amdgcn_readlane((int)z, 16 * row);
+        }
+        m = rm;
+        nf = rnf;
+        z = rz;
     }
 };
 
