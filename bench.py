@@ -45,8 +45,8 @@ LR = 1e-3
 # by what the same counters read on a plain 1 GiB copy (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000);
 # the runs and their raw figures are in profiles/bench_step_cfg2_hbm_traffic.txt
 MEASURED_TRAFFIC_BYTES = {
-    "quantize_X": 144555139, "quantize_dY": 16138036, "gemm_fwd": 33398274,
-    "gemm_bwd_data": 34284621, "gemm_wgrad": 60777600, "sgd_update": 1031358,
+    "quantize_X": 144555344, "quantize_dY": 16141620, "gemm_fwd": 33421826,
+    "gemm_bwd_data": 34288717, "gemm_wgrad": 53984201, "sgd_update": 1041803,
 }
 
 
