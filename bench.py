@@ -312,6 +312,22 @@ def all_configs_report(mp8, torch):
                      "frac_mfma_peak": flops / us / 1e6 / FP8_PEAK_TFLOPS,
                      "alg_gbs": nbytes / us / 1e3, "flop_per_byte": flops / nbytes})
         del a, b, out, ws
+    # configs[3] weight gradient the naive way: one call per timestep accumulating into an FP32
+    # tensor (acc_mode 2), 50 calls for what the stacked contraction above does in one
+    M, N, K = 128, 4096, 2048
+    a = (torch.randint(0, 256, (K, M), dtype=torch.uint8, device=dev) & 0x83) | 0x38
+    b = (torch.randint(0, 256, (N, M), dtype=torch.uint8, device=dev) & 0x83) | 0x38
+    acc = torch.zeros((K, N), dtype=torch.float32, device=dev)
+    out = torch.empty((K, N), dtype=torch.uint8, device=dev)
+    ws = torch.empty(max(mp8.gemm_fp8_workspace_bytes(mp8.WGRAD, M, N, K), 16), dtype=torch.uint8, device=dev)
+    us = graph_time_us(torch, lambda: mp8.gemm_fp8(mp8.WGRAD, M, N, K, a, b, out8=out, acc=acc, acc_mode=2,
+                                                   workspace=ws), 10)
+    rows.append({"kernel": "gemm_fp8", "case": "configs[3] wgrad, one timestep accumulated in FP32 "
+                 "(acc_mode 2); x50 for all timesteps", "us": us, "tflops": 2.0 * M * N * K / us / 1e6,
+                 "frac_mfma_peak": 2.0 * M * N * K / us / 1e6 / FP8_PEAK_TFLOPS,
+                 "alg_gbs": (K * M + N * M + 9 * K * N) / us / 1e3,
+                 "flop_per_byte": 2.0 * M * N * K / (K * M + N * M + 9 * K * N)})
+    del a, b, acc, out, ws
     n = 1 << 28
     src = torch.empty((1 << 14, 1 << 14), dtype=torch.float32, device=dev).normal_()
     d8 = torch.empty((1 << 14, 1 << 14), dtype=torch.uint8, device=dev)
@@ -406,6 +422,7 @@ def main():
         calibrate_copy(torch)
         return
 
+    props = torch.cuda.get_device_properties(0)
     lay = workloads.config2()
     wl = Workload(mp8, torch, lay)
     for _ in range(args.warmup):
@@ -442,6 +459,9 @@ def main():
         "pct_of_fp8_peak_whole_step": 100.0 * value / FP8_PEAK_TFLOPS,
         "gemm_only_tflops": gemm_flops / (gemm_us * 1e-6) / 1e12,
         "overflow_count_last_step": nonfinite,
+        "device": {"name": props.name, "compute_units": props.multi_processor_count,
+                   "max_clock_mhz": getattr(props, "clock_rate", 0) / 1e3 or None,
+                   "memory_gib": round(props.total_memory / 2 ** 30, 1)},
         "roofline": roofline,
         "kernels": kernels,
     }
