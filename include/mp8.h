@@ -134,6 +134,11 @@ mp8_status mp8_gemm_fp8_tuned(mp8_op op, int64_t M, int64_t N, int64_t K, const 
                               void *stream, int tile_config, int split_k);
 size_t mp8_gemm_fp8_workspace_bytes_tuned(mp8_op op, int64_t M, int64_t N, int64_t K,
                                           int tile_config, int split_k);
+/* Host only: which kernel an aligned call with these arguments would take -- *tile_out the tile
+ * configuration (1-based; 0 = the any-shape kernel), *splits_out the number of contraction
+ * slices.  For tests and tuning. */
+mp8_status mp8_gemm_fp8_plan(mp8_op op, int64_t M, int64_t N, int64_t K, int flags, int tile_config,
+                             int split_k, int *tile_out, int *splits_out);
 int mp8_gemm_num_tile_configs(void);
 /* Writes "BMxBNxBK" style description of tile_config (1-based) into buf. */
 int mp8_gemm_tile_config_name(int tile_config, char *buf, size_t buflen);

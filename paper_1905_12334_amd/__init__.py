@@ -27,6 +27,7 @@ EXPORTS = [
     "mp8_gemm_tile_config_name", "mp8_sgd_update_fp16_sr", "mp8_sr_bits", "mp8_philox4x32_10",
     "mp8_scaler_init", "mp8_scaler_update", "mp8_scaler_set_floor", "mp8_status_string",
     "mp8_conv3x3_fp8", "mp8_conv3x3_fp8_workspace_bytes", "mp8_sgd_momentum_fp16_sr",
+    "mp8_gemm_fp8_plan",
 ]
 
 
@@ -65,6 +66,8 @@ def lib() -> C.CDLL:
     L.mp8_gemm_fp8_workspace_bytes.argtypes = [ci, i64, i64, i64]
     L.mp8_gemm_fp8_workspace_bytes_tuned.restype = C.c_size_t
     L.mp8_gemm_fp8_workspace_bytes_tuned.argtypes = [ci, i64, i64, i64, ci, ci]
+    L.mp8_gemm_fp8_plan.restype = ci
+    L.mp8_gemm_fp8_plan.argtypes = [ci, i64, i64, i64, ci, ci, ci, C.POINTER(ci), C.POINTER(ci)]
     L.mp8_gemm_num_tile_configs.restype = ci
     L.mp8_gemm_num_tile_configs.argtypes = []
     L.mp8_gemm_tile_config_name.restype = ci
@@ -247,6 +250,14 @@ def conv3x3_fp8(op, B, H, W, Cin, Cout, a, b, out8=None, acc=None, acc_mode=0, a
                                _ptr(workspace), ws_bytes, _stream())
     _check(st, "mp8_conv3x3_fp8")
     return out8
+
+
+def gemm_fp8_plan(op, M, N, K, flags=0, tile_config=0, split_k=0):
+    """(tile configuration name or None for the any-shape kernel, contraction slices)."""
+    t, s = C.c_int(0), C.c_int(0)
+    _check(lib().mp8_gemm_fp8_plan(op, M, N, K, flags, tile_config, split_k, C.byref(t), C.byref(s)),
+           "mp8_gemm_fp8_plan")
+    return (gemm_tile_configs()[t.value - 1] if t.value else None), s.value
 
 
 def gemm_tile_configs():

@@ -966,6 +966,22 @@ extern "C" size_t mp8_gemm_fp8_workspace_bytes_tuned(mp8_op op, int64_t M, int64
     return need;
 }
 
+extern "C" mp8_status mp8_gemm_fp8_plan(mp8_op op, int64_t M, int64_t N, int64_t K, int flags,
+                                        int tile_config, int split_k, int *tile_out,
+                                        int *splits_out) {
+    using namespace mp8;
+    if (M <= 0 || N <= 0 || K <= 0 || (int)op < 0 || (int)op > 2) return MP8_ERR_INVALID_ARG;
+    if (tile_config < 0 || tile_config > kNumTiles || split_k < 0) return MP8_ERR_INVALID_ARG;
+    const bool atn = (flags & MP8_FLAG_A_CONTRACTION_MAJOR) != 0, btn = (flags & MP8_FLAG_B_CONTRACTION_MAJOR) != 0;
+    if (atn && !btn) return MP8_ERR_UNSUPPORTED;
+    int64_t rows, cols, kc;
+    op_dims(op, M, N, K, rows, cols, kc);
+    const Plan pl = make_plan(rows, cols, kc, tile_config, split_k, (atn ? 1 : 0) | (btn ? 2 : 0));
+    if (tile_out) *tile_out = pl.mfma ? pl.tile + 1 : 0;
+    if (splits_out) *splits_out = pl.splits;
+    return MP8_OK;
+}
+
 extern "C" size_t mp8_gemm_fp8_workspace_bytes(mp8_op op, int64_t M, int64_t N, int64_t K) {
     return mp8_gemm_fp8_workspace_bytes_tuned(op, M, N, K, 0, 0);
 }

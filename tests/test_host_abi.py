@@ -93,3 +93,71 @@ def test_workspace_query_is_consistent():
             assert mp8.gemm_fp8_workspace_bytes(op, M, N, K, 1, s) == s * rows * cols * 4
     assert len(mp8.gemm_tile_configs()) == mp8.lib().mp8_gemm_num_tile_configs() >= 4
     assert mp8.gemm_fp8_workspace_bytes(mp8.FWD, 100, 100, 100) == 0   # generic kernel
+
+
+def test_kernel_plans_are_sane_over_many_shapes():
+    """Host-side planning: for every operation, operand layout and a spread of shapes, the plan
+    names an existing tile configuration, uses between 1 and 64 contraction slices, never more
+    than there are 128-byte stages, and the workspace query covers one FP32 tile set per slice."""
+    names = mp8.gemm_tile_configs()
+    rng = np.random.default_rng(3)
+    shapes = [(25088, 128, 1152), (4096, 2048, 512), (4096, 512, 2048), (128, 4096, 2048), (6400, 4096, 2048),
+              (16384, 4096, 1024), (8192, 8192, 8192), (256, 256, 256), (1, 1, 128), (17, 33, 100)]
+    shapes += [tuple(int(16 * rng.integers(1, 400)) for _ in range(2)) + (int(128 * rng.integers(1, 200)),)
+               for _ in range(60)]
+    for M, N, K in shapes:
+        for op in (mp8.FWD, mp8.BWD_DATA, mp8.WGRAD):
+            rows, cols, kc = {mp8.FWD: (M, N, K), mp8.BWD_DATA: (M, K, N), mp8.WGRAD: (K, N, M)}[op]
+            for flags in (0, mp8.FLAG_B_CONTRACTION_MAJOR, mp8.FLAG_CONTRACTION_MAJOR):
+                tile, splits = mp8.gemm_fp8_plan(op, M, N, K, flags)
+                need = mp8.gemm_fp8_workspace_bytes(op, M, N, K)
+                if kc % 128 != 0:
+                    assert tile is None and splits == 1
+                    continue
+                if tile is None:            # contraction-major operands need rows / cols in 16s
+                    assert flags != 0 and (rows % 16 or cols % 16)
+                    continue
+                assert tile in names and 1 <= splits <= 64 and splits <= kc // 128
+                assert need >= splits * rows * cols * 4
+                bm, bn = (int(x) for x in tile.split("x")[:2])
+                tiles = -(-rows // bm) * -(-cols // bn)
+                if splits > 1:
+                    assert tiles < 128 and tiles * splits <= 512   # a split only when tiles are few
+    # the tuned form reports what it was given
+    assert mp8.gemm_fp8_plan(mp8.FWD, 4096, 4096, 4096, 0, 1, 3) == (names[0], 3)
+    with pytest.raises(mp8.Mp8Error):
+        mp8.gemm_fp8_plan(mp8.FWD, 128, 128, 128, mp8.FLAG_A_CONTRACTION_MAJOR)
+
+
+def test_c_program_links_and_calls_the_library(tmp_path):
+    """The boundary is a C ABI: a plain C translation unit that includes the header compiles with
+    gcc, links against the shared library and calls its host-side entry points."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_mp8.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include "mp8.h"
+int main(void) {
+    uint32_t ctr[4] = {0, 0, 0, 0}, key[2] = {0, 0}, out[4];
+    mp8_scaler s;
+    int tile = -1, splits = -1;
+    mp8_philox4x32_10(ctr, key, out);
+    mp8_scaler_init(&s, 4096.0, 1024.0, 2);
+    if (mp8_scaler_update(&s, 3) != 1 || s.scale != 2048.0) return 2;
+    if (mp8_gemm_fp8_plan(MP8_WGRAD, 25088, 128, 1152, MP8_FLAG_CONTRACTION_MAJOR, 0, 0, &tile, &splits) != MP8_OK) return 3;
+    if (mp8_quantize_e5m2(NULL, 0, NULL, NULL, -1, 4, 1.0f, MP8_RNE, 0, 0, 0, NULL, NULL) != MP8_ERR_INVALID_ARG) return 4;
+    printf("%08x %08x %08x %08x %d %d %s\n", out[0], out[1], out[2], out[3], tile, splits, mp8_status_string(MP8_ERR_WORKSPACE));
+    return 0;
+}
+''')
+    exe = tmp_path / "use_mp8"
+    libdir = os.path.dirname(mp8.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe),
+                    "-L", libdir, "-l:libmp8.so", f"-Wl,-rpath,{libdir}"], check=True)
+    res = subprocess.run([str(exe)], check=True, capture_output=True, text=True)
+    words = res.stdout.split()
+    assert words[:4] == ["6627e8d5", "e169c58d", "bc57ac4c", "9b00dbd8"]     # Philox known answer
+    assert int(words[4]) >= 1 and int(words[5]) >= 1
