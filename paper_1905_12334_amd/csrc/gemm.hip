@@ -26,6 +26,7 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstring>
+#include <type_traits>
 
 #include "mp8_device.hpp"
 
@@ -46,7 +47,11 @@ constexpr int BK = 128;  // bytes (= elements) of contraction per pipeline stage
 __device__ unsigned long long mp8_trace_buf[4][160][8];
 #define MP8_STAMP(pt) do { if (blockIdx.x == MP8_TRACE_BLOCK && lane == 0 && t < 159) mp8_trace_buf[wave][t][pt] = __builtin_readcyclecounter(); } while (0)
 #define MP8_STAMP_PHASE(pt) do { if (blockIdx.x == MP8_TRACE_BLOCK && (threadIdx.x & 63) == 0) mp8_trace_buf[threadIdx.x >> 6][159][pt] = __builtin_readcyclecounter(); } while (0)
+// constant-rate (100 MHz) clock stamps of every workgroup: [block][point]
+__device__ unsigned long long mp8_block_times[16384][4];
+#define MP8_BLOCK_STAMP(pt) do { if (threadIdx.x == 0 && blockIdx.x < 16384) mp8_block_times[blockIdx.x][pt] = wall_clock64(); } while (0)
 #else
+#define MP8_BLOCK_STAMP(pt) do { } while (0)
 #define MP8_STAMP(pt) do { } while (0)
 #define MP8_STAMP_PHASE(pt) do { } while (0)
 #endif
@@ -122,6 +127,7 @@ struct GemmArgs {
     FastDiv div_tiles;  // by tiles_m * tiles_n
     FastDiv div_band;   // by 8 * tiles_n
     FastDiv div_tail;   // by the height of the last band of tile rows (tiles_m % 8, or 8)
+    FastDiv div_tn;     // by tiles_n
     int ks_per, ks_extra;  // ksteps / splits and ksteps % splits
     float *partial;     // [splits, rows, cols] when splits > 1
     ConvArgs cv;
@@ -235,6 +241,48 @@ __device__ __forceinline__ void map_block(const GemmArgs &p, int &split, int &tm
     }
 }
 
+enum { EPI_PARTIAL = 0, EPI_RNE = 1, EPI_FULL = 2 };
+
+// What a tile kernel does with sixteen consecutive columns c .. c+15 (c % 16 == 0) of output row
+// r, per epilogue variant (described at the main kernel): FP32 to slice `split` of the workspace, the RNE-only
+// conversion, or the complete epilogue.
+template <int EPI>
+__device__ __forceinline__ void emit16(const GemmArgs &p, int split, int64_t r, int64_t c,
+                                       float v[16], StatsAcc &st, bool fast_cols) {
+    if constexpr (EPI == EPI_PARTIAL) {
+        float *dst = p.partial + ((int64_t)split * p.rows + r) * p.cols + c;
+        if (fast_cols) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                f32x4 o = {v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]};
+                reinterpret_cast<f32x4 *>(dst)[q] = o;
+            }
+        } else {
+#pragma nounroll
+            for (int e = 0; e < 16; ++e) {
+                float x = v[0];
+#pragma unroll
+                for (int k = 1; k < 16; ++k) x = (e == k) ? v[k] : x;
+                if (c + e < p.cols) dst[e] = x;
+            }
+        }
+    } else if constexpr (EPI == EPI_RNE) {
+        // the host sends only row lengths that are multiples of 16 here
+        uint32_t pk[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            float y[4] = {v[4 * q] * p.ep.alpha, v[4 * q + 1] * p.ep.alpha,
+                          v[4 * q + 2] * p.ep.alpha, v[4 * q + 3] * p.ep.alpha};
+            pk[q] = e5m2_pack4<false>(y, 0u, 0u, false);
+        }
+        if (p.ep.mask && conv_padding_row(p.ep, r)) pk[0] = pk[1] = pk[2] = pk[3] = 0;
+        u32x4 o = {pk[0], pk[1], pk[2], pk[3]};
+        *reinterpret_cast<u32x4 *>(p.ep.out8 + r * p.cols + c) = o;
+    } else {
+        finish16(p.ep, r, c, v, st);
+    }
+}
+
 // Wait until at most n vector-memory operations of this wave are outstanding and all of its
 // LDS operations have completed (gfx9 encoding: vmcnt in bits 3:0 and 15:14, lgkmcnt in
 // bits 11:8, expcnt left at "no wait").
@@ -294,7 +342,6 @@ __device__ __forceinline__ uint32_t lds_address(const void *p) {
 //                epilogue does not carry); the finishing kernel does the rest
 //   EPI_RNE      out8 = Q_RNE(alpha * acc), nothing else
 //   EPI_FULL     out8 with run-time rounding mode, saturation and statistics
-enum { EPI_PARTIAL = 0, EPI_RNE = 1, EPI_FULL = 2 };
 
 // CONV: 0 plain GEMM; 1 / 2 / 3 forward / backward-data / weight-gradient 3x3 convolution on
 // zero-padded channels-last tensors, where a tap of the filter is a shift of the pixel row:
@@ -660,38 +707,7 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
                     f32x4 x = src[q];
                     v[4 * q] = x.x; v[4 * q + 1] = x.y; v[4 * q + 2] = x.z; v[4 * q + 3] = x.w;
                 }
-                if constexpr (EPI == EPI_PARTIAL) {
-                    float *dst = p.partial + ((int64_t)split * p.rows + r) * p.cols + c;
-                    if (fast_cols) {
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            f32x4 o = {v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]};
-                            reinterpret_cast<f32x4 *>(dst)[q] = o;
-                        }
-                    } else {
-#pragma nounroll
-                        for (int e = 0; e < 16; ++e) {
-                            float x = v[0];
-#pragma unroll
-                            for (int k = 1; k < 16; ++k) x = (e == k) ? v[k] : x;
-                            if (c + e < p.cols) dst[e] = x;
-                        }
-                    }
-                } else if constexpr (EPI == EPI_RNE) {
-                    // the host sends only row lengths that are multiples of 16 here
-                    uint32_t pk[4];
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        float y[4] = {v[4 * q] * p.ep.alpha, v[4 * q + 1] * p.ep.alpha,
-                                      v[4 * q + 2] * p.ep.alpha, v[4 * q + 3] * p.ep.alpha};
-                        pk[q] = e5m2_pack4<false>(y, 0u, 0u, false);
-                    }
-                    if (p.ep.mask && conv_padding_row(p.ep, r)) pk[0] = pk[1] = pk[2] = pk[3] = 0;
-                    u32x4 o = {pk[0], pk[1], pk[2], pk[3]};
-                    *reinterpret_cast<u32x4 *>(p.ep.out8 + r * p.cols + c) = o;
-                } else {
-                    finish16(p.ep, r, c, v, st);
-                }
+                emit16<EPI>(p, split, r, c, v, st, fast_cols);
             }
         }
         MP8_STAMP_PHASE(6);
@@ -703,6 +719,152 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
         if (p.ep.stats != nullptr) st.flush(p.ep.stats);
     }
     MP8_STAMP_PHASE(4);
+}
+
+// Short contraction (one or two 128-byte stages, both operands row-major).  Such a GEMM is all
+// start-up and epilogue: every output byte costs only 128-256 bytes of MFMA input, so what
+// bounds it is how many output lines are in flight.  This kernel is cut for that:
+//   - one 128x128 tile per workgroup, all stages loaded at once (no ring, dynamic LDS of
+//     32 KB per stage, so four workgroups fit a CU);
+//   - wave w owns rows 32w .. 32w+31 and all 128 columns, so the wave writes whole 128-byte
+//     lines of the 8-bit output;
+//   - no LDS in the epilogue: the accumulator of a 32x32 tile has lane (row, h) hold columns
+//     8g + 4h + e (g, e = 0..3); one v_permlane32_swap per register pair (g, g+2) leaves
+//     lane (row, h) with the sixteen consecutive columns 16h .. 16h+15;
+//   - tiles are numbered row-major, so a CU's consecutive tiles write neighbouring lines.
+template <int EPI>
+__global__ __launch_bounds__(256, EPI == EPI_FULL ? 4 : 5) void gemm_shortk_kernel(const GemmArgs p) {
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds_dyn[];
+    constexpr int BM = 128, BN = 128, A_BYTES = BM * BK, STAGE = (BM + BN) * BK;
+    MP8_BLOCK_STAMP(0);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // consecutive workgroup ids sit on different XCDs: give each XCD a contiguous tile range
+    const uint32_t nb = gridDim.x, bid = blockIdx.x;
+    const uint32_t xcd = bid & 7, per = nb >> 3, rem = nb & 7;
+    const uint32_t pid = xcd * per + (xcd < rem ? xcd : rem) + (bid >> 3);
+    uint32_t tn_;
+    const int tm = __builtin_amdgcn_readfirstlane((int)fastdiv(pid, p.div_tn, tn_));
+    const int tn = __builtin_amdgcn_readfirstlane((int)tn_);
+    const int64_t row0 = (int64_t)tm * BM, col0 = (int64_t)tn * BN;
+    const int ksteps = p.ksteps;  // 1 or 2
+
+    // direct loads: same slab image as the main kernel (chunk c of row r in slot c ^ ((r>>1)&7))
+    const int lrow = lane >> 3, lchunk = (lane & 7) ^ ((4 * wave + (lane >> 4)) & 7);
+    const uint8_t *a_tile = uniform_ptr(p.a + row0 * p.lda);
+    const uint8_t *b_tile = uniform_ptr(p.b + col0 * p.ldb);
+    const uint32_t lds0 = lds_address(lds_dyn);
+    uint32_t oa[4], ob[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        int64_t r = 8 * (wave + 4 * q) + lrow, c = r;
+        r = row0 + r < p.rows ? r : p.rows - 1 - row0;  // clamped rows are never stored
+        c = col0 + c < p.cols ? c : p.cols - 1 - col0;
+        oa[q] = (uint32_t)(r * p.lda) + lchunk * 16;
+        ob[q] = (uint32_t)(c * p.ldb) + lchunk * 16;
+    }
+#pragma unroll
+    for (int st = 0; st < 2; ++st) {
+        if (st < ksteps) {
+            const uint32_t sa = lds0 + st * STAGE + wave * 1024;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) dma16(a_tile + st * BK, oa[q], sa + q * 4096);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) dma16(b_tile + st * BK, ob[q], sa + A_BYTES + q * 4096);
+        }
+    }
+
+    f32x16 acc[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[j][e] = 0.0f;
+    const int frow = lane & 31, fkb = lane >> 5;
+    const int fsw = (frow >> 1) & 7;
+#pragma unroll
+    for (int st = 0; st < 2; ++st) {
+        if (st < ksteps) {
+            if (st + 1 < ksteps) wait_vm_lds<8>();  // the eight loads of the next stage may fly
+            else wait_vm_lds<0>();
+            __syncthreads();
+            if (st == 0) MP8_BLOCK_STAMP(1);
+            const uint8_t *s = lds_dyn + st * STAGE;
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub) {
+                const int c0 = ((4 * sub + 2 * fkb) ^ fsw) * 16, c1 = ((4 * sub + 2 * fkb + 1) ^ fsw) * 16;
+                const uint8_t *ar = s + (32 * wave + frow) * BK;
+                const i32x4 a0 = *reinterpret_cast<const i32x4 *>(ar + c0);
+                const i32x4 a1 = *reinterpret_cast<const i32x4 *>(ar + c1);
+                const i32x8 av = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint8_t *br = s + A_BYTES + (32 * j + frow) * BK;
+                    const i32x4 b0 = *reinterpret_cast<const i32x4 *>(br + c0);
+                    const i32x4 b1 = *reinterpret_cast<const i32x4 *>(br + c1);
+                    const i32x8 bv = __builtin_shufflevector(b0, b1, 0, 1, 2, 3, 4, 5, 6, 7);
+                    // bf8 x bf8, unscaled; b as the "row" matrix: a lane gets output columns
+                    acc[j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(bv, av, acc[j], 1, 1, 0, 0, 0, 0);
+                }
+            }
+        }
+    }
+
+    const int64_t r = row0 + 32 * wave + frow;
+    MP8_BLOCK_STAMP(2);
+    if constexpr (EPI == EPI_RNE) {
+        // Codes first, then the exchange: four codes are one register, so a 32x32 tile needs two
+        // swaps.  After swap(pk[g], pk[g+2]) the lower half holds its own columns 8g .. 8g+3
+        // and the upper half's 8g+4 .. 8g+7; the upper half holds the lower half's
+        // 16+8g .. 16+8g+3 and its own 16+8g+4 .. 16+8g+7.
+        auto tiles = [&](auto unit_alpha) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                uint32_t pk[4];
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    float y[4] = {acc[j][4 * g], acc[j][4 * g + 1], acc[j][4 * g + 2], acc[j][4 * g + 3]};
+                    if constexpr (!decltype(unit_alpha)::value) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) y[e] *= p.ep.alpha;
+                    }
+                    pk[g] = e5m2_pack4<false>(y, 0u, 0u, false);
+                }
+                const auto s0 = __builtin_amdgcn_permlane32_swap(pk[0], pk[2], false, false);
+                const auto s1 = __builtin_amdgcn_permlane32_swap(pk[1], pk[3], false, false);
+                const int64_t c = col0 + 32 * j + 16 * fkb;
+                if (r < p.rows && c < p.cols) {
+                    u32x4 o = {s0[0], s0[1], s1[0], s1[1]};
+                    *reinterpret_cast<u32x4 *>(p.ep.out8 + r * p.cols + c) = o;
+                }
+            }
+        };
+        if (p.ep.alpha == 1.0f) tiles(std::true_type{});
+        else tiles(std::false_type{});
+        MP8_BLOCK_STAMP(3);
+        return;
+    }
+    StatsAcc stt;
+    const bool fast_cols = (p.cols & 15) == 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float v[16];
+#pragma unroll
+        for (int g = 0; g < 2; ++g)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                // lower half keeps its own columns 8g+e and receives the upper half's 8g+4+e;
+                // the upper half receives the lower half's 8(g+2)+e and keeps its 8(g+2)+4+e
+                const auto sw = __builtin_amdgcn_permlane32_swap(f2u(acc[j][4 * g + e]),
+                                                                 f2u(acc[j][4 * (g + 2) + e]), false, false);
+                v[8 * g + e] = u2f(sw[0]);
+                v[8 * g + 4 + e] = u2f(sw[1]);
+            }
+        const int64_t c = col0 + 32 * j + 16 * fkb;
+        if (r < p.rows && c < p.cols) emit16<EPI>(p, 0, r, c, v, stt, fast_cols);
+    }
+    if constexpr (EPI == EPI_FULL) {
+        if (p.ep.stats != nullptr) stt.flush(p.ep.stats);
+    }
 }
 
 // Finish four consecutive columns c .. c+3 (c % 4 == 0, row length a multiple of 4).
@@ -818,6 +980,8 @@ struct TileConfig {
     void (*kernel_tn[3])(const GemmArgs);  // both operands contraction-major; null if not built
     void (*kernel_bt[3])(const GemmArgs);  // only b contraction-major; null if not built
     void (*kernel_conv[3][3])(const GemmArgs);  // [mp8_op][EPI_*] 3x3 convolution; null if not built
+    int max_ksteps;      // 0: any contraction length; else the most stages the kernel takes
+    int lds_per_stage;   // dynamic LDS bytes per stage (kernels that load all stages at once)
 };
 
 #define MP8_TILE(BM, BN, WGM, WGN, NS, MB)                                   \
@@ -826,7 +990,7 @@ struct TileConfig {
       gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_RNE>,                    \
       gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_FULL>},                  \
      {nullptr, nullptr, nullptr}, {nullptr, nullptr, nullptr},                \
-     {{nullptr, nullptr, nullptr}, {nullptr, nullptr, nullptr}, {nullptr, nullptr, nullptr}}}
+     {{nullptr, nullptr, nullptr}, {nullptr, nullptr, nullptr}, {nullptr, nullptr, nullptr}}, 0, 0}
 #define MP8_TILE_TN(BM, BN, WGM, WGN, NS, MB)                                \
     {BM, BN, #BM "x" #BN "x128s" #NS,                                         \
      {gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_PARTIAL>,                \
@@ -846,12 +1010,17 @@ struct TileConfig {
        gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_FULL, false, false, 2>},  \
       {gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_PARTIAL, true, true, 3>,  \
        gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_RNE, true, true, 3>,      \
-       gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_FULL, true, true, 3>}}}
+       gemm_mfma_kernel<BM, BN, WGM, WGN, NS, MB, EPI_FULL, true, true, 3>}}, 0, 0}
+#define MP8_TILE_SHORTK                                                      \
+    {128, 128, "128x128x128k",                                                \
+     {gemm_shortk_kernel<EPI_PARTIAL>, gemm_shortk_kernel<EPI_RNE>, gemm_shortk_kernel<EPI_FULL>}, \
+     {nullptr, nullptr, nullptr}, {nullptr, nullptr, nullptr},                \
+     {{nullptr, nullptr, nullptr}, {nullptr, nullptr, nullptr}, {nullptr, nullptr, nullptr}}, 2, 32768}
 static const TileConfig kTiles[] = {
     MP8_TILE_TN(256, 256, 2, 2, 2, 1), MP8_TILE(256, 128, 2, 2, 3, 1), MP8_TILE(128, 256, 2, 2, 3, 1),
     MP8_TILE_TN(128, 128, 2, 2, 2, 2), MP8_TILE_TN(128, 128, 2, 2, 4, 1), MP8_TILE(64, 128, 1, 4, 3, 2),
     MP8_TILE(128, 64, 4, 1, 3, 2),  MP8_TILE_TN(64, 64, 2, 2, 4, 2), MP8_TILE(64, 128, 1, 4, 2, 3),
-    MP8_TILE(128, 64, 4, 1, 2, 3),  MP8_TILE_TN(64, 64, 2, 2, 2, 4),
+    MP8_TILE(128, 64, 4, 1, 2, 3),  MP8_TILE_TN(64, 64, 2, 2, 2, 4),   MP8_TILE_SHORTK,
 };
 constexpr int kNumTiles = (int)(sizeof(kTiles) / sizeof(kTiles[0]));
 constexpr int kCUs = 256;
@@ -879,7 +1048,7 @@ static void op_dims(mp8_op op, int64_t M, int64_t N, int64_t K, int64_t &rows, i
 // resident blocks per CU when the contraction is short, a deeper ring when it is long); small
 // outputs take 64x64 tiles and, if even those are too few, a split contraction -- kept to a
 // minimum because the second pass costs several microseconds.
-enum { T256x256 = 0, T128x128s2 = 3, T128x128s4 = 4, T128x64s2 = 9, T64x64s2 = 10 };
+enum { T256x256 = 0, T128x128s2 = 3, T128x128s4 = 4, T128x64s2 = 9, T64x64s2 = 10, T128x128k = 11 };
 static Plan make_plan(int64_t rows, int64_t cols, int64_t kc, int tile_config, int split_k,
                       int layout = 0) {  // bit 0: a contraction-major, bit 1: b
     Plan pl{};
@@ -891,6 +1060,9 @@ static Plan make_plan(int64_t rows, int64_t cols, int64_t kc, int tile_config, i
         (layout == 3 ? kTiles[tile_config - 1].kernel_tn[0] : kTiles[tile_config - 1].kernel_bt[0]) == nullptr)
         pl.mfma = false;
     const bool tn = layout != 0;
+    if (tile_config > 0 && kTiles[tile_config - 1].max_ksteps > 0 &&
+        (tn || kc / BK > kTiles[tile_config - 1].max_ksteps))
+        pl.mfma = false;
     if (!pl.mfma) {
         pl.splits = 1;
         return pl;
@@ -908,7 +1080,7 @@ static Plan make_plan(int64_t rows, int64_t cols, int64_t kc, int tile_config, i
         if (n256 >= 208 && fill256 >= 0.8 && ksteps >= 8) t = T256x256;
         else if (tn && (n128 < 16 || (n128 < 192 && ksteps <= 64))) t = T64x64s2;
         else if (tn) t = ksteps >= 64 ? T128x128s4 : T128x128s2;
-        else if (n128 >= 192 && ksteps <= 2) t = T128x64s2;  // all prologue and epilogue
+        else if (n128 >= 192 && ksteps <= 2) t = T128x128k;  // all prologue and epilogue
         else if (n128 >= 192) t = (ksteps >= 64 && n128 <= 2 * kCUs) ? T128x128s4 : T128x128s2;
         else t = T64x64s2;
     }
@@ -917,7 +1089,9 @@ static Plan make_plan(int64_t rows, int64_t cols, int64_t kc, int tile_config, i
     pl.tiles_n = (int)((cols + kTiles[t].bn - 1) / kTiles[t].bn);
     const int64_t nt = (int64_t)pl.tiles_m * pl.tiles_n;
     int s = 1;
-    if (split_k > 0) {
+    if (kTiles[t].max_ksteps > 0) {
+        s = 1;  // these kernels take the whole contraction at once
+    } else if (split_k > 0) {
         s = split_k;
     } else if (nt < kCUs / 2) {
         // about one and a half blocks per CU; two for the smallest tiles; fewer for the 128-row
@@ -1025,6 +1199,7 @@ static mp8_status launch_mfma(GemmArgs ga, const Epilogue &ep, const Plan &pl, i
     ga.div_tiles = make_fastdiv((uint32_t)(pl.tiles_m * pl.tiles_n));
     ga.div_band = make_fastdiv((uint32_t)(8 * pl.tiles_n));
     ga.div_tail = make_fastdiv((uint32_t)((pl.tiles_m & 7) ? (pl.tiles_m & 7) : 8));
+    ga.div_tn = make_fastdiv((uint32_t)pl.tiles_n);
     ga.ks_per = ga.ksteps / pl.splits;
     ga.ks_extra = ga.ksteps % pl.splits;
     ga.partial = partial;
@@ -1032,7 +1207,8 @@ static mp8_status launch_mfma(GemmArgs ga, const Epilogue &ep, const Plan &pl, i
     const int epi = two_pass ? EPI_PARTIAL
                              : (ep.sr || ep.sat || ep.stats != nullptr || out8 == nullptr) ? EPI_FULL
                                                                                             : EPI_RNE;
-    hipLaunchKernelGGL(pick[epi], dim3((unsigned)nblocks), dim3(256), 0, s, ga);
+    const size_t dyn_lds = (size_t)kTiles[pl.tile].lds_per_stage * (size_t)ga.ksteps;
+    hipLaunchKernelGGL(pick[epi], dim3((unsigned)nblocks), dim3(256), dyn_lds, s, ga);
     if (hipGetLastError() != hipSuccess) return MP8_ERR_HIP;
     if (two_pass) {
         const bool only_acc = fin.acc_mode == 0 && fin.out8 == nullptr && fin.out8_t == nullptr &&
@@ -1234,5 +1410,8 @@ extern "C" mp8_status mp8_conv3x3_fp8(mp8_op op, int64_t B, int64_t H, int64_t W
 #ifdef MP8_TRACE
 extern "C" int mp8_debug_read_trace(unsigned long long *host, size_t bytes) {
     return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(mp8::mp8_trace_buf), bytes);
+}
+extern "C" int mp8_debug_read_block_times(unsigned long long *host, size_t bytes) {
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(mp8::mp8_block_times), bytes);
 }
 #endif

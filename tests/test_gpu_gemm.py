@@ -97,11 +97,63 @@ def test_exact_sums_every_tile_config_and_split(mp8):
     want8 = oracle.round_ref_e5m2(ref)
     ntiles = len(mp8.gemm_tile_configs())
     for tile in range(0, ntiles + 1):
+        if tile > 0 and mp8.gemm_fp8_plan(mp8.FWD, rows, cols, kc, 0, tile)[0] is None:
+            with pytest.raises(mp8.Mp8Error):       # a kernel for short contractions only
+                run_gemm(mp8, a8, b8, tile_config=tile)
+            continue
         for split in (0, 1, 2, 3, 8):
             acc, out8, out8_t, _ = run_gemm(mp8, a8, b8, want_t=True, tile_config=tile, split_k=split)
             assert np.array_equal(acc.astype(np.float64), ref), (tile, split)
             assert np.array_equal(out8, want8), (tile, split)
             assert np.array_equal(out8_t, want8.T), (tile, split)
+
+
+@pytest.mark.parametrize("kc", [128, 256])
+def test_short_contraction_every_tile_config(mp8, kc):
+    """Contractions of one or two 128-byte stages, where a dedicated kernel exists: every tile
+    configuration gives the exact sums, on row and column counts ragged against every tile, with
+    the fused and the two-pass epilogue, RNE and SR, statistics and saturation."""
+    rng = np.random.default_rng(kc)
+    names = mp8.gemm_tile_configs()
+    for rows, cols in ((320, 288), (130, 200), (1, 16)):
+        a8, b8 = exact_sum_codes(rng, (rows, kc)), exact_sum_codes(rng, (cols, kc))
+        ref, _ = oracle.gemm_ref(a8, b8, want_abs=False)
+        want8 = oracle.round_ref_e5m2(ref)
+        used = set()
+        for tile in range(0, len(names) + 1):
+            used.add(mp8.gemm_fp8_plan(mp8.FWD, rows, cols, kc, 0, tile)[0])
+            acc, out8, out8_t, _ = run_gemm(mp8, a8, b8, want_t=True, tile_config=tile)
+            assert np.array_equal(acc.astype(np.float64), ref), (tile, rows, cols)
+            assert np.array_equal(out8, want8), (tile, rows, cols)
+            assert np.array_equal(out8_t, want8.T), (tile, rows, cols)
+        assert used >= set(names)               # every kernel, the short-contraction one included
+    # the dedicated kernel with everything its epilogue carries (large alpha: overflows)
+    short = 1 + [n.endswith("k") for n in names].index(True)
+    a8 = workloads.random_e5m2_codes(kc, (300, kc))
+    b8 = workloads.random_e5m2_codes(kc + 1, (272, kc))
+    a8, b8 = (a8 & 0x83) | 0x3C, (b8 & 0x83) | 0x3C
+    ref, absref = oracle.gemm_ref(a8, b8)
+    for mode, flags, alpha in ((oracle.RNE, 0, 1.0), (oracle.SR, 0, 0.37), (oracle.SR, oracle.FLAG_SATURATE, 3000.0),
+                               (oracle.RNE, 0, 3000.0)):
+        acc, out8, _, st = run_gemm(mp8, a8, b8, tile_config=short, round=mode, flags=flags, alpha=alpha,
+                                    seed=11, offset=5)
+        check_outputs(acc, out8, ref, absref, kc, mode=mode, seed=11, offset=5, alpha=alpha, flags=flags)
+        ost = oracle.Stats()
+        oracle.quantize_e5m2(acc, scale=alpha, mode=mode, seed=11, offset=5, flags=flags, stats=ost)
+        assert st == ost.as_tuple(), (mode, flags, alpha)
+
+
+def test_short_contraction_automatic_choice_full_size(mp8):
+    """A backward-data GEMM of the shape the planner gives to the short-contraction kernel
+    (2048 x 1536 outputs, contraction 128), checked element by element."""
+    rows, cols, kc = 2048, 1536, 128
+    assert mp8.gemm_fp8_plan(mp8.BWD_DATA, rows, kc, cols)[0].endswith("k")
+    a8 = workloads.random_e5m2_codes(31, (rows, kc))
+    b8 = workloads.random_e5m2_codes(32, (cols, kc))
+    a8, b8 = (a8 & 0x83) | 0x38, (b8 & 0x83) | 0x38
+    acc, out8, _, _ = run_gemm(mp8, a8, b8, op=mp8.BWD_DATA, dims=(rows, kc, cols))
+    ref, absref = oracle.gemm_ref(a8, b8)
+    check_outputs(acc, out8, ref, absref, kc)
 
 
 @pytest.mark.parametrize("shape", [(1, 1, 1), (3, 5, 7), (17, 33, 100), (64, 64, 128), (100, 36, 256),
