@@ -142,6 +142,11 @@ mp8_status mp8_gemm_fp8_plan(mp8_op op, int64_t M, int64_t N, int64_t K, int fla
 int mp8_gemm_num_tile_configs(void);
 /* Writes "BMxBNxBK" style description of tile_config (1-based) into buf. */
 int mp8_gemm_tile_config_name(int tile_config, char *buf, size_t buflen);
+/* Diagnostic (needs a device): bytes of statically allocated LDS of the row-major kernel of
+ * tile_config (1-based) with epilogue variant epi (0 FP32 tiles, 1 RNE only, 2 complete), as the
+ * runtime reports them; -1 on error.  The number of workgroups a CU holds hangs on it, so the
+ * tests pin it to what the tile shape implies. */
+int mp8_gemm_tile_config_lds_bytes(int tile_config, int epi);
 
 /*
  * The same primitive for a 3x3 convolution (stride 1, zero padding 1; Section 3 applies the

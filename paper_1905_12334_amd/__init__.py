@@ -27,7 +27,7 @@ EXPORTS = [
     "mp8_gemm_tile_config_name", "mp8_sgd_update_fp16_sr", "mp8_sr_bits", "mp8_philox4x32_10",
     "mp8_scaler_init", "mp8_scaler_update", "mp8_scaler_set_floor", "mp8_status_string",
     "mp8_conv3x3_fp8", "mp8_conv3x3_fp8_workspace_bytes", "mp8_sgd_momentum_fp16_sr",
-    "mp8_gemm_fp8_plan",
+    "mp8_gemm_fp8_plan", "mp8_gemm_tile_config_lds_bytes",
 ]
 
 
@@ -72,6 +72,8 @@ def lib() -> C.CDLL:
     L.mp8_gemm_num_tile_configs.argtypes = []
     L.mp8_gemm_tile_config_name.restype = ci
     L.mp8_gemm_tile_config_name.argtypes = [ci, C.c_char_p, C.c_size_t]
+    L.mp8_gemm_tile_config_lds_bytes.restype = ci
+    L.mp8_gemm_tile_config_lds_bytes.argtypes = [ci, ci]
     L.mp8_sgd_update_fp16_sr.restype = ci
     L.mp8_sgd_update_fp16_sr.argtypes = [vp, vp, i64, f32, f32, ci, u64, u64, vp, vp, vp, vp]
     L.mp8_sgd_momentum_fp16_sr.restype = ci
@@ -268,6 +270,11 @@ def gemm_tile_configs():
         lib().mp8_gemm_tile_config_name(i, buf, 64)
         names.append(buf.value.decode())
     return names
+
+
+def gemm_tile_config_lds_bytes(tile_config, epi):
+    """Static LDS bytes of a tile configuration's row-major kernel, as the runtime reports them."""
+    return lib().mp8_gemm_tile_config_lds_bytes(tile_config, epi)
 
 
 def sgd_update_fp16_sr(w16, g8, lr, inv_loss_scale, round=SR, seed=0, offset=0,

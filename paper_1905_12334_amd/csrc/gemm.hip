@@ -258,13 +258,10 @@ __device__ __forceinline__ void emit16(const GemmArgs &p, int split, int64_t r, 
                 reinterpret_cast<f32x4 *>(dst)[q] = o;
             }
         } else {
-#pragma nounroll
-            for (int e = 0; e < 16; ++e) {
-                float x = v[0];
+            // constant indices only: a run-time index would move v out of the registers
 #pragma unroll
-                for (int k = 1; k < 16; ++k) x = (e == k) ? v[k] : x;
-                if (c + e < p.cols) dst[e] = x;
-            }
+            for (int e = 0; e < 16; ++e)
+                if (c + e < p.cols) dst[e] = v[e];
         }
     } else if constexpr (EPI == EPI_RNE) {
         // the host sends only row lengths that are multiples of 16 here
@@ -815,7 +812,12 @@ __global__ __launch_bounds__(256, EPI == EPI_FULL ? 4 : 5) void gemm_shortk_kern
         // Codes first, then the exchange: four codes are one register, so a 32x32 tile needs two
         // swaps.  After swap(pk[g], pk[g+2]) the lower half holds its own columns 8g .. 8g+3
         // and the upper half's 8g+4 .. 8g+7; the upper half holds the lower half's
-        // 16+8g .. 16+8g+3 and its own 16+8g+4 .. 16+8g+7.
+        // 16+8g .. 16+8g+3 and its own 16+8g+4 .. 16+8g+7: lane (row, h) has the 16-byte piece
+        // 2j + h of its row.  The pieces then pass through the 4 KB of LDS that held this
+        // wave's own rows of a (nobody else reads or writes them any more), so that eight
+        // consecutive lanes store one whole 128-byte line: piece q of row rr sits in slot
+        // q ^ ((rr >> 1) & 7), which keeps both the writes and the reads free of bank conflicts.
+        uint8_t *mine = lds_dyn + 32 * wave * BK;
         auto tiles = [&](auto unit_alpha) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -831,15 +833,24 @@ __global__ __launch_bounds__(256, EPI == EPI_FULL ? 4 : 5) void gemm_shortk_kern
                 }
                 const auto s0 = __builtin_amdgcn_permlane32_swap(pk[0], pk[2], false, false);
                 const auto s1 = __builtin_amdgcn_permlane32_swap(pk[1], pk[3], false, false);
-                const int64_t c = col0 + 32 * j + 16 * fkb;
-                if (r < p.rows && c < p.cols) {
-                    u32x4 o = {s0[0], s0[1], s1[0], s1[1]};
-                    *reinterpret_cast<u32x4 *>(p.ep.out8 + r * p.cols + c) = o;
-                }
+                u32x4 o = {s0[0], s0[1], s1[0], s1[1]};
+                *reinterpret_cast<u32x4 *>(mine + frow * BK + (((2 * j + fkb) ^ fsw) << 4)) = o;
             }
         };
         if (p.ep.alpha == 1.0f) tiles(std::true_type{});
         else tiles(std::false_type{});
+        // the region is private to this wave: order its LDS writes before its reads
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const int64_t c = col0 + 16 * (lane & 7);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int rr = 8 * k + (lane >> 3);
+            const u32x4 o = *reinterpret_cast<const u32x4 *>(mine + rr * BK + (((lane & 7) ^ ((rr >> 1) & 7)) << 4));
+            const int64_t ro = row0 + 32 * wave + rr;
+            if (ro < p.rows && c < p.cols) *reinterpret_cast<u32x4 *>(p.ep.out8 + ro * p.cols + c) = o;
+        }
         MP8_BLOCK_STAMP(3);
         return;
     }
@@ -1124,6 +1135,14 @@ extern "C" int mp8_gemm_tile_config_name(int tile_config, char *buf, size_t bufl
     if (tile_config < 1 || tile_config > mp8::kNumTiles || !buf || buflen == 0) return -1;
     snprintf(buf, buflen, "%s", mp8::kTiles[tile_config - 1].name);
     return 0;
+}
+
+extern "C" int mp8_gemm_tile_config_lds_bytes(int tile_config, int epi) {
+    if (tile_config < 1 || tile_config > mp8::kNumTiles || epi < 0 || epi > 2) return -1;
+    hipFuncAttributes at;
+    if (hipFuncGetAttributes(&at, (const void *)mp8::kTiles[tile_config - 1].kernel[epi]) != hipSuccess)
+        return -1;
+    return (int)at.sharedSizeBytes;
 }
 
 extern "C" size_t mp8_gemm_fp8_workspace_bytes_tuned(mp8_op op, int64_t M, int64_t N, int64_t K,

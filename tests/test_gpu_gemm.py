@@ -108,6 +108,23 @@ def test_exact_sums_every_tile_config_and_split(mp8):
             assert np.array_equal(out8_t, want8.T), (tile, split)
 
 
+def test_static_lds_of_every_kernel_is_what_its_tile_implies(mp8):
+    """The number of workgroups a CU holds hangs on the LDS a kernel allocates: a ring of S
+    stages of (BM + BN) x 128 bytes and nothing else (a private array that the compiler moved
+    to LDS once cost a third of the speed of the split kernels without failing any test)."""
+    for i, name in enumerate(mp8.gemm_tile_configs(), start=1):
+        for epi in range(3):
+            got = mp8.gemm_tile_config_lds_bytes(i, epi)
+            if name.endswith("k"):          # all stages in dynamic LDS; statistics need 1 KB
+                assert 0 <= got <= 1024, (name, epi, got)
+            else:
+                bm, bn, rest = name.split("x")
+                stages = int(rest.split("s")[1])
+                ring = stages * (int(bm) + int(bn)) * 128
+                # (the FP32 row bands of the largest tile's epilogue need 4 KB more than its ring)
+                assert ring <= got <= ring + 4096 + 1024, (name, epi, got)   # + statistics
+
+
 @pytest.mark.parametrize("kc", [128, 256])
 def test_short_contraction_every_tile_config(mp8, kc):
     """Contractions of one or two 128-byte stages, where a dedicated kernel exists: every tile
