@@ -88,6 +88,10 @@ def lib():
         L.orc_sgd_momentum_fp16.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_float,
                                             C.c_float, C.c_float, C.c_float, C.c_int, C.c_uint64,
                                             C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.orc_adam_fp16.restype = None
+        L.orc_adam_fp16.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_float,
+                                    C.c_float, C.c_float, C.c_float, C.c_float, C.c_float, C.c_int64,
+                                    C.c_int, C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]
         L.orc_scaler_update.restype = C.c_int
         L.orc_scaler_update.argtypes = [C.POINTER(Scaler), C.c_uint32]
         L.orc_scaler_set_floor.restype = None
@@ -263,6 +267,24 @@ def sgd_momentum_fp16(w16, vel, g8, lr, inv_loss_scale, momentum, weight_decay=0
                                 float(momentum), float(weight_decay), mode, seed, offset, _p(sk),
                                 _p(w8), C.byref(stats) if stats is not None else None)
     return w, v, w8
+
+
+def adam_fp16(w16, m, v, g8, lr, inv_loss_scale, step, beta1=0.9, beta2=0.999, eps=1e-8,
+              weight_decay=0.0, mode=SR, seed=0, offset=0, skip=None, want_w8=False,
+              stats: Stats | None = None):
+    """ADAM with L2 regularisation on half master weights and FP32 moments (step counts from 1).
+    Returns (new_w16, new_m, new_v, w8 or None); inputs are not modified."""
+    w = np.array(w16, dtype=np.uint16, copy=True).reshape(-1)
+    m_ = np.array(m, dtype=np.float32, copy=True).reshape(-1)
+    v_ = np.array(v, dtype=np.float32, copy=True).reshape(-1)
+    g = _carr(g8, np.uint8).reshape(-1)
+    assert w.size == g.size == m_.size == v_.size and step >= 1
+    w8 = np.zeros(w.size, dtype=np.uint8) if want_w8 else None
+    sk = None if skip is None else np.array([skip], dtype=np.uint32)
+    lib().orc_adam_fp16(_p(w), _p(m_), _p(v_), _p(g), w.size, float(lr), float(inv_loss_scale),
+                        float(beta1), float(beta2), float(eps), float(weight_decay), int(step), mode,
+                        seed, offset, _p(sk), _p(w8), C.byref(stats) if stats is not None else None)
+    return w, m_, v_, w8
 
 
 def scaler_new(scale, floor, growth_interval) -> Scaler:

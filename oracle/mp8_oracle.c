@@ -570,6 +570,68 @@ void orc_sgd_momentum_fp16(uint16_t *w16, float *vel, const uint8_t *g8, int64_t
     }
 }
 
+/*
+ * The same path with the ADAM optimizer, which Section 4.2 names for the
+ * translation networks (GNMT, Transformer).  The paper gives no formula; this
+ * is the published algorithm (Kingma & Ba, Algorithm 1) with the L2
+ * regularisation gradient of Eq. 1 added to the un-scaled gradient as in
+ * orc_sgd_momentum_fp16.  Every operation is a separately rounded FP32
+ * operation ("the weight update operation is performed as a 32-bit
+ * operation", Section 3), the two moments are kept in FP32 (the paper is
+ * silent on the precision of optimizer state; same reading as the velocity):
+ *   g    = fl32(value(g8) * inv_loss_scale);  w = value(w16)
+ *   g    = fmaf(weight_decay, w, g)
+ *   m'   = fmaf(beta1, m, fl32((1 - beta1) * g))
+ *   v'   = fmaf(beta2, v, fl32((1 - beta2) * fl32(g * g)))
+ *   mhat = m' / c1,  vhat = v' / c2     c_i = fl32(1 - beta_i^step), step >= 1
+ *   w'   = fmaf(-lr, mhat / (sqrt(vhat) + eps), w)
+ *   w16  = half(w') rounded by `mode`
+ * (1 - beta_i) is the FP32 difference; beta_i^step is taken in double.
+ */
+void orc_adam_fp16(uint16_t *w16, float *m, float *v, const uint8_t *g8, int64_t n, float lr,
+                   float inv_loss_scale, float beta1, float beta2, float eps, float weight_decay,
+                   int64_t step, int mode, uint64_t seed, uint64_t offset, const uint32_t *skip,
+                   uint8_t *w8_out, orc_stats *stats)
+{
+    int64_t i;
+    uint32_t nonfinite = 0u;
+    const float omb1 = 1.0f - beta1, omb2 = 1.0f - beta2;
+    const float c1 = (float)(1.0 - pow((double)beta1, (double)step));
+    const float c2 = (float)(1.0 - pow((double)beta2, (double)step));
+#pragma omp parallel for reduction(+ : nonfinite)
+    for (i = 0; i < n; ++i)
+        if ((g8[i] & 0x7Cu) == 0x7Cu)
+            nonfinite++;
+    if (stats)
+        stats->nonfinite += nonfinite;
+    if (skip && *skip != 0u)
+        return;
+#pragma omp parallel for
+    for (i = 0; i < n; ++i) {
+        volatile float g0 = (float)orc_e5m2_decode(g8[i]) * inv_loss_scale;
+        float w = (float)orc_fp16_decode(w16[i]);
+        float g = fmaf(weight_decay, w, g0);
+        volatile float t1 = omb1 * g;
+        volatile float gg = g * g;
+        volatile float t2 = omb2 * gg;
+        float mn = fmaf(beta1, m[i], t1);
+        float vn = fmaf(beta2, v[i], t2);
+        volatile float mhat = mn / c1;
+        volatile float vhat = vn / c2;
+        volatile float root = sqrtf(vhat);
+        volatile float den = root + eps;
+        volatile float upd = mhat / den;
+        float wn = fmaf(-lr, upd, w);
+        uint32_t r16 = (mode == ORC_SR) ? orc_sr_bits(seed, offset, (uint64_t)i) : 0u;
+        uint16_t h = orc_fp16_encode((double)wn, mode, r16);
+        m[i] = mn;
+        v[i] = vn;
+        w16[i] = h;
+        if (w8_out)
+            w8_out[i] = orc_e5m2_encode(orc_fp16_decode(h), ORC_RNE, 0u, 0);
+    }
+}
+
 /* ------------------------------------------------------------------------- */
 /* Loss scaler (Section 3.1)                                                  */
 /* ------------------------------------------------------------------------- */

@@ -324,3 +324,108 @@ def test_momentum_update_against_float32_numpy():
     assert np.mean(got_v.view(np.uint32) != v.view(np.uint32)) < 1e-3
     same = got_v.view(np.uint32) == v.view(np.uint32)
     assert np.array_equal(got_w[same], wn.astype(np.float16).view(np.uint16)[same])
+
+
+# --- ADAM on the master weights (Section 4.2 names the optimizer; published algorithm) ----------
+
+def _half_grid_error(w16_codes, ref):
+    """|value(code) - ref| in units of the half-precision spacing at ref."""
+    got = np.asarray(w16_codes, np.uint16).view(np.float16).astype(np.float64)
+    spacing = np.maximum(np.spacing(np.abs(ref).astype(np.float16)).astype(np.float64), 2.0 ** -24)
+    return np.abs(got - ref) / spacing
+
+
+def test_adam_closed_forms_and_special_cases():
+    f16 = lambda x: np.array([x], np.float16).view(np.uint16)
+    z = np.zeros(1, np.float32)
+    one = np.array([0x3C], np.uint8)                                         # gradient 1.0
+    # first step from zero moments: mhat = g and vhat = g^2 whatever the betas, so the step is
+    # lr * g / (|g| + eps) -- the sign of the gradient times lr (the textbook property of ADAM)
+    for g8, sign in ((0x3C, 1.0), (0xBC, -1.0), (0x30, 1.0), (0xC4, -1.0), (0x54, 1.0)):
+        w, m, v, _ = oracle.adam_fp16(f16(1.0), z, z, np.array([g8], np.uint8), 2.0 ** -5, 1.0, 1,
+                                      beta1=0.5, beta2=0.75, eps=0.0, mode=oracle.RNE)
+        assert oracle.fp16_decode(int(w[0])) == 1.0 - sign * 2.0 ** -5
+        gval = oracle.e5m2_decode(g8)
+        assert m[0] == 0.5 * gval and v[0] == 0.25 * gval * gval            # (1-b1) g, (1-b2) g^2
+    # constant gradient: mhat = g and vhat = g^2 at EVERY step (the bias corrections undo the
+    # geometric sums exactly for these dyadic betas), so t steps move the weight by t * lr
+    w, m, v = f16(1.0), z, z
+    for t in range(1, 7):
+        w, m, v, _ = oracle.adam_fp16(w, m, v, one, 2.0 ** -6, 1.0, t, beta1=0.5, beta2=0.5, eps=0.0,
+                                      mode=oracle.RNE)
+        assert m[0] == 1.0 - 0.5 ** t and v[0] == 1.0 - 0.5 ** t
+        assert oracle.fp16_decode(int(w[0])) == 1.0 - t * 2.0 ** -6
+    # eps enters the denominator: g = 1, eps = 1 -> step lr / 2
+    w, _, _, _ = oracle.adam_fp16(f16(1.0), z, z, one, 2.0 ** -4, 1.0, 1, beta1=0.5, beta2=0.5, eps=1.0,
+                                  mode=oracle.RNE)
+    assert oracle.fp16_decode(int(w[0])) == 1.0 - 2.0 ** -5
+    # the loss scale is divided out before the moments: g8 = 4.0 with inv_loss_scale 1/4 is g = 1
+    w, m, _, _ = oracle.adam_fp16(f16(1.0), z, z, np.array([0x44], np.uint8), 2.0 ** -4, 0.25, 1, beta1=0.5,
+                                  beta2=0.5, eps=1.0, mode=oracle.RNE)
+    assert oracle.fp16_decode(int(w[0])) == 1.0 - 2.0 ** -5 and m[0] == 0.5
+    # zero gradient, zero moments, eps > 0: nothing moves (0 / (0 + eps) = 0)
+    w, m, v, _ = oracle.adam_fp16(f16(0.75), z, z, np.zeros(1, np.uint8), 0.1, 1.0, 3, eps=1e-8)
+    assert oracle.fp16_decode(int(w[0])) == 0.75 and m[0] == 0 and v[0] == 0
+    # regularisation alone (Eq. 1): the gradient is weight_decay * w; first step, eps = 0:
+    # w' = w - lr * sign(w)
+    w, m, _, _ = oracle.adam_fp16(f16(-2.0), z, z, np.zeros(1, np.uint8), 2.0 ** -3, 1.0, 1, beta1=0.5,
+                                  beta2=0.5, eps=0.0, weight_decay=0.5, mode=oracle.RNE)
+    assert oracle.fp16_decode(int(w[0])) == -2.0 + 2.0 ** -3 and m[0] == 0.5 * (0.5 * -2.0)
+    # skip flag: nothing changes, non-finite gradient codes are still counted
+    st = oracle.Stats()
+    w3 = np.array([0x3C00, 0x3C00, 0x3C00], np.uint16)
+    w4, m4, v4, _ = oracle.adam_fp16(w3, np.ones(3, np.float32), np.ones(3, np.float32),
+                                     np.array([0x7C, 0x3C, 0xFF], np.uint8), 0.1, 1.0, 2, skip=1, stats=st)
+    assert np.array_equal(w4, w3) and np.all(m4 == 1) and np.all(v4 == 1) and st.nonfinite == 2
+    # stochastic rounding of the new weight: r16 = 0 truncates toward zero (offset chosen freely:
+    # the expected value over many offsets is the FP32 result)
+    g = np.full(4096, 0x3C, np.uint8)
+    w0 = np.full(4096, 0x3C00, np.uint16)
+    zz = np.zeros(4096, np.float32)
+    ws, _, _, _ = oracle.adam_fp16(w0, zz, zz, g, 2.0 ** -13, 1.0, 1, beta1=0.5, beta2=0.5, eps=0.0,
+                                   mode=oracle.SR, seed=7, offset=9)
+    vals = ws.view(np.float16).astype(np.float64)                            # 1 - 2^-13: between 1-2^-11 and 1
+    assert set(np.unique(vals)) == {1.0 - 2.0 ** -11, 1.0}
+    assert abs(vals.mean() - (1.0 - 2.0 ** -13)) < 3 * 2.0 ** -11 * 0.5 / np.sqrt(4096) * 2
+
+
+def test_adam_against_float64_numpy_and_torch():
+    rng = np.random.default_rng(12)
+    n = 20000
+    w16 = (rng.standard_normal(n) * 0.1).astype(np.float16).view(np.uint16)
+    g8 = workloads.random_e5m2_codes(13, (n,))
+    g8 = (g8 & 0x83) | 0x48                               # |g8| in [32, 56]: un-scaled gradients ~ 0.04
+    m0 = (rng.standard_normal(n) * 0.01).astype(np.float32)
+    v0 = (rng.random(n) * 1e-3).astype(np.float32)
+    lr, inv, b1, b2, eps, wd, step = 1e-3, 1 / 1024.0, 0.9, 0.999, 1e-8, 1e-4, 5
+    got_w, got_m, got_v, got8 = oracle.adam_fp16(w16, m0, v0, g8, lr, inv, step, beta1=b1, beta2=b2, eps=eps,
+                                                 weight_decay=wd, mode=oracle.RNE, want_w8=True)
+    # the textbook formulas in float64
+    w = w16.view(np.float16).astype(np.float64)
+    g = (g8.astype(np.uint16) << 8).view(np.float16).astype(np.float64) * inv + wd * w
+    f = lambda x: float(np.float32(x))                    # the parameters are FP32 numbers
+    g = (g8.astype(np.uint16) << 8).view(np.float16).astype(np.float64) * f(inv) + f(wd) * w
+    omb1, omb2 = float(np.float32(1) - np.float32(b1)), float(np.float32(1) - np.float32(b2))
+    m = f(b1) * m0 + omb1 * g
+    v = f(b2) * v0 + omb2 * g * g
+    ref = w - f(lr) * (m / (1 - f(b1) ** step)) / (np.sqrt(v / (1 - f(b2) ** step)) + f(eps))
+    # a few FP32 roundings on terms of the size of the operands (the two terms of m may cancel)
+    assert np.all(np.abs(got_m - m) <= 3e-7 * (np.abs(f(b1) * m0) + np.abs(omb1 * g)))
+    assert np.all(np.abs(got_v - v) <= 3e-7 * v)
+    assert _half_grid_error(got_w, ref).max() <= 0.5 + 1e-3           # the nearest half, FP32 noise aside
+    assert np.array_equal(got8, oracle.quantize_e5m2(got_w.view(np.float16).reshape(1, -1))[0].reshape(-1))
+    # the library routine: torch's CPU ADAM in float32 on the same numbers (different operation
+    # order, so equal only to FP32 accuracy; its weights are compared on the half grid)
+    import torch
+    p = torch.nn.Parameter(torch.from_numpy(w16.view(np.float16).astype(np.float32)))
+    opt = torch.optim.Adam([p], lr=lr, betas=(b1, b2), eps=eps, weight_decay=wd)
+    opt.zero_grad()
+    p.grad = torch.from_numpy(((g8.astype(np.uint16) << 8).view(np.float16).astype(np.float32) * np.float32(inv)))
+    opt.state[p]["step"] = torch.tensor(float(step - 1))
+    opt.state[p]["exp_avg"] = torch.from_numpy(m0.copy())
+    opt.state[p]["exp_avg_sq"] = torch.from_numpy(v0.copy())
+    opt.step()
+    assert np.all(np.abs(got_m - opt.state[p]["exp_avg"].numpy()) <= 1e-6 * (np.abs(f(b1) * m0) + np.abs(omb1 * g)))
+    # torch forms 1 - beta2 in double (0.001); the FP32 difference 1 - fl32(0.999) is 4.7e-5 larger
+    assert np.all(np.abs(got_v - opt.state[p]["exp_avg_sq"].numpy()) <= 1e-6 * v + 6e-5 * omb2 * g * g)
+    assert _half_grid_error(got_w, p.detach().numpy().astype(np.float64)).max() <= 0.5 + 1e-2
