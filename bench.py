@@ -342,7 +342,19 @@ def all_configs_report(mp8, torch):
                                                                  seed=1, offset=3), 5)
         rows.append({"kernel": "sgd_update_fp16_sr", "case": f"2^28 elements, {rn}", "us": us,
                      "alg_gbs": 5.0 * n / us / 1e3, "frac_hbm_peak": 5.0 * n / us / 1e3 / HBM_PEAK_GBS})
-    del src, d8, w16
+    # optimizers with FP32 state: 13 (momentum) and 21 (ADAM) bytes per element
+    nm = 1 << 27
+    st0 = torch.zeros(nm, dtype=torch.float32, device=dev)
+    st1 = torch.zeros(nm, dtype=torch.float32, device=dev)
+    us = graph_time_us(torch, lambda: mp8.sgd_momentum_fp16_sr(w16[:nm], st0, g8[:nm], LR, 1.0 / LOSS_SCALE,
+                                                               0.9, 1e-4, round=mp8.SR, seed=1, offset=4), 5)
+    rows.append({"kernel": "sgd_momentum_fp16_sr", "case": "2^27 elements, SR", "us": us,
+                 "alg_gbs": 13.0 * nm / us / 1e3, "frac_hbm_peak": 13.0 * nm / us / 1e3 / HBM_PEAK_GBS})
+    us = graph_time_us(torch, lambda: mp8.adam_fp16_sr(w16[:nm], st0, st1, g8[:nm], LR, 1.0 / LOSS_SCALE, 10,
+                                                       weight_decay=1e-4, round=mp8.SR, seed=1, offset=5), 5)
+    rows.append({"kernel": "adam_fp16_sr", "case": "2^27 elements, SR", "us": us,
+                 "alg_gbs": 21.0 * nm / us / 1e3, "frac_hbm_peak": 21.0 * nm / us / 1e3 / HBM_PEAK_GBS})
+    del src, d8, w16, st0, st1
     x = torch.empty((100352, 1152), dtype=torch.float32, device=dev).normal_()
     q, qt = torch.empty((100352, 1152), dtype=torch.uint8, device=dev), torch.empty((1152, 100352), dtype=torch.uint8, device=dev)
     us = graph_time_us(torch, lambda: mp8.quantize_e5m2(x, q, qt), 5)

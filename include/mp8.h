@@ -211,6 +211,24 @@ mp8_status mp8_sgd_momentum_fp16_sr(uint16_t *w16, float *velocity, const uint8_
                                     uint64_t offset, const uint32_t *skip_if_nonzero,
                                     uint8_t *w8_out, mp8_stats *stats, void *stream);
 
+/*
+ * The same path with the ADAM optimizer, which Section 4.2 names for the translation networks
+ * (the paper gives no formula: Kingma & Ba, Algorithm 1), with the regularisation gradient of
+ * Eq. 1 as above.  Per element, every operation a separately rounded FP32 operation:
+ *     g  = fmaf(weight_decay, w, fl32(value(g8[i]) * inv_loss_scale))
+ *     m' = fmaf(beta1, m[i], (1 - beta1) * g);   v' = fmaf(beta2, v[i], (1 - beta2) * (g * g))
+ *     w' = fmaf(-lr, (m' / c1) / (sqrt(v' / c2) + eps), w),   c_i = fl32(1 - beta_i^step)
+ *     w16[i] = half(w') rounded by `round`
+ *   m, v    FP32 moments, in/out, 16-byte aligned (a skipped step leaves them untouched)
+ *   step    number of this update, counted from 1 (beta_i^step is formed in double on the host)
+ * Other arguments as for mp8_sgd_update_fp16_sr.  21 bytes of traffic per element.
+ */
+mp8_status mp8_adam_fp16_sr(uint16_t *w16, float *m, float *v, const uint8_t *g8, int64_t n, float lr,
+                            float inv_loss_scale, float beta1, float beta2, float eps,
+                            float weight_decay, int64_t step, mp8_round round, uint64_t seed,
+                            uint64_t offset, const uint32_t *skip_if_nonzero, uint8_t *w8_out,
+                            mp8_stats *stats, void *stream);
+
 /* out[i] = the 16 random bits element i would use (device array of n uint16), for tests. */
 mp8_status mp8_sr_bits(uint16_t *out, int64_t n, uint64_t seed, uint64_t offset, void *stream);
 

@@ -27,7 +27,7 @@ EXPORTS = [
     "mp8_gemm_tile_config_name", "mp8_sgd_update_fp16_sr", "mp8_sr_bits", "mp8_philox4x32_10",
     "mp8_scaler_init", "mp8_scaler_update", "mp8_scaler_set_floor", "mp8_status_string",
     "mp8_conv3x3_fp8", "mp8_conv3x3_fp8_workspace_bytes", "mp8_sgd_momentum_fp16_sr",
-    "mp8_gemm_fp8_plan", "mp8_gemm_tile_config_lds_bytes",
+    "mp8_gemm_fp8_plan", "mp8_gemm_tile_config_lds_bytes", "mp8_adam_fp16_sr",
 ]
 
 
@@ -78,6 +78,9 @@ def lib() -> C.CDLL:
     L.mp8_sgd_update_fp16_sr.argtypes = [vp, vp, i64, f32, f32, ci, u64, u64, vp, vp, vp, vp]
     L.mp8_sgd_momentum_fp16_sr.restype = ci
     L.mp8_sgd_momentum_fp16_sr.argtypes = [vp, vp, vp, i64, f32, f32, f32, f32, ci, u64, u64, vp, vp, vp, vp]
+    L.mp8_adam_fp16_sr.restype = ci
+    L.mp8_adam_fp16_sr.argtypes = [vp, vp, vp, vp, i64, f32, f32, f32, f32, f32, f32, i64, ci, u64, u64,
+                                   vp, vp, vp, vp]
     L.mp8_sr_bits.restype = ci
     L.mp8_sr_bits.argtypes = [vp, i64, u64, u64, vp]
     L.mp8_philox4x32_10.restype = None
@@ -310,6 +313,27 @@ def sgd_momentum_fp16_sr(w16, velocity, g8, lr, inv_loss_scale, momentum, weight
                                         round, seed, offset, _ptr(skip_if_nonzero), _ptr(w8_out),
                                         _ptr(stats), _stream())
     _check(st, "mp8_sgd_momentum_fp16_sr")
+    return w16
+
+
+def adam_fp16_sr(w16, m, v, g8, lr, inv_loss_scale, step, beta1=0.9, beta2=0.999, eps=1e-8,
+                 weight_decay=0.0, round=SR, seed=0, offset=0, skip_if_nonzero=None, w8_out=None,
+                 stats=None):
+    """mp8_adam_fp16_sr: ADAM with L2 regularisation, FP32 moments in place (step counts from 1)."""
+    import torch
+    _dev(w16, "w16", (torch.float16, torch.int16, torch.uint16))
+    _dev(m, "m", torch.float32)
+    _dev(v, "v", torch.float32)
+    _dev(g8, "g8", torch.uint8)
+    _dev(w8_out, "w8_out", torch.uint8)
+    n = w16.numel()
+    if g8.numel() != n or m.numel() != n or v.numel() != n or (w8_out is not None and w8_out.numel() != n):
+        raise Mp8Error("m / v / g8 / w8_out size does not match w16")
+    st = lib().mp8_adam_fp16_sr(_ptr(w16), _ptr(m), _ptr(v), _ptr(g8), n, float(lr), float(inv_loss_scale),
+                                float(beta1), float(beta2), float(eps), float(weight_decay), int(step),
+                                round, seed, offset, _ptr(skip_if_nonzero), _ptr(w8_out), _ptr(stats),
+                                _stream())
+    _check(st, "mp8_adam_fp16_sr")
     return w16
 
 

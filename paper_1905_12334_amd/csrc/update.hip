@@ -6,6 +6,8 @@
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
+#include <cmath>
+
 #include "mp8_device.hpp"
 
 namespace mp8 {
@@ -30,18 +32,49 @@ __device__ __forceinline__ uint32_t update_one(uint32_t w16, uint32_t g8, float 
     }
 }
 
-// The same with the momentum optimizer and the L2 regularisation gradient in front of the
-// weight step; the velocity stays in FP32.  Every operation is rounded on its own (FP32).
-template <bool kSR>
-__device__ __forceinline__ uint32_t momentum_one(uint32_t w16, uint32_t g8, float &vel, float neg_lr,
-                                                 float inv_scale, float mu, float wd, uint32_t r16) {
-    float g = e5m2_to_f32(g8) * inv_scale;
+// Optimizers with FP32 state in front of the same conversion.  A rule turns the un-scaled
+// gradient g, the weight w and its state words into the new FP32 weight; every operation is a
+// separately rounded FP32 operation in the order written (the build forbids contraction).
+//
+// Momentum with the L2 regularisation gradient:   g += wd * w;  v' = mu * v + g;  w' = w - lr * v'
+struct MomentumRule {
+    static constexpr int kStates = 1;
+    float neg_lr, mu, wd;
+    __device__ __forceinline__ float operator()(float w, float g, float *st) const {
+        g = __builtin_fmaf(wd, w, g);
+        const float v = __builtin_fmaf(mu, st[0], g);
+        st[0] = v;
+        return __builtin_fmaf(neg_lr, v, w);
+    }
+};
+
+// ADAM (Kingma & Ba, Algorithm 1) with the same regularisation gradient:
+//   m' = b1 * m + (1 - b1) * g;  v' = b2 * v + (1 - b2) * g^2
+//   w' = w - lr * (m' / c1) / (sqrt(v' / c2) + eps),   c_i = 1 - b_i^step (from the host)
+// Division and square root are the correctly rounded IEEE operations (the compiler's default
+// for FP32 `/` and sqrt in HIP code; the approximate intrinsics are not used).
+struct AdamRule {
+    static constexpr int kStates = 2;
+    float neg_lr, b1, b2, omb1, omb2, c1, c2, eps, wd;
+    __device__ __forceinline__ float operator()(float w, float g, float *st) const {
+        g = __builtin_fmaf(wd, w, g);
+        const float m = __builtin_fmaf(b1, st[0], omb1 * g);
+        const float v = __builtin_fmaf(b2, st[1], omb2 * (g * g));
+        st[0] = m;
+        st[1] = v;
+        const float mhat = m / c1, vhat = v / c2;
+        const float upd = mhat / (__builtin_sqrtf(vhat) + eps);
+        return __builtin_fmaf(neg_lr, upd, w);
+    }
+};
+
+template <bool kSR, class Rule>
+__device__ __forceinline__ uint32_t rule_one(const Rule &rule, uint32_t w16, uint32_t g8, float *st,
+                                             float inv_scale, uint32_t r16) {
+    const float g = e5m2_to_f32(g8) * inv_scale;
     const float w = __half2float(__ushort_as_half((unsigned short)w16));
-    g = __builtin_fmaf(wd, w, g);
-    const float v = __builtin_fmaf(mu, vel, g);
-    float wn = __builtin_fmaf(neg_lr, v, w);
+    float wn = rule(w, g, st);
     asm volatile("" : "+v"(wn));  // keep the conversion a separate, second rounding
-    vel = v;
     if constexpr (kSR) {
         return f16_from_f32_bits<true>(f2u(wn), r16);
     } else {
@@ -144,17 +177,21 @@ __global__ __launch_bounds__(256) void sgd_update_kernel(uint16_t *__restrict__ 
     }
 }
 
-// Momentum variant: the same item shape (eight elements) plus 32 bytes of velocity read and
-// written per item; 13 bytes of traffic per element (+1 with the 8-bit copy).
-template <bool kSR, bool kW8>
-__global__ __launch_bounds__(256) void sgd_momentum_kernel(uint16_t *__restrict__ w16,
-                                                           float *__restrict__ vel,
+// Optimizers with state: the same item shape (eight elements) plus 32 bytes of every state
+// array read and written per item; 13 bytes of traffic per element with one state array
+// (momentum), 21 with two (ADAM), +1 with the 8-bit copy.
+template <bool kSR, bool kW8, class Rule>
+__global__ __launch_bounds__(256) void state_update_kernel(uint16_t *__restrict__ w16,
+                                                           float *__restrict__ s0,
+                                                           float *__restrict__ s1,
                                                            const uint8_t *__restrict__ g8, int64_t n,
-                                                           float neg_lr, float inv_scale, float mu,
-                                                           float wd, uint64_t seed, uint64_t offset,
+                                                           const Rule rule, float inv_scale,
+                                                           uint64_t seed, uint64_t offset,
                                                            const uint32_t *__restrict__ skip,
                                                            uint8_t *__restrict__ w8_out,
                                                            mp8_stats *stats) {
+    constexpr int NS = Rule::kStates;
+    float *const sp[2] = {s0, s1};
     const Philox rng(seed, offset);
     const bool skipping = (skip != nullptr) && (*skip != 0u);
     if (skipping && stats == nullptr) return;
@@ -169,9 +206,14 @@ __global__ __launch_bounds__(256) void sgd_momentum_kernel(uint16_t *__restrict_
             nonfinite += __builtin_popcount(((gw[q] & 0x7C7C7C7Cu) + 0x04040404u) & 0x80808080u);
         if (skipping) continue;
         const u32x4 wr = __builtin_nontemporal_load(reinterpret_cast<u32x4 *>(w16) + t);
-        f32x4 v0 = __builtin_nontemporal_load(reinterpret_cast<f32x4 *>(vel) + 2 * t);
-        f32x4 v1 = __builtin_nontemporal_load(reinterpret_cast<f32x4 *>(vel) + 2 * t + 1);
-        float vv[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+        float sv[8][NS];  // [element][state]
+#pragma unroll
+        for (int k = 0; k < NS; ++k) {
+            const f32x4 a = __builtin_nontemporal_load(reinterpret_cast<f32x4 *>(sp[k]) + 2 * t);
+            const f32x4 b = __builtin_nontemporal_load(reinterpret_cast<f32x4 *>(sp[k]) + 2 * t + 1);
+            sv[0][k] = a.x; sv[1][k] = a.y; sv[2][k] = a.z; sv[3][k] = a.w;
+            sv[4][k] = b.x; sv[5][k] = b.y; sv[6][k] = b.z; sv[7][k] = b.w;
+        }
         uint32_t ww[4] = {wr.x, wr.y, wr.z, wr.w};
         uint32_t rw[4] = {0, 0, 0, 0};
         if constexpr (kSR) {
@@ -183,20 +225,21 @@ __global__ __launch_bounds__(256) void sgd_momentum_kernel(uint16_t *__restrict_
         for (int j = 0; j < 4; ++j) {  // pair j = elements 2j, 2j+1
             const uint32_t g_lo = (gw[j >> 1] >> (16 * (j & 1))) & 0xFFu;
             const uint32_t g_hi = (gw[j >> 1] >> (16 * (j & 1) + 8)) & 0xFFu;
-            const uint32_t h_lo = momentum_one<kSR>(ww[j] & 0xFFFFu, g_lo, vv[2 * j], neg_lr, inv_scale, mu,
-                                                    wd, rw[j] & 0xFFFFu);
-            const uint32_t h_hi = momentum_one<kSR>(ww[j] >> 16, g_hi, vv[2 * j + 1], neg_lr, inv_scale, mu,
-                                                    wd, rw[j] >> 16);
+            const uint32_t h_lo = rule_one<kSR>(rule, ww[j] & 0xFFFFu, g_lo, sv[2 * j], inv_scale, rw[j] & 0xFFFFu);
+            const uint32_t h_hi = rule_one<kSR>(rule, ww[j] >> 16, g_hi, sv[2 * j + 1], inv_scale, rw[j] >> 16);
             ww[j] = h_lo | (h_hi << 16);
             if constexpr (kW8)
                 w8[j >> 1] |= (e5m2_of_half(h_lo) | (e5m2_of_half(h_hi) << 8)) << (16 * (j & 1));
         }
         u32x4 o = {ww[0], ww[1], ww[2], ww[3]};
         __builtin_nontemporal_store(o, reinterpret_cast<u32x4 *>(w16) + t);
-        v0 = f32x4{vv[0], vv[1], vv[2], vv[3]};
-        v1 = f32x4{vv[4], vv[5], vv[6], vv[7]};
-        __builtin_nontemporal_store(v0, reinterpret_cast<f32x4 *>(vel) + 2 * t);
-        __builtin_nontemporal_store(v1, reinterpret_cast<f32x4 *>(vel) + 2 * t + 1);
+#pragma unroll
+        for (int k = 0; k < NS; ++k) {
+            const f32x4 a = {sv[0][k], sv[1][k], sv[2][k], sv[3][k]};
+            const f32x4 b = {sv[4][k], sv[5][k], sv[6][k], sv[7][k]};
+            __builtin_nontemporal_store(a, reinterpret_cast<f32x4 *>(sp[k]) + 2 * t);
+            __builtin_nontemporal_store(b, reinterpret_cast<f32x4 *>(sp[k]) + 2 * t + 1);
+        }
         if constexpr (kW8) {
             u32x2 o8 = {w8[0], w8[1]};
             __builtin_nontemporal_store(o8, reinterpret_cast<u32x2 *>(w8_out) + t);
@@ -210,9 +253,12 @@ __global__ __launch_bounds__(256) void sgd_momentum_kernel(uint16_t *__restrict_
             if (!skipping) {
                 uint32_t r16 = 0;
                 if constexpr (kSR) r16 = philox_half(rng.block((uint64_t)i >> 3), (int)(i & 7));
-                float v = vel[i];
-                const uint32_t h = momentum_one<kSR>(w16[i], gc, v, neg_lr, inv_scale, mu, wd, r16);
-                vel[i] = v;
+                float st[NS];
+#pragma unroll
+                for (int k = 0; k < NS; ++k) st[k] = sp[k][i];
+                const uint32_t h = rule_one<kSR>(rule, w16[i], gc, st, inv_scale, r16);
+#pragma unroll
+                for (int k = 0; k < NS; ++k) sp[k][i] = st[k];
                 w16[i] = (uint16_t)h;
                 if constexpr (kW8) w8_out[i] = (uint8_t)e5m2_of_half(h);
             }
@@ -225,6 +271,32 @@ __global__ __launch_bounds__(256) void sgd_momentum_kernel(uint16_t *__restrict_
     }
 }
 
+// Argument checks and launch shared by the optimizers with state.
+template <class Rule>
+static mp8_status launch_state_update(uint16_t *w16, float *s0, float *s1, const uint8_t *g8, int64_t n,
+                                      const Rule &rule, float inv_loss_scale, mp8_round round,
+                                      uint64_t seed, uint64_t offset, const uint32_t *skip,
+                                      uint8_t *w8_out, mp8_stats *stats, void *stream) {
+    if (n < 0) return MP8_ERR_INVALID_ARG;
+    if (round != MP8_RNE && round != MP8_SR) return MP8_ERR_INVALID_ARG;
+    if (n == 0) return MP8_OK;
+    if (!w16 || !g8 || !s0 || (Rule::kStates > 1 && !s1)) return MP8_ERR_INVALID_ARG;
+    if (((uintptr_t)w16 | (uintptr_t)g8 | (uintptr_t)w8_out | (uintptr_t)s0 | (uintptr_t)s1) & 15u)
+        return MP8_ERR_ALIGNMENT;
+    int64_t blocks = ((n >> 3) + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    if (blocks > (stats != nullptr ? 2048 : (1 << 22))) blocks = stats != nullptr ? 2048 : (1 << 22);
+    hipStream_t s = (hipStream_t)stream;
+#define MP8_M(SR, W8)                                                                                \
+    hipLaunchKernelGGL((state_update_kernel<SR, W8, Rule>), dim3((unsigned)blocks), dim3(256), 0, s, \
+                       w16, s0, s1, g8, n, rule, inv_loss_scale, seed, offset, skip, w8_out, stats)
+    const bool sr = round == MP8_SR, w8 = w8_out != nullptr;
+    if (sr) { if (w8) MP8_M(true, true); else MP8_M(true, false); }
+    else    { if (w8) MP8_M(false, true); else MP8_M(false, false); }
+#undef MP8_M
+    return hipGetLastError() == hipSuccess ? MP8_OK : MP8_ERR_HIP;
+}
+
 }  // namespace mp8
 
 extern "C" mp8_status mp8_sgd_momentum_fp16_sr(uint16_t *w16, float *velocity, const uint8_t *g8,
@@ -233,27 +305,24 @@ extern "C" mp8_status mp8_sgd_momentum_fp16_sr(uint16_t *w16, float *velocity, c
                                                uint64_t seed, uint64_t offset,
                                                const uint32_t *skip_if_nonzero, uint8_t *w8_out,
                                                mp8_stats *stats, void *stream) {
-    using namespace mp8;
-    if (n < 0) return MP8_ERR_INVALID_ARG;
-    if (round != MP8_RNE && round != MP8_SR) return MP8_ERR_INVALID_ARG;
-    if (n == 0) return MP8_OK;
-    if (!w16 || !g8 || !velocity) return MP8_ERR_INVALID_ARG;
-    if (((uintptr_t)w16 | (uintptr_t)g8 | (uintptr_t)w8_out | (uintptr_t)velocity) & 15u)
-        return MP8_ERR_ALIGNMENT;
-    int64_t blocks = ((n >> 3) + 255) / 256;
-    if (blocks < 1) blocks = 1;
-    if (blocks > (stats != nullptr ? 2048 : (1 << 22))) blocks = stats != nullptr ? 2048 : (1 << 22);
-    hipStream_t s = (hipStream_t)stream;
-    const float neg_lr = -lr;
-#define MP8_M(SR, W8)                                                                             \
-    hipLaunchKernelGGL((sgd_momentum_kernel<SR, W8>), dim3((unsigned)blocks), dim3(256), 0, s, w16, \
-                       velocity, g8, n, neg_lr, inv_loss_scale, momentum, weight_decay, seed,      \
-                       offset, skip_if_nonzero, w8_out, stats)
-    const bool sr = round == MP8_SR, w8 = w8_out != nullptr;
-    if (sr) { if (w8) MP8_M(true, true); else MP8_M(true, false); }
-    else    { if (w8) MP8_M(false, true); else MP8_M(false, false); }
-#undef MP8_M
-    return hipGetLastError() == hipSuccess ? MP8_OK : MP8_ERR_HIP;
+    const mp8::MomentumRule rule{-lr, momentum, weight_decay};
+    return mp8::launch_state_update(w16, velocity, nullptr, g8, n, rule, inv_loss_scale, round, seed,
+                                    offset, skip_if_nonzero, w8_out, stats, stream);
+}
+
+extern "C" mp8_status mp8_adam_fp16_sr(uint16_t *w16, float *m, float *v, const uint8_t *g8, int64_t n,
+                                       float lr, float inv_loss_scale, float beta1, float beta2,
+                                       float eps, float weight_decay, int64_t step, mp8_round round,
+                                       uint64_t seed, uint64_t offset,
+                                       const uint32_t *skip_if_nonzero, uint8_t *w8_out,
+                                       mp8_stats *stats, void *stream) {
+    if (step < 1) return MP8_ERR_INVALID_ARG;
+    // bias corrections: the powers in double, the result as FP32
+    const float c1 = (float)(1.0 - std::pow((double)beta1, (double)step));
+    const float c2 = (float)(1.0 - std::pow((double)beta2, (double)step));
+    const mp8::AdamRule rule{-lr, beta1, beta2, 1.0f - beta1, 1.0f - beta2, c1, c2, eps, weight_decay};
+    return mp8::launch_state_update(w16, m, v, g8, n, rule, inv_loss_scale, round, seed, offset,
+                                    skip_if_nonzero, w8_out, stats, stream);
 }
 
 extern "C" mp8_status mp8_sgd_update_fp16_sr(uint16_t *w16, const uint8_t *g8, int64_t n,

@@ -147,3 +147,66 @@ def test_momentum_update_skip_and_reduction_to_plain_update(mp8):
     mp8.sgd_momentum_fp16_sr(b, v, gpu(g8), 1e-2, 1 / 64.0, 0.9, 0.0, skip_if_nonzero=flag)
     torch.cuda.synchronize()
     assert torch.equal(b, b0) and torch.equal(v, v0)
+
+
+def _same_f32(got, want):
+    """Bit-exact FP32 arrays except for the payload of NaNs."""
+    ok = ~np.isnan(want)
+    return np.array_equal(np.isnan(got), ~ok) and np.array_equal(got[ok].view(np.uint32), want[ok].view(np.uint32))
+
+
+@pytest.mark.parametrize("n", [1, 7, 4099, 1 << 20])
+@pytest.mark.parametrize("rnd", [oracle.RNE, oracle.SR])
+def test_adam_update_matches_oracle_over_several_steps(mp8, n, rnd):
+    """ADAM with L2 regularisation: weights, both FP32 moments and the 8-bit weight copy bit-exact
+    against the oracle over four chained steps (division and square root included); the second
+    step's gradients contain Inf / NaN codes."""
+    import torch
+    rng = np.random.default_rng(3 * n + rnd)
+    w16 = (rng.standard_normal(n) * np.exp2(rng.integers(-20, 1, n))).astype(np.float16).view(np.uint16)
+    m0 = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    v0 = (rng.random(n) * 1e-5).astype(np.float32)
+    v0[::7] = 0.0                                      # sqrt(0) + eps in the denominator
+    lr, inv, b1, b2, eps, wd = 1e-3, 1.0 / 4096, 0.9, 0.999, 1e-8, 1e-4
+    wdev, md, vd = gpu(w16.view(np.int16)), gpu(m0), gpu(v0)
+    w8d = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    ow, om, ov = w16, m0, v0
+    for step in range(1, 5):
+        g8 = workloads.random_e5m2_codes(100 * step + n % 89, (n,), finite_only=(step != 2))
+        st = mp8.new_stats()
+        mp8.adam_fp16_sr(wdev, md, vd, gpu(g8), lr, inv, step, beta1=b1, beta2=b2, eps=eps, weight_decay=wd,
+                         round=rnd, seed=8, offset=step, w8_out=w8d, stats=st)
+        torch.cuda.synchronize()
+        ost = oracle.Stats()
+        ow, om, ov, o8 = oracle.adam_fp16(ow, om, ov, g8, lr, inv, step, beta1=b1, beta2=b2, eps=eps,
+                                          weight_decay=wd, mode=rnd, seed=8, offset=step, want_w8=True, stats=ost)
+        assert _same_f32(host(md), om) and _same_f32(host(vd), ov), step
+        assert np.array_equal(host(wdev).view(np.uint16), ow), step
+        assert np.array_equal(host(w8d), o8), step
+        assert mp8.read_stats(st)[1] == ost.nonfinite
+
+
+def test_adam_update_wide_range_of_moments_skip_and_errors(mp8):
+    """Moments and gradients across the whole FP32 / 8-bit range (denormal second moments, huge
+    first moments, eps = 0 with zero denominators): still bit for bit; the skip flag; bad steps."""
+    import torch
+    n = 1 << 16
+    rng = np.random.default_rng(77)
+    w16 = rng.integers(0, 1 << 16, n).astype(np.uint16)          # every class of half, NaN and Inf too
+    m0 = (rng.standard_normal(n) * np.exp2(rng.integers(-140, 100, n).astype(np.float64))).astype(np.float32)
+    v0 = np.exp2(rng.integers(-149, 120, n).astype(np.float64)).astype(np.float32)
+    g8 = rng.integers(0, 256, n).astype(np.uint8)
+    for eps, step in ((0.0, 1), (1e-8, 1000)):
+        wdev, md, vd = gpu(w16.view(np.int16)), gpu(m0), gpu(v0)
+        mp8.adam_fp16_sr(wdev, md, vd, gpu(g8), 0.01, 1.0 / 128, step, eps=eps, round=mp8.RNE)
+        torch.cuda.synchronize()
+        ow, om, ov, _ = oracle.adam_fp16(w16, m0, v0, g8, 0.01, 1.0 / 128, step, eps=eps, mode=oracle.RNE)
+        assert _same_f32(host(md), om) and _same_f32(host(vd), ov)
+        assert np.array_equal(host(wdev).view(np.uint16), ow)
+    flag = torch.ones(1, dtype=torch.int32, device="cuda")
+    w_before, m_before = wdev.clone(), md.clone()
+    mp8.adam_fp16_sr(wdev, md, vd, gpu(g8), 0.01, 1.0, 3, skip_if_nonzero=flag)
+    torch.cuda.synchronize()
+    assert torch.equal(wdev.view(torch.int16), w_before.view(torch.int16)) and torch.equal(md.view(torch.int32), m_before.view(torch.int32))
+    with pytest.raises(mp8.Mp8Error):
+        mp8.adam_fp16_sr(wdev, md, vd, gpu(g8), 0.01, 1.0, 0)
