@@ -71,6 +71,31 @@ def parse_args():
     return ap.parse_args()
 
 
+class StatsRing:
+    """Every step accumulates its overflow statistics into a slot of its own (16 bytes); the
+    slots are cleared together, by one small fill kernel (no memset node, so the steps can be
+    captured), each time the ring wraps around: one clearing launch per `size` steps instead of
+    one per step.  The host reads a step's slot at its leisure (the loss scaler needs the count
+    only before the next update of the scale)."""
+
+    def __init__(self, torch, size=10):
+        self.slots = torch.zeros((size, 4), dtype=torch.int32, device="cuda")
+        self.size, self.index = size, -1
+
+    def resize(self, size):
+        """Start over with `size` slots (the next step is the first of a ring period)."""
+        self.slots = self.slots.new_zeros((size, 4))
+        self.size, self.index = size, -1
+
+    def advance(self):
+        self.index += 1
+        if self.index % self.size == 0:
+            self.slots.zero_()
+
+    def current(self):
+        return self.slots[max(self.index, 0) % self.size]
+
+
 class Workload:
     """Device buffers and launch closures for the configs[1] layer."""
 
@@ -90,7 +115,7 @@ class Workload:
         self.Y8 = torch.empty((M, N), dtype=u8, device=dev)
         self.dX8 = torch.empty((M, K), dtype=u8, device=dev)
         self.G8 = torch.empty((K, N), dtype=u8, device=dev)
-        self.stats = mp8.new_stats()
+        self.ring = StatsRing(torch)
         ws = max(mp8.gemm_fp8_workspace_bytes(op, M, N, K) for op in (mp8.FWD, mp8.BWD_DATA, mp8.WGRAD))
         self.ws = torch.empty(max(ws, 16), dtype=u8, device=dev)
         self.step_no = 0
@@ -126,8 +151,12 @@ class Workload:
                                     seed=0x1905_1233_4000_0002, offset=self.step_no,
                                     skip_if_nonzero=self.stats[1:2], w8_out=self.W8)
 
+    @property
+    def stats(self):
+        return self.ring.current()
+
     def step(self):
-        self.stats.zero_()     # a small fill kernel (no memset node, so the step can be captured)
+        self.ring.advance()
         for _, fn, _, _, _ in self.kernels:
             fn()
 
@@ -162,7 +191,7 @@ class ConvWorkload:
         self.Y8 = torch.empty((P, C), dtype=u8, device=dev)
         self.dX8 = torch.empty((P, C), dtype=u8, device=dev)
         self.G8 = torch.empty((9 * C, C), dtype=u8, device=dev)
-        self.stats = mp8.new_stats()
+        self.ring = StatsRing(torch)
         ws = max(mp8.conv3x3_fp8_workspace_bytes(op, *self.dims) for op in (mp8.FWD, mp8.BWD_DATA, mp8.WGRAD))
         self.ws = torch.empty(max(ws, 16), dtype=u8, device=dev)
         self.step_no = 0
@@ -187,8 +216,12 @@ class ConvWorkload:
                                     seed=0x1905_1233_4000_0003, offset=self.step_no,
                                     skip_if_nonzero=self.stats[1:2], w8_out=self.W8)
 
+    @property
+    def stats(self):
+        return self.ring.current()
+
     def step(self):
-        self.stats.zero_()
+        self.ring.advance()
         for _, fn, _, _, _ in self.kernels:
             fn()
 
@@ -220,6 +253,7 @@ def time_steps(torch, wl, steps, launch):
         torch.cuda.synchronize()
         return s.elapsed_time(e) / steps
     per_graph = max(d for d in range(1, 11) if steps % d == 0)
+    wl.ring.resize(per_graph)          # one graph = one period of the statistics ring
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         for _ in range(per_graph):
