@@ -367,6 +367,7 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     __shared__ __attribute__((aligned(1024))) uint8_t lds[LDS_BYTES];
 
     MP8_STAMP_PHASE(0);
+    MP8_BLOCK_STAMP(0);
     int split, tm, tn;
     map_block(p, split, tm, tn);
     split = __builtin_amdgcn_readfirstlane(split);
@@ -577,6 +578,7 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
 #pragma unroll
     for (int n = 0; n < 2 * F; ++n) read_half(0, 0, frag_order(n / 2), n & 1, f0);
     MP8_STAMP_PHASE(2);
+    MP8_BLOCK_STAMP(1);
 
     // One stage = 2*NM "slots", one MFMA each, fenced so that the order below is the issue
     // order.  Everything else a stage needs is spread over the slots so that it issues in the
@@ -657,6 +659,7 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     }
     wait_vm_lds<0>();
     MP8_STAMP_PHASE(3);
+    MP8_BLOCK_STAMP(2);
 
     // Epilogue.  acc[i][j][4g + e] is output row  wm*WTM + 32i + lane%32  and column
     // wn*WTN + 32j + 8g + 4*(lane/32) + e.  Each wave passes its tile through LDS one band
@@ -668,6 +671,63 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     constexpr int BANDS = MT >= 2 ? 2 : 1;         // bands staged per pass
     static_assert(4 * BANDS * 32 * EP_LD * 4 <= LDS_BYTES, "band buffers fit in LDS");
     __syncthreads();                               // all waves are done with the operand ring
+    if constexpr (EPI == EPI_RNE) {
+        // RNE only: convert in registers (four codes = one register), join the two half-wave
+        // column sets of every 32x32 tile with two v_permlane32_swap -- lane (row, h) then
+        // holds the 16-byte piece of columns 32j + 16h .. +15 -- and collect the whole block
+        // tile of codes (BM x BN bytes) in LDS, piece q of row r in slot q ^ f(r) with
+        // f(r) = (r / rows per 256 bytes) mod pieces per row: conflict-free for the writes
+        // (16 rows, one piece) and for the reads (consecutive pieces of a row).  Then the
+        // block stores whole rows of the tile: BN / 16 consecutive lanes per row.
+        constexpr int NP = BN / 16;                // pieces per tile row
+        constexpr int RP = 256 / BN > 0 ? 256 / BN : 1;  // tile rows per 256 bytes of LDS
+        static_assert(BM * BN <= LDS_BYTES, "code tile fits in LDS");
+        auto slot = [&](int r, int q) { return r * BN + ((q ^ ((r / RP) & (NP - 1))) << 4); };
+        auto tiles = [&](auto unit_alpha) {
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                for (int j = 0; j < NT; ++j) {
+                    uint32_t pk[4];
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        float y[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2],
+                                      acc[i][j][4 * g + 3]};
+                        if constexpr (!decltype(unit_alpha)::value) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) y[e] *= p.ep.alpha;
+                        }
+                        pk[g] = e5m2_pack4<false>(y, 0u, 0u, false);
+                    }
+                    // after swap(pk[g], pk[g+2]): lower half = own columns 8g .. 8g+3 and the
+                    // upper half's 8g+4 .. 8g+7; upper half = the lower half's 16+8g .. +3 and
+                    // its own 16+8g+4 .. +7
+                    const auto s0 = __builtin_amdgcn_permlane32_swap(pk[0], pk[2], false, false);
+                    const auto s1 = __builtin_amdgcn_permlane32_swap(pk[1], pk[3], false, false);
+                    u32x4 o = {s0[0], s0[1], s1[0], s1[1]};
+                    *reinterpret_cast<u32x4 *>(lds + slot(wm * WTM + 32 * i + frow,
+                                                          (wn * WTN + 32 * j) / 16 + fkb)) = o;
+                }
+        };
+        if (p.ep.alpha == 1.0f) tiles(std::true_type{});
+        else tiles(std::false_type{});
+        __syncthreads();
+        const int q = threadIdx.x % NP;
+        const int64_t c = col0 + 16 * q;
+#pragma unroll
+        for (int k = 0; k < BM * NP / 256; ++k) {
+            const int rr = k * (256 / NP) + threadIdx.x / NP;
+            u32x4 o = *reinterpret_cast<const u32x4 *>(lds + slot(rr, q));
+            const int64_t r = row0 + rr;
+            if (r < p.rows && c < p.cols) {
+                if (p.ep.mask && conv_padding_row(p.ep, r)) o = u32x4{0u, 0u, 0u, 0u};
+                *reinterpret_cast<u32x4 *>(p.ep.out8 + r * p.cols + c) = o;
+            }
+        }
+        MP8_STAMP_PHASE(4);
+        MP8_BLOCK_STAMP(3);
+        return;
+    }
     float *band = reinterpret_cast<float *>(lds) + wave * BANDS * 32 * EP_LD;
     StatsAcc st;
     const bool fast_cols = (p.cols & 15) == 0;
@@ -716,6 +776,7 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
         if (p.ep.stats != nullptr) st.flush(p.ep.stats);
     }
     MP8_STAMP_PHASE(4);
+    MP8_BLOCK_STAMP(3);
 }
 
 // Short contraction (one or two 128-byte stages, both operands row-major).  Such a GEMM is all
