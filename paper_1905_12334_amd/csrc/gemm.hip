@@ -392,13 +392,21 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     // Contraction-major operands (ATN: a is [kc, rows]; BTN: b is [kc, cols]) use the same LDS
     // geometry with the roles swapped: a slab is cut into panels of 128 tile rows, each panel
     // is 128 contraction rows of 128 bytes, chunk c of contraction row k sits in slot
-    // c ^ ((k >> 1) & 7).  Chunks that would start beyond the matrix are clamped to its last
-    // 16 rows (never stored).
+    // c ^ (2 * ((k >> 1) & 3)).  Chunks that would start beyond the matrix are clamped to its
+    // last 16 rows (never stored).
     // A tile of only 64 rows is one panel of 128 contraction rows of 64 bytes: a direct load
     // then covers 16 contraction rows, lane i lands at (row i/4, slot i%4), and chunk c of
-    // contraction row k sits in slot c ^ ((k >> 2) & 3).
+    // contraction row k sits in slot c ^ (2 * ((k >> 2) & 1)).
+    // These two swizzles are cut for the transposing reads below, which the LDS serves 32 lanes
+    // at a time: lanes 0..15 name contraction rows k0 .. k0+7 of one chunk, lanes 16..31 the
+    // same rows of the next chunk.  Rows of equal parity (wide) or equal position within a
+    // 256-byte bank period (narrow) fall on the same banks unless their slots differ, so the
+    // rows' slots must differ in bit 1 or above (bit 0 tells the two chunks apart): the 32 lanes
+    // then cover all 64 banks exactly once.  (With the fragment swizzle of the row-major slabs
+    // half of the LDS cycles of these reads were bank conflicts.)
     const int lrow = lane >> 3, lchunk = (lane & 7) ^ ((4 * wave + (lane >> 4)) & 7);
-    const int lrow64 = lane >> 2, lchunk64 = (lane & 3) ^ ((lane >> 4) & 3);
+    const int lchunk_t = (lane & 7) ^ (((lane >> 4) & 3) << 1);
+    const int lrow64 = lane >> 2, lchunk64 = (lane & 3) ^ (((lane >> 4) & 1) << 1);
     const int64_t a_kstep = ATN ? (int64_t)BK * p.lda : BK, b_kstep = BTN ? (int64_t)BK * p.ldb : BK;
     auto tap_shift = [&](uint32_t tap) {  // pixel-row shift of filter tap (r, s) = (tap / 3, tap % 3)
         const int r = (int)((tap * 11u) >> 5);
@@ -443,7 +451,7 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     for (int q = 0; q < A_DMA; ++q) {
         if constexpr (ATN) {
             const int64_t krow = BM == 64 ? 16 * (wave + 4 * q) + lrow64 : 8 * (wave + 4 * (q & 3)) + lrow;
-            int64_t m = BM == 64 ? 16 * lchunk64 : 128 * (q >> 2) + 16 * lchunk;
+            int64_t m = BM == 64 ? 16 * lchunk64 : 128 * (q >> 2) + 16 * lchunk_t;
             m = row0 + m + 16 <= p.rows ? m : p.rows - 16 - row0;
             oa[q] = (uint32_t)(krow * p.lda + m);
         } else {
@@ -456,7 +464,7 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     for (int q = 0; q < B_DMA; ++q) {
         if constexpr (BTN) {
             const int64_t krow = BN == 64 ? 16 * (wave + 4 * q) + lrow64 : 8 * (wave + 4 * (q & 3)) + lrow;
-            int64_t m = BN == 64 ? 16 * lchunk64 : 128 * (q >> 2) + 16 * lchunk;
+            int64_t m = BN == 64 ? 16 * lchunk64 : 128 * (q >> 2) + 16 * lchunk_t;
             m = col0 + m + 16 <= p.cols ? m : p.cols - 16 - col0;
             ob[q] = (uint32_t)(krow * p.ldb + m);
         } else {
@@ -507,8 +515,8 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
                 const int k = 64 * sub + 32 * fkb + 8 * (2 * half + e) + (t >> 1);
-                const int off = obase + (narrow ? k * 64 + ((mc ^ ((k >> 2) & 3)) << 4)
-                                                : k * 128 + ((mc ^ ((k >> 1) & 7)) << 4)) + 8 * (t & 1);
+                const int off = obase + (narrow ? k * 64 + ((mc ^ (((k >> 2) & 1) << 1)) << 4)
+                                                : k * 128 + ((mc ^ (((k >> 1) & 3) << 1)) << 4)) + 8 * (t & 1);
                 part[e] = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
                     (__attribute__((address_space(3))) i32x2 *)(s + off));
             }
