@@ -787,6 +787,164 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     MP8_BLOCK_STAMP(3);
 }
 
+// Small output, long contraction, both operands contraction-major (the weight gradient read
+// from row-major activations and errors): the contraction is divided among the four WAVES of a
+// workgroup as well.  In the general kernel a 64x64 tile gives each wave one 32x32 MFMA per
+// half stage behind a workgroup barrier, and every stage costs a chain of latencies (load,
+// barrier, LDS read, MFMA) with nothing to overlap them.  Here every wave computes the whole
+// 64x64 tile (four MFMAs per half stage, each fragment used twice) for every fourth stage of
+// the workgroup's slice, from a two-stage ring of its own (2 x 16 KB) that it fills with its
+// own direct loads and waits for with its own counter: no barrier inside the loop, and eight
+// stage loads in flight per CU.  At the end the four FP32 tiles meet in LDS and are added in
+// wave order; each thread then owns sixteen consecutive columns of one row for the epilogue.
+// CONV = 3: the weight gradient of the 3x3 convolution (tap shift per tile row), else 0.
+template <int EPI, int CONV>
+__global__ __launch_bounds__(256, 1) void gemm_wavek_kernel(const GemmArgs p) {
+    static_assert(CONV == 0 || CONV == 3, "plain or convolution weight gradient");
+    constexpr int BM = 64, BN = 64;
+    constexpr int SLAB = 64 * BK;           // 128 contraction rows of 64 bytes
+    constexpr int STAGE = 2 * SLAB;         // a, then b
+    constexpr int WAVE_LDS = 2 * STAGE;     // ring of two stages per wave
+    constexpr int RED_LD = BN + 4;          // floats per row of a tile parked for the reduction
+    static_assert(4 * BM * RED_LD * 4 <= 4 * WAVE_LDS, "reduction buffers fit in the rings");
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[4 * WAVE_LDS];
+
+    int split, tm, tn;
+    map_block(p, split, tm, tn);
+    split = __builtin_amdgcn_readfirstlane(split);
+    tm = __builtin_amdgcn_readfirstlane(tm);
+    tn = __builtin_amdgcn_readfirstlane(tn);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t row0 = (int64_t)tm * BM, col0 = (int64_t)tn * BN;
+    const int per = p.ks_per, extra = p.ks_extra;
+    const int ks_begin = split * per + (split < extra ? split : extra);
+    const int ks_count = per + (split < extra ? 1 : 0);
+    // this wave's stages: ks_begin + wave, + 4, + 8, ...
+    const int mine = __builtin_amdgcn_readfirstlane(ks_count > wave ? (ks_count - wave + 3) >> 2 : 0);
+
+    const int64_t a_kstep = (int64_t)BK * p.lda, b_kstep = (int64_t)BK * p.ldb;
+    const uint8_t *a_origin;
+    if constexpr (CONV == 3) {
+        uint32_t ci0;
+        const uint32_t tap = fastdiv((uint32_t)row0, p.cv.div_ci, ci0);
+        const int r = (int)((tap * 11u) >> 5);
+        const int shift = (r - 1) * p.cv.w2 + ((int)tap - 3 * r - 1);
+        a_origin = p.a + (int64_t)shift * p.lda + ci0;
+    } else {
+        a_origin = p.a + row0;
+    }
+    const uint8_t *a_tile = uniform_ptr(a_origin + (int64_t)(ks_begin + wave) * a_kstep);
+    const uint8_t *b_tile = uniform_ptr(p.b + col0 + (int64_t)(ks_begin + wave) * b_kstep);
+    // Direct loads: one covers 16 contraction rows of 64 bytes; lane i lands at (row i/4, slot
+    // i%4) and fetches the chunk that belongs there under the swizzle of the narrow slabs.
+    // Chunks that would start beyond the matrix are clamped to its last 16 rows (never stored).
+    const int lchunk64 = (lane & 3) ^ (((lane >> 4) & 1) << 1);
+    int64_t am = 16 * lchunk64, bm_ = 16 * lchunk64;
+    am = row0 + am + 16 <= p.rows ? am : p.rows - 16 - row0;
+    bm_ = col0 + bm_ + 16 <= p.cols ? bm_ : p.cols - 16 - col0;
+    const uint32_t oa = (uint32_t)((lane >> 2) * p.lda + am), ob = (uint32_t)((lane >> 2) * p.ldb + bm_);
+    uint8_t *ring = lds + wave * WAVE_LDS;
+    const uint32_t ring0 = lds_address(ring);
+    auto issue = [&](int j) {  // stage j of this wave into buffer j % 2: 16 loads
+        const uint8_t *ak = a_tile + (int64_t)(4 * j) * a_kstep;
+        const uint8_t *bk = b_tile + (int64_t)(4 * j) * b_kstep;
+        const uint32_t sa = ring0 + (j & 1) * STAGE;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) dma16(ak + (int64_t)(16 * q) * p.lda, oa, sa + q * 1024);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) dma16(bk + (int64_t)(16 * q) * p.ldb, ob, sa + SLAB + q * 1024);
+    };
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+    const int frow = lane & 31, fkb = lane >> 5, t16 = lane & 15;
+    // fragment f (0, 1: a tile rows 32f ..; 2, 3: b) of half stage `sub` from buffer `s`: four
+    // transposing reads of eight contraction indices each (see the general kernel)
+    auto fragment = [&](const uint8_t *s, int sub, int f) -> i32x8 {
+        const int m = (f & 1) * 32 + (frow & 16);
+        const int mc = m >> 4;
+        i32x2 part[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int k = 64 * sub + 32 * fkb + 8 * e + (t16 >> 1);
+            const int off = (f >> 1) * SLAB + k * 64 + ((mc ^ (((k >> 2) & 1) << 1)) << 4) + 8 * (t16 & 1);
+            part[e] = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
+                (__attribute__((address_space(3))) i32x2 *)(s + off));
+        }
+        return i32x8{part[0].x, part[0].y, part[1].x, part[1].y, part[2].x, part[2].y, part[3].x, part[3].y};
+    };
+
+    // (Issuing the fragment reads of a half stage ahead of the MFMAs of the one before it, as
+    // the general kernel does, was measured and gained nothing here: the loop waits for loads.)
+    if (mine > 0) issue(0);
+    if (mine > 1) issue(1);
+    for (int j = 0; j < mine; ++j) {
+        if (j + 1 < mine) wait_vm_lds<16>();  // the sixteen loads of the next stage may fly
+        else wait_vm_lds<0>();
+        const uint8_t *s = ring + (j & 1) * STAGE;
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            const i32x8 a0 = fragment(s, sub, 0), a1 = fragment(s, sub, 1);
+            const i32x8 b0 = fragment(s, sub, 2), b1 = fragment(s, sub, 3);
+            // bf8 x bf8, unscaled; b as the "row" matrix: a lane gets consecutive output columns
+            acc[0][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b0, a0, acc[0][0], 1, 1, 0, 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b1, a0, acc[0][1], 1, 1, 0, 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b0, a1, acc[1][0], 1, 1, 0, 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b1, a1, acc[1][1], 1, 1, 0, 0, 0, 0);
+        }
+        if (j + 2 < mine) {
+            // the loads below are invisible to the compiler (it could sink the multiplications
+            // and their wait below them): wait for this wave's LDS reads explicitly
+            wait_vm_lds<63>();
+            issue(j + 2);
+        }
+    }
+    wait_vm_lds<0>();
+
+    // The four tiles meet in LDS: acc[i][j][4g + e] is row 32i + lane%32, column
+    // 32j + 8g + 4*(lane/32) + e of this wave's tile.
+    __syncthreads();  // every wave is done with its ring
+    float *red = reinterpret_cast<float *>(lds);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                f32x4 o = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                *reinterpret_cast<f32x4 *>(red + (wave * BM + 32 * i + frow) * RED_LD + 32 * j + 8 * g + 4 * fkb) = o;
+            }
+    __syncthreads();
+    StatsAcc st;
+    const bool fast_cols = (p.cols & 15) == 0;
+    {
+        const int rr = threadIdx.x >> 2, cg = threadIdx.x & 3;
+        const int64_t r = row0 + rr, c = col0 + 16 * cg;
+        float v[16];
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f32x4 x = *reinterpret_cast<const f32x4 *>(red + (w * BM + rr) * RED_LD + 16 * cg + 4 * q);
+                if (w == 0) {
+                    v[4 * q] = x.x; v[4 * q + 1] = x.y; v[4 * q + 2] = x.z; v[4 * q + 3] = x.w;
+                } else {
+                    v[4 * q] += x.x; v[4 * q + 1] += x.y; v[4 * q + 2] += x.z; v[4 * q + 3] += x.w;
+                }
+            }
+        if (r < p.rows && c < p.cols) emit16<EPI>(p, split, r, c, v, st, fast_cols);
+    }
+    if constexpr (EPI == EPI_FULL) {
+        if (p.ep.stats != nullptr) st.flush(p.ep.stats);
+    }
+}
+
 // Short contraction (one or two 128-byte stages, both operands row-major).  Such a GEMM is all
 // start-up and epilogue: every output byte costs only 128-256 bytes of MFMA input, so what
 // bounds it is how many output lines are in flight.  This kernel is cut for that:
@@ -1096,11 +1254,18 @@ struct TileConfig {
      {gemm_shortk_kernel<EPI_PARTIAL>, gemm_shortk_kernel<EPI_RNE>, gemm_shortk_kernel<EPI_FULL>}, \
      {nullptr, nullptr, nullptr}, {nullptr, nullptr, nullptr},                \
      {{nullptr, nullptr, nullptr}, {nullptr, nullptr, nullptr}, {nullptr, nullptr, nullptr}}, 2, 32768}
+#define MP8_TILE_WAVEK                                                       \
+    {64, 64, "64x64x128w", {nullptr, nullptr, nullptr},                        \
+     {gemm_wavek_kernel<EPI_PARTIAL, 0>, gemm_wavek_kernel<EPI_RNE, 0>, gemm_wavek_kernel<EPI_FULL, 0>}, \
+     {nullptr, nullptr, nullptr},                                              \
+     {{nullptr, nullptr, nullptr}, {nullptr, nullptr, nullptr},                \
+      {gemm_wavek_kernel<EPI_PARTIAL, 3>, gemm_wavek_kernel<EPI_RNE, 3>, gemm_wavek_kernel<EPI_FULL, 3>}}, 0, 0}
 static const TileConfig kTiles[] = {
     MP8_TILE_TN(256, 256, 2, 2, 2, 1), MP8_TILE(256, 128, 2, 2, 3, 1), MP8_TILE(128, 256, 2, 2, 3, 1),
     MP8_TILE_TN(128, 128, 2, 2, 2, 2), MP8_TILE_TN(128, 128, 2, 2, 4, 1), MP8_TILE(64, 128, 1, 4, 3, 2),
     MP8_TILE(128, 64, 4, 1, 3, 2),  MP8_TILE_TN(64, 64, 2, 2, 4, 2), MP8_TILE(64, 128, 1, 4, 2, 3),
     MP8_TILE(128, 64, 4, 1, 2, 3),  MP8_TILE_TN(64, 64, 2, 2, 2, 4),   MP8_TILE_SHORTK,
+    MP8_TILE_WAVEK,
 };
 constexpr int kNumTiles = (int)(sizeof(kTiles) / sizeof(kTiles[0]));
 constexpr int kCUs = 256;
@@ -1128,7 +1293,7 @@ static void op_dims(mp8_op op, int64_t M, int64_t N, int64_t K, int64_t &rows, i
 // resident blocks per CU when the contraction is short, a deeper ring when it is long); small
 // outputs take 64x64 tiles and, if even those are too few, a split contraction -- kept to a
 // minimum because the second pass costs several microseconds.
-enum { T256x256 = 0, T128x128s2 = 3, T128x128s4 = 4, T128x64s2 = 9, T64x64s2 = 10, T128x128k = 11 };
+enum { T256x256 = 0, T128x128s2 = 3, T128x128s4 = 4, T128x64s2 = 9, T64x64s2 = 10, T128x128k = 11, T64x64w = 12 };
 static Plan make_plan(int64_t rows, int64_t cols, int64_t kc, int tile_config, int split_k,
                       int layout = 0) {  // bit 0: a contraction-major, bit 1: b
     Plan pl{};
@@ -1140,6 +1305,7 @@ static Plan make_plan(int64_t rows, int64_t cols, int64_t kc, int tile_config, i
         (layout == 3 ? kTiles[tile_config - 1].kernel_tn[0] : kTiles[tile_config - 1].kernel_bt[0]) == nullptr)
         pl.mfma = false;
     const bool tn = layout != 0;
+    if (layout == 0 && tile_config > 0 && kTiles[tile_config - 1].kernel[0] == nullptr) pl.mfma = false;
     if (tile_config > 0 && kTiles[tile_config - 1].max_ksteps > 0 &&
         (tn || kc / BK > kTiles[tile_config - 1].max_ksteps))
         pl.mfma = false;
@@ -1157,7 +1323,9 @@ static Plan make_plan(int64_t rows, int64_t cols, int64_t kc, int tile_config, i
     } else {
         const int64_t n256 = count(T256x256), n128 = count(T128x128s2);
         const double fill256 = (double)n256 / (double)(((n256 + kCUs - 1) / kCUs) * kCUs);
+        const int64_t n64 = count(T64x64s2);
         if (n256 >= 208 && fill256 >= 0.8 && ksteps >= 8) t = T256x256;
+        else if (layout == 3 && n64 <= kCUs && ksteps >= 16) t = T64x64w;  // one workgroup per CU
         else if (tn && (n128 < 16 || (n128 < 192 && ksteps <= 64))) t = T64x64s2;
         else if (tn) t = ksteps >= 64 ? T128x128s4 : T128x128s2;
         else if (n128 >= 192 && ksteps <= 2) t = T128x128k;  // all prologue and epilogue
@@ -1171,6 +1339,11 @@ static Plan make_plan(int64_t rows, int64_t cols, int64_t kc, int tile_config, i
     int s = 1;
     if (kTiles[t].max_ksteps > 0) {
         s = 1;  // these kernels take the whole contraction at once
+    } else if (split_k == 0 && t == T64x64w) {
+        // one workgroup per CU and never more workgroups than CUs (a second round would double
+        // the time); at least two stages for each of the four waves
+        s = (int)std::max<int64_t>(1, std::min<int64_t>(kCUs / nt, ksteps / 8));
+        s = std::min(s, kMaxSplits);
     } else if (split_k > 0) {
         s = split_k;
     } else if (nt < kCUs / 2) {
@@ -1209,8 +1382,9 @@ extern "C" int mp8_gemm_tile_config_name(int tile_config, char *buf, size_t bufl
 extern "C" int mp8_gemm_tile_config_lds_bytes(int tile_config, int epi) {
     if (tile_config < 1 || tile_config > mp8::kNumTiles || epi < 0 || epi > 2) return -1;
     hipFuncAttributes at;
-    if (hipFuncGetAttributes(&at, (const void *)mp8::kTiles[tile_config - 1].kernel[epi]) != hipSuccess)
-        return -1;
+    const mp8::TileConfig &tc = mp8::kTiles[tile_config - 1];
+    const void *fn = tc.kernel[epi] ? (const void *)tc.kernel[epi] : (const void *)tc.kernel_tn[epi];
+    if (fn == nullptr || hipFuncGetAttributes(&at, fn) != hipSuccess) return -1;
     return (int)at.sharedSizeBytes;
 }
 
