@@ -393,6 +393,57 @@ def test_contraction_major_operands_random(mp8, shape):
     check_outputs(acc, out8, ref, absref, kc, mode=oracle.SR, seed=4, offset=9)
 
 
+def test_wave_split_kernel_all_epilogues_and_uneven_slices(mp8):
+    """The kernel that divides the contraction among the waves of a workgroup: a contraction of
+    37 stages (uneven over four waves and over the slices), rows and columns ragged against its
+    64x64 tile, every epilogue it carries -- FP32 accumulator out and accumulate-into, RNE and SR,
+    saturation, statistics -- against the oracle; and the planner's own choice of it."""
+    import torch
+    names = mp8.gemm_tile_configs()
+    wk = 1 + [n.endswith("w") for n in names].index(True)
+    rows, cols, kc = 208, 144, 128 * 37
+    a_km = (workloads.random_e5m2_codes(41, (kc, rows)) & 0x83) | 0x38
+    b_km = (workloads.random_e5m2_codes(42, (kc, cols)) & 0x83) | 0x38
+    ref, absref = oracle.gemm_ref(np.ascontiguousarray(a_km.T), np.ascontiguousarray(b_km.T))
+    a, b = gpu(a_km), gpu(b_km)
+    flags = mp8.FLAG_CONTRACTION_MAJOR
+    for split in (0, 1, 2, 5):
+        tile = 0 if split == 0 else wk
+        assert mp8.gemm_fp8_plan(mp8.FWD, rows, cols, kc, flags, tile, split)[0] == names[wk - 1]
+        ws = torch.empty(max(mp8.gemm_fp8_workspace_bytes(mp8.FWD, rows, cols, kc, tile, split), 16),
+                         dtype=torch.uint8, device="cuda")
+        for mode, fl, alpha in ((oracle.RNE, 0, 1.0), (oracle.SR, 0, 0.01), (oracle.SR, oracle.FLAG_SATURATE, 40.0),
+                                (oracle.RNE, 0, 40.0)):
+            acc = torch.full((rows * cols + 16,), 7.0, dtype=torch.float32, device="cuda")
+            obuf = torch.full((rows * cols + 64,), 0xAA, dtype=torch.uint8, device="cuda")
+            st = mp8.new_stats()
+            mp8.gemm_fp8(mp8.FWD, rows, cols, kc, a, b, out8=obuf[: rows * cols], acc=acc[: rows * cols], acc_mode=1,
+                         alpha=alpha, round=mode, flags=flags | fl, seed=3, offset=8, stats=st, workspace=ws,
+                         tile_config=tile, split_k=split)
+            # the same without the FP32 output: the epilogue runs inside the kernel when unsplit
+            o2 = torch.full((rows * cols + 64,), 0xAA, dtype=torch.uint8, device="cuda")
+            st2 = mp8.new_stats()
+            mp8.gemm_fp8(mp8.FWD, rows, cols, kc, a, b, out8=o2[: rows * cols], alpha=alpha, round=mode,
+                         flags=flags | fl, seed=3, offset=8, stats=st2, workspace=ws, tile_config=tile, split_k=split)
+            torch.cuda.synchronize()
+            assert bool((obuf[rows * cols:] == 0xAA).all()) and bool((o2[rows * cols:] == 0xAA).all())
+            assert bool((acc[rows * cols:] == 7.0).all())
+            acc_h, out8 = host(acc[: rows * cols]).reshape(rows, cols), host(obuf[: rows * cols]).reshape(rows, cols)
+            check_outputs(acc_h, out8, ref, absref, kc, mode=mode, seed=3, offset=8, alpha=alpha, flags=fl)
+            assert np.array_equal(host(o2[: rows * cols]).reshape(rows, cols), out8), (split, mode, fl)
+            ost = oracle.Stats()
+            oracle.quantize_e5m2(acc_h, scale=alpha, mode=mode, seed=3, offset=8, flags=fl, stats=ost)
+            assert mp8.read_stats(st) == ost.as_tuple() == mp8.read_stats(st2), (split, mode, fl)
+        # accumulate into an FP32 buffer across two calls (acc_mode 2): twice the sum
+        acc2 = torch.zeros(rows * cols, dtype=torch.float32, device="cuda")
+        for _ in range(2):
+            mp8.gemm_fp8(mp8.FWD, rows, cols, kc, a, b, acc=acc2, acc_mode=2, flags=flags, workspace=ws,
+                         tile_config=tile, split_k=split)
+        torch.cuda.synchronize()
+        ok, worst, _ = acc_tolerance_ok(host(acc2).reshape(rows, cols) / 2, ref, absref, kc)
+        assert ok, worst
+
+
 def test_weight_gradient_from_row_major_activations_and_errors(mp8):
     """The weight gradient straight from X8 [M, K] and dY8 [M, N] as the Q node writes them
     equals the one computed from the transposed copies."""
