@@ -787,22 +787,24 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     MP8_BLOCK_STAMP(3);
 }
 
-// Small output, long contraction, both operands contraction-major (the weight gradient read
-// from row-major activations and errors): the contraction is divided among the four WAVES of a
-// workgroup as well.  In the general kernel a 64x64 tile gives each wave one 32x32 MFMA per
-// half stage behind a workgroup barrier, and every stage costs a chain of latencies (load,
-// barrier, LDS read, MFMA) with nothing to overlap them.  Here every wave computes the whole
-// 64x64 tile (four MFMAs per half stage, each fragment used twice) for every fourth stage of
-// the workgroup's slice, from a two-stage ring of its own (2 x 16 KB) that it fills with its
-// own direct loads and waits for with its own counter: no barrier inside the loop, and eight
-// stage loads in flight per CU.  At the end the four FP32 tiles meet in LDS and are added in
-// wave order; each thread then owns sixteen consecutive columns of one row for the epilogue.
-// CONV = 3: the weight gradient of the 3x3 convolution (tap shift per tile row), else 0.
-template <int EPI, int CONV>
+// Small output, long contraction (weight gradients, skinny layers): the contraction is divided
+// among the four WAVES of a workgroup as well.  In the general kernel a 64x64 tile gives each
+// wave one 32x32 MFMA per half stage behind a workgroup barrier, and every stage costs a chain
+// of latencies (load, barrier, LDS read, MFMA) with nothing to overlap them.  Here every wave
+// computes the whole 64x64 tile (four MFMAs per half stage, each fragment used twice) for every
+// fourth stage of the workgroup's slice, from a two-stage ring of its own (2 x 16 KB) that it
+// fills with its own direct loads and waits for with its own counter: no barrier inside the
+// loop, and eight stage loads in flight per CU.  At the end the four FP32 tiles meet in LDS and
+// are added in wave order; each thread then owns sixteen consecutive columns of one row for
+// the epilogue.  Operand layouts and slab images as in the general kernel (ATN / BTN:
+// contraction-major).  CONV = 3: the weight gradient of the 3x3 convolution (tap shift per tile
+// row), else 0.
+template <int EPI, bool ATN, bool BTN, int CONV>
 __global__ __launch_bounds__(256, 1) void gemm_wavek_kernel(const GemmArgs p) {
-    static_assert(CONV == 0 || CONV == 3, "plain or convolution weight gradient");
+    static_assert(CONV == 0 || (CONV == 3 && ATN && BTN), "plain or convolution weight gradient");
+    static_assert(BTN || !ATN, "a alone contraction-major is not built");
     constexpr int BM = 64, BN = 64;
-    constexpr int SLAB = 64 * BK;           // 128 contraction rows of 64 bytes
+    constexpr int SLAB = 64 * BK;           // 64 rows of 128 bytes, or 128 contraction rows of 64
     constexpr int STAGE = 2 * SLAB;         // a, then b
     constexpr int WAVE_LDS = 2 * STAGE;     // ring of two stages per wave
     constexpr int RED_LD = BN + 4;          // floats per row of a tile parked for the reduction
@@ -823,7 +825,7 @@ __global__ __launch_bounds__(256, 1) void gemm_wavek_kernel(const GemmArgs p) {
     // this wave's stages: ks_begin + wave, + 4, + 8, ...
     const int mine = __builtin_amdgcn_readfirstlane(ks_count > wave ? (ks_count - wave + 3) >> 2 : 0);
 
-    const int64_t a_kstep = (int64_t)BK * p.lda, b_kstep = (int64_t)BK * p.ldb;
+    const int64_t a_kstep = ATN ? (int64_t)BK * p.lda : BK, b_kstep = BTN ? (int64_t)BK * p.ldb : BK;
     const uint8_t *a_origin;
     if constexpr (CONV == 3) {
         uint32_t ci0;
@@ -832,18 +834,38 @@ __global__ __launch_bounds__(256, 1) void gemm_wavek_kernel(const GemmArgs p) {
         const int shift = (r - 1) * p.cv.w2 + ((int)tap - 3 * r - 1);
         a_origin = p.a + (int64_t)shift * p.lda + ci0;
     } else {
-        a_origin = p.a + row0;
+        a_origin = ATN ? p.a + row0 : p.a + row0 * p.lda;
     }
+    const uint8_t *b_origin = BTN ? p.b + col0 : p.b + col0 * p.ldb;
     const uint8_t *a_tile = uniform_ptr(a_origin + (int64_t)(ks_begin + wave) * a_kstep);
-    const uint8_t *b_tile = uniform_ptr(p.b + col0 + (int64_t)(ks_begin + wave) * b_kstep);
-    // Direct loads: one covers 16 contraction rows of 64 bytes; lane i lands at (row i/4, slot
-    // i%4) and fetches the chunk that belongs there under the swizzle of the narrow slabs.
-    // Chunks that would start beyond the matrix are clamped to its last 16 rows (never stored).
-    const int lchunk64 = (lane & 3) ^ (((lane >> 4) & 1) << 1);
-    int64_t am = 16 * lchunk64, bm_ = 16 * lchunk64;
-    am = row0 + am + 16 <= p.rows ? am : p.rows - 16 - row0;
-    bm_ = col0 + bm_ + 16 <= p.cols ? bm_ : p.cols - 16 - col0;
-    const uint32_t oa = (uint32_t)((lane >> 2) * p.lda + am), ob = (uint32_t)((lane >> 2) * p.ldb + bm_);
+    const uint8_t *b_tile = uniform_ptr(b_origin + (int64_t)(ks_begin + wave) * b_kstep);
+    // Direct loads, eight per operand and stage.  Row-major operand: load q brings tile rows
+    // 8q .. 8q+7, lane i lands at (row i/8, slot i%8) and fetches chunk (i%8) ^ ((row >> 1) & 7);
+    // rows beyond the matrix are clamped to its last row.  Contraction-major operand: load q
+    // brings contraction rows 16q .. 16q+15 of 64 bytes, lane i lands at (row i/4, slot i%4) and
+    // fetches the chunk that belongs there under the swizzle of the narrow slabs; chunks that
+    // would start beyond the matrix are clamped to its last 16 rows.  (Clamped data is never
+    // stored.)
+    auto lane_offsets = [&](bool km, int64_t first, int64_t limit, int64_t ld, uint32_t off[8]) {
+        if (km) {
+            const int chunk = (lane & 3) ^ (((lane >> 4) & 1) << 1);
+            int64_t m = 16 * chunk;
+            m = first + m + 16 <= limit ? m : limit - 16 - first;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) off[q] = (uint32_t)((16 * q + (lane >> 2)) * ld + m);
+        } else {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                int64_t r = 8 * q + (lane >> 3);
+                const int chunk = (lane & 7) ^ ((r >> 1) & 7);
+                r = first + r < limit ? r : limit - 1 - first;
+                off[q] = (uint32_t)(r * ld) + chunk * 16;
+            }
+        }
+    };
+    uint32_t oa[8], ob[8];
+    lane_offsets(ATN, row0, p.rows, p.lda, oa);
+    lane_offsets(BTN, col0, p.cols, p.ldb, ob);
     uint8_t *ring = lds + wave * WAVE_LDS;
     const uint32_t ring0 = lds_address(ring);
     auto issue = [&](int j) {  // stage j of this wave into buffer j % 2: 16 loads
@@ -851,9 +873,9 @@ __global__ __launch_bounds__(256, 1) void gemm_wavek_kernel(const GemmArgs p) {
         const uint8_t *bk = b_tile + (int64_t)(4 * j) * b_kstep;
         const uint32_t sa = ring0 + (j & 1) * STAGE;
 #pragma unroll
-        for (int q = 0; q < 8; ++q) dma16(ak + (int64_t)(16 * q) * p.lda, oa, sa + q * 1024);
+        for (int q = 0; q < 8; ++q) dma16(ak, oa[q], sa + q * 1024);
 #pragma unroll
-        for (int q = 0; q < 8; ++q) dma16(bk + (int64_t)(16 * q) * p.ldb, ob, sa + SLAB + q * 1024);
+        for (int q = 0; q < 8; ++q) dma16(bk, ob[q], sa + SLAB + q * 1024);
     };
 
     f32x16 acc[2][2];
@@ -864,20 +886,32 @@ __global__ __launch_bounds__(256, 1) void gemm_wavek_kernel(const GemmArgs p) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
     const int frow = lane & 31, fkb = lane >> 5, t16 = lane & 15;
-    // fragment f (0, 1: a tile rows 32f ..; 2, 3: b) of half stage `sub` from buffer `s`: four
-    // transposing reads of eight contraction indices each (see the general kernel)
+    // fragment f (0, 1: a tile rows 32f ..; 2, 3: b) of half stage `sub` from buffer `s`: lane l
+    // supplies tile row 32f + l%32 and contraction indices 64*sub + 32*(l/32) .. +31 -- two
+    // 16-byte reads of a row-major slab, four transposing reads of eight contraction indices
+    // each of a contraction-major one (see the general kernel)
     auto fragment = [&](const uint8_t *s, int sub, int f) -> i32x8 {
-        const int m = (f & 1) * 32 + (frow & 16);
-        const int mc = m >> 4;
-        i32x2 part[4];
+        const uint8_t *slab = s + (f >> 1) * SLAB;
+        if ((f < 2 && ATN) || (f >= 2 && BTN)) {
+            const int m = (f & 1) * 32 + (frow & 16);
+            const int mc = m >> 4;
+            i32x2 part[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int k = 64 * sub + 32 * fkb + 8 * e + (t16 >> 1);
-            const int off = (f >> 1) * SLAB + k * 64 + ((mc ^ (((k >> 2) & 1) << 1)) << 4) + 8 * (t16 & 1);
-            part[e] = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
-                (__attribute__((address_space(3))) i32x2 *)(s + off));
+            for (int e = 0; e < 4; ++e) {
+                const int k = 64 * sub + 32 * fkb + 8 * e + (t16 >> 1);
+                const int off = k * 64 + ((mc ^ (((k >> 2) & 1) << 1)) << 4) + 8 * (t16 & 1);
+                part[e] = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
+                    (__attribute__((address_space(3))) i32x2 *)(slab + off));
+            }
+            return i32x8{part[0].x, part[0].y, part[1].x, part[1].y, part[2].x, part[2].y, part[3].x, part[3].y};
+        } else {
+            const int row = (f & 1) * 32 + frow;
+            const uint8_t *rp = slab + row * BK;
+            const int sw = (row >> 1) & 7;
+            const i32x4 h0 = *reinterpret_cast<const i32x4 *>(rp + (((4 * sub + 2 * fkb) ^ sw) << 4));
+            const i32x4 h1 = *reinterpret_cast<const i32x4 *>(rp + (((4 * sub + 2 * fkb + 1) ^ sw) << 4));
+            return __builtin_shufflevector(h0, h1, 0, 1, 2, 3, 4, 5, 6, 7);
         }
-        return i32x8{part[0].x, part[0].y, part[1].x, part[1].y, part[2].x, part[2].y, part[3].x, part[3].y};
     };
 
     // (Issuing the fragment reads of a half stage ahead of the MFMAs of the one before it, as
@@ -1254,12 +1288,13 @@ struct TileConfig {
      {gemm_shortk_kernel<EPI_PARTIAL>, gemm_shortk_kernel<EPI_RNE>, gemm_shortk_kernel<EPI_FULL>}, \
      {nullptr, nullptr, nullptr}, {nullptr, nullptr, nullptr},                \
      {{nullptr, nullptr, nullptr}, {nullptr, nullptr, nullptr}, {nullptr, nullptr, nullptr}}, 2, 32768}
+#define MP8_WAVEK(ATN, BTN, CONV)                                            \
+    {gemm_wavek_kernel<EPI_PARTIAL, ATN, BTN, CONV>, gemm_wavek_kernel<EPI_RNE, ATN, BTN, CONV>, \
+     gemm_wavek_kernel<EPI_FULL, ATN, BTN, CONV>}
 #define MP8_TILE_WAVEK                                                       \
-    {64, 64, "64x64x128w", {nullptr, nullptr, nullptr},                        \
-     {gemm_wavek_kernel<EPI_PARTIAL, 0>, gemm_wavek_kernel<EPI_RNE, 0>, gemm_wavek_kernel<EPI_FULL, 0>}, \
-     {nullptr, nullptr, nullptr},                                              \
-     {{nullptr, nullptr, nullptr}, {nullptr, nullptr, nullptr},                \
-      {gemm_wavek_kernel<EPI_PARTIAL, 3>, gemm_wavek_kernel<EPI_RNE, 3>, gemm_wavek_kernel<EPI_FULL, 3>}}, 0, 0}
+    {64, 64, "64x64x128w", MP8_WAVEK(false, false, 0), MP8_WAVEK(true, true, 0),  \
+     MP8_WAVEK(false, true, 0),                                                \
+     {{nullptr, nullptr, nullptr}, {nullptr, nullptr, nullptr}, MP8_WAVEK(true, true, 3)}, 0, 0}
 static const TileConfig kTiles[] = {
     MP8_TILE_TN(256, 256, 2, 2, 2, 1), MP8_TILE(256, 128, 2, 2, 3, 1), MP8_TILE(128, 256, 2, 2, 3, 1),
     MP8_TILE_TN(128, 128, 2, 2, 2, 2), MP8_TILE_TN(128, 128, 2, 2, 4, 1), MP8_TILE(64, 128, 1, 4, 3, 2),
@@ -1325,7 +1360,7 @@ static Plan make_plan(int64_t rows, int64_t cols, int64_t kc, int tile_config, i
         const double fill256 = (double)n256 / (double)(((n256 + kCUs - 1) / kCUs) * kCUs);
         const int64_t n64 = count(T64x64s2);
         if (n256 >= 208 && fill256 >= 0.8 && ksteps >= 8) t = T256x256;
-        else if (layout == 3 && n64 <= kCUs && ksteps >= 16) t = T64x64w;  // one workgroup per CU
+        else if (n64 <= kCUs && ksteps >= 16) t = T64x64w;  // one workgroup per CU, one round
         else if (tn && (n128 < 16 || (n128 < 192 && ksteps <= 64))) t = T64x64s2;
         else if (tn) t = ksteps >= 64 ? T128x128s4 : T128x128s2;
         else if (n128 >= 192 && ksteps <= 2) t = T128x128k;  // all prologue and epilogue
@@ -1341,9 +1376,11 @@ static Plan make_plan(int64_t rows, int64_t cols, int64_t kc, int tile_config, i
         s = 1;  // these kernels take the whole contraction at once
     } else if (split_k == 0 && t == T64x64w) {
         // one workgroup per CU and never more workgroups than CUs (a second round would double
-        // the time); at least two stages for each of the four waves
+        // the time); at least two stages for each of the four waves.  A split costs the finishing
+        // pass (about 4 us, the time of some 32 stages of one wave), so it must save more than that.
         s = (int)std::max<int64_t>(1, std::min<int64_t>(kCUs / nt, ksteps / 8));
         s = std::min(s, kMaxSplits);
+        if ((int64_t)ksteps * (s - 1) <= (int64_t)40 * s) s = 1;
     } else if (split_k > 0) {
         s = split_k;
     } else if (nt < kCUs / 2) {
