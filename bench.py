@@ -58,6 +58,8 @@ def parse_args():
     ap.add_argument("--launch", choices=("graph", "eager"), default="graph",
                     help="how the timed steps are launched: replay of a captured HIP graph "
                          "(default) or one Python call per kernel")
+    ap.add_argument("--batch-quantize", action="store_true",
+                    help="run the two Q nodes of the step as one mp8_quantize_e5m2_batch launch")
     ap.add_argument("--kernel-reps", type=int, default=50,
                     help="back-to-back launches per graph in the per-kernel timing")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -99,7 +101,7 @@ class StatsRing:
 class Workload:
     """Device buffers and launch closures for the configs[1] layer."""
 
-    def __init__(self, mp8, torch, lay):
+    def __init__(self, mp8, torch, lay, batch_quantize=False):
         self.mp8, self.torch = mp8, torch
         M, N, K = lay.M, lay.N, lay.K
         self.M, self.N, self.K = M, N, K
@@ -139,6 +141,12 @@ class Workload:
              M * K + M * N + K * N, 2 * M * N * K, "mfma"),
             ("sgd_update", self._update, 6 * K * N, 0, "hbm"),
         ]
+        if batch_quantize:
+            # both Q nodes of the step in one launch (measured: no faster inside the step)
+            self.kernels[:2] = [("quantize_X_dY", lambda: mp8_.quantize_e5m2_batch([
+                dict(src=self.X, dst=self.X8),
+                dict(src=self.dY, dst=self.E8, scale=LOSS_SCALE, stats=self.stats)]),
+                5 * M * K + 5 * M * N, 0, "hbm")]
         # the weights of the first step: Q(W16), outside the timed region
         mp8_.quantize_e5m2(self.W16.view(K, N), self.W8)
 
@@ -376,6 +384,16 @@ def all_configs_report(mp8, torch):
                                                                  seed=1, offset=3), 5)
         rows.append({"kernel": "sgd_update_fp16_sr", "case": f"2^28 elements, {rn}", "us": us,
                      "alg_gbs": 5.0 * n / us / 1e3, "frac_hbm_peak": 5.0 * n / us / 1e3 / HBM_PEAK_GBS})
+    # many small tensors (the weights of eight layers of configs[1]): eight launches or one
+    small = [torch.empty(1152 * 128, dtype=torch.float32, device=dev).normal_(0, 0.04) for _ in range(8)]
+    small8 = [torch.empty(1152 * 128, dtype=torch.uint8, device=dev) for _ in range(8)]
+    us = graph_time_us(torch, lambda: [mp8.quantize_e5m2(x.view(1, -1), y) for x, y in zip(small, small8)], 5)
+    rows.append({"kernel": "quantize_e5m2", "case": "8 tensors of 147456 elements, 8 launches", "us": us,
+                 "alg_gbs": 5.0 * 8 * 147456 / us / 1e3, "frac_hbm_peak": 5.0 * 8 * 147456 / us / 1e3 / HBM_PEAK_GBS})
+    us = graph_time_us(torch, lambda: mp8.quantize_e5m2_batch([dict(src=x, dst=y) for x, y in zip(small, small8)]), 5)
+    rows.append({"kernel": "quantize_e5m2_batch", "case": "8 tensors of 147456 elements, 1 launch", "us": us,
+                 "alg_gbs": 5.0 * 8 * 147456 / us / 1e3, "frac_hbm_peak": 5.0 * 8 * 147456 / us / 1e3 / HBM_PEAK_GBS})
+    del small, small8
     # optimizers with FP32 state: 13 (momentum) and 21 (ADAM) bytes per element
     nm = 1 << 27
     st0 = torch.zeros(nm, dtype=torch.float32, device=dev)
@@ -470,7 +488,7 @@ def main():
 
     props = torch.cuda.get_device_properties(0)
     lay = workloads.config2()
-    wl = Workload(mp8, torch, lay)
+    wl = Workload(mp8, torch, lay, batch_quantize=args.batch_quantize)
     for _ in range(args.warmup):
         wl.step()
     ms_per_step = time_steps(torch, wl, args.steps, args.launch)

@@ -82,6 +82,30 @@ mp8_status mp8_quantize_e5m2(const void *src, int src_is_f16, uint8_t *dst, uint
                              void *stream);
 
 /*
+ * Several Q nodes in one launch: a training step quantises its activations and its errors (and
+ * whatever else is due) at the same point of the flow of Figure 1a, and short tensors cost
+ * little more than their bytes when they run beside a long one.  Item i gives exactly the
+ * result of
+ *     mp8_quantize_e5m2(src, src_is_f16, dst, NULL, 1, n, scale, round, flags, seed, offset, stats)
+ * (flat tensors, no transposed copy; SR uses the element index).  `items` is a host array, read
+ * before the call returns; count <= MP8_QUANTIZE_BATCH_MAX.  Items must not overlap each other's
+ * outputs; items may share one mp8_stats.  On error nothing is enqueued.
+ */
+#define MP8_QUANTIZE_BATCH_MAX 8
+typedef struct {
+    const void *src;  /* device, FP32 or IEEE half, 16-byte aligned */
+    int src_is_f16;
+    uint8_t *dst;     /* device, 16-byte aligned */
+    int64_t n;        /* elements; 0 is valid */
+    float scale;
+    mp8_round round;
+    int flags;        /* MP8_FLAG_SATURATE or 0 */
+    uint64_t seed, offset;
+    mp8_stats *stats; /* nullable, device */
+} mp8_quantize_item;
+mp8_status mp8_quantize_e5m2_batch(const mp8_quantize_item *items, int count, void *stream);
+
+/*
  * The FP8 compute primitive of Section 3: two 8-bit operands, FP32 accumulation, and the
  * result rounded once to 8 bits in the epilogue (the Q node after each GEMM in Figure 1a).
  *

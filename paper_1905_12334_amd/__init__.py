@@ -28,6 +28,7 @@ EXPORTS = [
     "mp8_scaler_init", "mp8_scaler_update", "mp8_scaler_set_floor", "mp8_status_string",
     "mp8_conv3x3_fp8", "mp8_conv3x3_fp8_workspace_bytes", "mp8_sgd_momentum_fp16_sr",
     "mp8_gemm_fp8_plan", "mp8_gemm_tile_config_lds_bytes", "mp8_adam_fp16_sr",
+    "mp8_quantize_e5m2_batch",
 ]
 
 
@@ -78,6 +79,8 @@ def lib() -> C.CDLL:
     L.mp8_sgd_update_fp16_sr.argtypes = [vp, vp, i64, f32, f32, ci, u64, u64, vp, vp, vp, vp]
     L.mp8_sgd_momentum_fp16_sr.restype = ci
     L.mp8_sgd_momentum_fp16_sr.argtypes = [vp, vp, vp, i64, f32, f32, f32, f32, ci, u64, u64, vp, vp, vp, vp]
+    L.mp8_quantize_e5m2_batch.restype = ci
+    L.mp8_quantize_e5m2_batch.argtypes = [vp, ci, vp]
     L.mp8_adam_fp16_sr.restype = ci
     L.mp8_adam_fp16_sr.argtypes = [vp, vp, vp, vp, i64, f32, f32, f32, f32, f32, f32, i64, ci, u64, u64,
                                    vp, vp, vp, vp]
@@ -157,6 +160,35 @@ def quantize_e5m2(src, dst, dst_t=None, scale=1.0, round=RNE, flags=0, seed=0, o
                                  _ptr(stats), _stream())
     _check(st, "mp8_quantize_e5m2")
     return dst
+
+
+QUANTIZE_BATCH_MAX = 8
+
+
+class _QuantizeItem(C.Structure):
+    _fields_ = [("src", C.c_void_p), ("src_is_f16", C.c_int), ("dst", C.c_void_p), ("n", C.c_int64),
+                ("scale", C.c_float), ("round", C.c_int), ("flags", C.c_int), ("seed", C.c_uint64),
+                ("offset", C.c_uint64), ("stats", C.c_void_p)]
+
+
+def quantize_e5m2_batch(items):
+    """mp8_quantize_e5m2_batch: several flat Q nodes in one launch.  `items` is a sequence of
+    dicts with keys src, dst and optionally scale, round, flags, seed, offset, stats (as the
+    arguments of quantize_e5m2; tensors of any shape are taken flat, no transposed copy)."""
+    import torch
+    arr = (_QuantizeItem * max(len(items), 1))()
+    for i, it in enumerate(items):
+        src, dst = it["src"], it["dst"]
+        _dev(src, "src", (torch.float32, torch.float16))
+        _dev(dst, "dst", torch.uint8)
+        if dst.numel() != src.numel():
+            raise Mp8Error("dst size does not match src")
+        stats = it.get("stats")
+        arr[i] = _QuantizeItem(src.data_ptr(), int(src.dtype == torch.float16), dst.data_ptr(), src.numel(),
+                               float(it.get("scale", 1.0)), it.get("round", RNE), it.get("flags", 0),
+                               it.get("seed", 0), it.get("offset", 0),
+                               None if stats is None else stats.data_ptr())
+    _check(lib().mp8_quantize_e5m2_batch(arr, len(items), _stream()), "mp8_quantize_e5m2_batch")
 
 
 def _op_dims(op, M, N, K):

@@ -13,6 +13,7 @@
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <type_traits>
 
 #include "mp8_device.hpp"
@@ -75,19 +76,18 @@ __device__ __forceinline__ uint32_t round1(float x, float scale, bool sat, const
 constexpr int kFlatUnroll = 4;  // 16-byte loads in flight per thread
 constexpr int kStatsBlocks = 512;  // grid limit of the variants that end in atomics
 
-template <bool kF16, bool kSR, bool kStats>
-__global__ __launch_bounds__(kStats ? 1024 : 256) void quantize_flat_kernel(const void *__restrict__ src,
-                                                            uint8_t *__restrict__ dst, int64_t n,
-                                                            float scale, int sat, uint64_t seed,
-                                                            uint64_t offset, mp8_stats *stats) {
+// The flat loop of one tensor for workgroup `block` of `nblocks` (NT threads each).
+template <bool kF16, bool kSR, bool kStats, int NT>
+__device__ __forceinline__ void flat_body(const void *__restrict__ src, uint8_t *__restrict__ dst,
+                                          int64_t n, float scale, int sat, uint64_t seed,
+                                          uint64_t offset, mp8_stats *stats, int64_t block,
+                                          int64_t nblocks) {
     const Philox rng(seed, offset);
     StatsAcc st;
     const int64_t n4 = n >> 2;  // groups of four elements
     uint32_t *dst4 = reinterpret_cast<uint32_t *>(dst);
-    constexpr int NT = kStats ? 1024 : 256;  // the stats variant runs few, large blocks
-    const int64_t stride = (int64_t)gridDim.x * NT * kFlatUnroll;
-    for (int64_t base = (int64_t)blockIdx.x * NT * kFlatUnroll + threadIdx.x; base < n4;
-         base += stride) {
+    const int64_t stride = nblocks * NT * kFlatUnroll;
+    for (int64_t base = block * NT * kFlatUnroll + threadIdx.x; base < n4; base += stride) {
         float v[kFlatUnroll][4];
 #pragma unroll
         for (int u = 0; u < kFlatUnroll; ++u) {
@@ -104,12 +104,70 @@ __global__ __launch_bounds__(kStats ? 1024 : 256) void quantize_flat_kernel(cons
         }
     }
     // ragged tail (< 4 elements)
-    if (blockIdx.x == 0 && threadIdx.x < 4) {
+    if (block == 0 && threadIdx.x < 4) {
         const int64_t i = (n4 << 2) + threadIdx.x;
         if (i < n)
             dst[i] = (uint8_t)round1<kSR, kStats>(load_src<kF16>(src, i), scale, sat != 0, rng, i, st);
     }
     if constexpr (kStats) st.flush(stats);
+}
+
+template <bool kF16, bool kSR, bool kStats>
+__global__ __launch_bounds__(kStats ? 1024 : 256) void quantize_flat_kernel(const void *__restrict__ src,
+                                                            uint8_t *__restrict__ dst, int64_t n,
+                                                            float scale, int sat, uint64_t seed,
+                                                            uint64_t offset, mp8_stats *stats) {
+    // the stats variant runs few, large blocks
+    flat_body<kF16, kSR, kStats, kStats ? 1024 : 256>(src, dst, n, scale, sat, seed, offset, stats,
+                                                      blockIdx.x, gridDim.x);
+}
+
+// Several tensors in one launch: a step that quantises activations and errors (and whatever
+// else is due) pays one launch, and the short tensors' start-up and tail hide behind the long
+// ones' streaming.  Workgroups [first[k], first[k+1]) belong to tensor k.
+constexpr int kBatchMax = 8;
+struct BatchItem {
+    const void *src;
+    uint8_t *dst;
+    int64_t n;
+    float scale;
+    int f16, sr, sat;
+    uint64_t seed, offset;
+    mp8_stats *stats;
+};
+struct BatchArgs {
+    BatchItem item[kBatchMax];
+    unsigned int first[kBatchMax + 1];
+    int count;
+};
+
+__global__ __launch_bounds__(256) void quantize_batch_kernel(const BatchArgs b) {
+    int k = 0;
+#pragma unroll
+    for (int i = 1; i < kBatchMax; ++i)
+        if (i < b.count && blockIdx.x >= b.first[i]) k = i;
+    k = __builtin_amdgcn_readfirstlane(k);
+    // a copy of the one descriptor in scalar registers (constant indices only)
+    BatchItem it = b.item[0];
+#pragma unroll
+    for (int i = 1; i < kBatchMax; ++i)
+        if (k == i) it = b.item[i];
+    unsigned int lo = b.first[0], hi = b.first[1];
+#pragma unroll
+    for (int i = 1; i < kBatchMax; ++i)
+        if (k == i) { lo = b.first[i]; hi = b.first[i + 1]; }
+    const int64_t block = blockIdx.x - lo, nblocks = hi - lo;
+#define MP8_B(F16, SR, ST) \
+    flat_body<F16, SR, ST, 256>(it.src, it.dst, it.n, it.scale, it.sat, it.seed, it.offset, it.stats, block, nblocks)
+    const bool st = it.stats != nullptr;
+    if (it.f16) {
+        if (it.sr) { if (st) MP8_B(true, true, true); else MP8_B(true, true, false); }
+        else       { if (st) MP8_B(true, false, true); else MP8_B(true, false, false); }
+    } else {
+        if (it.sr) { if (st) MP8_B(false, true, true); else MP8_B(false, true, false); }
+        else       { if (st) MP8_B(false, false, true); else MP8_B(false, false, false); }
+    }
+#undef MP8_B
 }
 
 // Transpose a 4x4 byte block held as four row dwords into four column dwords
@@ -474,6 +532,60 @@ extern "C" mp8_status mp8_quantize_e5m2(const void *src, int src_is_f16, uint8_t
     }
 #undef MP8_Q
     return e == hipSuccess ? MP8_OK : MP8_ERR_HIP;
+}
+
+extern "C" mp8_status mp8_quantize_e5m2_batch(const mp8_quantize_item *items, int count,
+                                              void *stream) {
+    using namespace mp8;
+    if (count < 0 || count > kBatchMax || (count > 0 && !items)) return MP8_ERR_INVALID_ARG;
+    // validate everything first: on error nothing is enqueued
+    for (int i = 0; i < count; ++i) {
+        const mp8_quantize_item &q = items[i];
+        if (q.n < 0 || (q.round != MP8_RNE && q.round != MP8_SR)) return MP8_ERR_INVALID_ARG;
+        if (q.n > 0 && (!q.src || !q.dst)) return MP8_ERR_INVALID_ARG;
+        if (((uintptr_t)q.src | (uintptr_t)q.dst) & 15u) return MP8_ERR_ALIGNMENT;
+    }
+    // Workgroups per tensor: one per 4096 elements (256 threads x 4 loads of 4 elements);
+    // tensors with statistics at most kStatsBlocks, because every workgroup ends in atomics on
+    // the one mp8_stats.  Tensors whose workgroups loop longest go first, so that they run
+    // beside the others instead of after them.
+    int order[kBatchMax];
+    int64_t nblk[kBatchMax], iters[kBatchMax];
+    int m = 0;
+    for (int i = 0; i < count; ++i) {
+        if (items[i].n == 0) continue;
+        const int64_t want = ((items[i].n >> 2) + 256 * kFlatUnroll - 1) / (256 * kFlatUnroll);
+        int64_t nb = std::max<int64_t>(want, 1);
+        nb = std::min<int64_t>(nb, items[i].stats ? kStatsBlocks : (1 << 20));
+        nblk[i] = nb;
+        iters[i] = (want + nb - 1) / nb;
+        order[m++] = i;
+    }
+    if (m == 0) return MP8_OK;
+    std::stable_sort(order, order + m, [&](int x, int y) { return iters[x] > iters[y]; });
+    BatchArgs args{};
+    int64_t total = 0;
+    for (int j = 0; j < m; ++j) {
+        const mp8_quantize_item &q = items[order[j]];
+        BatchItem &it = args.item[j];
+        it.src = q.src;
+        it.dst = q.dst;
+        it.n = q.n;
+        it.scale = q.scale;
+        it.f16 = q.src_is_f16 != 0;
+        it.sr = q.round == MP8_SR;
+        it.sat = (q.flags & MP8_FLAG_SATURATE) ? 1 : 0;
+        it.seed = q.seed;
+        it.offset = q.offset;
+        it.stats = q.stats;
+        args.first[j] = (unsigned int)total;
+        total += nblk[order[j]];
+    }
+    for (int j = m; j <= kBatchMax; ++j) args.first[j] = (unsigned int)total;
+    args.count = m;
+    if (total > 0x7FFFFFFFLL) return MP8_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(quantize_batch_kernel, dim3((unsigned)total), dim3(256), 0, (hipStream_t)stream, args);
+    return hipGetLastError() == hipSuccess ? MP8_OK : MP8_ERR_HIP;
 }
 
 extern "C" mp8_status mp8_sr_bits(uint16_t *out, int64_t n, uint64_t seed, uint64_t offset,

@@ -203,3 +203,53 @@ def test_no_stats_and_empty_and_determinism(mp8):
     assert st[1] == 128
     _, _, st = _run(mp8, big, flags=oracle.FLAG_SATURATE)
     assert st[1] == 0
+
+
+def test_batched_quantize_equals_separate_calls_and_the_oracle(mp8):
+    """Several Q nodes in one launch: FP32 and half sources, RNE and SR, saturation, statistics
+    (two items share one statistics struct), sizes from 1 element to millions with ragged tails,
+    an empty item -- each item bit for bit what the oracle gives for it alone."""
+    import torch
+    rng = np.random.default_rng(91)
+    specs = [  # n, half source, scale, round, flags, seed, offset, statistics slot
+        (3 * 1000 * 1000 + 3, False, 4096.0, oracle.RNE, 0, 0, 0, 0),
+        (1, False, 1.0, oracle.SR, 0, 5, 6, None),
+        (40961, True, 0.5, oracle.SR, oracle.FLAG_SATURATE, 7, 8, 1),
+        (0, False, 1.0, oracle.RNE, 0, 0, 0, None),
+        (8 * 1000 * 1000, False, 1.0, oracle.RNE, 0, 0, 0, None),
+        (123457, False, 3.0e4, oracle.RNE, oracle.FLAG_SATURATE, 0, 0, 1),
+        (77, True, 1.0, oracle.RNE, 0, 0, 0, None),
+        (65536, False, 1e-3, oracle.SR, 0, 9, 10, None),
+    ]
+    stats = [mp8.new_stats(), mp8.new_stats()]
+    ostats = [oracle.Stats(), oracle.Stats()]
+    items, hosts, outs = [], [], []
+    for n, half, scale, rnd, fl, seed, off, slot in specs:
+        x = (rng.standard_normal(n) * np.exp2(rng.integers(-18, 17, n))).astype(np.float16 if half else np.float32)
+        if n > 100:
+            x[5], x[17], x[33] = np.inf, np.nan, -np.inf
+        hosts.append(x)
+        o = torch.full((n + 64,), 0xAA, dtype=torch.uint8, device="cuda")
+        outs.append(o)
+        items.append(dict(src=gpu(x), dst=o[:n], scale=scale, round=rnd, flags=fl, seed=seed, offset=off,
+                          stats=None if slot is None else stats[slot]))
+    mp8.quantize_e5m2_batch(items)
+    torch.cuda.synchronize()
+    for (n, half, scale, rnd, fl, seed, off, slot), x, o in zip(specs, hosts, outs):
+        assert bool((o[n:] == 0xAA).all()), "write past the end of an item"
+        if n == 0:
+            continue
+        want, _ = oracle.quantize_e5m2(x.reshape(1, -1), scale=scale, mode=rnd, flags=fl, seed=seed, offset=off,
+                                       stats=None if slot is None else ostats[slot])
+        assert np.array_equal(host(o[:n]), want.reshape(-1)), (n, half, rnd, fl)
+    for s, os_ in zip(stats, ostats):
+        assert mp8.read_stats(s) == os_.as_tuple()
+    # one item is the plain call; too many items or a bad round are refused before any launch
+    o1 = torch.empty(specs[0][0], dtype=torch.uint8, device="cuda")
+    mp8.quantize_e5m2(gpu(hosts[0]).view(1, -1), o1, scale=specs[0][2])
+    torch.cuda.synchronize()
+    assert torch.equal(o1, outs[0][: specs[0][0]])
+    with pytest.raises(mp8.Mp8Error):
+        mp8.quantize_e5m2_batch(items + [items[0]])
+    with pytest.raises(mp8.Mp8Error):
+        mp8.quantize_e5m2_batch([dict(items[1], round=7)])
