@@ -9,6 +9,7 @@ ResNet-50-style 3x3 convolution layer taken as a GEMM (M=25088, N=128, K=1152):
     backward-data dX8 = Q(E8 . W8^T)            contraction N
     weight-grad   G8  = Q(X8^T . E8)            contraction M (split, summed in FP32, one rounding)
     update        W16 <- half_SR(W16 - lr * G8 / 2^12),  W8 <- Q(W16) for the next step
+                  (applied by the pass that rounds G8: one call, mp8_wgrad_update_fp16_sr)
 
 Every tensor exists once, row-major, as its producer wrote it: the GEMMs read X8 [M,K],
 E8 [M,N] and W8 [K,N] in whichever orientation they need (contraction-major operands go
@@ -47,6 +48,7 @@ LR = 1e-3
 MEASURED_TRAFFIC_BYTES = {
     "quantize_X": 144555344, "quantize_dY": 16141620, "gemm_fwd": 33421826,
     "gemm_bwd_data": 34288717, "gemm_wgrad": 53984201, "sgd_update": 1041803,
+    "gemm_wgrad_update": 53984201 + 1041803,
 }
 
 
@@ -58,6 +60,9 @@ def parse_args():
     ap.add_argument("--launch", choices=("graph", "eager"), default="graph",
                     help="how the timed steps are launched: replay of a captured HIP graph "
                          "(default) or one Python call per kernel")
+    ap.add_argument("--separate-update", action="store_true",
+                    help="weight gradient and master-weight update as two calls (mp8_gemm_fp8, "
+                         "mp8_sgd_update_fp16_sr) instead of one mp8_wgrad_update_fp16_sr")
     ap.add_argument("--batch-quantize", action="store_true",
                     help="run the two Q nodes of the step as one mp8_quantize_e5m2_batch launch")
     ap.add_argument("--kernel-reps", type=int, default=50,
@@ -101,7 +106,7 @@ class StatsRing:
 class Workload:
     """Device buffers and launch closures for the configs[1] layer."""
 
-    def __init__(self, mp8, torch, lay, batch_quantize=False):
+    def __init__(self, mp8, torch, lay, batch_quantize=False, fused_update=False):
         self.mp8, self.torch = mp8, torch
         M, N, K = lay.M, lay.N, lay.K
         self.M, self.N, self.K = M, N, K
@@ -141,6 +146,11 @@ class Workload:
              M * K + M * N + K * N, 2 * M * N * K, "mfma"),
             ("sgd_update", self._update, 6 * K * N, 0, "hbm"),
         ]
+        if fused_update:
+            # Figure 1b in one call: the pass that rounds the weight gradient also updates the
+            # master weights and writes the next step's 8-bit weights
+            self.kernels[-2:] = [("gemm_wgrad_update", self._wgrad_update,
+                                  M * K + M * N + K * N + 6 * K * N, 2 * M * N * K, "mfma")]
         if batch_quantize:
             # both Q nodes of the step in one launch (measured: no faster inside the step)
             self.kernels[:2] = [("quantize_X_dY", lambda: mp8_.quantize_e5m2_batch([
@@ -149,6 +159,14 @@ class Workload:
                 5 * M * K + 5 * M * N, 0, "hbm")]
         # the weights of the first step: Q(W16), outside the timed region
         mp8_.quantize_e5m2(self.W16.view(K, N), self.W8)
+
+    def _wgrad_update(self):
+        self.step_no += 1
+        mp8 = self.mp8
+        mp8.wgrad_update_fp16_sr(self.M, self.N, self.K, self.X8, self.E8, self.W16, LR, 1.0 / LOSS_SCALE,
+                                 g8_out=self.G8, flags=mp8.FLAG_CONTRACTION_MAJOR, w_round=mp8.SR,
+                                 w_seed=0x1905_1233_4000_0002, w_offset=self.step_no,
+                                 skip_if_nonzero=self.stats[1:2], w8_out=self.W8, workspace=self.ws)
 
     def _update(self):
         # every step draws from its own Philox offset; the overflow count of the error tensor
@@ -488,7 +506,7 @@ def main():
 
     props = torch.cuda.get_device_properties(0)
     lay = workloads.config2()
-    wl = Workload(mp8, torch, lay, batch_quantize=args.batch_quantize)
+    wl = Workload(mp8, torch, lay, batch_quantize=args.batch_quantize, fused_update=not args.separate_update)
     for _ in range(args.warmup):
         wl.step()
     ms_per_step = time_steps(torch, wl, args.steps, args.launch)

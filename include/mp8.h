@@ -253,6 +253,28 @@ mp8_status mp8_adam_fp16_sr(uint16_t *w16, float *m, float *v, const uint8_t *g8
                             uint64_t offset, const uint32_t *skip_if_nonzero, uint8_t *w8_out,
                             mp8_stats *stats, void *stream);
 
+/*
+ * Figure 1b from the weight-gradient GEMM to the next step's weights in one call: the weight
+ * gradient is accumulated in FP32 and rounded once to 8 bits (as mp8_gemm_fp8 with MP8_WGRAD:
+ * a, lda, b, ldb, alpha, flags incl. the contraction-major ones, g_round / g_seed / g_offset for
+ * that rounding, stats), and the finishing pass that rounds it also applies
+ * mp8_sgd_update_fp16_sr to the master weights w16 [K, N] with the codes it has just produced
+ * (lr, inv_loss_scale, w_round / w_seed / w_offset, skip_if_nonzero, w8_out as there).  The
+ * results are bit for bit those of the two separate calls.
+ *   g8_out     nullable [K, N]: the 8-bit weight gradient, if the caller wants to keep it
+ *   workspace  at least mp8_gemm_fp8_workspace_bytes(MP8_WGRAD, M, N, K) bytes, always needed
+ *              when that is non-zero
+ * Shapes that only the any-shape GEMM kernel takes run as the two separate launches and need
+ * g8_out (MP8_ERR_UNSUPPORTED without it).
+ */
+mp8_status mp8_wgrad_update_fp16_sr(int64_t M, int64_t N, int64_t K, const uint8_t *a, int64_t lda,
+                                    const uint8_t *b, int64_t ldb, float alpha, uint8_t *g8_out,
+                                    mp8_round g_round, int flags, uint64_t g_seed, uint64_t g_offset,
+                                    mp8_stats *stats, uint16_t *w16, float lr, float inv_loss_scale,
+                                    mp8_round w_round, uint64_t w_seed, uint64_t w_offset,
+                                    const uint32_t *skip_if_nonzero, uint8_t *w8_out, void *workspace,
+                                    size_t workspace_bytes, void *stream);
+
 /* out[i] = the 16 random bits element i would use (device array of n uint16), for tests. */
 mp8_status mp8_sr_bits(uint16_t *out, int64_t n, uint64_t seed, uint64_t offset, void *stream);
 

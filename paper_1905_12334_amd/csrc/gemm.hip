@@ -87,6 +87,7 @@ struct Epilogue {
     int sat;
     uint64_t seed, offset;
     mp8_stats *stats;
+    int want_codes;  // the caller consumes the returned codes even if nothing is stored
     int64_t rows, cols;
     // Convolution outputs live on the zero-padded pixel grid (rows = padded pixels): rows that
     // are padding receive zero codes and stay out of the statistics.  mask = 0: no masking.
@@ -136,18 +137,18 @@ struct GemmArgs {
 
 // One output element, any shape: optional FP32 accumulate / store, one rounding to 8 bits,
 // optional transposed copy, statistics.  Only the finishing kernels use it (ragged shapes).
-__device__ __forceinline__ void finish1(const Epilogue &ep, int64_t r, int64_t c, float v,
-                                        StatsAcc &st) {
+__device__ __forceinline__ uint32_t finish1(const Epilogue &ep, int64_t r, int64_t c, float v,
+                                            StatsAcc &st) {
     const int64_t i = r * ep.cols + c;
     if (ep.acc_mode != 0) {
         if (ep.acc_mode == 2) v += ep.acc[i];
         ep.acc[i] = v;
     }
-    if (ep.out8 == nullptr && ep.out8_t == nullptr && ep.stats == nullptr) return;
+    if (ep.out8 == nullptr && ep.out8_t == nullptr && ep.stats == nullptr && !ep.want_codes) return 0;
     if (ep.mask && conv_padding_row(ep, r)) {
         if (ep.out8 != nullptr) ep.out8[i] = 0;
         if (ep.out8_t != nullptr) ep.out8_t[c * ep.rows + r] = 0;
-        return;
+        return 0;
     }
     const float y = v * ep.alpha;
     uint32_t code;
@@ -161,6 +162,7 @@ __device__ __forceinline__ void finish1(const Epilogue &ep, int64_t r, int64_t c
     if (ep.stats != nullptr) st.add1(y, code);
     if (ep.out8 != nullptr) ep.out8[i] = (uint8_t)code;
     if (ep.out8_t != nullptr) ep.out8_t[c * ep.rows + r] = (uint8_t)code;
+    return code;
 }
 
 // Finish sixteen consecutive columns c .. c+15 (c % 16 == 0) of output row r of an output
@@ -1140,8 +1142,8 @@ __global__ __launch_bounds__(256, EPI == EPI_FULL ? 4 : 5) void gemm_shortk_kern
 }
 
 // Finish four consecutive columns c .. c+3 (c % 4 == 0, row length a multiple of 4).
-__device__ __forceinline__ void finish4(const Epilogue &ep, int64_t r, int64_t c, float v[4],
-                                        StatsAcc &st) {
+__device__ __forceinline__ uint32_t finish4(const Epilogue &ep, int64_t r, int64_t c, float v[4],
+                                            StatsAcc &st) {
     const int64_t i0 = r * ep.cols + c;
     if (ep.acc_mode != 0) {
         f32x4 *p = reinterpret_cast<f32x4 *>(ep.acc + i0);
@@ -1152,7 +1154,7 @@ __device__ __forceinline__ void finish4(const Epilogue &ep, int64_t r, int64_t c
         f32x4 n = {v[0], v[1], v[2], v[3]};
         *p = n;
     }
-    if (ep.out8 == nullptr && ep.out8_t == nullptr && ep.stats == nullptr) return;
+    if (ep.out8 == nullptr && ep.out8_t == nullptr && ep.stats == nullptr && !ep.want_codes) return 0;
     uint32_t r01 = 0, r23 = 0;
     if (ep.sr) {
         // elements i0..i0+3 are halfwords (i0 % 8) .. +3 of Philox block i0 / 8
@@ -1173,14 +1175,66 @@ __device__ __forceinline__ void finish4(const Epilogue &ep, int64_t r, int64_t c
         t[2 * ep.rows] = (uint8_t)(pk >> 16);
         t[3 * ep.rows] = (uint8_t)(pk >> 24);
     }
+    return pk;
+}
+
+// Optional second half of Figure 1b in the finishing pass: the 8-bit weight gradient that was
+// just rounded is un-scaled and applied to the half-precision master weights, exactly as
+// mp8_sgd_update_fp16_sr would do it from memory (same arithmetic, same random stream: element
+// i uses halfword i % 8 of block i / 8 of the update's own Philox stream).  w16 == nullptr:
+// no update.
+struct UpdateHook {
+    uint16_t *w16;
+    uint8_t *w8_out;
+    const uint32_t *skip;
+    float neg_lr, inv_scale;
+    int sr;
+    uint64_t seed, offset;
+};
+
+__device__ __forceinline__ void update_element(const UpdateHook &u, int64_t i, uint32_t code, uint32_t r16) {
+    const uint32_t h = u.sr ? update_one<true>(u.w16[i], code, u.neg_lr, u.inv_scale, r16)
+                            : update_one<false>(u.w16[i], code, u.neg_lr, u.inv_scale, 0u);
+    u.w16[i] = (uint16_t)h;
+    if (u.w8_out != nullptr) u.w8_out[i] = (uint8_t)e5m2_of_half(h);
+}
+
+// Elements i0 .. i0+3 (i0 % 4 == 0) from their four packed gradient codes.
+__device__ __forceinline__ void update4(const UpdateHook &u, int64_t i0, uint32_t pk) {
+    uint32_t r01 = 0, r23 = 0;
+    if (u.sr) {
+        const Philox rng(u.seed, u.offset);
+        const uint4 w = rng.block((uint64_t)i0 >> 3);
+        r01 = (i0 & 4) ? w.z : w.x;
+        r23 = (i0 & 4) ? w.w : w.y;
+    }
+    u32x2 *wp = reinterpret_cast<u32x2 *>(u.w16 + i0);
+    const u32x2 wr = *wp;
+    uint32_t h[4];
+    const uint32_t w16v[4] = {wr.x & 0xFFFFu, wr.x >> 16, wr.y & 0xFFFFu, wr.y >> 16};
+    const uint32_t r16[4] = {r01 & 0xFFFFu, r01 >> 16, r23 & 0xFFFFu, r23 >> 16};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t code = (pk >> (8 * j)) & 0xFFu;
+        h[j] = u.sr ? update_one<true>(w16v[j], code, u.neg_lr, u.inv_scale, r16[j])
+                    : update_one<false>(w16v[j], code, u.neg_lr, u.inv_scale, 0u);
+    }
+    const u32x2 o = {h[0] | (h[1] << 16), h[2] | (h[3] << 16)};
+    *wp = o;
+    if (u.w8_out != nullptr)
+        *reinterpret_cast<uint32_t *>(u.w8_out + i0) =
+            e5m2_of_half(h[0]) | (e5m2_of_half(h[1]) << 8) | (e5m2_of_half(h[2]) << 16) | (e5m2_of_half(h[3]) << 24);
 }
 
 // Sum the FP32 tiles of the contraction slices in slice order and finish: the complete sum is
 // rounded once.  One thread per four columns (per element when the row length is not a
 // multiple of four).
 __global__ __launch_bounds__(256) void splitk_finish_kernel(const float *__restrict__ partial,
-                                                            int splits, const Epilogue ep) {
+                                                            int splits, const Epilogue ep,
+                                                            const UpdateHook upd) {
     StatsAcc st;
+    // an overflowed step leaves the master weights alone (the gradient codes are still written)
+    const bool updating = upd.w16 != nullptr && !(upd.skip != nullptr && *upd.skip != 0u);
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const int64_t slice = ep.rows * ep.cols;
     if ((ep.cols & 3) == 0) {
@@ -1204,14 +1258,23 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const float *__restr
                 f32x4 x = *reinterpret_cast<const f32x4 *>(partial + (int64_t)s * slice + i0);
                 v[0] += x.x; v[1] += x.y; v[2] += x.z; v[3] += x.w;
             }
-            finish4(ep, r, c, v, st);
+            const uint32_t pk = finish4(ep, r, c, v, st);
+            if (updating) update4(upd, i0, pk);
         }
     } else {
         for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < slice; i += stride) {
             float v = 0.f;
             for (int s = 0; s < splits; ++s) v += partial[(int64_t)s * slice + i];
             const int64_t r = i / ep.cols;
-            finish1(ep, r, i - r * ep.cols, v, st);
+            const uint32_t code = finish1(ep, r, i - r * ep.cols, v, st);
+            if (updating) {
+                uint32_t r16 = 0;
+                if (upd.sr) {
+                    const Philox rng(upd.seed, upd.offset);
+                    r16 = philox_half(rng.block((uint64_t)i >> 3), (int)(i & 7));
+                }
+                update_element(upd, i, code, r16);
+            }
         }
     }
     if (ep.stats != nullptr) st.flush(ep.stats);
@@ -1466,15 +1529,17 @@ namespace mp8 {
 // epilogue fields are filled in here.
 static mp8_status launch_mfma(GemmArgs ga, const Epilogue &ep, const Plan &pl, int64_t kc,
                               void (*const pick[3])(const GemmArgs), void *workspace,
-                              size_t workspace_bytes, hipStream_t s) {
+                              size_t workspace_bytes, hipStream_t s, const UpdateHook *upd = nullptr) {
     const int64_t rows = ep.rows, cols = ep.cols;
     const int acc_mode = ep.acc_mode;
     float *acc = ep.acc;
     uint8_t *out8 = ep.out8, *out8_t = ep.out8_t;
-    // Fused epilogue or two passes?
-    const bool two_pass = pl.splits > 1 || (cols & 15) != 0 || acc_mode != 0 || out8_t != nullptr;
+    // Fused epilogue or two passes?  (The master-weight update lives in the finishing pass.)
+    const bool two_pass = pl.splits > 1 || (cols & 15) != 0 || acc_mode != 0 || out8_t != nullptr ||
+                          upd != nullptr;
     float *partial = nullptr;
     Epilogue fin = ep;  // what the finishing kernel applies
+    fin.want_codes = upd != nullptr;
     if (two_pass) {
         if (pl.splits == 1 && acc_mode == 1) {
             partial = acc;  // the tile goes straight into acc; the finishing kernel reads it there
@@ -1511,12 +1576,12 @@ static mp8_status launch_mfma(GemmArgs ga, const Epilogue &ep, const Plan &pl, i
     if (hipGetLastError() != hipSuccess) return MP8_ERR_HIP;
     if (two_pass) {
         const bool only_acc = fin.acc_mode == 0 && fin.out8 == nullptr && fin.out8_t == nullptr &&
-                              fin.stats == nullptr;
+                              fin.stats == nullptr && upd == nullptr;
         if (!only_acc) {
             const int64_t items = (cols & 3) == 0 ? rows * cols / 4 : rows * cols;
             int64_t blocks = std::min<int64_t>((items + 255) / 256, 256 * 16);
             hipLaunchKernelGGL(splitk_finish_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
-                               (const float *)partial, pl.splits, fin);
+                               (const float *)partial, pl.splits, fin, upd ? *upd : UpdateHook{});
             if (hipGetLastError() != hipSuccess) return MP8_ERR_HIP;
         }
     }
@@ -1525,15 +1590,15 @@ static mp8_status launch_mfma(GemmArgs ga, const Epilogue &ep, const Plan &pl, i
 
 }  // namespace mp8
 
-extern "C" mp8_status mp8_gemm_fp8_tuned(mp8_op op, int64_t M, int64_t N, int64_t K,
-                                         const uint8_t *a, int64_t lda, const uint8_t *b,
-                                         int64_t ldb, float alpha, float *acc, int acc_mode,
-                                         uint8_t *out8, uint8_t *out8_t, mp8_round round,
-                                         int flags, uint64_t seed, uint64_t offset,
-                                         mp8_stats *stats, void *workspace,
-                                         size_t workspace_bytes, void *stream, int tile_config,
-                                         int split_k) {
-    using namespace mp8;
+namespace mp8 {
+
+// mp8_gemm_fp8_tuned, optionally with the master-weight update applied to the rounded result
+// (`upd`; only kernels with a finishing pass carry it: MP8_ERR_UNSUPPORTED otherwise).
+static mp8_status gemm_impl(mp8_op op, int64_t M, int64_t N, int64_t K, const uint8_t *a, int64_t lda,
+                            const uint8_t *b, int64_t ldb, float alpha, float *acc, int acc_mode,
+                            uint8_t *out8, uint8_t *out8_t, mp8_round round, int flags, uint64_t seed,
+                            uint64_t offset, mp8_stats *stats, void *workspace, size_t workspace_bytes,
+                            void *stream, int tile_config, int split_k, const UpdateHook *upd) {
     if ((int)op < 0 || (int)op > 2) return MP8_ERR_INVALID_ARG;
     if (M < 0 || N < 0 || K < 0) return MP8_ERR_INVALID_ARG;
     if (round != MP8_RNE && round != MP8_SR) return MP8_ERR_INVALID_ARG;
@@ -1579,6 +1644,7 @@ extern "C" mp8_status mp8_gemm_fp8_tuned(mp8_op op, int64_t M, int64_t N, int64_
     if (tile_config > 0 && !pl.mfma) return MP8_ERR_UNSUPPORTED;
 
     if (!pl.mfma || kc == 0) {
+        if (upd != nullptr) return MP8_ERR_UNSUPPORTED;
         int64_t blocks = std::min<int64_t>((rows * cols + 255) / 256, 1 << 20);
         hipLaunchKernelGGL(gemm_generic_kernel, dim3((unsigned)blocks), dim3(256), 0, s, a, lda, b,
                            ldb, kc, (atn ? 1 : 0) | (btn ? 2 : 0), ep);
@@ -1592,7 +1658,58 @@ extern "C" mp8_status mp8_gemm_fp8_tuned(mp8_op op, int64_t M, int64_t N, int64_
     ga.ldb = ldb;
     const TileConfig &tc = kTiles[pl.tile];
     return launch_mfma(ga, ep, pl, kc, atn ? tc.kernel_tn : btn ? tc.kernel_bt : tc.kernel, workspace,
-                       workspace_bytes, s);
+                       workspace_bytes, s, upd);
+}
+
+}  // namespace mp8
+
+extern "C" mp8_status mp8_gemm_fp8_tuned(mp8_op op, int64_t M, int64_t N, int64_t K,
+                                         const uint8_t *a, int64_t lda, const uint8_t *b,
+                                         int64_t ldb, float alpha, float *acc, int acc_mode,
+                                         uint8_t *out8, uint8_t *out8_t, mp8_round round,
+                                         int flags, uint64_t seed, uint64_t offset,
+                                         mp8_stats *stats, void *workspace,
+                                         size_t workspace_bytes, void *stream, int tile_config,
+                                         int split_k) {
+    return mp8::gemm_impl(op, M, N, K, a, lda, b, ldb, alpha, acc, acc_mode, out8, out8_t, round, flags,
+                          seed, offset, stats, workspace, workspace_bytes, stream, tile_config, split_k,
+                          nullptr);
+}
+
+extern "C" mp8_status mp8_wgrad_update_fp16_sr(int64_t M, int64_t N, int64_t K, const uint8_t *a,
+                                               int64_t lda, const uint8_t *b, int64_t ldb, float alpha,
+                                               uint8_t *g8_out, mp8_round g_round, int flags,
+                                               uint64_t g_seed, uint64_t g_offset, mp8_stats *stats,
+                                               uint16_t *w16, float lr, float inv_loss_scale,
+                                               mp8_round w_round, uint64_t w_seed, uint64_t w_offset,
+                                               const uint32_t *skip_if_nonzero, uint8_t *w8_out,
+                                               void *workspace, size_t workspace_bytes, void *stream) {
+    using namespace mp8;
+    if (M < 0 || N < 0 || K < 0) return MP8_ERR_INVALID_ARG;
+    if (w_round != MP8_RNE && w_round != MP8_SR) return MP8_ERR_INVALID_ARG;
+    if (K == 0 || N == 0) return MP8_OK;
+    if (!w16) return MP8_ERR_INVALID_ARG;
+    if (((uintptr_t)w16 | (uintptr_t)w8_out) & 15u) return MP8_ERR_ALIGNMENT;
+    UpdateHook upd{};
+    upd.w16 = w16;
+    upd.w8_out = w8_out;
+    upd.skip = skip_if_nonzero;
+    upd.neg_lr = -lr;
+    upd.inv_scale = inv_loss_scale;
+    upd.sr = w_round == MP8_SR;
+    upd.seed = w_seed;
+    upd.offset = w_offset;
+    const mp8_status st = gemm_impl(MP8_WGRAD, M, N, K, a, lda, b, ldb, alpha, nullptr, 0, g8_out, nullptr,
+                                    g_round, flags, g_seed, g_offset, stats, workspace, workspace_bytes,
+                                    stream, 0, 0, &upd);
+    if (st != MP8_ERR_UNSUPPORTED || g8_out == nullptr) return st;
+    // shapes that only the any-shape kernel takes: two launches through the 8-bit gradient
+    const mp8_status sg = mp8_gemm_fp8(MP8_WGRAD, M, N, K, a, lda, b, ldb, alpha, nullptr, 0, g8_out, nullptr,
+                                       g_round, flags, g_seed, g_offset, stats, workspace, workspace_bytes,
+                                       stream);
+    if (sg != MP8_OK) return sg;
+    return mp8_sgd_update_fp16_sr(w16, g8_out, K * N, lr, inv_loss_scale, w_round, w_seed, w_offset,
+                                  skip_if_nonzero, w8_out, nullptr, stream);
 }
 
 extern "C" mp8_status mp8_gemm_fp8(mp8_op op, int64_t M, int64_t N, int64_t K, const uint8_t *a,

@@ -324,4 +324,34 @@ struct StatsAcc {
     }
 };
 
+// ---------------------------------------------------------------------------------------
+// One element of the master-weight update of Figure 1b (shared by the update kernels and by
+// the weight-gradient finishing pass that applies the update in place).
+// ---------------------------------------------------------------------------------------
+// value(g8) * inv_scale, FP32 weight, one fused multiply-add, rounded to half.
+template <bool kSR>
+__device__ __forceinline__ uint32_t update_one(uint32_t w16, uint32_t g8, float neg_lr,
+                                               float inv_scale, uint32_t r16) {
+    float g = e5m2_to_f32(g8) * inv_scale;
+    float w = __half2float(__ushort_as_half((unsigned short)w16));
+    float wn = __builtin_fmaf(neg_lr, g, w);
+    // The update is an FP32 operation whose FP32 result is then converted to half: keep the
+    // compiler from merging the two into one mixed-precision instruction that rounds once.
+    asm volatile("" : "+v"(wn));
+    if constexpr (kSR) {
+        return f16_from_f32_bits<true>(f2u(wn), r16);
+    } else {
+        // v_cvt_f16_f32 rounds to nearest even exactly like the bit-level routine for every
+        // input that is not a NaN (checked over all 2^32 inputs); NaN is made canonical
+        uint32_t h = __half_as_ushort(__float2half_rn(wn));
+        return (wn != wn) ? 0x7E00u : h;
+    }
+}
+
+// The 8-bit (RNE) copy of a half-precision weight: the next step's operand.
+__device__ __forceinline__ uint32_t e5m2_of_half(uint32_t h) {
+    return e5m2_from_f32_bits<false>(f2u(__half2float(__ushort_as_half((unsigned short)h))), 0u,
+                                     false);
+}
+
 }  // namespace mp8

@@ -12,26 +12,6 @@
 
 namespace mp8 {
 
-// value(g8) * inv_scale, FP32 weight, one fused multiply-add, rounded to half.
-template <bool kSR>
-__device__ __forceinline__ uint32_t update_one(uint32_t w16, uint32_t g8, float neg_lr,
-                                               float inv_scale, uint32_t r16) {
-    float g = e5m2_to_f32(g8) * inv_scale;
-    float w = __half2float(__ushort_as_half((unsigned short)w16));
-    float wn = __builtin_fmaf(neg_lr, g, w);
-    // The update is an FP32 operation whose FP32 result is then converted to half: keep the
-    // compiler from merging the two into one mixed-precision instruction that rounds once.
-    asm volatile("" : "+v"(wn));
-    if constexpr (kSR) {
-        return f16_from_f32_bits<true>(f2u(wn), r16);
-    } else {
-        // v_cvt_f16_f32 rounds to nearest even exactly like the bit-level routine for every
-        // input that is not a NaN (checked over all 2^32 inputs); NaN is made canonical
-        uint32_t h = __half_as_ushort(__float2half_rn(wn));
-        return (wn != wn) ? 0x7E00u : h;
-    }
-}
-
 // Optimizers with FP32 state in front of the same conversion.  A rule turns the un-scaled
 // gradient g, the weight w and its state words into the new FP32 weight; every operation is a
 // separately rounded FP32 operation in the order written (the build forbids contraction).
@@ -81,11 +61,6 @@ __device__ __forceinline__ uint32_t rule_one(const Rule &rule, uint32_t w16, uin
         uint32_t h = __half_as_ushort(__float2half_rn(wn));
         return (wn != wn) ? 0x7E00u : h;
     }
-}
-
-__device__ __forceinline__ uint32_t e5m2_of_half(uint32_t h) {
-    return e5m2_from_f32_bits<false>(f2u(__half2float(__ushort_as_half((unsigned short)h))), 0u,
-                                     false);
 }
 
 constexpr int kUpdUnroll = 2;  // groups of eight elements in flight per thread

@@ -210,3 +210,57 @@ def test_adam_update_wide_range_of_moments_skip_and_errors(mp8):
     assert torch.equal(wdev.view(torch.int16), w_before.view(torch.int16)) and torch.equal(md.view(torch.int32), m_before.view(torch.int32))
     with pytest.raises(mp8.Mp8Error):
         mp8.adam_fp16_sr(wdev, md, vd, gpu(g8), 0.01, 1.0, 0)
+
+
+@pytest.mark.parametrize("layout", ["row-major", "contraction-major"])
+def test_weight_gradient_and_update_in_one_call_against_the_oracle_chain(mp8, layout):
+    """mp8_wgrad_update_fp16_sr = GEMM, one rounding to 8 bits, update of the half master
+    weights.  Operands whose sums are exact in FP32 make the accumulator equal the oracle's
+    reference, so the whole chain -- gradient codes, new master weights, new 8-bit weights -- is
+    compared with the oracle's own chain bit for bit: split and unsplit contractions, a ragged
+    column count (per-element path), RNE and SR for both roundings, the skip flag."""
+    import torch
+    from test_gpu_gemm import exact_sum_codes
+    rng = np.random.default_rng(17)
+    for (M, N, K) in ((1024, 64, 256), (4736, 128, 384), (512, 50, 128), (8192, 64, 64)):
+        if layout == "contraction-major" and N % 16:
+            continue                                    # that layout wants rows and columns in 16s
+        xt, et = exact_sum_codes(rng, (K, M)), exact_sum_codes(rng, (N, M))      # X^T [K, M], dY^T [N, M]
+        if M == 8192:                                   # keep the sums exact: three of four terms are zero
+            xt[:, rng.random(M) < 0.75] = 0
+            assert mp8.gemm_fp8_plan(mp8.WGRAD, M, N, K, 0 if layout == "row-major" else mp8.FLAG_CONTRACTION_MAJOR)[1] > 1
+        ref, _ = oracle.gemm_ref(xt, et, want_abs=False)                          # dW [K, N], exact
+        w16 = (rng.standard_normal(K * N) * 0.05).astype(np.float16).view(np.uint16)
+        alpha, lr, inv = 2.0 ** -9, 0.05, 1.0 / 64
+        if layout == "row-major":
+            a, b, flags = gpu(xt), gpu(et), 0
+        else:
+            a, b, flags = gpu(np.ascontiguousarray(xt.T)), gpu(np.ascontiguousarray(et.T)), mp8.FLAG_CONTRACTION_MAJOR
+        ws = torch.empty(max(mp8.gemm_fp8_workspace_bytes(mp8.WGRAD, M, N, K), 16), dtype=torch.uint8, device="cuda")
+        for g_round, w_round, skip in ((oracle.RNE, oracle.SR, 0), (oracle.SR, oracle.RNE, 0), (oracle.RNE, oracle.SR, 3)):
+            want_g = oracle.quantize_e5m2(ref.astype(np.float32), scale=alpha, mode=g_round, seed=21, offset=22)[0]
+            want_w, want_w8 = oracle.sgd_update_fp16(w16, want_g.reshape(-1), lr, inv, mode=w_round, seed=23, offset=24,
+                                                     skip=skip or None, want_w8=True)
+            wd = gpu(w16.view(np.int16))
+            g8 = torch.full((K * N + 64,), 0xAA, dtype=torch.uint8, device="cuda")
+            w8 = torch.full((K * N + 64,), 0x55, dtype=torch.uint8, device="cuda")
+            flag = torch.full((1,), skip, dtype=torch.int32, device="cuda")
+            st = mp8.new_stats()
+            mp8.wgrad_update_fp16_sr(M, N, K, a, b, wd, lr, inv, g8_out=g8[: K * N], alpha=alpha, g_round=g_round,
+                                     flags=flags, g_seed=21, g_offset=22, stats=st, w_round=w_round, w_seed=23,
+                                     w_offset=24, skip_if_nonzero=flag, w8_out=w8[: K * N], workspace=ws)
+            torch.cuda.synchronize()
+            assert np.array_equal(host(g8[: K * N]).reshape(K, N), want_g), (M, N, K, g_round)
+            assert bool((g8[K * N:] == 0xAA).all()) and bool((w8[K * N:] == 0x55).all())
+            assert np.array_equal(host(wd).view(np.uint16), want_w), (M, N, K, w_round, skip)
+            if skip:
+                assert bool((w8[: K * N] == 0x55).all())           # a skipped step writes no weights
+            else:
+                assert np.array_equal(host(w8[: K * N]), want_w8), (M, N, K, w_round)
+            # the same without keeping the gradient codes
+            wd2 = gpu(w16.view(np.int16))
+            mp8.wgrad_update_fp16_sr(M, N, K, a, b, wd2, lr, inv, alpha=alpha, g_round=g_round, flags=flags,
+                                     g_seed=21, g_offset=22, w_round=w_round, w_seed=23, w_offset=24,
+                                     skip_if_nonzero=flag, workspace=ws)
+            torch.cuda.synchronize()
+            assert torch.equal(wd2, wd)
