@@ -230,17 +230,18 @@ class ConvWorkload:
             ("conv_fwd", lambda: conv(mp8.FWD, self.X8, self.W8, self.Y8), 2 * P * C + 9 * C * C, flops, "mfma"),
             ("conv_bwd_data", lambda: conv(mp8.BWD_DATA, self.E8, self.W8, self.dX8),
              2 * P * C + 9 * C * C, flops, "mfma"),
-            ("conv_wgrad", lambda: conv(mp8.WGRAD, self.X8, self.E8, self.G8), 2 * P * C + 9 * C * C, flops,
-             "mfma"),
-            ("sgd_update", self._update, 6 * 9 * C * C, 0, "hbm"),
+            # weight gradient, its rounding and the master-weight update in one call
+            ("conv_wgrad_update", self._wgrad_update, 2 * P * C + 9 * C * C + 6 * 9 * C * C, flops, "mfma"),
         ]
         mp8.quantize_e5m2(self.W16.view(9 * C, C), self.W8)
 
-    def _update(self):
+    def _wgrad_update(self):
         self.step_no += 1
-        self.mp8.sgd_update_fp16_sr(self.W16, self.G8, LR, 1.0 / LOSS_SCALE, round=self.mp8.SR,
-                                    seed=0x1905_1233_4000_0003, offset=self.step_no,
-                                    skip_if_nonzero=self.stats[1:2], w8_out=self.W8)
+        mp8 = self.mp8
+        mp8.conv3x3_wgrad_update_fp16_sr(*self.dims, self.X8, self.E8, self.W16, LR, 1.0 / LOSS_SCALE,
+                                         g8_out=self.G8, w_round=mp8.SR, w_seed=0x1905_1233_4000_0003,
+                                         w_offset=self.step_no, skip_if_nonzero=self.stats[1:2],
+                                         w8_out=self.W8, workspace=self.ws)
 
     @property
     def stats(self):

@@ -275,6 +275,17 @@ mp8_status mp8_wgrad_update_fp16_sr(int64_t M, int64_t N, int64_t K, const uint8
                                     const uint32_t *skip_if_nonzero, uint8_t *w8_out, void *workspace,
                                     size_t workspace_bytes, void *stream);
 
+/* The same for the weight gradient of the 3x3 convolution (operands as mp8_conv3x3_fp8 with
+ * MP8_WGRAD: x8 and e8 padded channels-last; w16, g8_out, w8_out are [3, 3, Cin, Cout]).  The
+ * workspace (mp8_conv3x3_fp8_workspace_bytes for MP8_WGRAD, at least 36 * Cin * Cout bytes) is
+ * always needed. */
+mp8_status mp8_conv3x3_wgrad_update_fp16_sr(
+    int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t Cout, int64_t prows, const uint8_t *x8,
+    const uint8_t *e8, float alpha, uint8_t *g8_out, mp8_round g_round, int flags, uint64_t g_seed,
+    uint64_t g_offset, mp8_stats *stats, uint16_t *w16, float lr, float inv_loss_scale,
+    mp8_round w_round, uint64_t w_seed, uint64_t w_offset, const uint32_t *skip_if_nonzero,
+    uint8_t *w8_out, void *workspace, size_t workspace_bytes, void *stream);
+
 /* out[i] = the 16 random bits element i would use (device array of n uint16), for tests. */
 mp8_status mp8_sr_bits(uint16_t *out, int64_t n, uint64_t seed, uint64_t offset, void *stream);
 

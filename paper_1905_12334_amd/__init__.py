@@ -28,7 +28,7 @@ EXPORTS = [
     "mp8_scaler_init", "mp8_scaler_update", "mp8_scaler_set_floor", "mp8_status_string",
     "mp8_conv3x3_fp8", "mp8_conv3x3_fp8_workspace_bytes", "mp8_sgd_momentum_fp16_sr",
     "mp8_gemm_fp8_plan", "mp8_gemm_tile_config_lds_bytes", "mp8_adam_fp16_sr",
-    "mp8_quantize_e5m2_batch", "mp8_wgrad_update_fp16_sr",
+    "mp8_quantize_e5m2_batch", "mp8_wgrad_update_fp16_sr", "mp8_conv3x3_wgrad_update_fp16_sr",
 ]
 
 
@@ -82,6 +82,10 @@ def lib() -> C.CDLL:
     L.mp8_wgrad_update_fp16_sr.restype = ci
     L.mp8_wgrad_update_fp16_sr.argtypes = [i64, i64, i64, vp, i64, vp, i64, f32, vp, ci, ci, u64, u64, vp,
                                            vp, f32, f32, ci, u64, u64, vp, vp, vp, C.c_size_t, vp]
+    L.mp8_conv3x3_wgrad_update_fp16_sr.restype = ci
+    L.mp8_conv3x3_wgrad_update_fp16_sr.argtypes = [i64, i64, i64, i64, i64, i64, vp, vp, f32, vp, ci, ci, u64,
+                                                   u64, vp, vp, f32, f32, ci, u64, u64, vp, vp, vp,
+                                                   C.c_size_t, vp]
     L.mp8_quantize_e5m2_batch.restype = ci
     L.mp8_quantize_e5m2_batch.argtypes = [vp, ci, vp]
     L.mp8_adam_fp16_sr.restype = ci
@@ -290,6 +294,36 @@ def conv3x3_fp8(op, B, H, W, Cin, Cout, a, b, out8=None, acc=None, acc_mode=0, a
                                _ptr(workspace), ws_bytes, _stream())
     _check(st, "mp8_conv3x3_fp8")
     return out8
+
+
+def conv3x3_wgrad_update_fp16_sr(B, H, W, Cin, Cout, x8, e8, w16, lr, inv_loss_scale, g8_out=None, alpha=1.0,
+                                 g_round=RNE, flags=0, g_seed=0, g_offset=0, stats=None, w_round=SR, w_seed=0,
+                                 w_offset=0, skip_if_nonzero=None, w8_out=None, workspace=None, prows=None):
+    """mp8_conv3x3_wgrad_update_fp16_sr: weight gradient of the 3x3 convolution, its rounding to
+    8 bits and the update of the FP16 master weights w16 [3, 3, Cin, Cout] in one call."""
+    import torch
+    prows = conv_prows(B, H, W) if prows is None else prows
+    _dev(x8, "x8", torch.uint8)
+    _dev(e8, "e8", torch.uint8)
+    _dev(w16, "w16", (torch.float16, torch.int16, torch.uint16))
+    _dev(g8_out, "g8_out", torch.uint8)
+    _dev(w8_out, "w8_out", torch.uint8)
+    if x8.numel() != prows * Cin or e8.numel() != prows * Cout:
+        raise Mp8Error("x8 / e8 do not have the sizes the operation implies")
+    for t, name in ((w16, "w16"), (g8_out, "g8_out"), (w8_out, "w8_out")):
+        if t is not None and t.numel() != 9 * Cin * Cout:
+            raise Mp8Error(f"{name} must have 9*Cin*Cout elements")
+    if not _has_guard(x8, (W + 3) * Cin):
+        raise Mp8Error("the padded tensor x8 needs W+3 readable guard rows before and after "
+                       "(allocate it with conv_buffer)")
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = lib().mp8_conv3x3_wgrad_update_fp16_sr(B, H, W, Cin, Cout, prows, _ptr(x8), _ptr(e8), float(alpha),
+                                                _ptr(g8_out), g_round, flags, g_seed, g_offset, _ptr(stats),
+                                                _ptr(w16), float(lr), float(inv_loss_scale), w_round, w_seed,
+                                                w_offset, _ptr(skip_if_nonzero), _ptr(w8_out), _ptr(workspace),
+                                                ws_bytes, _stream())
+    _check(st, "mp8_conv3x3_wgrad_update_fp16_sr")
+    return w16
 
 
 def gemm_fp8_plan(op, M, N, K, flags=0, tile_config=0, split_k=0):

@@ -1766,13 +1766,15 @@ extern "C" size_t mp8_conv3x3_fp8_workspace_bytes(mp8_op op, int64_t B, int64_t 
     return plan_workspace(conv_plan(op, d, Ci), d.rows, d.cols);
 }
 
-extern "C" mp8_status mp8_conv3x3_fp8(mp8_op op, int64_t B, int64_t H, int64_t W, int64_t Ci,
-                                      int64_t Co, int64_t prows, const uint8_t *a,
-                                      const uint8_t *b, float alpha, float *acc, int acc_mode,
-                                      uint8_t *out8, mp8_round round, int flags, uint64_t seed,
-                                      uint64_t offset, mp8_stats *stats, void *workspace,
-                                      size_t workspace_bytes, void *stream) {
-    using namespace mp8;
+namespace mp8 {
+
+// mp8_conv3x3_fp8, optionally (weight gradient only) with the master-weight update applied to
+// the rounded result by the finishing pass.
+static mp8_status conv_impl(mp8_op op, int64_t B, int64_t H, int64_t W, int64_t Ci, int64_t Co,
+                            int64_t prows, const uint8_t *a, const uint8_t *b, float alpha, float *acc,
+                            int acc_mode, uint8_t *out8, mp8_round round, int flags, uint64_t seed,
+                            uint64_t offset, mp8_stats *stats, void *workspace, size_t workspace_bytes,
+                            void *stream, const UpdateHook *upd) {
     ConvDims d;
     if (B < 0 || H < 0 || W < 0 || Ci < 0 || Co < 0 || prows < 0) return MP8_ERR_INVALID_ARG;
     if (!conv_dims(op, prows, Ci, Co, d)) return MP8_ERR_INVALID_ARG;
@@ -1820,7 +1822,43 @@ extern "C" mp8_status mp8_conv3x3_fp8(mp8_op op, int64_t B, int64_t H, int64_t W
     ga.cv.b_tap_stride = Ci * Co;
     ga.cv.div_ci = make_fastdiv((uint32_t)Ci);
     return launch_mfma(ga, ep, pl, d.kc, kTiles[pl.tile].kernel_conv[(int)op], workspace, workspace_bytes,
-                       (hipStream_t)stream);
+                       (hipStream_t)stream, upd);
+}
+
+}  // namespace mp8
+
+extern "C" mp8_status mp8_conv3x3_fp8(mp8_op op, int64_t B, int64_t H, int64_t W, int64_t Ci,
+                                      int64_t Co, int64_t prows, const uint8_t *a,
+                                      const uint8_t *b, float alpha, float *acc, int acc_mode,
+                                      uint8_t *out8, mp8_round round, int flags, uint64_t seed,
+                                      uint64_t offset, mp8_stats *stats, void *workspace,
+                                      size_t workspace_bytes, void *stream) {
+    return mp8::conv_impl(op, B, H, W, Ci, Co, prows, a, b, alpha, acc, acc_mode, out8, round, flags, seed,
+                          offset, stats, workspace, workspace_bytes, stream, nullptr);
+}
+
+extern "C" mp8_status mp8_conv3x3_wgrad_update_fp16_sr(
+    int64_t B, int64_t H, int64_t W, int64_t Ci, int64_t Co, int64_t prows, const uint8_t *x8,
+    const uint8_t *e8, float alpha, uint8_t *g8_out, mp8_round g_round, int flags, uint64_t g_seed,
+    uint64_t g_offset, mp8_stats *stats, uint16_t *w16, float lr, float inv_loss_scale,
+    mp8_round w_round, uint64_t w_seed, uint64_t w_offset, const uint32_t *skip_if_nonzero,
+    uint8_t *w8_out, void *workspace, size_t workspace_bytes, void *stream) {
+    using namespace mp8;
+    if (w_round != MP8_RNE && w_round != MP8_SR) return MP8_ERR_INVALID_ARG;
+    if (B == 0 || H == 0 || W == 0 || Ci == 0 || Co == 0) return MP8_OK;
+    if (!w16) return MP8_ERR_INVALID_ARG;
+    if (((uintptr_t)w16 | (uintptr_t)w8_out) & 15u) return MP8_ERR_ALIGNMENT;
+    UpdateHook upd{};
+    upd.w16 = w16;
+    upd.w8_out = w8_out;
+    upd.skip = skip_if_nonzero;
+    upd.neg_lr = -lr;
+    upd.inv_scale = inv_loss_scale;
+    upd.sr = w_round == MP8_SR;
+    upd.seed = w_seed;
+    upd.offset = w_offset;
+    return conv_impl(MP8_WGRAD, B, H, W, Ci, Co, prows, x8, e8, alpha, nullptr, 0, g8_out, g_round, flags,
+                     g_seed, g_offset, stats, workspace, workspace_bytes, stream, &upd);
 }
 
 #ifdef MP8_TRACE

@@ -89,6 +89,31 @@ def test_conv_exact_sums_all_three_operations(mp8, dims):
     assert np.array_equal(out8.reshape(3, 3, Ci, Co), oracle.round_ref_e5m2(ref, alpha=alpha))
 
 
+def test_conv_weight_gradient_and_update_in_one_call(mp8):
+    """mp8_conv3x3_wgrad_update_fp16_sr against the oracle's chain (direct convolution weight
+    gradient -> one rounding -> FP16 update) on exact-sum operands: gradient codes, new master
+    weights and their 8-bit copies bit for bit."""
+    import torch
+    B, H, W, Ci, Co = 2, 6, 5, 128, 128
+    rng = np.random.default_rng(77)
+    x, e = exact_codes(rng, (B, H, W, Ci)), exact_codes(rng, (B, H, W, Co))
+    ref, _ = oracle.conv3x3_ref("wgrad", x, e, want_abs=False)
+    w16 = (rng.standard_normal(9 * Ci * Co) * 0.05).astype(np.float16).view(np.uint16)
+    alpha, lr, inv = 1.0 / 32, 0.05, 1.0 / 16
+    want_g = oracle.round_ref_e5m2(ref, alpha=alpha).reshape(-1)
+    want_w, want_w8 = oracle.sgd_update_fp16(w16, want_g, lr, inv, mode=oracle.SR, seed=5, offset=6, want_w8=True)
+    xd, ed = to_padded(mp8, x), to_padded(mp8, e)
+    ws = torch.empty(max(mp8.conv3x3_fp8_workspace_bytes(mp8.WGRAD, B, H, W, Ci, Co), 16), dtype=torch.uint8, device="cuda")
+    wd = gpu(w16.view(np.int16))
+    g8 = torch.full((9 * Ci * Co,), 0xAA, dtype=torch.uint8, device="cuda")
+    w8 = torch.full((9 * Ci * Co,), 0x55, dtype=torch.uint8, device="cuda")
+    mp8.conv3x3_wgrad_update_fp16_sr(B, H, W, Ci, Co, xd, ed, wd, lr, inv, g8_out=g8, alpha=alpha, w_round=mp8.SR,
+                                     w_seed=5, w_offset=6, w8_out=w8, workspace=ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(g8), want_g)
+    assert np.array_equal(host(wd).view(np.uint16), want_w) and np.array_equal(host(w8), want_w8)
+
+
 def test_conv_random_operands_sr_epilogue_and_statistics(mp8):
     B, H, W, Ci, Co = 2, 7, 9, 128, 128
     dims = (B, H, W, Ci, Co)
