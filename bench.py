@@ -46,9 +46,8 @@ LR = 1e-3
 # by what the same counters read on a plain 1 GiB copy (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000);
 # the runs and their raw figures are in profiles/bench_step_cfg2_hbm_traffic.txt
 MEASURED_TRAFFIC_BYTES = {
-    "quantize_X": 144555344, "quantize_dY": 16141620, "gemm_fwd": 33421826,
-    "gemm_bwd_data": 34288717, "gemm_wgrad": 53984201, "sgd_update": 1041803,
-    "gemm_wgrad_update": 53984201 + 1041803,
+    "quantize_X": 144555139, "quantize_dY": 16142644, "gemm_fwd": 33417730,
+    "gemm_bwd_data": 33494112, "gemm_wgrad_update": 51606442,
 }
 
 
