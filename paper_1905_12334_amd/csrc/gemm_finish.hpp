@@ -1,0 +1,174 @@
+// Second pass of a GEMM whose epilogue is not fused (split contraction, FP32 / transposed
+// outputs, ragged columns), optionally with the master-weight update of Figure 1b applied to the
+// codes it has just rounded; and the any-shape fallback kernel.
+#pragma once
+
+#include "gemm_common.hpp"
+
+namespace mp8 {
+
+// Finish four consecutive columns c .. c+3 (c % 4 == 0, row length a multiple of 4).
+__device__ __forceinline__ uint32_t finish4(const Epilogue &ep, int64_t r, int64_t c, float v[4],
+                                            StatsAcc &st) {
+    const int64_t i0 = r * ep.cols + c;
+    if (ep.acc_mode != 0) {
+        f32x4 *p = reinterpret_cast<f32x4 *>(ep.acc + i0);
+        if (ep.acc_mode == 2) {
+            f32x4 o = *p;
+            v[0] += o.x; v[1] += o.y; v[2] += o.z; v[3] += o.w;
+        }
+        f32x4 n = {v[0], v[1], v[2], v[3]};
+        *p = n;
+    }
+    if (ep.out8 == nullptr && ep.out8_t == nullptr && ep.stats == nullptr && !ep.want_codes) return 0;
+    uint32_t r01 = 0, r23 = 0;
+    if (ep.sr) {
+        // elements i0..i0+3 are halfwords (i0 % 8) .. +3 of Philox block i0 / 8
+        const Philox rng(ep.seed, ep.offset);
+        uint4 w = rng.block((uint64_t)i0 >> 3);
+        r01 = (i0 & 4) ? w.z : w.x;
+        r23 = (i0 & 4) ? w.w : w.y;
+    }
+    float y[4] = {v[0] * ep.alpha, v[1] * ep.alpha, v[2] * ep.alpha, v[3] * ep.alpha};
+    uint32_t pk = e5m2_pack4_rt(y, r01, r23, ep.sr != 0, ep.sat != 0);
+    if (ep.mask && conv_padding_row(ep, r)) pk = 0;
+    else if (ep.stats != nullptr) st.add4(y, pk);
+    if (ep.out8 != nullptr) *reinterpret_cast<uint32_t *>(ep.out8 + i0) = pk;
+    if (ep.out8_t != nullptr) {
+        uint8_t *t = ep.out8_t + c * ep.rows + r;
+        t[0] = (uint8_t)pk;
+        t[ep.rows] = (uint8_t)(pk >> 8);
+        t[2 * ep.rows] = (uint8_t)(pk >> 16);
+        t[3 * ep.rows] = (uint8_t)(pk >> 24);
+    }
+    return pk;
+}
+
+// Optional second half of Figure 1b in the finishing pass: the 8-bit weight gradient that was
+// just rounded is un-scaled and applied to the half-precision master weights, exactly as
+// mp8_sgd_update_fp16_sr would do it from memory (same arithmetic, same random stream: element
+// i uses halfword i % 8 of block i / 8 of the update's own Philox stream).  w16 == nullptr:
+// no update.
+struct UpdateHook {
+    uint16_t *w16;
+    uint8_t *w8_out;
+    const uint32_t *skip;
+    float neg_lr, inv_scale;
+    int sr;
+    uint64_t seed, offset;
+};
+
+__device__ __forceinline__ void update_element(const UpdateHook &u, int64_t i, uint32_t code, uint32_t r16) {
+    const uint32_t h = u.sr ? update_one<true>(u.w16[i], code, u.neg_lr, u.inv_scale, r16)
+                            : update_one<false>(u.w16[i], code, u.neg_lr, u.inv_scale, 0u);
+    u.w16[i] = (uint16_t)h;
+    if (u.w8_out != nullptr) u.w8_out[i] = (uint8_t)e5m2_of_half(h);
+}
+
+// Elements i0 .. i0+3 (i0 % 4 == 0) from their four packed gradient codes.
+__device__ __forceinline__ void update4(const UpdateHook &u, int64_t i0, uint32_t pk) {
+    uint32_t r01 = 0, r23 = 0;
+    if (u.sr) {
+        const Philox rng(u.seed, u.offset);
+        const uint4 w = rng.block((uint64_t)i0 >> 3);
+        r01 = (i0 & 4) ? w.z : w.x;
+        r23 = (i0 & 4) ? w.w : w.y;
+    }
+    u32x2 *wp = reinterpret_cast<u32x2 *>(u.w16 + i0);
+    const u32x2 wr = *wp;
+    uint32_t h[4];
+    const uint32_t w16v[4] = {wr.x & 0xFFFFu, wr.x >> 16, wr.y & 0xFFFFu, wr.y >> 16};
+    const uint32_t r16[4] = {r01 & 0xFFFFu, r01 >> 16, r23 & 0xFFFFu, r23 >> 16};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t code = (pk >> (8 * j)) & 0xFFu;
+        h[j] = u.sr ? update_one<true>(w16v[j], code, u.neg_lr, u.inv_scale, r16[j])
+                    : update_one<false>(w16v[j], code, u.neg_lr, u.inv_scale, 0u);
+    }
+    const u32x2 o = {h[0] | (h[1] << 16), h[2] | (h[3] << 16)};
+    *wp = o;
+    if (u.w8_out != nullptr)
+        *reinterpret_cast<uint32_t *>(u.w8_out + i0) =
+            e5m2_of_half(h[0]) | (e5m2_of_half(h[1]) << 8) | (e5m2_of_half(h[2]) << 16) | (e5m2_of_half(h[3]) << 24);
+}
+
+// Sum the FP32 tiles of the contraction slices in slice order and finish: the complete sum is
+// rounded once.  One thread per four columns (per element when the row length is not a
+// multiple of four).
+__global__ __launch_bounds__(256) void splitk_finish_kernel(const float *__restrict__ partial,
+                                                            int splits, const Epilogue ep,
+                                                            const UpdateHook upd) {
+    StatsAcc st;
+    // an overflowed step leaves the master weights alone (the gradient codes are still written)
+    const bool updating = upd.w16 != nullptr && !(upd.skip != nullptr && *upd.skip != 0u);
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t slice = ep.rows * ep.cols;
+    if ((ep.cols & 3) == 0) {
+        const int64_t total = slice >> 2;
+        for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += stride) {
+            const int64_t i0 = t << 2;
+            const int64_t r = i0 / ep.cols, c = i0 - r * ep.cols;
+            float v[4] = {0.f, 0.f, 0.f, 0.f};
+            int s = 0;
+            for (; s + 4 <= splits; s += 4) {  // four loads in flight, added in slice order
+                f32x4 x0 = *reinterpret_cast<const f32x4 *>(partial + (int64_t)s * slice + i0);
+                f32x4 x1 = *reinterpret_cast<const f32x4 *>(partial + (int64_t)(s + 1) * slice + i0);
+                f32x4 x2 = *reinterpret_cast<const f32x4 *>(partial + (int64_t)(s + 2) * slice + i0);
+                f32x4 x3 = *reinterpret_cast<const f32x4 *>(partial + (int64_t)(s + 3) * slice + i0);
+                v[0] += x0.x; v[1] += x0.y; v[2] += x0.z; v[3] += x0.w;
+                v[0] += x1.x; v[1] += x1.y; v[2] += x1.z; v[3] += x1.w;
+                v[0] += x2.x; v[1] += x2.y; v[2] += x2.z; v[3] += x2.w;
+                v[0] += x3.x; v[1] += x3.y; v[2] += x3.z; v[3] += x3.w;
+            }
+            for (; s < splits; ++s) {
+                f32x4 x = *reinterpret_cast<const f32x4 *>(partial + (int64_t)s * slice + i0);
+                v[0] += x.x; v[1] += x.y; v[2] += x.z; v[3] += x.w;
+            }
+            const uint32_t pk = finish4(ep, r, c, v, st);
+            if (updating) update4(upd, i0, pk);
+        }
+    } else {
+        for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < slice; i += stride) {
+            float v = 0.f;
+            for (int s = 0; s < splits; ++s) v += partial[(int64_t)s * slice + i];
+            const int64_t r = i / ep.cols;
+            const uint32_t code = finish1(ep, r, i - r * ep.cols, v, st);
+            if (updating) {
+                uint32_t r16 = 0;
+                if (upd.sr) {
+                    const Philox rng(upd.seed, upd.offset);
+                    r16 = philox_half(rng.block((uint64_t)i >> 3), (int)(i & 7));
+                }
+                update_element(upd, i, code, r16);
+            }
+        }
+    }
+    if (ep.stats != nullptr) st.flush(ep.stats);
+}
+
+// Any-shape fallback: one thread per output element, operands decoded one by one, FP32 fused
+// multiply-adds in contraction order.  Used when the contraction length is not a multiple of
+// 128 or the operands are not 16-byte aligned.
+__global__ __launch_bounds__(256) void gemm_generic_kernel(const uint8_t *__restrict__ a,
+                                                           int64_t lda,
+                                                           const uint8_t *__restrict__ b,
+                                                           int64_t ldb, int64_t kc, int tn,
+                                                           const Epilogue ep) {
+    const int64_t total = ep.rows * ep.cols;
+    StatsAcc st;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += stride) {
+        const int64_t r = t / ep.cols, c = t - r * ep.cols;
+        // element (r, j) of a: a[r * lda + j], or a[j * lda + r] when a is contraction-major
+        // (bit 0 of tn; bit 1 likewise for b)
+        const uint8_t *ar = (tn & 1) ? a + r : a + r * lda, *bc = (tn & 2) ? b + c : b + c * ldb;
+        const int64_t sa = (tn & 1) ? lda : 1, sb = (tn & 2) ? ldb : 1;
+        float s = 0.f;
+        for (int64_t j = 0; j < kc; ++j)
+            s = __builtin_fmaf(e5m2_to_f32(ar[j * sa]), e5m2_to_f32(bc[j * sb]), s);
+        finish1(ep, r, c, s, st);
+    }
+    if (ep.stats != nullptr) st.flush(ep.stats);
+}
+
+}  // namespace mp8
