@@ -11,6 +11,7 @@ ResNet-50-style 3x3 convolution layer taken as a GEMM (M=25088, N=128, K=1152):
     update        W16 <- half_SR(W16 - lr * G8 / 2^12),  W8 <- Q(W16) for the next step
                   (applied by the pass that rounds G8: one call, mp8_wgrad_update_fp16_sr)
 
+(Launched in the order Q(dY), backward-data, Q(X), forward, weight-grad + update.)
 Every tensor exists once, row-major, as its producer wrote it: the GEMMs read X8 [M,K],
 E8 [M,N] and W8 [K,N] in whichever orientation they need (contraction-major operands go
 through transposing LDS reads), and the Q node on the weights is part of the update kernel.
@@ -156,6 +157,12 @@ class Workload:
                 dict(src=self.X, dst=self.X8),
                 dict(src=self.dY, dst=self.E8, scale=LOSS_SCALE, stats=self.stats)]),
                 5 * M * K + 5 * M * N, 0, "hbm")]
+        if not batch_quantize:
+            # error path first, then the activation path: the forward GEMM and the weight gradient
+            # find X8 freshly written (measured 0.7 us per step against the order of the list above)
+            by_name = {k[0]: k for k in self.kernels}
+            order = ["quantize_dY", "gemm_bwd_data", "quantize_X", "gemm_fwd"]
+            self.kernels = [by_name[n] for n in order] + [k for k in self.kernels if k[0] not in order]
         # the weights of the first step: Q(W16), outside the timed region
         mp8_.quantize_e5m2(self.W16.view(K, N), self.W8)
 
