@@ -484,3 +484,54 @@ def test_forward_from_row_major_weights(mp8):
         mp8.gemm_fp8(mp8.FWD, 128, 128, 128, gpu(X8[:128, :128].copy()), gpu(W8t[:, :128].copy()),
                      out8=torch.zeros((128, 128), dtype=torch.uint8, device="cuda"),
                      flags=mp8.FLAG_A_CONTRACTION_MAJOR)
+
+
+def test_random_shapes_layouts_and_leading_dimensions(mp8):
+    """Seeded random shapes through whatever kernel the planner picks: rows and columns from 1
+    to 700 (some around 2000), contractions of 1 to 48 stages (and some that are not multiples of 128), the three
+    operand layouts, leading dimensions larger than needed -- FP32 accumulator within tolerance,
+    8-bit output equal to the oracle's rounding of it, nothing written out of bounds."""
+    import torch
+    rng = np.random.default_rng(20260)
+    kernels = set()
+    for case in range(48):
+        layout = (0, 0, mp8.FLAG_B_CONTRACTION_MAJOR, mp8.FLAG_CONTRACTION_MAJOR)[case % 4]
+        step = 16 if layout else 1
+        rows = int(rng.integers(1, 700 // step + 1)) * step
+        cols = int(rng.integers(1, 700 // step + 1)) * step
+        if layout == mp8.FLAG_B_CONTRACTION_MAJOR:
+            rows = int(rng.integers(1, 701))              # only b is contraction-major: any row count
+        kc = int(rng.integers(1, 49)) * 128 if case % 8 else int(rng.integers(1, 300))
+        if case % 6 == 5:                                 # enough 128x128 tiles for the large-tile kernels
+            rows, cols, kc = 16 * int(rng.integers(100, 150)), 16 * int(rng.integers(100, 150)), 128 * int(rng.integers(1, 5))
+        a_km, b_km = bool(layout & mp8.FLAG_A_CONTRACTION_MAJOR), bool(layout & mp8.FLAG_B_CONTRACTION_MAJOR)
+        pad_a, pad_b = 16 * int(rng.integers(0, 3)), 16 * int(rng.integers(0, 3))
+        a_rm = (workloads.random_e5m2_codes(1000 + case, (rows, kc)) & 0x83) | 0x38     # logical [rows, kc]
+        b_rm = (workloads.random_e5m2_codes(2000 + case, (cols, kc)) & 0x83) | 0x38
+        ref, absref = oracle.gemm_ref(a_rm, b_rm)
+
+        def stored(x_rm, km, pad):
+            """The operand as the call wants it: [n, kc] or [kc, n] with a padded leading dimension."""
+            x = np.ascontiguousarray(x_rm.T) if km else x_rm
+            buf = np.full((x.shape[0], x.shape[1] + pad), 0x7E, np.uint8)   # NaN codes in the padding
+            buf[:, : x.shape[1]] = x
+            return gpu(buf), x.shape[1] + pad
+
+        a, lda = stored(a_rm, a_km, pad_a)
+        b, ldb = stored(b_rm, b_km, pad_b)
+        kernels.add(mp8.gemm_fp8_plan(mp8.FWD, rows, cols, kc, layout))
+        ws = torch.empty(max(mp8.gemm_fp8_workspace_bytes(mp8.FWD, rows, cols, kc), 16), dtype=torch.uint8, device="cuda")
+        acc = torch.full((rows * cols + 16,), 7.0, dtype=torch.float32, device="cuda")
+        o1 = torch.full((rows * cols + 64,), 0xAA, dtype=torch.uint8, device="cuda")
+        o2 = torch.full((rows * cols + 64,), 0xAA, dtype=torch.uint8, device="cuda")
+        mp8.gemm_fp8(mp8.FWD, rows, cols, kc, a, b, out8=o1[: rows * cols], acc=acc[: rows * cols], acc_mode=1,
+                     flags=layout, workspace=ws, lda=lda, ldb=ldb)
+        mp8.gemm_fp8(mp8.FWD, rows, cols, kc, a, b, out8=o2[: rows * cols], flags=layout, workspace=ws, lda=lda, ldb=ldb)
+        torch.cuda.synchronize()
+        what = (case, rows, cols, kc, layout, lda, ldb)
+        assert bool((o1[rows * cols:] == 0xAA).all()) and bool((o2[rows * cols:] == 0xAA).all()), what
+        assert bool((acc[rows * cols:] == 7.0).all()), what
+        out8 = host(o1[: rows * cols]).reshape(rows, cols)
+        check_outputs(host(acc[: rows * cols]).reshape(rows, cols), out8, ref, absref, kc)
+        assert np.array_equal(host(o2[: rows * cols]).reshape(rows, cols), out8), what
+    assert len({k[0] for k in kernels}) >= 5        # the cases reach most kernels, the any-shape one too
