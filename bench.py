@@ -270,6 +270,7 @@ def kernel_table(kernels, times_ms, traffic=None):
                     "peak": peak, "unit": unit, "frac": achieved / peak,
                     "alg_bytes": nbytes, "flops": flops,
                     "hbm_gbs": nbytes / (ms * 1e-3) / 1e9,
+                    "frac_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                     "traffic": (traffic or {}).get(name)})
     return out
 
