@@ -286,6 +286,33 @@ mp8_status mp8_conv3x3_wgrad_update_fp16_sr(
     mp8_round w_round, uint64_t w_seed, uint64_t w_offset, const uint32_t *skip_if_nonzero,
     uint8_t *w8_out, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * The Q node on the activations and the forward GEMM it feeds (Figure 1a) in one call:
+ *     x8_out = Q(fl32(x * x_scale))            exactly as mp8_quantize_e5m2 (FP32 source, x_round,
+ *                                              x_flags, x_seed / x_offset, x_stats)
+ *     out    = x8_out [M, K] . w8 [K, N]       exactly as mp8_gemm_fp8 with MP8_FWD and
+ *                                              MP8_FLAG_B_CONTRACTION_MAJOR (alpha, acc, acc_mode,
+ *                                              out8, out8_t, round, flags, seed / offset, stats)
+ * The results are bit for bit those of the two separate calls.  When the layer has at most 128
+ * output columns (N a multiple of 16, K a multiple of 128) the GEMM reads the activations only
+ * once, and one kernel does both: it reads x, rounds it, writes x8_out (the weight gradient needs
+ * it later) and multiplies from the codes it holds.  Every other shape runs as the two calls.
+ *   x          [M, K] FP32, dense, 16-byte aligned (device)
+ *   x8_out     [M, K] 8-bit codes, dense, 16-byte aligned; always written
+ *   w8         [K, N] 8-bit codes, row stride ldw >= N (the layout mp8_sgd_update_fp16_sr's
+ *              w8_out produces); 16-byte aligned rows for the fused kernel
+ *   flags      MP8_FLAG_SATURATE or 0, for the output rounding; x_flags the same for x8_out
+ *   workspace  as mp8_gemm_fp8_workspace_bytes(MP8_FWD, M, N, K) says; the fused kernel needs none
+ * M*K == 0 or N == 0 is valid.  On error nothing is enqueued.
+ */
+mp8_status mp8_quantize_gemm_fwd_fp8(int64_t M, int64_t N, int64_t K, const float *x, float x_scale,
+                                     mp8_round x_round, int x_flags, uint64_t x_seed, uint64_t x_offset,
+                                     mp8_stats *x_stats, uint8_t *x8_out, const uint8_t *w8, int64_t ldw,
+                                     float alpha, float *acc, int acc_mode, uint8_t *out8,
+                                     uint8_t *out8_t, mp8_round round, int flags, uint64_t seed,
+                                     uint64_t offset, mp8_stats *stats, void *workspace,
+                                     size_t workspace_bytes, void *stream);
+
 /* out[i] = the 16 random bits element i would use (device array of n uint16), for tests. */
 mp8_status mp8_sr_bits(uint16_t *out, int64_t n, uint64_t seed, uint64_t offset, void *stream);
 

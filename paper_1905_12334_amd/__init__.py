@@ -29,6 +29,7 @@ EXPORTS = [
     "mp8_conv3x3_fp8", "mp8_conv3x3_fp8_workspace_bytes", "mp8_sgd_momentum_fp16_sr",
     "mp8_gemm_fp8_plan", "mp8_gemm_tile_config_lds_bytes", "mp8_adam_fp16_sr",
     "mp8_quantize_e5m2_batch", "mp8_wgrad_update_fp16_sr", "mp8_conv3x3_wgrad_update_fp16_sr",
+    "mp8_quantize_gemm_fwd_fp8",
 ]
 
 
@@ -86,6 +87,9 @@ def lib() -> C.CDLL:
     L.mp8_conv3x3_wgrad_update_fp16_sr.argtypes = [i64, i64, i64, i64, i64, i64, vp, vp, f32, vp, ci, ci, u64,
                                                    u64, vp, vp, f32, f32, ci, u64, u64, vp, vp, vp,
                                                    C.c_size_t, vp]
+    L.mp8_quantize_gemm_fwd_fp8.restype = ci
+    L.mp8_quantize_gemm_fwd_fp8.argtypes = [i64, i64, i64, vp, f32, ci, ci, u64, u64, vp, vp, vp, i64, f32,
+                                            vp, ci, vp, vp, ci, ci, u64, u64, vp, vp, C.c_size_t, vp]
     L.mp8_quantize_e5m2_batch.restype = ci
     L.mp8_quantize_e5m2_batch.argtypes = [vp, ci, vp]
     L.mp8_adam_fp16_sr.restype = ci
@@ -239,6 +243,37 @@ def gemm_fp8(op, M, N, K, a, b, out8=None, out8_t=None, acc=None, acc_mode=0, al
                                   _ptr(stats), _ptr(workspace), ws_bytes, _stream(), tile_config,
                                   split_k)
     _check(st, "mp8_gemm_fp8")
+    return out8
+
+
+def quantize_gemm_fwd_fp8(M, N, K, x, x8_out, w8, out8=None, out8_t=None, acc=None, acc_mode=0,
+                          x_scale=1.0, x_round=RNE, x_flags=0, x_seed=0, x_offset=0, x_stats=None,
+                          alpha=1.0, round=RNE, flags=0, seed=0, offset=0, stats=None, workspace=None,
+                          ldw=None):
+    """mp8_quantize_gemm_fwd_fp8: x8_out = Q(x * x_scale) [M, K] and out = x8_out . w8 [K, N] in one
+    call (one kernel when N <= 128)."""
+    import torch
+    _dev(x, "x", torch.float32)
+    _dev(x8_out, "x8_out", torch.uint8)
+    _dev(w8, "w8", torch.uint8)
+    _dev(out8, "out8", torch.uint8)
+    _dev(out8_t, "out8_t", torch.uint8)
+    _dev(acc, "acc", torch.float32)
+    ldw = N if ldw is None else ldw
+    if x.numel() != M * K or x8_out.numel() != M * K:
+        raise Mp8Error("x and x8_out must have M*K elements")
+    if K > 0 and N > 0 and w8.numel() < (K - 1) * ldw + N:
+        raise Mp8Error("w8 is smaller than its shape and leading dimension require")
+    for t, name in ((out8, "out8"), (out8_t, "out8_t"), (acc, "acc")):
+        if t is not None and t.numel() < M * N:
+            raise Mp8Error(f"{name} is smaller than M*N")
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = lib().mp8_quantize_gemm_fwd_fp8(M, N, K, _ptr(x), float(x_scale), x_round, x_flags, x_seed,
+                                         x_offset, _ptr(x_stats), _ptr(x8_out), _ptr(w8), ldw,
+                                         float(alpha), _ptr(acc), acc_mode, _ptr(out8), _ptr(out8_t),
+                                         round, flags, seed, offset, _ptr(stats), _ptr(workspace),
+                                         ws_bytes, _stream())
+    _check(st, "mp8_quantize_gemm_fwd_fp8")
     return out8
 
 

@@ -29,6 +29,7 @@
 #include "gemm_mfma.hpp"
 #include "gemm_shortk.hpp"
 #include "gemm_wavek.hpp"
+#include "gemm_qfwd.hpp"
 
 namespace mp8 {
 
@@ -448,6 +449,79 @@ extern "C" mp8_status mp8_gemm_fp8(mp8_op op, int64_t M, int64_t N, int64_t K, c
     return mp8_gemm_fp8_tuned(op, M, N, K, a, lda, b, ldb, alpha, acc, acc_mode, out8, out8_t,
                               round, flags, seed, offset, stats, workspace, workspace_bytes,
                               stream, 0, 0);
+}
+
+// ---------------------------------------------------------------------------------------
+// GEMMs that quantise their own FP32 operand
+
+extern "C" mp8_status mp8_quantize_gemm_fwd_fp8(int64_t M, int64_t N, int64_t K, const float *x,
+                                                float x_scale, mp8_round x_round, int x_flags,
+                                                uint64_t x_seed, uint64_t x_offset, mp8_stats *x_stats,
+                                                uint8_t *x8_out, const uint8_t *w8, int64_t ldw,
+                                                float alpha, float *acc, int acc_mode, uint8_t *out8,
+                                                uint8_t *out8_t, mp8_round round, int flags,
+                                                uint64_t seed, uint64_t offset, mp8_stats *stats,
+                                                void *workspace, size_t workspace_bytes, void *stream) {
+    using namespace mp8;
+    if (M < 0 || N < 0 || K < 0) return MP8_ERR_INVALID_ARG;
+    if ((x_round != MP8_RNE && x_round != MP8_SR) || (round != MP8_RNE && round != MP8_SR))
+        return MP8_ERR_INVALID_ARG;
+    if (acc_mode < 0 || acc_mode > 2) return MP8_ERR_INVALID_ARG;
+    if (M == 0) return MP8_OK;  // nothing to round, nothing to multiply
+    if (acc_mode != 0 && acc == nullptr && N > 0) return MP8_ERR_INVALID_ARG;
+    if (K > 0 && (!x || !x8_out)) return MP8_ERR_INVALID_ARG;
+    if (N > 0 && K > 0 && (!w8 || ldw < N)) return MP8_ERR_INVALID_ARG;
+    if (((uintptr_t)x | (uintptr_t)x8_out | (uintptr_t)acc | (uintptr_t)out8 | (uintptr_t)out8_t) & 15u)
+        return MP8_ERR_ALIGNMENT;
+    const bool fused = N >= 16 && N <= 128 && (N & 15) == 0 && K > 0 && (K & (BK - 1)) == 0 &&
+                       ((uintptr_t)w8 & 15u) == 0 && (ldw & 15) == 0 && ldw < (1 << 24) &&
+                       M <= (INT64_MAX / 8) / K && (M + 63) / 64 <= 0x7FFFFFFFLL;
+    if (!fused) {
+        // any other shape: the two calls this one stands for
+        const mp8_status sq = mp8_quantize_e5m2(x, 0, x8_out, nullptr, M, K, x_scale, x_round, x_flags,
+                                                x_seed, x_offset, x_stats, stream);
+        if (sq != MP8_OK) return sq;
+        return mp8_gemm_fp8(MP8_FWD, M, N, K, x8_out, K, w8, ldw, alpha, acc, acc_mode, out8, out8_t,
+                            round, (flags & MP8_FLAG_SATURATE) | MP8_FLAG_B_CONTRACTION_MAJOR, seed,
+                            offset, stats, workspace, workspace_bytes, stream);
+    }
+    GemmArgs ga{};
+    ga.b = w8;
+    ga.ldb = ldw;
+    ga.rows = M;
+    ga.cols = N;
+    ga.ksteps = (int)(K / BK);
+    ga.splits = 1;
+    Epilogue &ep = ga.ep;
+    ep.alpha = alpha;
+    ep.acc = acc_mode ? acc : nullptr;
+    ep.acc_mode = acc_mode;
+    ep.out8 = out8;
+    ep.out8_t = out8_t;
+    ep.sr = round == MP8_SR;
+    ep.sat = (flags & MP8_FLAG_SATURATE) ? 1 : 0;
+    ep.seed = seed;
+    ep.offset = offset;
+    ep.stats = stats;
+    ep.rows = M;
+    ep.cols = N;
+    QuantArgs qa{};
+    qa.x = x;
+    qa.x8 = x8_out;
+    qa.scale = x_scale;
+    qa.sr = x_round == MP8_SR;
+    qa.sat = (x_flags & MP8_FLAG_SATURATE) ? 1 : 0;
+    qa.seed = x_seed;
+    qa.offset = x_offset;
+    qa.stats = x_stats;
+    const bool plain = acc_mode == 0 && out8_t == nullptr && !ep.sr && !ep.sat && stats == nullptr &&
+                       out8 != nullptr;
+    const bool qplain = !qa.sr && !qa.sat && x_stats == nullptr;
+    void (*const kernel)(const GemmArgs, const QuantArgs) =
+        plain ? (qplain ? gemm_qfwd_kernel<EPI_RNE, true> : gemm_qfwd_kernel<EPI_RNE, false>)
+              : (qplain ? gemm_qfwd_kernel<EPI_FULL, true> : gemm_qfwd_kernel<EPI_FULL, false>);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)((M + 63) / 64)), dim3(256), 0, (hipStream_t)stream, ga, qa);
+    return hipGetLastError() == hipSuccess ? MP8_OK : MP8_ERR_HIP;
 }
 
 // ---------------------------------------------------------------------------------------
