@@ -520,7 +520,7 @@ extern "C" mp8_status mp8_quantize_gemm_fwd_fp8(int64_t M, int64_t N, int64_t K,
     void (*const kernel)(const GemmArgs, const QuantArgs) =
         plain ? (qplain ? gemm_qfwd_kernel<EPI_RNE, true> : gemm_qfwd_kernel<EPI_RNE, false>)
               : (qplain ? gemm_qfwd_kernel<EPI_FULL, true> : gemm_qfwd_kernel<EPI_FULL, false>);
-    hipLaunchKernelGGL(kernel, dim3((unsigned)((M + 63) / 64)), dim3(256), 0, (hipStream_t)stream, ga, qa);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)((M + 63) / 64)), dim3(512), 0, (hipStream_t)stream, ga, qa);
     return hipGetLastError() == hipSuccess ? MP8_OK : MP8_ERR_HIP;
 }
 
