@@ -47,8 +47,10 @@ LR = 1e-3
 # by what the same counters read on a plain 1 GiB copy (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000);
 # the runs and their raw figures are in profiles/bench_step_cfg2_hbm_traffic.txt
 MEASURED_TRAFFIC_BYTES = {
-    "quantize_X": 144555139, "quantize_dY": 16142644, "gemm_fwd": 33417730,
-    "gemm_bwd_data": 33494112, "gemm_wgrad_update": 51606442,
+    "quantize_X_gemm_fwd": 149061938, "quantize_dY": 16142644, "gemm_bwd_data": 33493088,
+    "gemm_wgrad_update": 51596816,
+    # with --separate-quantize (measured before the two were fused)
+    "quantize_X": 144555139, "gemm_fwd": 33417730,
 }
 
 
