@@ -517,10 +517,18 @@ extern "C" mp8_status mp8_quantize_gemm_fwd_fp8(int64_t M, int64_t N, int64_t K,
     const bool plain = acc_mode == 0 && out8_t == nullptr && !ep.sr && !ep.sat && stats == nullptr &&
                        out8 != nullptr;
     const bool qplain = !qa.sr && !qa.sat && x_stats == nullptr;
-    void (*const kernel)(const GemmArgs, const QuantArgs) =
-        plain ? (qplain ? gemm_qfwd_kernel<EPI_RNE, true> : gemm_qfwd_kernel<EPI_RNE, false>)
-              : (qplain ? gemm_qfwd_kernel<EPI_FULL, true> : gemm_qfwd_kernel<EPI_FULL, false>);
-    hipLaunchKernelGGL(kernel, dim3((unsigned)((M + 63) / 64)), dim3(512), 0, (hipStream_t)stream, ga, qa);
+    // 128 rows per workgroup once that still gives every other CU a workgroup
+    const bool tall = (M + 127) / 128 >= 128;
+    void (*kernel)(const GemmArgs, const QuantArgs);
+    if (tall)
+        kernel = plain ? (qplain ? gemm_qfwd_kernel<EPI_RNE, true, 128> : gemm_qfwd_kernel<EPI_RNE, false, 128>)
+                       : (qplain ? gemm_qfwd_kernel<EPI_FULL, true, 128> : gemm_qfwd_kernel<EPI_FULL, false, 128>);
+    else
+        kernel = plain ? (qplain ? gemm_qfwd_kernel<EPI_RNE, true, 64> : gemm_qfwd_kernel<EPI_RNE, false, 64>)
+                       : (qplain ? gemm_qfwd_kernel<EPI_FULL, true, 64> : gemm_qfwd_kernel<EPI_FULL, false, 64>);
+    const int bm = tall ? 128 : 64;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)((M + bm - 1) / bm)), dim3(4 * bm + 256), 0,
+                       (hipStream_t)stream, ga, qa);
     return hipGetLastError() == hipSuccess ? MP8_OK : MP8_ERR_HIP;
 }
 

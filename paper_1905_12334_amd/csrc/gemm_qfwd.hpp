@@ -26,16 +26,16 @@ __device__ __forceinline__ void wait_vm_lds_fence() {
 
 // y8[M, N] = Q(alpha * Q(x * scale)[M, K] . w8[K, N]) for N <= 128, writing Q(x * scale) as well.
 // With one column tile the activations are read exactly once by the GEMM, so the kernel that
-// rounds them can be the GEMM itself.  A workgroup owns 64 rows and has eight waves in two roles:
+// rounds them can be the GEMM itself.  A workgroup owns 64 (or 128) rows and has eight (twelve) waves in two roles:
 //
-//   waves 0-3, the readers: per 128-element stage of the contraction they load 64 x 128 FP32
+//   the first four (eight) waves, the readers: per 128-element stage of the contraction they load 64 x 128 FP32
 //     (16-byte loads, a wave's load covering 512 contiguous bytes of two rows, two stages in
 //     flight in registers), round each four to one dword of codes and put the codes into the
 //     row-major slab image of the MFMA kernels in LDS.  Their vector-memory queue holds nothing
 //     but these loads: the kernel moves 5 bytes per activation and 4 of them come through here.
-//   waves 4-7, the multipliers: one stage behind, they bring the weights' stage (128 contraction
+//   the last four waves, the multipliers: one stage behind, they bring the weights' stage (128 contraction
 //     rows x 128 columns, contraction-major, direct loads two stages ahead into a ring of three),
-//     multiply (wave 4 + v: rows 32 (v & 1) .., columns 64 (v >> 1) .. of the tile, transposing
+//     multiply (multiplier v: rows (BM/2) (v & 1) .., columns 64 (v >> 1) .. of the tile, transposing
 //     LDS reads for the weights), and copy the stage's codes from LDS to the 8-bit tensor in HBM
 //     as whole 128-byte lines.
 //
@@ -47,15 +47,24 @@ __device__ __forceinline__ void wait_vm_lds_fence() {
 // i - 1 (ksteps + 1 iterations).  Rows beyond the matrix are clamped to its last row in every
 // respect (source, random stream, destination): their threads recompute and rewrite that row's
 // codes, which keeps the number of memory operations per stage the same for every wave.
-// Multiplier's queue per iteration, in issue order: 4 direct loads (stage s + 2), 2 stores (stage
-// s); before the barrier it waits for the direct loads of stage s + 1, after which only the 2 + 4
-// + 2 younger operations may be outstanding.
+// Multiplier's queue per iteration, in issue order: 4 direct loads (stage s + 2), BM/32 stores
+// (stage s); before the barrier it waits for the direct loads of stage s + 1, after which only
+// the younger operations (stores, 4 loads, stores) may be outstanding.
 //
 // QPLAIN: the activations are rounded to nearest even without saturation or statistics (the
 // common case, kept free of the other cases' code).
-template <int EPI, bool QPLAIN>
-__global__ __launch_bounds__(512, 2) void gemm_qfwd_kernel(const GemmArgs p, const QuantArgs q) {
-    constexpr int BM = 64, A_STAGE = BM * BK, B_SLAB = BK * 64, B_STAGE = 2 * B_SLAB;
+//
+// BM = 64 or 128 rows per workgroup (4 or 8 reading waves, always 4 multiplying waves).  Every
+// workgroup passes over all of the weights once, and all workgroups want the same stage of them
+// at the same time; with 128 rows that traffic through the L2 halves (measured 3 us of the 32
+// at 64 rows), at the price of only ceil(M / 128) workgroups.
+template <int EPI, bool QPLAIN, int BM>
+__global__ __launch_bounds__(4 * BM + 256, BM == 64 ? 2 : 1) void gemm_qfwd_kernel(const GemmArgs p,
+                                                                                  const QuantArgs q) {
+    static_assert(BM == 64 || BM == 128, "rows per workgroup");
+    constexpr int READERS = 4 * BM;   // threads that read; 256 more multiply
+    constexpr int RB = BM / 64;       // 32-row blocks per multiplying wave
+    constexpr int A_STAGE = BM * BK, B_SLAB = BK * 64, B_STAGE = 2 * B_SLAB;
     __shared__ __attribute__((aligned(1024))) uint8_t lds[2 * A_STAGE + 3 * B_STAGE];
     uint8_t *lds_a = lds, *lds_b = lds + 2 * A_STAGE;
     const int lane = threadIdx.x & 63;
@@ -65,16 +74,16 @@ __global__ __launch_bounds__(512, 2) void gemm_qfwd_kernel(const GemmArgs p, con
     const int64_t kc = (int64_t)ksteps * BK;
     StatsAcc stx, st;
 
-    if (wave < 4) {
+    if (wave < READERS / 64) {
         // ---- readers: item u (0..7) of a thread is four elements (one 16-byte load, one dword of
-        // codes) of tile row 8u + t/32
+        // codes) of tile row (BM / 8) u + t/32
         const int trow = threadIdx.x >> 5, c4 = threadIdx.x & 31;
         const float *src[8];
         bool valid[8];
         uint32_t a_slot[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            const int row = 8 * u + trow;
+            const int row = (BM / 8) * u + trow;
             valid[u] = row0 + row < p.rows;
             const int64_t rr = valid[u] ? row0 + row : p.rows - 1;
             src[u] = q.x + rr * kc + 4 * c4;
@@ -138,7 +147,7 @@ __global__ __launch_bounds__(512, 2) void gemm_qfwd_kernel(const GemmArgs p, con
         __syncthreads();  // the multipliers' last iteration
     } else {
         // ---- multipliers
-        const int v = wave - 4, wr = v & 1, wc = v >> 1;
+        const int v = wave - READERS / 64, wr = v & 1, wc = v >> 1;
         // weights: wave v brings contraction rows 64 (v & 1) .. + 63 of the 64-column slab v >> 1;
         // a load covers 16 contraction rows of 64 bytes, lane l lands at (row l/4, slot l%4) and
         // fetches the chunk that belongs there under the swizzle of the narrow slabs
@@ -162,22 +171,25 @@ __global__ __launch_bounds__(512, 2) void gemm_qfwd_kernel(const GemmArgs p, con
         };
         // the codes of a stage go to HBM as 16-byte pieces: piece q of tile row r sits in slot
         // q ^ ((r >> 1) & 7) of the slab; eight lanes store one 128-byte line
-        const int ct = threadIdx.x - 256;
-        uint32_t piece_lds[2];
-        uint8_t *piece_dst[2];
+        constexpr int PIECES = BM / 32;  // per thread and stage
+        const int ct = threadIdx.x - READERS;
+        uint32_t piece_lds[PIECES];
+        uint8_t *piece_dst[PIECES];
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
+        for (int h = 0; h < PIECES; ++h) {
             const int pi = ct + 256 * h, row = pi >> 3, qq = pi & 7;
             const int64_t rr = row0 + row < p.rows ? row0 + row : p.rows - 1;
             piece_lds[h] = (uint32_t)(row * BK + ((qq ^ ((row >> 1) & 7)) << 4));
             piece_dst[h] = q.x8 + rr * kc + 16 * qq;
         }
 
-        f32x16 acc[2];
+        f32x16 acc[RB][2];
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int i = 0; i < RB; ++i)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[j][e] = 0.0f;
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
         const int frow = lane & 31, fkb = lane >> 5, t16 = lane & 15;
         const int fsw = (frow >> 1) & 7;
 
@@ -193,10 +205,7 @@ __global__ __launch_bounds__(512, 2) void gemm_qfwd_kernel(const GemmArgs p, con
             ring = ring == 2 ? 0 : ring + 1;
 #pragma unroll
             for (int sub = 0; sub < 2; ++sub) {
-                const uint8_t *ar = sa + (32 * wr + frow) * BK;
-                const i32x4 a0 = *reinterpret_cast<const i32x4 *>(ar + (((4 * sub + 2 * fkb) ^ fsw) << 4));
-                const i32x4 a1 = *reinterpret_cast<const i32x4 *>(ar + (((4 * sub + 2 * fkb + 1) ^ fsw) << 4));
-                const i32x8 av = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
+                i32x8 bv[2];
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
                     const int mc = (32 * j + (frow & 16)) >> 4;
@@ -208,43 +217,56 @@ __global__ __launch_bounds__(512, 2) void gemm_qfwd_kernel(const GemmArgs p, con
                         part[e] = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
                             (__attribute__((address_space(3))) i32x2 *)(sb + off));
                     }
-                    const i32x8 bv = {part[0].x, part[0].y, part[1].x, part[1].y,
-                                      part[2].x, part[2].y, part[3].x, part[3].y};
+                    bv[j] = i32x8{part[0].x, part[0].y, part[1].x, part[1].y,
+                                  part[2].x, part[2].y, part[3].x, part[3].y};
+                }
+#pragma unroll
+                for (int i = 0; i < RB; ++i) {
+                    const uint8_t *ar = sa + ((BM / 2) * wr + 32 * i + frow) * BK;
+                    const i32x4 a0 = *reinterpret_cast<const i32x4 *>(ar + (((4 * sub + 2 * fkb) ^ fsw) << 4));
+                    const i32x4 a1 = *reinterpret_cast<const i32x4 *>(ar + (((4 * sub + 2 * fkb + 1) ^ fsw) << 4));
+                    const i32x8 av = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
                     // bf8 x bf8, unscaled; b as the "row" matrix: a lane gets consecutive output columns
-                    acc[j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(bv, av, acc[j], 1, 1, 0, 0, 0, 0);
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(bv[j], av, acc[i][j], 1, 1, 0, 0, 0, 0);
                 }
             }
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
+            for (int h = 0; h < PIECES; ++h) {
                 const u32x4 o = *reinterpret_cast<const u32x4 *>(sa + piece_lds[h]);
                 *reinterpret_cast<u32x4 *>(piece_dst[h] + (int64_t)s * BK) = o;
             }
             // this wave's part of stage s + 1 of the weights, requested one iteration ago (before the
-            // loop for s = 0); younger: 2 stores (not for s = 0), 4 direct loads, 2 stores
-            if (s > 0) wait_vm_lds_fence<8>();
-            else wait_vm_lds_fence<6>();
+            // loop for s = 0); younger: the stores of stage s - 1 (not for s = 0), 4 direct loads, the
+            // stores of stage s
+            if (s > 0) wait_vm_lds_fence<4 + 2 * PIECES>();
+            else wait_vm_lds_fence<4 + PIECES>();
             __syncthreads();  // stage s + 1 of the codes and of the weights is complete
         }
         wait_vm_lds_fence<0>();  // the loads beyond the last stage
 
-        // acc[j][4g + e]: row 32 wr + lane%32, column 64 wc + 32 j + 8g + 4 (lane/32) + e; one
-        // exchange between the wave's halves leaves lane (row, h) with columns 16h .. 16h+15 of tile j
+        // acc[i][j][4g + e]: row (BM/2) wr + 32 i + lane%32, column 64 wc + 32 j + 8g + 4 (lane/32) + e;
+        // one exchange between the wave's halves leaves lane (row, h) with columns 16h .. 16h+15
         const bool fast_cols = (p.cols & 15) == 0;
-        const int64_t r = row0 + 32 * wr + frow;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            float vv[16];
+        for (int i = 0; i < RB; ++i) {
+            const int64_t r = row0 + (BM / 2) * wr + 32 * i + frow;
 #pragma unroll
-            for (int g = 0; g < 2; ++g)
+            for (int j = 0; j < 2; ++j) {
+                float vv[16];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const auto sw = __builtin_amdgcn_permlane32_swap(f2u(acc[j][4 * g + e]),
-                                                                     f2u(acc[j][4 * (g + 2) + e]), false, false);
-                    vv[8 * g + e] = u2f(sw[0]);
-                    vv[8 * g + 4 + e] = u2f(sw[1]);
-                }
-            const int64_t c = 64 * wc + 32 * j + 16 * fkb;
-            if (r < p.rows && c < p.cols) emit16<EPI>(p, 0, r, c, vv, st, fast_cols);
+                for (int g = 0; g < 2; ++g)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const auto sw = __builtin_amdgcn_permlane32_swap(f2u(acc[i][j][4 * g + e]),
+                                                                         f2u(acc[i][j][4 * (g + 2) + e]), false, false);
+                        vv[8 * g + e] = u2f(sw[0]);
+                        vv[8 * g + 4 + e] = u2f(sw[1]);
+                    }
+                const int64_t c = 64 * wc + 32 * j + 16 * fkb;
+                if (r < p.rows && c < p.cols) emit16<EPI>(p, 0, r, c, vv, st, fast_cols);
+            }
         }
     }
     if constexpr (!QPLAIN) {

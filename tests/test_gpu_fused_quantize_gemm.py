@@ -197,3 +197,38 @@ def test_fused_forward_full_size_layer(mp8):
     check_outputs(host(acc)[rows], host(out)[rows], ref, absref, K)
     assert np.array_equal(host(out), sout)
 
+
+
+def test_fused_forward_many_rows_every_option(mp8):
+    """Enough rows for the kernel variant with 128 rows per workgroup, a ragged last workgroup, and
+    every option at once (SR of the activations, saturation, special values, statistics of both
+    tensors, alpha, SR of the output, FP32 result); then the lean variant on the same data."""
+    from gpu_util import acc_tolerance_ok
+    M, N, K = 128 * 128 + 37, 48, 256
+    rng = np.random.default_rng(4242)
+    x = activations(rng, (M, K), specials=True)
+    w8 = finite_codes(rng, (K, N))
+    ost = oracle.Stats()
+    want8, _ = oracle.quantize_e5m2(x, scale=2.0, mode=oracle.SR, flags=1, seed=31, offset=2, stats=ost)
+    ref, absref = oracle.gemm_ref(want8, np.ascontiguousarray(w8.T))
+    x8, acc, out8, xst, st = run_fused(mp8, x, w8, x_scale=2.0, x_round=mp8.SR, x_flags=1, x_seed=31,
+                                       x_offset=2, alpha=0.5, round=mp8.SR, seed=8, offset=1, flags=1)
+    assert np.array_equal(x8, want8), "x8_out differs from the oracle's quantize"
+    assert xst == ost.as_tuple(), "statistics of x differ from the oracle's"
+    check_rounding_of_gpu_accumulator(acc, out8, 0.5, oracle.SR, 1, 8, 1)
+    assert np.array_equal(np.isnan(acc), np.isnan(ref)) and np.array_equal(np.isinf(acc), np.isinf(ref))
+    rows = moderate_rows(want8)
+    ok, worst, _ = acc_tolerance_ok(acc[rows], ref[rows], absref[rows], K)
+    assert ok, f"accumulator outside tolerance (worst ratio {worst})"
+    s8, sout, sxst, sst = separate_calls(mp8, x, w8, dict(scale=2.0, round=mp8.SR, flags=1, seed=31, offset=2),
+                                         dict(alpha=0.5, round=mp8.SR, seed=8, offset=1, flags=1))
+    assert np.array_equal(s8, x8) and np.array_equal(sout, out8) and sxst == xst and sst == st
+    # RNE, no statistics, no FP32 result
+    xp = activations(rng, (M, K), specials=False)
+    wantp, _ = oracle.quantize_e5m2(xp)
+    x8p, _, out8p, _, _ = run_fused(mp8, xp, w8, want_acc=False, with_x_stats=False, with_stats=False)
+    assert np.array_equal(x8p, wantp)
+    _, accp, out8q, _, _ = run_fused(mp8, xp, w8, with_x_stats=False, with_stats=False)
+    assert np.array_equal(out8q, out8p)
+    refp, absrefp = oracle.gemm_ref(wantp, np.ascontiguousarray(w8.T))
+    check_outputs(accp, out8p, refp, absrefp, K)
