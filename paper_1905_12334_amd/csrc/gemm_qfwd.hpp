@@ -29,8 +29,8 @@ __device__ __forceinline__ void wait_vm_lds_fence() {
 // rounds them can be the GEMM itself.  A workgroup owns 64 (or 128) rows and has eight (twelve) waves in two roles:
 //
 //   the first four (eight) waves, the readers: per 128-element stage of the contraction they load 64 x 128 FP32
-//     (16-byte loads, a wave's load covering 512 contiguous bytes of two rows, two stages in
-//     flight in registers), round each four to one dword of codes and put the codes into the
+//     (16-byte loads, a wave's load covering 512 contiguous bytes of two rows, two or three
+//     stages in flight in registers), round each four to one dword of codes and put the codes into the
 //     row-major slab image of the MFMA kernels in LDS.  Their vector-memory queue holds nothing
 //     but these loads: the kernel moves 5 bytes per activation and 4 of them come through here.
 //   the last four waves, the multipliers: one stage behind, they bring the weights' stage (128 contraction
@@ -64,6 +64,8 @@ __global__ __launch_bounds__(4 * BM + 256, BM == 64 ? 2 : 1) void gemm_qfwd_kern
     static_assert(BM == 64 || BM == 128, "rows per workgroup");
     constexpr int READERS = 4 * BM;   // threads that read; 256 more multiply
     constexpr int RB = BM / 64;       // 32-row blocks per multiplying wave
+    // stages of activations in flight: three where the registers allow it (768 threads, lean rounding)
+    constexpr int DEPTH = (BM == 128 && QPLAIN) ? 3 : 2;
     constexpr int A_STAGE = BM * BK, B_SLAB = BK * 64, B_STAGE = 2 * B_SLAB;
     __shared__ __attribute__((aligned(1024))) uint8_t lds[2 * A_STAGE + 3 * B_STAGE];
     uint8_t *lds_a = lds, *lds_b = lds + 2 * A_STAGE;
@@ -91,7 +93,7 @@ __global__ __launch_bounds__(4 * BM + 256, BM == 64 ? 2 : 1) void gemm_qfwd_kern
         }
         const Philox rng(q.seed, q.offset);
         const bool x_stats = q.stats != nullptr;
-        f32x4 f[2][8];
+        f32x4 f[DEPTH][8];
         // Stages beyond the last one are "loaded" too (the first 16 bytes of x in every lane): the
         // number of loads in flight is then the same in every iteration, and the compiler's
         // placement of the waits for them stays exact across the loop.
@@ -125,7 +127,7 @@ __global__ __launch_bounds__(4 * BM + 256, BM == 64 ? 2 : 1) void gemm_qfwd_kern
                     if (x_stats && valid[u]) stx.add4(y, codes[u]);
                 }
             }
-            issue_x(par, ks + 2);
+            issue_x(par, ks + DEPTH);
             uint8_t *sa = lds_a + (ks & 1) * A_STAGE;
 #pragma unroll
             for (int u = 0; u < 8; ++u) *reinterpret_cast<uint32_t *>(sa + a_slot[u]) = codes[u];
@@ -134,16 +136,33 @@ __global__ __launch_bounds__(4 * BM + 256, BM == 64 ? 2 : 1) void gemm_qfwd_kern
         // (the empty statements keep the two batches in this order: the compiler's bookkeeping of
         // loads in flight at the head of the loop is exact only if the way into the loop and the
         // way around it leave the same picture)
-        issue_x(std::integral_constant<int, 0>{}, 0);
+        const std::integral_constant<int, 0> c0{};
+        const std::integral_constant<int, 1> c1{};
+        issue_x(c0, 0);
         asm volatile("" ::: "memory");
-        issue_x(std::integral_constant<int, 1>{}, 1);
+        issue_x(c1, 1);
         asm volatile("" ::: "memory");
         int ks = 0;
-        for (; ks + 1 < ksteps; ks += 2) {  // whole pairs of stages: no way out of the middle
-            stage(std::integral_constant<int, 0>{}, ks);
-            stage(std::integral_constant<int, 1>{}, ks + 1);
+        if constexpr (DEPTH == 2) {
+            for (; ks + 1 < ksteps; ks += 2) {  // whole groups of stages: no way out of the middle
+                stage(c0, ks);
+                stage(c1, ks + 1);
+            }
+            if (ks < ksteps) stage(c0, ks);
+        } else {
+            const std::integral_constant<int, 2> c2{};
+            issue_x(c2, 2);
+            asm volatile("" ::: "memory");
+            for (; ks + 2 < ksteps; ks += 3) {
+                stage(c0, ks);
+                stage(c1, ks + 1);
+                stage(c2, ks + 2);
+            }
+            if (ks < ksteps) {
+                stage(c0, ks);
+                if (ks + 1 < ksteps) stage(c1, ks + 1);
+            }
         }
-        if (ks < ksteps) stage(std::integral_constant<int, 0>{}, ks);
         __syncthreads();  // the multipliers' last iteration
     } else {
         // ---- multipliers
