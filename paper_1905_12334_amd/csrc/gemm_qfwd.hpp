@@ -47,9 +47,9 @@ __device__ __forceinline__ void wait_vm_lds_fence() {
 // i - 1 (ksteps + 1 iterations).  Rows beyond the matrix are clamped to its last row in every
 // respect (source, random stream, destination): their threads recompute and rewrite that row's
 // codes, which keeps the number of memory operations per stage the same for every wave.
-// Multiplier's queue per iteration, in issue order: 4 direct loads (stage s + 2), BM/32 stores
-// (stage s); before the barrier it waits for the direct loads of stage s + 1, after which only
-// the younger operations (stores, 4 loads, stores) may be outstanding.
+// Multiplier's queue per iteration, in issue order: 4 direct loads (stage s + 2, while there is
+// one), BM/32 stores (stage s); before the barrier it waits for the direct loads of stage s + 1,
+// after which only the younger operations (stores, 4 loads, stores) may be outstanding.
 //
 // QPLAIN: the activations are rounded to nearest even without saturation or statistics (the
 // common case, kept free of the other cases' code).
@@ -181,9 +181,10 @@ __global__ __launch_bounds__(4 * BM + 256, BM == 64 ? 2 : 1) void gemm_qfwd_kern
                 ob[qq] = (uint32_t)((16 * (4 * (v & 1) + qq) + (lane >> 2)) * p.ldb + m);
         }
         const uint32_t lds_b0 = lds_address(lds_b) + (v >> 1) * B_SLAB + 4 * (v & 1) * 1024;
-        // stage ks into ring slot `ring` (= ks % 3); beyond the last stage, the last one again
+        // stage ks into ring slot `ring` (= ks % 3); nothing beyond the last stage
         auto issue_b = [&](int ks, int ring) {
-            const uint8_t *bk = b_base + (int64_t)(ks < ksteps ? ks : ksteps - 1) * BK * p.ldb;
+            if (ks >= ksteps) return;
+            const uint8_t *bk = b_base + (int64_t)ks * BK * p.ldb;
             const uint32_t s = lds_b0 + ring * B_STAGE;
 #pragma unroll
             for (int qq = 0; qq < 4; ++qq) dma16(bk, ob[qq], s + qq * 1024);
@@ -214,7 +215,8 @@ __global__ __launch_bounds__(4 * BM + 256, BM == 64 ? 2 : 1) void gemm_qfwd_kern
 
         issue_b(0, 0);
         issue_b(1, 1);
-        wait_vm_lds_fence<4>();  // stage 0 of the weights (this wave's part)
+        if (ksteps > 1) wait_vm_lds_fence<4>();  // stage 0 of the weights (this wave's part)
+        else wait_vm_lds_fence<0>();
         __syncthreads();         // iteration 0: the readers produce stage 0
         int ring = 0;            // ring slot of the weights of the current stage
         for (int s = 0; s < ksteps; ++s) {
@@ -259,11 +261,15 @@ __global__ __launch_bounds__(4 * BM + 256, BM == 64 ? 2 : 1) void gemm_qfwd_kern
             // this wave's part of stage s + 1 of the weights, requested one iteration ago (before the
             // loop for s = 0); younger: the stores of stage s - 1 (not for s = 0), 4 direct loads, the
             // stores of stage s
-            if (s > 0) wait_vm_lds_fence<4 + 2 * PIECES>();
-            else wait_vm_lds_fence<4 + PIECES>();
+            if (s + 2 < ksteps) {
+                if (s > 0) wait_vm_lds_fence<4 + 2 * PIECES>();
+                else wait_vm_lds_fence<4 + PIECES>();
+            } else {  // no direct loads were issued in this iteration
+                if (s > 0) wait_vm_lds_fence<2 * PIECES>();
+                else wait_vm_lds_fence<PIECES>();
+            }
             __syncthreads();  // stage s + 1 of the codes and of the weights is complete
         }
-        wait_vm_lds_fence<0>();  // the loads beyond the last stage
 
         // acc[i][j][4g + e]: row (BM/2) wr + 32 i + lane%32, column 64 wc + 32 j + 8g + 4 (lane/32) + e;
         // one exchange between the wave's halves leaves lane (row, h) with columns 16h .. 16h+15

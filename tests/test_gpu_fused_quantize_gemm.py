@@ -232,3 +232,33 @@ def test_fused_forward_many_rows_every_option(mp8):
     assert np.array_equal(out8q, out8p)
     refp, absrefp = oracle.gemm_ref(wantp, np.ascontiguousarray(w8.T))
     check_outputs(accp, out8p, refp, absrefp, K)
+
+
+def test_fused_forward_rejects_bad_arguments_and_enqueues_nothing(mp8):
+    """Null or misaligned tensors, a weight row stride below N, bad enums: a status, and the outputs
+    stay as they were."""
+    import torch
+    M, N, K = 64, 64, 128
+    x = torch.ones((M, K), dtype=torch.float32, device="cuda")
+    w8 = torch.full((K, N), 0x3C, dtype=torch.uint8, device="cuda")
+    x8 = torch.full((M * K + 16,), 0xAA, dtype=torch.uint8, device="cuda")
+    out = torch.full((M * N + 16,), 0xAA, dtype=torch.uint8, device="cuda")
+    good = dict(out8=out[: M * N])
+    bad_calls = [
+        lambda: mp8.quantize_gemm_fwd_fp8(M, N, K, x, x8[: M * K], w8, ldw=N - 16, **good),       # row stride < N
+        lambda: mp8.quantize_gemm_fwd_fp8(M, N, K, x, x8[1: M * K + 1], w8, **good),               # misaligned x8_out
+        lambda: mp8.quantize_gemm_fwd_fp8(M, N, K, x, x8[: M * K], w8, out8=out[1: M * N + 1]),    # misaligned out8
+        lambda: mp8.quantize_gemm_fwd_fp8(M, N, K, x, x8[: M * K], w8, x_round=7, **good),         # bad rounding mode
+        lambda: mp8.quantize_gemm_fwd_fp8(M, N, K, x, x8[: M * K], w8, round=-1, **good),
+        lambda: mp8.quantize_gemm_fwd_fp8(M, N, K, x, x8[: M * K], w8, acc_mode=1, **good),        # acc_mode without acc
+        lambda: mp8.quantize_gemm_fwd_fp8(M, N, K, x, x8[: M * K], w8, acc_mode=3, **good),
+    ]
+    for call in bad_calls:
+        with pytest.raises(mp8.Mp8Error):
+            call()
+    torch.cuda.synchronize()
+    assert bool((x8 == 0xAA).all()) and bool((out == 0xAA).all()), "a rejected call wrote something"
+    # and the same call with good arguments works: 1.0 * 1.0 summed over K = 128
+    mp8.quantize_gemm_fwd_fp8(M, N, K, x, x8[: M * K], w8, **good)
+    torch.cuda.synchronize()
+    assert bool((x8[: M * K] == 0x3C).all()) and bool((out[: M * N] == oracle.e5m2_encode(128.0)).all())
