@@ -68,6 +68,8 @@ def parse_args():
     ap.add_argument("--separate-quantize", action="store_true",
                     help="activations quantised by a call of their own (mp8_quantize_e5m2, "
                          "mp8_gemm_fp8) instead of inside the forward GEMM (mp8_quantize_gemm_fwd_fp8)")
+    ap.add_argument("--two-streams", action="store_true",
+                    help="error path (Q(dY), backward data) on a second stream beside the activation path")
     ap.add_argument("--batch-quantize", action="store_true",
                     help="run the two Q nodes of the step as one mp8_quantize_e5m2_batch launch")
     ap.add_argument("--kernel-reps", type=int, default=50,
@@ -111,7 +113,8 @@ class StatsRing:
 class Workload:
     """Device buffers and launch closures for the configs[1] layer."""
 
-    def __init__(self, mp8, torch, lay, batch_quantize=False, fused_update=False, fused_quantize=False):
+    def __init__(self, mp8, torch, lay, batch_quantize=False, fused_update=False, fused_quantize=False,
+                 two_streams=False):
         self.mp8, self.torch = mp8, torch
         M, N, K = lay.M, lay.N, lay.K
         self.M, self.N, self.K = M, N, K
@@ -179,6 +182,7 @@ class Workload:
             self.kernels = [by_name[n] for n in order] + [k for k in self.kernels if k[0] not in order]
         # the weights of the first step: Q(W16), outside the timed region
         mp8_.quantize_e5m2(self.W16.view(K, N), self.W8)
+        self.side = torch.cuda.Stream() if two_streams else None
 
     def _wgrad_update(self):
         self.step_no += 1
@@ -203,8 +207,24 @@ class Workload:
 
     def step(self):
         self.ring.advance()
-        for _, fn, _, _, _ in self.kernels:
+        if self.side is None:
+            for _, fn, _, _, _ in self.kernels:
+                fn()
+            return
+        # the error path beside the activation path; both need the previous step's weights, the
+        # weight gradient needs both
+        torch = self.torch
+        main = torch.cuda.current_stream()
+        error_path = [k for k in self.kernels if k[0] in ("quantize_dY", "gemm_bwd_data")]
+        rest = [k for k in self.kernels if k not in error_path]
+        self.side.wait_stream(main)
+        with torch.cuda.stream(self.side):
+            for _, fn, _, _, _ in error_path:
+                fn()
+        for _, fn, _, _, _ in rest[:-1]:
             fn()
+        main.wait_stream(self.side)
+        rest[-1][1]()
 
 
 class ConvWorkload:
@@ -529,7 +549,7 @@ def main():
     props = torch.cuda.get_device_properties(0)
     lay = workloads.config2()
     wl = Workload(mp8, torch, lay, batch_quantize=args.batch_quantize, fused_update=not args.separate_update,
-                  fused_quantize=not args.separate_quantize)
+                  fused_quantize=not args.separate_quantize, two_streams=args.two_streams)
     for _ in range(args.warmup):
         wl.step()
     ms_per_step = time_steps(torch, wl, args.steps, args.launch)
