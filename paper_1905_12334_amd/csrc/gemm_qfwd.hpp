@@ -39,9 +39,12 @@ __device__ __forceinline__ void wait_vm_lds_fence() {
 //     LDS reads for the weights), and copy the stage's codes from LDS to the 8-bit tensor in HBM
 //     as whole 128-byte lines.
 //
-// The split is there because a wave's memory operations complete in issue order: with loads,
-// direct loads and stores in one queue every activation load also waited for the stores and
-// weight loads issued before it (measured: 32 us against 21 us for the loads alone).
+// What the split buys is bookkeeping, not time (a version with four waves that did everything
+// took the same 32 us at 64 rows): a wave's memory operations complete in issue order, and with
+// activation loads (which the compiler sees and places waits for), direct loads (which it does
+// not) and stores in one queue, neither its counts nor hand-written ones stay simple.  Here the
+// readers' queue holds nothing but loads the compiler knows, and only the multipliers count by
+// hand; and the codes leave as whole lines instead of dwords.
 //
 // One barrier per iteration; iteration i: readers produce stage i, multipliers consume stage
 // i - 1 (ksteps + 1 iterations).  Rows beyond the matrix are clamped to its last row in every
