@@ -313,6 +313,30 @@ mp8_status mp8_quantize_gemm_fwd_fp8(int64_t M, int64_t N, int64_t K, const floa
                                      uint64_t offset, mp8_stats *stats, void *workspace,
                                      size_t workspace_bytes, void *stream);
 
+/*
+ * mp8_wgrad_update_fp16_sr and mp8_conv3x3_wgrad_update_fp16_sr with the momentum optimizer of
+ * mp8_sgd_momentum_fp16_sr in the finishing pass (the weight-update path of Figure 1b passes the
+ * un-scaled gradients to a momentum optimizer): velocity [K, N] (or [3, 3, Cin, Cout]) FP32, in/out, 16-byte aligned; momentum
+ * and weight_decay as there; every other argument as in the calls they extend.  The results --
+ * gradient codes, master weights, velocity, 8-bit weights -- are bit for bit those of the
+ * weight-gradient call followed by mp8_sgd_momentum_fp16_sr.
+ */
+mp8_status mp8_wgrad_momentum_fp16_sr(int64_t M, int64_t N, int64_t K, const uint8_t *a, int64_t lda,
+                                      const uint8_t *b, int64_t ldb, float alpha, uint8_t *g8_out,
+                                      mp8_round g_round, int flags, uint64_t g_seed, uint64_t g_offset,
+                                      mp8_stats *stats, uint16_t *w16, float *velocity, float lr,
+                                      float inv_loss_scale, float momentum, float weight_decay,
+                                      mp8_round w_round, uint64_t w_seed, uint64_t w_offset,
+                                      const uint32_t *skip_if_nonzero, uint8_t *w8_out, void *workspace,
+                                      size_t workspace_bytes, void *stream);
+mp8_status mp8_conv3x3_wgrad_momentum_fp16_sr(
+    int64_t B, int64_t H, int64_t W, int64_t Cin, int64_t Cout, int64_t prows, const uint8_t *x8,
+    const uint8_t *e8, float alpha, uint8_t *g8_out, mp8_round g_round, int flags, uint64_t g_seed,
+    uint64_t g_offset, mp8_stats *stats, uint16_t *w16, float *velocity, float lr, float inv_loss_scale,
+    float momentum, float weight_decay, mp8_round w_round, uint64_t w_seed, uint64_t w_offset,
+    const uint32_t *skip_if_nonzero, uint8_t *w8_out, void *workspace, size_t workspace_bytes,
+    void *stream);
+
 /* out[i] = the 16 random bits element i would use (device array of n uint16), for tests. */
 mp8_status mp8_sr_bits(uint16_t *out, int64_t n, uint64_t seed, uint64_t offset, void *stream);
 

@@ -440,6 +440,46 @@ extern "C" mp8_status mp8_wgrad_update_fp16_sr(int64_t M, int64_t N, int64_t K, 
                                   skip_if_nonzero, w8_out, nullptr, stream);
 }
 
+extern "C" mp8_status mp8_wgrad_momentum_fp16_sr(int64_t M, int64_t N, int64_t K, const uint8_t *a, int64_t lda,
+                                                 const uint8_t *b, int64_t ldb, float alpha, uint8_t *g8_out,
+                                                 mp8_round g_round, int flags, uint64_t g_seed,
+                                                 uint64_t g_offset, mp8_stats *stats, uint16_t *w16,
+                                                 float *velocity, float lr, float inv_loss_scale,
+                                                 float momentum, float weight_decay, mp8_round w_round,
+                                                 uint64_t w_seed, uint64_t w_offset,
+                                                 const uint32_t *skip_if_nonzero, uint8_t *w8_out,
+                                                 void *workspace, size_t workspace_bytes, void *stream) {
+    using namespace mp8;
+    if (M < 0 || N < 0 || K < 0) return MP8_ERR_INVALID_ARG;
+    if (w_round != MP8_RNE && w_round != MP8_SR) return MP8_ERR_INVALID_ARG;
+    if (K == 0 || N == 0) return MP8_OK;
+    if (!w16 || !velocity) return MP8_ERR_INVALID_ARG;
+    if (((uintptr_t)w16 | (uintptr_t)w8_out | (uintptr_t)velocity) & 15u) return MP8_ERR_ALIGNMENT;
+    UpdateHook upd{};
+    upd.w16 = w16;
+    upd.w8_out = w8_out;
+    upd.skip = skip_if_nonzero;
+    upd.neg_lr = -lr;
+    upd.inv_scale = inv_loss_scale;
+    upd.sr = w_round == MP8_SR;
+    upd.seed = w_seed;
+    upd.offset = w_offset;
+    upd.velocity = velocity;
+    upd.mu = momentum;
+    upd.wd = weight_decay;
+    const mp8_status st = gemm_impl(MP8_WGRAD, M, N, K, a, lda, b, ldb, alpha, nullptr, 0, g8_out, nullptr,
+                                    g_round, flags, g_seed, g_offset, stats, workspace, workspace_bytes,
+                                    stream, 0, 0, &upd);
+    if (st != MP8_ERR_UNSUPPORTED || g8_out == nullptr) return st;
+    // shapes that only the any-shape kernel takes: two launches through the 8-bit gradient
+    const mp8_status sg = mp8_gemm_fp8(MP8_WGRAD, M, N, K, a, lda, b, ldb, alpha, nullptr, 0, g8_out, nullptr,
+                                       g_round, flags, g_seed, g_offset, stats, workspace, workspace_bytes,
+                                       stream);
+    if (sg != MP8_OK) return sg;
+    return mp8_sgd_momentum_fp16_sr(w16, velocity, g8_out, K * N, lr, inv_loss_scale, momentum, weight_decay,
+                                    w_round, w_seed, w_offset, skip_if_nonzero, w8_out, nullptr, stream);
+}
+
 extern "C" mp8_status mp8_gemm_fp8(mp8_op op, int64_t M, int64_t N, int64_t K, const uint8_t *a,
                                    int64_t lda, const uint8_t *b, int64_t ldb, float alpha,
                                    float *acc, int acc_mode, uint8_t *out8, uint8_t *out8_t,
@@ -666,6 +706,34 @@ extern "C" mp8_status mp8_conv3x3_wgrad_update_fp16_sr(
     upd.sr = w_round == MP8_SR;
     upd.seed = w_seed;
     upd.offset = w_offset;
+    return conv_impl(MP8_WGRAD, B, H, W, Ci, Co, prows, x8, e8, alpha, nullptr, 0, g8_out, g_round, flags,
+                     g_seed, g_offset, stats, workspace, workspace_bytes, stream, &upd);
+}
+
+extern "C" mp8_status mp8_conv3x3_wgrad_momentum_fp16_sr(
+    int64_t B, int64_t H, int64_t W, int64_t Ci, int64_t Co, int64_t prows, const uint8_t *x8,
+    const uint8_t *e8, float alpha, uint8_t *g8_out, mp8_round g_round, int flags, uint64_t g_seed,
+    uint64_t g_offset, mp8_stats *stats, uint16_t *w16, float *velocity, float lr, float inv_loss_scale,
+    float momentum, float weight_decay, mp8_round w_round, uint64_t w_seed, uint64_t w_offset,
+    const uint32_t *skip_if_nonzero, uint8_t *w8_out, void *workspace, size_t workspace_bytes,
+    void *stream) {
+    using namespace mp8;
+    if (w_round != MP8_RNE && w_round != MP8_SR) return MP8_ERR_INVALID_ARG;
+    if (B == 0 || H == 0 || W == 0 || Ci == 0 || Co == 0) return MP8_OK;
+    if (!w16 || !velocity) return MP8_ERR_INVALID_ARG;
+    if (((uintptr_t)w16 | (uintptr_t)w8_out | (uintptr_t)velocity) & 15u) return MP8_ERR_ALIGNMENT;
+    UpdateHook upd{};
+    upd.w16 = w16;
+    upd.w8_out = w8_out;
+    upd.skip = skip_if_nonzero;
+    upd.neg_lr = -lr;
+    upd.inv_scale = inv_loss_scale;
+    upd.sr = w_round == MP8_SR;
+    upd.seed = w_seed;
+    upd.offset = w_offset;
+    upd.velocity = velocity;
+    upd.mu = momentum;
+    upd.wd = weight_decay;
     return conv_impl(MP8_WGRAD, B, H, W, Ci, Co, prows, x8, e8, alpha, nullptr, 0, g8_out, g_round, flags,
                      g_seed, g_offset, stats, workspace, workspace_bytes, stream, &upd);
 }

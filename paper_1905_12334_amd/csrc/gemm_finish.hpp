@@ -56,11 +56,27 @@ struct UpdateHook {
     float neg_lr, inv_scale;
     int sr;
     uint64_t seed, offset;
+    float *velocity;  // non-null: momentum SGD with L2 regularisation (MomentumRule), state in place
+    float mu, wd;
 };
 
+// One master weight from its gradient code: plain SGD, or the momentum rule when the hook
+// carries a velocity array -- the same arithmetic as the stand-alone update kernels.
+__device__ __forceinline__ uint32_t hook_one(const UpdateHook &u, uint32_t w16, uint32_t code, float *vel,
+                                             uint32_t r16) {
+    if (u.velocity != nullptr) {
+        const MomentumRule rule{u.neg_lr, u.mu, u.wd};
+        return u.sr ? rule_one<true>(rule, w16, code, vel, u.inv_scale, r16)
+                    : rule_one<false>(rule, w16, code, vel, u.inv_scale, 0u);
+    }
+    return u.sr ? update_one<true>(w16, code, u.neg_lr, u.inv_scale, r16)
+                : update_one<false>(w16, code, u.neg_lr, u.inv_scale, 0u);
+}
+
 __device__ __forceinline__ void update_element(const UpdateHook &u, int64_t i, uint32_t code, uint32_t r16) {
-    const uint32_t h = u.sr ? update_one<true>(u.w16[i], code, u.neg_lr, u.inv_scale, r16)
-                            : update_one<false>(u.w16[i], code, u.neg_lr, u.inv_scale, 0u);
+    float vel = u.velocity != nullptr ? u.velocity[i] : 0.0f;
+    const uint32_t h = hook_one(u, u.w16[i], code, &vel, r16);
+    if (u.velocity != nullptr) u.velocity[i] = vel;
     u.w16[i] = (uint16_t)h;
     if (u.w8_out != nullptr) u.w8_out[i] = (uint8_t)e5m2_of_half(h);
 }
@@ -79,11 +95,19 @@ __device__ __forceinline__ void update4(const UpdateHook &u, int64_t i0, uint32_
     uint32_t h[4];
     const uint32_t w16v[4] = {wr.x & 0xFFFFu, wr.x >> 16, wr.y & 0xFFFFu, wr.y >> 16};
     const uint32_t r16[4] = {r01 & 0xFFFFu, r01 >> 16, r23 & 0xFFFFu, r23 >> 16};
+    float vel[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (u.velocity != nullptr) {
+        const f32x4 vv = *reinterpret_cast<const f32x4 *>(u.velocity + i0);
+        vel[0] = vv.x; vel[1] = vv.y; vel[2] = vv.z; vel[3] = vv.w;
+    }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const uint32_t code = (pk >> (8 * j)) & 0xFFu;
-        h[j] = u.sr ? update_one<true>(w16v[j], code, u.neg_lr, u.inv_scale, r16[j])
-                    : update_one<false>(w16v[j], code, u.neg_lr, u.inv_scale, 0u);
+        h[j] = hook_one(u, w16v[j], code, &vel[j], r16[j]);
+    }
+    if (u.velocity != nullptr) {
+        const f32x4 vv = {vel[0], vel[1], vel[2], vel[3]};
+        *reinterpret_cast<f32x4 *>(u.velocity + i0) = vv;
     }
     const u32x2 o = {h[0] | (h[1] << 16), h[2] | (h[3] << 16)};
     *wp = o;

@@ -354,4 +354,55 @@ __device__ __forceinline__ uint32_t e5m2_of_half(uint32_t h) {
                                      false);
 }
 
+// Optimizers with FP32 state in front of the same conversion.  A rule turns the un-scaled
+// gradient g, the weight w and its state words into the new FP32 weight; every operation is a
+// separately rounded FP32 operation in the order written (the build forbids contraction).
+//
+// Momentum with the L2 regularisation gradient:   g += wd * w;  v' = mu * v + g;  w' = w - lr * v'
+struct MomentumRule {
+    static constexpr int kStates = 1;
+    float neg_lr, mu, wd;
+    __device__ __forceinline__ float operator()(float w, float g, float *st) const {
+        g = __builtin_fmaf(wd, w, g);
+        const float v = __builtin_fmaf(mu, st[0], g);
+        st[0] = v;
+        return __builtin_fmaf(neg_lr, v, w);
+    }
+};
+
+// ADAM (Kingma & Ba, Algorithm 1) with the same regularisation gradient:
+//   m' = b1 * m + (1 - b1) * g;  v' = b2 * v + (1 - b2) * g^2
+//   w' = w - lr * (m' / c1) / (sqrt(v' / c2) + eps),   c_i = 1 - b_i^step (from the host)
+// Division and square root are the correctly rounded IEEE operations (the compiler's default
+// for FP32 `/` and sqrt in HIP code; the approximate intrinsics are not used).
+struct AdamRule {
+    static constexpr int kStates = 2;
+    float neg_lr, b1, b2, omb1, omb2, c1, c2, eps, wd;
+    __device__ __forceinline__ float operator()(float w, float g, float *st) const {
+        g = __builtin_fmaf(wd, w, g);
+        const float m = __builtin_fmaf(b1, st[0], omb1 * g);
+        const float v = __builtin_fmaf(b2, st[1], omb2 * (g * g));
+        st[0] = m;
+        st[1] = v;
+        const float mhat = m / c1, vhat = v / c2;
+        const float upd = mhat / (__builtin_sqrtf(vhat) + eps);
+        return __builtin_fmaf(neg_lr, upd, w);
+    }
+};
+
+template <bool kSR, class Rule>
+__device__ __forceinline__ uint32_t rule_one(const Rule &rule, uint32_t w16, uint32_t g8, float *st,
+                                             float inv_scale, uint32_t r16) {
+    const float g = e5m2_to_f32(g8) * inv_scale;
+    const float w = __half2float(__ushort_as_half((unsigned short)w16));
+    float wn = rule(w, g, st);
+    asm volatile("" : "+v"(wn));  // keep the conversion a separate, second rounding
+    if constexpr (kSR) {
+        return f16_from_f32_bits<true>(f2u(wn), r16);
+    } else {
+        uint32_t h = __half_as_ushort(__float2half_rn(wn));
+        return (wn != wn) ? 0x7E00u : h;
+    }
+}
+
 }  // namespace mp8

@@ -114,6 +114,36 @@ def test_conv_weight_gradient_and_update_in_one_call(mp8):
     assert np.array_equal(host(wd).view(np.uint16), want_w) and np.array_equal(host(w8), want_w8)
 
 
+def test_conv_weight_gradient_and_momentum_update_in_one_call(mp8):
+    """mp8_conv3x3_wgrad_momentum_fp16_sr against the oracle's chain (direct convolution weight
+    gradient -> one rounding -> momentum update with L2 regularisation) on exact-sum operands, two
+    steps in a row: gradient codes, master weights, velocity and 8-bit weights bit for bit."""
+    import torch
+    B, H, W, Ci, Co = 2, 6, 5, 128, 128
+    rng = np.random.default_rng(78)
+    x, e = exact_codes(rng, (B, H, W, Ci)), exact_codes(rng, (B, H, W, Co))
+    ref, _ = oracle.conv3x3_ref("wgrad", x, e, want_abs=False)
+    w_ref = (rng.standard_normal(9 * Ci * Co) * 0.05).astype(np.float16).view(np.uint16)
+    v_ref = (rng.standard_normal(9 * Ci * Co) * 0.01).astype(np.float32)
+    alpha, lr, inv, mu, wd_ = 1.0 / 32, 0.05, 1.0 / 16, 0.9, 1e-3
+    want_g = oracle.round_ref_e5m2(ref, alpha=alpha).reshape(-1)
+    xd, ed = to_padded(mp8, x), to_padded(mp8, e)
+    ws = torch.empty(max(mp8.conv3x3_fp8_workspace_bytes(mp8.WGRAD, B, H, W, Ci, Co), 16), dtype=torch.uint8, device="cuda")
+    wdev, vdev = gpu(w_ref.view(np.int16)), gpu(v_ref)
+    g8 = torch.full((9 * Ci * Co,), 0xAA, dtype=torch.uint8, device="cuda")
+    w8 = torch.full((9 * Ci * Co,), 0x55, dtype=torch.uint8, device="cuda")
+    for step in (1, 2):
+        w_ref, v_ref, want_w8 = oracle.sgd_momentum_fp16(w_ref, v_ref, want_g, lr, inv, mu, wd_, mode=oracle.SR,
+                                                         seed=5, offset=step, want_w8=True)
+        mp8.conv3x3_wgrad_momentum_fp16_sr(B, H, W, Ci, Co, xd, ed, wdev, vdev, lr, inv, mu, wd_, g8_out=g8,
+                                           alpha=alpha, w_round=mp8.SR, w_seed=5, w_offset=step, w8_out=w8,
+                                           workspace=ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(host(g8), want_g)
+        assert np.array_equal(host(wdev).view(np.uint16), w_ref) and np.array_equal(host(w8), want_w8)
+        assert np.array_equal(host(vdev).view(np.uint32), v_ref.view(np.uint32))
+
+
 def test_conv_random_operands_sr_epilogue_and_statistics(mp8):
     B, H, W, Ci, Co = 2, 7, 9, 128, 128
     dims = (B, H, W, Ci, Co)

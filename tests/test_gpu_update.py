@@ -264,3 +264,69 @@ def test_weight_gradient_and_update_in_one_call_against_the_oracle_chain(mp8, la
                                      skip_if_nonzero=flag, workspace=ws)
             torch.cuda.synchronize()
             assert torch.equal(wd2, wd)
+
+
+@pytest.mark.parametrize("layout", ["row-major", "contraction-major"])
+def test_weight_gradient_and_momentum_update_in_one_call_against_the_oracle_chain(mp8, layout):
+    """mp8_wgrad_momentum_fp16_sr over two consecutive steps (the velocity carries over) on exact-sum
+    operands: gradient codes, master weights, velocity and 8-bit weights bit for bit the oracle's
+    chain GEMM -> one rounding -> momentum update with L2 regularisation; split and unsplit
+    contractions, a ragged column count, RNE and SR, the skip flag."""
+    import torch
+    from test_gpu_gemm import exact_sum_codes
+    rng = np.random.default_rng(29)
+    for (M, N, K) in ((1024, 64, 256), (512, 50, 128), (8192, 64, 64)):
+        if layout == "contraction-major" and N % 16:
+            continue
+        xt, et = exact_sum_codes(rng, (K, M)), exact_sum_codes(rng, (N, M))
+        if M == 8192:
+            xt[:, rng.random(M) < 0.75] = 0
+        ref, _ = oracle.gemm_ref(xt, et, want_abs=False)
+        alpha, lr, inv, mu, wd_ = 2.0 ** -9, 0.05, 1.0 / 64, 0.9, 1e-3
+        if layout == "row-major":
+            a, b, flags = gpu(xt), gpu(et), 0
+        else:
+            a, b, flags = gpu(np.ascontiguousarray(xt.T)), gpu(np.ascontiguousarray(et.T)), mp8.FLAG_CONTRACTION_MAJOR
+        ws = torch.empty(max(mp8.gemm_fp8_workspace_bytes(mp8.WGRAD, M, N, K), 16), dtype=torch.uint8, device="cuda")
+        for g_round, w_round, skip in ((oracle.RNE, oracle.SR, 0), (oracle.SR, oracle.RNE, 0), (oracle.RNE, oracle.SR, 2)):
+            w_ref = (rng.standard_normal(K * N) * 0.05).astype(np.float16).view(np.uint16)
+            v_ref = (rng.standard_normal(K * N) * 0.01).astype(np.float32)
+            wdev, vdev = gpu(w_ref.view(np.int16)), gpu(v_ref)
+            g8 = torch.full((K * N + 64,), 0xAA, dtype=torch.uint8, device="cuda")
+            w8 = torch.full((K * N + 64,), 0x55, dtype=torch.uint8, device="cuda")
+            flag = torch.full((1,), skip, dtype=torch.int32, device="cuda")
+            for step in (1, 2):
+                want_g = oracle.quantize_e5m2(ref.astype(np.float32), scale=alpha, mode=g_round, seed=31, offset=step)[0]
+                w_ref, v_ref, want_w8 = oracle.sgd_momentum_fp16(w_ref, v_ref, want_g.reshape(-1), lr, inv, mu, wd_,
+                                                                 mode=w_round, seed=33, offset=step,
+                                                                 skip=skip or None, want_w8=True)
+                mp8.wgrad_momentum_fp16_sr(M, N, K, a, b, wdev, vdev, lr, inv, mu, wd_, g8_out=g8[: K * N],
+                                           alpha=alpha, g_round=g_round, flags=flags, g_seed=31, g_offset=step,
+                                           w_round=w_round, w_seed=33, w_offset=step, skip_if_nonzero=flag,
+                                           w8_out=w8[: K * N], workspace=ws)
+                torch.cuda.synchronize()
+                assert np.array_equal(host(g8[: K * N]).reshape(K, N), want_g), (M, N, K, g_round, step)
+                assert np.array_equal(host(wdev).view(np.uint16), w_ref), (M, N, K, w_round, skip, step)
+                assert np.array_equal(host(vdev).view(np.uint32), v_ref.view(np.uint32)), (M, N, K, skip, step)
+                if skip:
+                    assert bool((w8[: K * N] == 0x55).all())
+                else:
+                    assert np.array_equal(host(w8[: K * N]), want_w8)
+            assert bool((g8[K * N:] == 0xAA).all()) and bool((w8[K * N:] == 0x55).all())
+    # and on random operands: the one call equals the two calls it stands for
+    M, N, K = 4736, 128, 384
+    x8 = workloads.random_e5m2_codes(5, (M, K)) & 0xBF
+    e8 = workloads.random_e5m2_codes(6, (M, N)) & 0xBF
+    a, b = gpu(x8), gpu(e8)
+    ws = torch.empty(max(mp8.gemm_fp8_workspace_bytes(mp8.WGRAD, M, N, K), 16), dtype=torch.uint8, device="cuda")
+    w0 = (rng.standard_normal(K * N) * 0.05).astype(np.float16).view(np.int16)
+    v0 = (rng.standard_normal(K * N) * 0.01).astype(np.float32)
+    w1, v1, g1, q1 = gpu(w0), gpu(v0), torch.zeros(K * N, dtype=torch.uint8, device="cuda"), torch.zeros(K * N, dtype=torch.uint8, device="cuda")
+    mp8.wgrad_momentum_fp16_sr(M, N, K, a, b, w1, v1, 0.01, 1 / 16, 0.9, 5e-4, g8_out=g1, flags=mp8.FLAG_CONTRACTION_MAJOR,
+                               w_seed=3, w_offset=4, w8_out=q1, workspace=ws)
+    w2, v2, g2, q2 = gpu(w0), gpu(v0), torch.zeros((K, N), dtype=torch.uint8, device="cuda"), torch.zeros(K * N, dtype=torch.uint8, device="cuda")
+    mp8.gemm_fp8(mp8.WGRAD, M, N, K, a, b, out8=g2, flags=mp8.FLAG_CONTRACTION_MAJOR, workspace=ws)
+    mp8.sgd_momentum_fp16_sr(w2, v2, g2.view(-1), 0.01, 1 / 16, 0.9, 5e-4, round=mp8.SR, seed=3, offset=4, w8_out=q2)
+    torch.cuda.synchronize()
+    assert torch.equal(g1, g2.view(-1)) and torch.equal(w1, w2) and torch.equal(v1.view(torch.int32), v2.view(torch.int32))
+    assert torch.equal(q1, q2)
