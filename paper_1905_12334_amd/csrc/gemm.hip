@@ -389,6 +389,26 @@ static mp8_status gemm_impl(mp8_op op, int64_t M, int64_t N, int64_t K, const ui
                        workspace_bytes, s, upd);
 }
 
+
+// The master-weight update a finishing pass applies: plain SGD, or momentum SGD with L2
+// regularisation when a velocity array is given.
+static UpdateHook make_update_hook(uint16_t *w16, uint8_t *w8_out, const uint32_t *skip, float lr,
+                                   float inv_loss_scale, mp8_round w_round, uint64_t w_seed, uint64_t w_offset,
+                                   float *velocity = nullptr, float momentum = 0.0f, float weight_decay = 0.0f) {
+    UpdateHook upd{};
+    upd.w16 = w16;
+    upd.w8_out = w8_out;
+    upd.skip = skip;
+    upd.neg_lr = -lr;
+    upd.inv_scale = inv_loss_scale;
+    upd.sr = w_round == MP8_SR;
+    upd.seed = w_seed;
+    upd.offset = w_offset;
+    upd.velocity = velocity;
+    upd.mu = momentum;
+    upd.wd = weight_decay;
+    return upd;
+}
 }  // namespace mp8
 
 extern "C" mp8_status mp8_gemm_fp8_tuned(mp8_op op, int64_t M, int64_t N, int64_t K,
@@ -418,15 +438,7 @@ extern "C" mp8_status mp8_wgrad_update_fp16_sr(int64_t M, int64_t N, int64_t K, 
     if (K == 0 || N == 0) return MP8_OK;
     if (!w16) return MP8_ERR_INVALID_ARG;
     if (((uintptr_t)w16 | (uintptr_t)w8_out) & 15u) return MP8_ERR_ALIGNMENT;
-    UpdateHook upd{};
-    upd.w16 = w16;
-    upd.w8_out = w8_out;
-    upd.skip = skip_if_nonzero;
-    upd.neg_lr = -lr;
-    upd.inv_scale = inv_loss_scale;
-    upd.sr = w_round == MP8_SR;
-    upd.seed = w_seed;
-    upd.offset = w_offset;
+    UpdateHook upd = make_update_hook(w16, w8_out, skip_if_nonzero, lr, inv_loss_scale, w_round, w_seed, w_offset);
     const mp8_status st = gemm_impl(MP8_WGRAD, M, N, K, a, lda, b, ldb, alpha, nullptr, 0, g8_out, nullptr,
                                     g_round, flags, g_seed, g_offset, stats, workspace, workspace_bytes,
                                     stream, 0, 0, &upd);
@@ -455,18 +467,8 @@ extern "C" mp8_status mp8_wgrad_momentum_fp16_sr(int64_t M, int64_t N, int64_t K
     if (K == 0 || N == 0) return MP8_OK;
     if (!w16 || !velocity) return MP8_ERR_INVALID_ARG;
     if (((uintptr_t)w16 | (uintptr_t)w8_out | (uintptr_t)velocity) & 15u) return MP8_ERR_ALIGNMENT;
-    UpdateHook upd{};
-    upd.w16 = w16;
-    upd.w8_out = w8_out;
-    upd.skip = skip_if_nonzero;
-    upd.neg_lr = -lr;
-    upd.inv_scale = inv_loss_scale;
-    upd.sr = w_round == MP8_SR;
-    upd.seed = w_seed;
-    upd.offset = w_offset;
-    upd.velocity = velocity;
-    upd.mu = momentum;
-    upd.wd = weight_decay;
+    UpdateHook upd = make_update_hook(w16, w8_out, skip_if_nonzero, lr, inv_loss_scale, w_round, w_seed, w_offset,
+                                      velocity, momentum, weight_decay);
     const mp8_status st = gemm_impl(MP8_WGRAD, M, N, K, a, lda, b, ldb, alpha, nullptr, 0, g8_out, nullptr,
                                     g_round, flags, g_seed, g_offset, stats, workspace, workspace_bytes,
                                     stream, 0, 0, &upd);
@@ -697,15 +699,7 @@ extern "C" mp8_status mp8_conv3x3_wgrad_update_fp16_sr(
     if (B == 0 || H == 0 || W == 0 || Ci == 0 || Co == 0) return MP8_OK;
     if (!w16) return MP8_ERR_INVALID_ARG;
     if (((uintptr_t)w16 | (uintptr_t)w8_out) & 15u) return MP8_ERR_ALIGNMENT;
-    UpdateHook upd{};
-    upd.w16 = w16;
-    upd.w8_out = w8_out;
-    upd.skip = skip_if_nonzero;
-    upd.neg_lr = -lr;
-    upd.inv_scale = inv_loss_scale;
-    upd.sr = w_round == MP8_SR;
-    upd.seed = w_seed;
-    upd.offset = w_offset;
+    UpdateHook upd = make_update_hook(w16, w8_out, skip_if_nonzero, lr, inv_loss_scale, w_round, w_seed, w_offset);
     return conv_impl(MP8_WGRAD, B, H, W, Ci, Co, prows, x8, e8, alpha, nullptr, 0, g8_out, g_round, flags,
                      g_seed, g_offset, stats, workspace, workspace_bytes, stream, &upd);
 }
@@ -722,18 +716,8 @@ extern "C" mp8_status mp8_conv3x3_wgrad_momentum_fp16_sr(
     if (B == 0 || H == 0 || W == 0 || Ci == 0 || Co == 0) return MP8_OK;
     if (!w16 || !velocity) return MP8_ERR_INVALID_ARG;
     if (((uintptr_t)w16 | (uintptr_t)w8_out | (uintptr_t)velocity) & 15u) return MP8_ERR_ALIGNMENT;
-    UpdateHook upd{};
-    upd.w16 = w16;
-    upd.w8_out = w8_out;
-    upd.skip = skip_if_nonzero;
-    upd.neg_lr = -lr;
-    upd.inv_scale = inv_loss_scale;
-    upd.sr = w_round == MP8_SR;
-    upd.seed = w_seed;
-    upd.offset = w_offset;
-    upd.velocity = velocity;
-    upd.mu = momentum;
-    upd.wd = weight_decay;
+    UpdateHook upd = make_update_hook(w16, w8_out, skip_if_nonzero, lr, inv_loss_scale, w_round, w_seed, w_offset,
+                                      velocity, momentum, weight_decay);
     return conv_impl(MP8_WGRAD, B, H, W, Ci, Co, prows, x8, e8, alpha, nullptr, 0, g8_out, g_round, flags,
                      g_seed, g_offset, stats, workspace, workspace_bytes, stream, &upd);
 }
