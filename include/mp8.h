@@ -337,6 +337,20 @@ mp8_status mp8_conv3x3_wgrad_momentum_fp16_sr(
     const uint32_t *skip_if_nonzero, uint8_t *w8_out, void *workspace, size_t workspace_bytes,
     void *stream);
 
+/*
+ * The same with ADAM (mp8_adam_fp16_sr: m, v [K, N] FP32 moments in place, beta1, beta2, eps,
+ * weight_decay, step counted from 1) in the finishing pass of the weight-gradient GEMM; bit for
+ * bit the weight-gradient call followed by mp8_adam_fp16_sr.
+ */
+mp8_status mp8_wgrad_adam_fp16_sr(int64_t M, int64_t N, int64_t K, const uint8_t *a, int64_t lda,
+                                  const uint8_t *b, int64_t ldb, float alpha, uint8_t *g8_out,
+                                  mp8_round g_round, int flags, uint64_t g_seed, uint64_t g_offset,
+                                  mp8_stats *stats, uint16_t *w16, float *m, float *v, float lr,
+                                  float inv_loss_scale, float beta1, float beta2, float eps,
+                                  float weight_decay, int64_t step, mp8_round w_round, uint64_t w_seed,
+                                  uint64_t w_offset, const uint32_t *skip_if_nonzero, uint8_t *w8_out,
+                                  void *workspace, size_t workspace_bytes, void *stream);
+
 /* out[i] = the 16 random bits element i would use (device array of n uint16), for tests. */
 mp8_status mp8_sr_bits(uint16_t *out, int64_t n, uint64_t seed, uint64_t offset, void *stream);
 

@@ -30,6 +30,7 @@ EXPORTS = [
     "mp8_gemm_fp8_plan", "mp8_gemm_tile_config_lds_bytes", "mp8_adam_fp16_sr",
     "mp8_quantize_e5m2_batch", "mp8_wgrad_update_fp16_sr", "mp8_conv3x3_wgrad_update_fp16_sr",
     "mp8_quantize_gemm_fwd_fp8", "mp8_wgrad_momentum_fp16_sr", "mp8_conv3x3_wgrad_momentum_fp16_sr",
+    "mp8_wgrad_adam_fp16_sr",
 ]
 
 
@@ -91,6 +92,10 @@ def lib() -> C.CDLL:
     L.mp8_wgrad_momentum_fp16_sr.argtypes = [i64, i64, i64, vp, i64, vp, i64, f32, vp, ci, ci, u64, u64, vp,
                                              vp, vp, f32, f32, f32, f32, ci, u64, u64, vp, vp, vp, C.c_size_t,
                                              vp]
+    L.mp8_wgrad_adam_fp16_sr.restype = ci
+    L.mp8_wgrad_adam_fp16_sr.argtypes = [i64, i64, i64, vp, i64, vp, i64, f32, vp, ci, ci, u64, u64, vp,
+                                         vp, vp, vp, f32, f32, f32, f32, f32, f32, i64, ci, u64, u64, vp, vp, vp,
+                                         C.c_size_t, vp]
     L.mp8_conv3x3_wgrad_momentum_fp16_sr.restype = ci
     L.mp8_conv3x3_wgrad_momentum_fp16_sr.argtypes = [i64, i64, i64, i64, i64, i64, vp, vp, f32, vp, ci, ci, u64,
                                                      u64, vp, vp, vp, f32, f32, f32, f32, ci, u64, u64, vp, vp,
@@ -401,6 +406,41 @@ def wgrad_momentum_fp16_sr(M, N, K, a, b, w16, velocity, lr, inv_loss_scale, mom
                                           _ptr(skip_if_nonzero), _ptr(w8_out), _ptr(workspace), ws_bytes,
                                           _stream())
     _check(st, "mp8_wgrad_momentum_fp16_sr")
+    return w16
+
+
+def wgrad_adam_fp16_sr(M, N, K, a, b, w16, m, v, lr, inv_loss_scale, step, beta1=0.9, beta2=0.999, eps=1e-8,
+                       weight_decay=0.0, g8_out=None, alpha=1.0, g_round=RNE, flags=0, g_seed=0, g_offset=0,
+                       stats=None, w_round=SR, w_seed=0, w_offset=0, skip_if_nonzero=None, w8_out=None,
+                       workspace=None, lda=None, ldb=None):
+    """mp8_wgrad_adam_fp16_sr: wgrad_update_fp16_sr with ADAM (m, v [K, N] FP32 in place, step from 1)
+    in the finishing pass."""
+    import torch
+    _dev(a, "a", torch.uint8)
+    _dev(b, "b", torch.uint8)
+    _dev(w16, "w16", (torch.float16, torch.int16, torch.uint16))
+    _dev(m, "m", torch.float32)
+    _dev(v, "v", torch.float32)
+    _dev(g8_out, "g8_out", torch.uint8)
+    _dev(w8_out, "w8_out", torch.uint8)
+    rows, cols, kc = _op_dims(WGRAD, M, N, K)
+    a_km, b_km = bool(flags & FLAG_A_CONTRACTION_MAJOR), bool(flags & FLAG_B_CONTRACTION_MAJOR)
+    lda = (rows if a_km else kc) if lda is None else lda
+    ldb = (cols if b_km else kc) if ldb is None else ldb
+    need_a = ((kc - 1) * lda + rows if a_km else (rows - 1) * lda + kc) if rows > 0 and kc > 0 else 0
+    need_b = ((kc - 1) * ldb + cols if b_km else (cols - 1) * ldb + kc) if cols > 0 and kc > 0 else 0
+    if a.numel() < need_a or b.numel() < need_b:
+        raise Mp8Error("a / b is smaller than its shape and leading dimension require")
+    for t, name in ((w16, "w16"), (m, "m"), (v, "v"), (g8_out, "g8_out"), (w8_out, "w8_out")):
+        if t is not None and t.numel() != rows * cols:
+            raise Mp8Error(f"{name} must have K*N elements")
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = lib().mp8_wgrad_adam_fp16_sr(M, N, K, _ptr(a), lda, _ptr(b), ldb, float(alpha), _ptr(g8_out), g_round,
+                                      flags, g_seed, g_offset, _ptr(stats), _ptr(w16), _ptr(m), _ptr(v),
+                                      float(lr), float(inv_loss_scale), float(beta1), float(beta2), float(eps),
+                                      float(weight_decay), int(step), w_round, w_seed, w_offset,
+                                      _ptr(skip_if_nonzero), _ptr(w8_out), _ptr(workspace), ws_bytes, _stream())
+    _check(st, "mp8_wgrad_adam_fp16_sr")
     return w16
 
 

@@ -20,6 +20,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstdio>
 #include <cstring>
 #include <type_traits>
@@ -391,7 +392,7 @@ static mp8_status gemm_impl(mp8_op op, int64_t M, int64_t N, int64_t K, const ui
 
 
 // The master-weight update a finishing pass applies: plain SGD, or momentum SGD with L2
-// regularisation when a velocity array is given.
+// regularisation when a velocity array is given (mp8_wgrad_adam_fp16_sr fills in ADAM's fields).
 static UpdateHook make_update_hook(uint16_t *w16, uint8_t *w8_out, const uint32_t *skip, float lr,
                                    float inv_loss_scale, mp8_round w_round, uint64_t w_seed, uint64_t w_offset,
                                    float *velocity = nullptr, float momentum = 0.0f, float weight_decay = 0.0f) {
@@ -404,7 +405,8 @@ static UpdateHook make_update_hook(uint16_t *w16, uint8_t *w8_out, const uint32_
     upd.sr = w_round == MP8_SR;
     upd.seed = w_seed;
     upd.offset = w_offset;
-    upd.velocity = velocity;
+    upd.states = velocity != nullptr ? 1 : 0;
+    upd.state0 = velocity;
     upd.mu = momentum;
     upd.wd = weight_decay;
     return upd;
@@ -480,6 +482,47 @@ extern "C" mp8_status mp8_wgrad_momentum_fp16_sr(int64_t M, int64_t N, int64_t K
     if (sg != MP8_OK) return sg;
     return mp8_sgd_momentum_fp16_sr(w16, velocity, g8_out, K * N, lr, inv_loss_scale, momentum, weight_decay,
                                     w_round, w_seed, w_offset, skip_if_nonzero, w8_out, nullptr, stream);
+}
+
+extern "C" mp8_status mp8_wgrad_adam_fp16_sr(int64_t M, int64_t N, int64_t K, const uint8_t *a, int64_t lda,
+                                             const uint8_t *b, int64_t ldb, float alpha, uint8_t *g8_out,
+                                             mp8_round g_round, int flags, uint64_t g_seed, uint64_t g_offset,
+                                             mp8_stats *stats, uint16_t *w16, float *m, float *v, float lr,
+                                             float inv_loss_scale, float beta1, float beta2, float eps,
+                                             float weight_decay, int64_t step, mp8_round w_round,
+                                             uint64_t w_seed, uint64_t w_offset,
+                                             const uint32_t *skip_if_nonzero, uint8_t *w8_out,
+                                             void *workspace, size_t workspace_bytes, void *stream) {
+    using namespace mp8;
+    if (M < 0 || N < 0 || K < 0 || step < 1) return MP8_ERR_INVALID_ARG;
+    if (w_round != MP8_RNE && w_round != MP8_SR) return MP8_ERR_INVALID_ARG;
+    if (K == 0 || N == 0) return MP8_OK;
+    if (!w16 || !m || !v) return MP8_ERR_INVALID_ARG;
+    if (((uintptr_t)w16 | (uintptr_t)w8_out | (uintptr_t)m | (uintptr_t)v) & 15u) return MP8_ERR_ALIGNMENT;
+    UpdateHook upd = make_update_hook(w16, w8_out, skip_if_nonzero, lr, inv_loss_scale, w_round, w_seed, w_offset);
+    upd.states = 2;
+    upd.state0 = m;
+    upd.state1 = v;
+    upd.wd = weight_decay;
+    upd.b1 = beta1;
+    upd.b2 = beta2;
+    upd.omb1 = 1.0f - beta1;
+    upd.omb2 = 1.0f - beta2;
+    // bias corrections as in mp8_adam_fp16_sr: the powers in double, the result as FP32
+    upd.c1 = (float)(1.0 - std::pow((double)beta1, (double)step));
+    upd.c2 = (float)(1.0 - std::pow((double)beta2, (double)step));
+    upd.eps = eps;
+    const mp8_status st = gemm_impl(MP8_WGRAD, M, N, K, a, lda, b, ldb, alpha, nullptr, 0, g8_out, nullptr,
+                                    g_round, flags, g_seed, g_offset, stats, workspace, workspace_bytes,
+                                    stream, 0, 0, &upd);
+    if (st != MP8_ERR_UNSUPPORTED || g8_out == nullptr) return st;
+    // shapes that only the any-shape kernel takes: two launches through the 8-bit gradient
+    const mp8_status sg = mp8_gemm_fp8(MP8_WGRAD, M, N, K, a, lda, b, ldb, alpha, nullptr, 0, g8_out, nullptr,
+                                       g_round, flags, g_seed, g_offset, stats, workspace, workspace_bytes,
+                                       stream);
+    if (sg != MP8_OK) return sg;
+    return mp8_adam_fp16_sr(w16, m, v, g8_out, K * N, lr, inv_loss_scale, beta1, beta2, eps, weight_decay, step,
+                            w_round, w_seed, w_offset, skip_if_nonzero, w8_out, nullptr, stream);
 }
 
 extern "C" mp8_status mp8_gemm_fp8(mp8_op op, int64_t M, int64_t N, int64_t K, const uint8_t *a,

@@ -56,27 +56,37 @@ struct UpdateHook {
     float neg_lr, inv_scale;
     int sr;
     uint64_t seed, offset;
-    float *velocity;  // non-null: momentum SGD with L2 regularisation (MomentumRule), state in place
-    float mu, wd;
+    // optimizer state, in place: none (plain SGD), the velocity of momentum SGD (state0), or the
+    // two moments of ADAM (state0, state1) -- the rules of the stand-alone update kernels
+    int states;
+    float *state0, *state1;
+    float mu, wd;                            // momentum; L2 regularisation of either rule
+    float b1, b2, omb1, omb2, c1, c2, eps;   // ADAM
 };
 
-// One master weight from its gradient code: plain SGD, or the momentum rule when the hook
-// carries a velocity array -- the same arithmetic as the stand-alone update kernels.
-__device__ __forceinline__ uint32_t hook_one(const UpdateHook &u, uint32_t w16, uint32_t code, float *vel,
+// One master weight from its gradient code, with the same arithmetic as the stand-alone update
+// kernels; st points at this element's state words.
+__device__ __forceinline__ uint32_t hook_one(const UpdateHook &u, uint32_t w16, uint32_t code, float *st,
                                              uint32_t r16) {
-    if (u.velocity != nullptr) {
+    if (u.states == 1) {
         const MomentumRule rule{u.neg_lr, u.mu, u.wd};
-        return u.sr ? rule_one<true>(rule, w16, code, vel, u.inv_scale, r16)
-                    : rule_one<false>(rule, w16, code, vel, u.inv_scale, 0u);
+        return u.sr ? rule_one<true>(rule, w16, code, st, u.inv_scale, r16)
+                    : rule_one<false>(rule, w16, code, st, u.inv_scale, 0u);
+    }
+    if (u.states == 2) {
+        const AdamRule rule{u.neg_lr, u.b1, u.b2, u.omb1, u.omb2, u.c1, u.c2, u.eps, u.wd};
+        return u.sr ? rule_one<true>(rule, w16, code, st, u.inv_scale, r16)
+                    : rule_one<false>(rule, w16, code, st, u.inv_scale, 0u);
     }
     return u.sr ? update_one<true>(w16, code, u.neg_lr, u.inv_scale, r16)
                 : update_one<false>(w16, code, u.neg_lr, u.inv_scale, 0u);
 }
 
 __device__ __forceinline__ void update_element(const UpdateHook &u, int64_t i, uint32_t code, uint32_t r16) {
-    float vel = u.velocity != nullptr ? u.velocity[i] : 0.0f;
-    const uint32_t h = hook_one(u, u.w16[i], code, &vel, r16);
-    if (u.velocity != nullptr) u.velocity[i] = vel;
+    float st[2] = {u.states >= 1 ? u.state0[i] : 0.0f, u.states == 2 ? u.state1[i] : 0.0f};
+    const uint32_t h = hook_one(u, u.w16[i], code, st, r16);
+    if (u.states >= 1) u.state0[i] = st[0];
+    if (u.states == 2) u.state1[i] = st[1];
     u.w16[i] = (uint16_t)h;
     if (u.w8_out != nullptr) u.w8_out[i] = (uint8_t)e5m2_of_half(h);
 }
@@ -95,19 +105,27 @@ __device__ __forceinline__ void update4(const UpdateHook &u, int64_t i0, uint32_
     uint32_t h[4];
     const uint32_t w16v[4] = {wr.x & 0xFFFFu, wr.x >> 16, wr.y & 0xFFFFu, wr.y >> 16};
     const uint32_t r16[4] = {r01 & 0xFFFFu, r01 >> 16, r23 & 0xFFFFu, r23 >> 16};
-    float vel[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-    if (u.velocity != nullptr) {
-        const f32x4 vv = *reinterpret_cast<const f32x4 *>(u.velocity + i0);
-        vel[0] = vv.x; vel[1] = vv.y; vel[2] = vv.z; vel[3] = vv.w;
+    float st[4][2] = {{0.0f, 0.0f}, {0.0f, 0.0f}, {0.0f, 0.0f}, {0.0f, 0.0f}};
+    if (u.states >= 1) {
+        const f32x4 x = *reinterpret_cast<const f32x4 *>(u.state0 + i0);
+        st[0][0] = x.x; st[1][0] = x.y; st[2][0] = x.z; st[3][0] = x.w;
+    }
+    if (u.states == 2) {
+        const f32x4 x = *reinterpret_cast<const f32x4 *>(u.state1 + i0);
+        st[0][1] = x.x; st[1][1] = x.y; st[2][1] = x.z; st[3][1] = x.w;
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const uint32_t code = (pk >> (8 * j)) & 0xFFu;
-        h[j] = hook_one(u, w16v[j], code, &vel[j], r16[j]);
+        h[j] = hook_one(u, w16v[j], code, st[j], r16[j]);
     }
-    if (u.velocity != nullptr) {
-        const f32x4 vv = {vel[0], vel[1], vel[2], vel[3]};
-        *reinterpret_cast<f32x4 *>(u.velocity + i0) = vv;
+    if (u.states >= 1) {
+        const f32x4 x = {st[0][0], st[1][0], st[2][0], st[3][0]};
+        *reinterpret_cast<f32x4 *>(u.state0 + i0) = x;
+    }
+    if (u.states == 2) {
+        const f32x4 x = {st[0][1], st[1][1], st[2][1], st[3][1]};
+        *reinterpret_cast<f32x4 *>(u.state1 + i0) = x;
     }
     const u32x2 o = {h[0] | (h[1] << 16), h[2] | (h[3] << 16)};
     *wp = o;

@@ -330,3 +330,65 @@ def test_weight_gradient_and_momentum_update_in_one_call_against_the_oracle_chai
     torch.cuda.synchronize()
     assert torch.equal(g1, g2.view(-1)) and torch.equal(w1, w2) and torch.equal(v1.view(torch.int32), v2.view(torch.int32))
     assert torch.equal(q1, q2)
+
+
+def test_weight_gradient_and_adam_update_in_one_call_against_the_oracle_chain(mp8):
+    """mp8_wgrad_adam_fp16_sr over two consecutive steps (moments and bias corrections carry over)
+    on exact-sum operands: gradient codes, master weights, both moments and the 8-bit weights bit
+    for bit the oracle's chain GEMM -> one rounding -> ADAM; split and unsplit contractions, a
+    ragged column count, SR and RNE, the skip flag; then the one call against the two calls on
+    random operands."""
+    import torch
+    from test_gpu_gemm import exact_sum_codes
+    rng = np.random.default_rng(41)
+    for (M, N, K) in ((1024, 64, 256), (512, 50, 128), (8192, 64, 64)):
+        xt, et = exact_sum_codes(rng, (K, M)), exact_sum_codes(rng, (N, M))
+        if M == 8192:
+            xt[:, rng.random(M) < 0.75] = 0
+        ref, _ = oracle.gemm_ref(xt, et, want_abs=False)
+        alpha, lr, inv, wd_ = 2.0 ** -9, 0.01, 1.0 / 64, 1e-3
+        a, b = gpu(xt), gpu(et)
+        ws = torch.empty(max(mp8.gemm_fp8_workspace_bytes(mp8.WGRAD, M, N, K), 16), dtype=torch.uint8, device="cuda")
+        for w_round, skip in ((oracle.SR, 0), (oracle.RNE, 0), (oracle.SR, 5)):
+            w_ref = (rng.standard_normal(K * N) * 0.05).astype(np.float16).view(np.uint16)
+            m_ref = (rng.standard_normal(K * N) * 0.01).astype(np.float32)
+            v_ref = (rng.random(K * N) * 1e-3).astype(np.float32)
+            wdev, mdev, vdev = gpu(w_ref.view(np.int16)), gpu(m_ref), gpu(v_ref)
+            g8 = torch.full((K * N + 64,), 0xAA, dtype=torch.uint8, device="cuda")
+            w8 = torch.full((K * N + 64,), 0x55, dtype=torch.uint8, device="cuda")
+            flag = torch.full((1,), skip, dtype=torch.int32, device="cuda")
+            want_g = oracle.quantize_e5m2(ref.astype(np.float32), scale=alpha)[0]
+            for step in (1, 2):
+                w_ref, m_ref, v_ref, want_w8 = oracle.adam_fp16(w_ref, m_ref, v_ref, want_g.reshape(-1), lr, inv, step,
+                                                                weight_decay=wd_, mode=w_round, seed=43, offset=step,
+                                                                skip=skip or None, want_w8=True)
+                mp8.wgrad_adam_fp16_sr(M, N, K, a, b, wdev, mdev, vdev, lr, inv, step, weight_decay=wd_,
+                                       g8_out=g8[: K * N], alpha=alpha, w_round=w_round, w_seed=43, w_offset=step,
+                                       skip_if_nonzero=flag, w8_out=w8[: K * N], workspace=ws)
+                torch.cuda.synchronize()
+                assert np.array_equal(host(g8[: K * N]).reshape(K, N), want_g), (M, N, K, step)
+                assert np.array_equal(host(wdev).view(np.uint16), w_ref), (M, N, K, w_round, skip, step)
+                assert np.array_equal(host(mdev).view(np.uint32), m_ref.view(np.uint32)), (M, N, K, skip, step)
+                assert np.array_equal(host(vdev).view(np.uint32), v_ref.view(np.uint32)), (M, N, K, skip, step)
+                if skip:
+                    assert bool((w8[: K * N] == 0x55).all())
+                else:
+                    assert np.array_equal(host(w8[: K * N]), want_w8)
+            assert bool((g8[K * N:] == 0xAA).all()) and bool((w8[K * N:] == 0x55).all())
+    M, N, K = 4736, 128, 384
+    a, b = gpu(workloads.random_e5m2_codes(7, (M, K)) & 0xBF), gpu(workloads.random_e5m2_codes(8, (M, N)) & 0xBF)
+    ws = torch.empty(max(mp8.gemm_fp8_workspace_bytes(mp8.WGRAD, M, N, K), 16), dtype=torch.uint8, device="cuda")
+    w0 = (rng.standard_normal(K * N) * 0.05).astype(np.float16).view(np.int16)
+    m0 = (rng.standard_normal(K * N) * 0.01).astype(np.float32)
+    v0 = (rng.random(K * N) * 1e-3).astype(np.float32)
+    w1, m1, v1 = gpu(w0), gpu(m0), gpu(v0)
+    g1, q1 = torch.zeros(K * N, dtype=torch.uint8, device="cuda"), torch.zeros(K * N, dtype=torch.uint8, device="cuda")
+    mp8.wgrad_adam_fp16_sr(M, N, K, a, b, w1, m1, v1, 1e-3, 1 / 16, 3, g8_out=g1, flags=mp8.FLAG_CONTRACTION_MAJOR,
+                           w_seed=3, w_offset=4, w8_out=q1, workspace=ws)
+    w2, m2, v2 = gpu(w0), gpu(m0), gpu(v0)
+    g2, q2 = torch.zeros((K, N), dtype=torch.uint8, device="cuda"), torch.zeros(K * N, dtype=torch.uint8, device="cuda")
+    mp8.gemm_fp8(mp8.WGRAD, M, N, K, a, b, out8=g2, flags=mp8.FLAG_CONTRACTION_MAJOR, workspace=ws)
+    mp8.adam_fp16_sr(w2, m2, v2, g2.view(-1), 1e-3, 1 / 16, 3, round=mp8.SR, seed=3, offset=4, w8_out=q2)
+    torch.cuda.synchronize()
+    assert torch.equal(g1, g2.view(-1)) and torch.equal(w1, w2) and torch.equal(q1, q2)
+    assert torch.equal(m1.view(torch.int32), m2.view(torch.int32)) and torch.equal(v1.view(torch.int32), v2.view(torch.int32))
