@@ -309,8 +309,11 @@ static mp8_status launch_mfma(GemmArgs ga, const Epilogue &ep, const Plan &pl, i
         if (!only_acc) {
             const int64_t items = (cols & 3) == 0 ? rows * cols / 4 : rows * cols;
             int64_t blocks = std::min<int64_t>((items + 255) / 256, 256 * 16);
-            hipLaunchKernelGGL(splitk_finish_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
-                               (const float *)partial, pl.splits, fin, upd ? *upd : UpdateHook{});
+            const int states = upd ? upd->states : 0;
+            hipLaunchKernelGGL(states == 2 ? splitk_finish_kernel<2>
+                                           : states == 1 ? splitk_finish_kernel<1> : splitk_finish_kernel<0>,
+                               dim3((unsigned)blocks), dim3(256), 0, s, (const float *)partial, pl.splits, fin,
+                               upd ? *upd : UpdateHook{});
             if (hipGetLastError() != hipSuccess) return MP8_ERR_HIP;
         }
     }

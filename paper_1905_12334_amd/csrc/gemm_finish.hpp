@@ -66,14 +66,15 @@ struct UpdateHook {
 
 // One master weight from its gradient code, with the same arithmetic as the stand-alone update
 // kernels; st points at this element's state words.
+template <int STATES>
 __device__ __forceinline__ uint32_t hook_one(const UpdateHook &u, uint32_t w16, uint32_t code, float *st,
                                              uint32_t r16) {
-    if (u.states == 1) {
+    if constexpr (STATES == 1) {
         const MomentumRule rule{u.neg_lr, u.mu, u.wd};
         return u.sr ? rule_one<true>(rule, w16, code, st, u.inv_scale, r16)
                     : rule_one<false>(rule, w16, code, st, u.inv_scale, 0u);
     }
-    if (u.states == 2) {
+    if constexpr (STATES == 2) {
         const AdamRule rule{u.neg_lr, u.b1, u.b2, u.omb1, u.omb2, u.c1, u.c2, u.eps, u.wd};
         return u.sr ? rule_one<true>(rule, w16, code, st, u.inv_scale, r16)
                     : rule_one<false>(rule, w16, code, st, u.inv_scale, 0u);
@@ -82,16 +83,20 @@ __device__ __forceinline__ uint32_t hook_one(const UpdateHook &u, uint32_t w16, 
                 : update_one<false>(w16, code, u.neg_lr, u.inv_scale, 0u);
 }
 
+template <int STATES>
 __device__ __forceinline__ void update_element(const UpdateHook &u, int64_t i, uint32_t code, uint32_t r16) {
-    float st[2] = {u.states >= 1 ? u.state0[i] : 0.0f, u.states == 2 ? u.state1[i] : 0.0f};
-    const uint32_t h = hook_one(u, u.w16[i], code, st, r16);
-    if (u.states >= 1) u.state0[i] = st[0];
-    if (u.states == 2) u.state1[i] = st[1];
+    float st[2] = {0.0f, 0.0f};
+    if constexpr (STATES >= 1) st[0] = u.state0[i];
+    if constexpr (STATES == 2) st[1] = u.state1[i];
+    const uint32_t h = hook_one<STATES>(u, u.w16[i], code, st, r16);
+    if constexpr (STATES >= 1) u.state0[i] = st[0];
+    if constexpr (STATES == 2) u.state1[i] = st[1];
     u.w16[i] = (uint16_t)h;
     if (u.w8_out != nullptr) u.w8_out[i] = (uint8_t)e5m2_of_half(h);
 }
 
 // Elements i0 .. i0+3 (i0 % 4 == 0) from their four packed gradient codes.
+template <int STATES>
 __device__ __forceinline__ void update4(const UpdateHook &u, int64_t i0, uint32_t pk) {
     uint32_t r01 = 0, r23 = 0;
     if (u.sr) {
@@ -106,24 +111,24 @@ __device__ __forceinline__ void update4(const UpdateHook &u, int64_t i0, uint32_
     const uint32_t w16v[4] = {wr.x & 0xFFFFu, wr.x >> 16, wr.y & 0xFFFFu, wr.y >> 16};
     const uint32_t r16[4] = {r01 & 0xFFFFu, r01 >> 16, r23 & 0xFFFFu, r23 >> 16};
     float st[4][2] = {{0.0f, 0.0f}, {0.0f, 0.0f}, {0.0f, 0.0f}, {0.0f, 0.0f}};
-    if (u.states >= 1) {
+    if constexpr (STATES >= 1) {
         const f32x4 x = *reinterpret_cast<const f32x4 *>(u.state0 + i0);
         st[0][0] = x.x; st[1][0] = x.y; st[2][0] = x.z; st[3][0] = x.w;
     }
-    if (u.states == 2) {
+    if constexpr (STATES == 2) {
         const f32x4 x = *reinterpret_cast<const f32x4 *>(u.state1 + i0);
         st[0][1] = x.x; st[1][1] = x.y; st[2][1] = x.z; st[3][1] = x.w;
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const uint32_t code = (pk >> (8 * j)) & 0xFFu;
-        h[j] = hook_one(u, w16v[j], code, st[j], r16[j]);
+        h[j] = hook_one<STATES>(u, w16v[j], code, st[j], r16[j]);
     }
-    if (u.states >= 1) {
+    if constexpr (STATES >= 1) {
         const f32x4 x = {st[0][0], st[1][0], st[2][0], st[3][0]};
         *reinterpret_cast<f32x4 *>(u.state0 + i0) = x;
     }
-    if (u.states == 2) {
+    if constexpr (STATES == 2) {
         const f32x4 x = {st[0][1], st[1][1], st[2][1], st[3][1]};
         *reinterpret_cast<f32x4 *>(u.state1 + i0) = x;
     }
@@ -136,7 +141,9 @@ __device__ __forceinline__ void update4(const UpdateHook &u, int64_t i0, uint32_
 
 // Sum the FP32 tiles of the contraction slices in slice order and finish: the complete sum is
 // rounded once.  One thread per four columns (per element when the row length is not a
-// multiple of four).
+// multiple of four).  STATES: state words per weight of the update rule the hook carries (0: plain
+// SGD or no update at all, 1: momentum, 2: ADAM).
+template <int STATES>
 __global__ __launch_bounds__(256) void splitk_finish_kernel(const float *__restrict__ partial,
                                                             int splits, const Epilogue ep,
                                                             const UpdateHook upd) {
@@ -167,7 +174,7 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const float *__restr
                 v[0] += x.x; v[1] += x.y; v[2] += x.z; v[3] += x.w;
             }
             const uint32_t pk = finish4(ep, r, c, v, st);
-            if (updating) update4(upd, i0, pk);
+            if (updating) update4<STATES>(upd, i0, pk);
         }
     } else {
         for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < slice; i += stride) {
@@ -181,7 +188,7 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const float *__restr
                     const Philox rng(upd.seed, upd.offset);
                     r16 = philox_half(rng.block((uint64_t)i >> 3), (int)(i & 7));
                 }
-                update_element(upd, i, code, r16);
+                update_element<STATES>(upd, i, code, r16);
             }
         }
     }
