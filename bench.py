@@ -47,8 +47,8 @@ LR = 1e-3
 # by what the same counters read on a plain 1 GiB copy (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000);
 # the runs and their raw figures are in profiles/bench_step_cfg2_hbm_traffic.txt
 MEASURED_TRAFFIC_BYTES = {
-    "quantize_X_gemm_fwd": 149117027, "quantize_dY": 16142644, "gemm_bwd_data": 33497184,
-    "gemm_wgrad_update": 51609719,
+    "quantize_X_gemm_fwd": 149119098, "quantize_dY": 16142647, "gemm_bwd_data": 33493089,
+    "gemm_wgrad_update": 51595802,
     # with --separate-quantize (measured before the two were fused)
     "quantize_X": 144555139, "gemm_fwd": 33417730,
 }
