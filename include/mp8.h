@@ -265,7 +265,11 @@ mp8_status mp8_adam_fp16_sr(uint16_t *w16, float *m, float *v, const uint8_t *g8
  *   workspace  at least mp8_gemm_fp8_workspace_bytes(MP8_WGRAD, M, N, K) bytes, always needed
  *              when that is non-zero
  * Shapes that only the any-shape GEMM kernel takes run as the two separate launches and need
- * g8_out (MP8_ERR_UNSUPPORTED without it).
+ * g8_out (MP8_ERR_UNSUPPORTED without it).  A weight gradient whose contraction is not split
+ * rounds in the GEMM's own epilogue; it is then followed by the update kernel instead of being
+ * forced through a finishing pass (cheaper: no FP32 copy of the result is written), with the codes
+ * in g8_out, or in the first K*N bytes of the workspace if the caller passes no g8_out and the
+ * workspace is that large.
  */
 mp8_status mp8_wgrad_update_fp16_sr(int64_t M, int64_t N, int64_t K, const uint8_t *a, int64_t lda,
                                     const uint8_t *b, int64_t ldb, float alpha, uint8_t *g8_out,

@@ -414,6 +414,22 @@ static UpdateHook make_update_hook(uint16_t *w16, uint8_t *w8_out, const uint32_
     upd.wd = weight_decay;
     return upd;
 }
+
+// Where the 8-bit weight gradient goes when the update is cheaper as a launch of its own: a
+// weight-gradient GEMM that runs unsplit rounds in its own epilogue, and forcing a finishing pass
+// on it just to carry the update would write and re-read the whole FP32 result (measured: 1024 x
+// 4096 from 16384 tokens 91 against 77 us).  Then the codes go to g8_out, or to the workspace if
+// the caller keeps no gradient, and the stand-alone update kernel follows.  Null: use the
+// finishing pass.
+static uint8_t *codes_for_separate_update(int64_t M, int64_t N, int64_t K, int flags, uint8_t *g8_out,
+                                          void *workspace, size_t workspace_bytes) {
+    const bool atn = (flags & MP8_FLAG_A_CONTRACTION_MAJOR) != 0, btn = (flags & MP8_FLAG_B_CONTRACTION_MAJOR) != 0;
+    if ((atn && !btn) || (N & 15) != 0 || K > (INT64_MAX / 8) / std::max<int64_t>(N, 1)) return nullptr;
+    const Plan pl = make_plan(K, N, M, 0, 0, (atn ? 1 : 0) | (btn ? 2 : 0));
+    if (!pl.mfma || pl.splits != 1) return nullptr;
+    if (g8_out != nullptr) return g8_out;
+    return workspace != nullptr && workspace_bytes >= (size_t)(K * N) ? (uint8_t *)workspace : nullptr;
+}
 }  // namespace mp8
 
 extern "C" mp8_status mp8_gemm_fp8_tuned(mp8_op op, int64_t M, int64_t N, int64_t K,
@@ -443,6 +459,13 @@ extern "C" mp8_status mp8_wgrad_update_fp16_sr(int64_t M, int64_t N, int64_t K, 
     if (K == 0 || N == 0) return MP8_OK;
     if (!w16) return MP8_ERR_INVALID_ARG;
     if (((uintptr_t)w16 | (uintptr_t)w8_out) & 15u) return MP8_ERR_ALIGNMENT;
+    if (uint8_t *codes = codes_for_separate_update(M, N, K, flags, g8_out, workspace, workspace_bytes)) {
+        const mp8_status sg = mp8_gemm_fp8(MP8_WGRAD, M, N, K, a, lda, b, ldb, alpha, nullptr, 0, codes, nullptr,
+                                           g_round, flags, g_seed, g_offset, stats, nullptr, 0, stream);
+        if (sg != MP8_OK) return sg;
+        return mp8_sgd_update_fp16_sr(w16, codes, K * N, lr, inv_loss_scale, w_round, w_seed, w_offset,
+                                      skip_if_nonzero, w8_out, nullptr, stream);
+    }
     UpdateHook upd = make_update_hook(w16, w8_out, skip_if_nonzero, lr, inv_loss_scale, w_round, w_seed, w_offset);
     const mp8_status st = gemm_impl(MP8_WGRAD, M, N, K, a, lda, b, ldb, alpha, nullptr, 0, g8_out, nullptr,
                                     g_round, flags, g_seed, g_offset, stats, workspace, workspace_bytes,
@@ -472,6 +495,13 @@ extern "C" mp8_status mp8_wgrad_momentum_fp16_sr(int64_t M, int64_t N, int64_t K
     if (K == 0 || N == 0) return MP8_OK;
     if (!w16 || !velocity) return MP8_ERR_INVALID_ARG;
     if (((uintptr_t)w16 | (uintptr_t)w8_out | (uintptr_t)velocity) & 15u) return MP8_ERR_ALIGNMENT;
+    if (uint8_t *codes = codes_for_separate_update(M, N, K, flags, g8_out, workspace, workspace_bytes)) {
+        const mp8_status sg = mp8_gemm_fp8(MP8_WGRAD, M, N, K, a, lda, b, ldb, alpha, nullptr, 0, codes, nullptr,
+                                           g_round, flags, g_seed, g_offset, stats, nullptr, 0, stream);
+        if (sg != MP8_OK) return sg;
+        return mp8_sgd_momentum_fp16_sr(w16, velocity, codes, K * N, lr, inv_loss_scale, momentum, weight_decay,
+                                        w_round, w_seed, w_offset, skip_if_nonzero, w8_out, nullptr, stream);
+    }
     UpdateHook upd = make_update_hook(w16, w8_out, skip_if_nonzero, lr, inv_loss_scale, w_round, w_seed, w_offset,
                                       velocity, momentum, weight_decay);
     const mp8_status st = gemm_impl(MP8_WGRAD, M, N, K, a, lda, b, ldb, alpha, nullptr, 0, g8_out, nullptr,
@@ -502,6 +532,13 @@ extern "C" mp8_status mp8_wgrad_adam_fp16_sr(int64_t M, int64_t N, int64_t K, co
     if (K == 0 || N == 0) return MP8_OK;
     if (!w16 || !m || !v) return MP8_ERR_INVALID_ARG;
     if (((uintptr_t)w16 | (uintptr_t)w8_out | (uintptr_t)m | (uintptr_t)v) & 15u) return MP8_ERR_ALIGNMENT;
+    if (uint8_t *codes = codes_for_separate_update(M, N, K, flags, g8_out, workspace, workspace_bytes)) {
+        const mp8_status sg = mp8_gemm_fp8(MP8_WGRAD, M, N, K, a, lda, b, ldb, alpha, nullptr, 0, codes, nullptr,
+                                           g_round, flags, g_seed, g_offset, stats, nullptr, 0, stream);
+        if (sg != MP8_OK) return sg;
+        return mp8_adam_fp16_sr(w16, m, v, codes, K * N, lr, inv_loss_scale, beta1, beta2, eps, weight_decay, step,
+                                w_round, w_seed, w_offset, skip_if_nonzero, w8_out, nullptr, stream);
+    }
     UpdateHook upd = make_update_hook(w16, w8_out, skip_if_nonzero, lr, inv_loss_scale, w_round, w_seed, w_offset);
     upd.states = 2;
     upd.state0 = m;
