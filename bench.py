@@ -430,6 +430,24 @@ def all_configs_report(mp8, torch):
                  "alg_gbs": (K * M + N * M + 9 * K * N) / us / 1e3,
                  "flop_per_byte": 2.0 * M * N * K / (K * M + N * M + 9 * K * N)})
     del a, b, acc, out, ws
+    # configs[4] as a whole: weight gradient from the row-major X8 [tokens, 1024] and E8 [tokens, 4096],
+    # rounded stochastically to 8 bits, then the FP16 master-weight step with stochastic rounding
+    # (mp8_wgrad_update_fp16_sr; lr 1e-3, loss scale 2^14)
+    M, N, K = 16384, 4096, 1024
+    x8 = (torch.randint(0, 256, (M, K), dtype=torch.uint8, device=dev) & 0x83) | 0x38
+    e8 = (torch.randint(0, 256, (M, N), dtype=torch.uint8, device=dev) & 0x83) | 0x38
+    w16 = torch.empty(K * N, dtype=torch.float16, device=dev).normal_(0, 0.02)
+    g8 = torch.empty(K * N, dtype=torch.uint8, device=dev)
+    ws = torch.empty(max(mp8.gemm_fp8_workspace_bytes(mp8.WGRAD, M, N, K), 16), dtype=torch.uint8, device=dev)
+    us = graph_time_us(torch, lambda: mp8.wgrad_update_fp16_sr(
+        M, N, K, x8, e8, w16, 1e-3, 2.0 ** -14, g8_out=g8, g_round=mp8.SR, flags=mp8.FLAG_CONTRACTION_MAJOR,
+        g_seed=5, g_offset=1, w_round=mp8.SR, w_seed=6, w_offset=1, workspace=ws), 10)
+    rows.append({"kernel": "wgrad_update_fp16_sr", "case": "configs[4] wgrad (SR) + FP16 SR update, row-major operands",
+                 "us": us, "tflops": 2.0 * M * N * K / us / 1e6,
+                 "frac_mfma_peak": 2.0 * M * N * K / us / 1e6 / FP8_PEAK_TFLOPS,
+                 "alg_gbs": (M * K + M * N + 6 * K * N) / us / 1e3,
+                 "flop_per_byte": 2.0 * M * N * K / (M * K + M * N + 6 * K * N)})
+    del x8, e8, w16, g8, ws
     n = 1 << 28
     src = torch.empty((1 << 14, 1 << 14), dtype=torch.float32, device=dev).normal_()
     d8 = torch.empty((1 << 14, 1 << 14), dtype=torch.uint8, device=dev)
