@@ -426,24 +426,20 @@ def all_configs_report(mp8, torch):
         rows.append({"kernel": "gemm_fp8", "case": name, "us": us, "tflops": flops / us / 1e6,
                      "frac_mfma_peak": flops / us / 1e6 / FP8_PEAK_TFLOPS,
                      "alg_gbs": nbytes / us / 1e3, "flop_per_byte": flops / nbytes})
-        if name.startswith("large") and hasattr(torch, "float8_e5m2") and hasattr(torch, "_scaled_mm"):
+        if hasattr(torch, "float8_e5m2") and hasattr(torch, "_scaled_mm"):
             # context, not a target: the vendor library's GEMM on the same codes, same box, same minute
             try:
                 one = torch.ones((), device=dev)
                 af, bf = a.view(torch.float8_e5m2), b.view(torch.float8_e5m2).t()
                 vendor = lambda: torch._scaled_mm(af, bf, scale_a=one, scale_b=one, out_dtype=torch.float8_e5m2)
-                for _ in range(3):
+                for _ in range(3):  # lets the library pick its kernel and workspace before the capture
                     vendor()
-                s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                s.record()
-                for _ in range(40):  # eager: a launch is far shorter than these kernels
-                    vendor()
-                e.record()
                 torch.cuda.synchronize()
-                vus = s.elapsed_time(e) / 40 * 1e3
+                vus = graph_time_us(torch, vendor)
                 rows.append({"kernel": "torch._scaled_mm (vendor library, for context)", "case": name, "us": vus,
                              "tflops": flops / vus / 1e6, "frac_mfma_peak": flops / vus / 1e6 / FP8_PEAK_TFLOPS})
             except Exception as exc:  # the table does not depend on it
+                torch.cuda.synchronize()
                 rows.append({"kernel": "torch._scaled_mm (vendor library, for context)", "case": name,
                              "error": repr(exc)[:200]})
         del a, b, out, ws
