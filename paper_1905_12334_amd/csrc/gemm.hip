@@ -87,12 +87,22 @@ struct TileConfig {
     {64, 64, "64x64x128w", MP8_WAVEK(false, false, 0), MP8_WAVEK(true, true, 0),  \
      MP8_WAVEK(false, true, 0),                                                \
      {{nullptr, nullptr, nullptr}, {nullptr, nullptr, nullptr}, MP8_WAVEK(true, true, 3)}, 0, 0}
+#define MP8_WAVEK32(BTN, BN)                                                 \
+    {gemm_wavek_kernel<EPI_PARTIAL, false, BTN, 0, 32, BN>, gemm_wavek_kernel<EPI_RNE, false, BTN, 0, 32, BN>, \
+     gemm_wavek_kernel<EPI_FULL, false, BTN, 0, 32, BN>}
+#define MP8_NO_KERNELS {nullptr, nullptr, nullptr}
+#define MP8_TILE_WAVEK32x64                                                  \
+    {32, 64, "32x64x128w", MP8_WAVEK32(false, 64), MP8_NO_KERNELS, MP8_WAVEK32(true, 64), \
+     {MP8_NO_KERNELS, MP8_NO_KERNELS, MP8_NO_KERNELS}, 0, 0}
+#define MP8_TILE_WAVEK32x32                                                  \
+    {32, 32, "32x32x128w", MP8_WAVEK32(false, 32), MP8_NO_KERNELS, MP8_NO_KERNELS, \
+     {MP8_NO_KERNELS, MP8_NO_KERNELS, MP8_NO_KERNELS}, 0, 0}
 static const TileConfig kTiles[] = {
     MP8_TILE_TN(256, 256, 2, 2, 2, 1), MP8_TILE(256, 128, 2, 2, 3, 1), MP8_TILE(128, 256, 2, 2, 3, 1),
     MP8_TILE_TN(128, 128, 2, 2, 2, 2), MP8_TILE_TN(128, 128, 2, 2, 4, 1), MP8_TILE(64, 128, 1, 4, 3, 2),
     MP8_TILE(128, 64, 4, 1, 3, 2),  MP8_TILE_TN(64, 64, 2, 2, 4, 2), MP8_TILE(64, 128, 1, 4, 2, 3),
     MP8_TILE(128, 64, 4, 1, 2, 3),  MP8_TILE_TN(64, 64, 2, 2, 2, 4),   MP8_TILE_SHORTK,
-    MP8_TILE_WAVEK,
+    MP8_TILE_WAVEK, MP8_TILE_WAVEK32x64, MP8_TILE_WAVEK32x32,
 };
 constexpr int kNumTiles = (int)(sizeof(kTiles) / sizeof(kTiles[0]));
 constexpr int kCUs = 256;
@@ -120,7 +130,8 @@ static void op_dims(mp8_op op, int64_t M, int64_t N, int64_t K, int64_t &rows, i
 // resident blocks per CU when the contraction is short, a deeper ring when it is long); small
 // outputs take 64x64 tiles and, if even those are too few, a split contraction -- kept to a
 // minimum because the second pass costs several microseconds.
-enum { T256x256 = 0, T128x128s2 = 3, T128x128s4 = 4, T128x64s2 = 9, T64x64s2 = 10, T128x128k = 11, T64x64w = 12 };
+enum { T256x256 = 0, T128x128s2 = 3, T128x128s4 = 4, T128x64s2 = 9, T64x64s2 = 10, T128x128k = 11, T64x64w = 12,
+       T32x64w = 13, T32x32w = 14 };
 static Plan make_plan(int64_t rows, int64_t cols, int64_t kc, int tile_config, int split_k,
                       int layout = 0) {  // bit 0: a contraction-major, bit 1: b
     Plan pl{};
@@ -152,6 +163,12 @@ static Plan make_plan(int64_t rows, int64_t cols, int64_t kc, int tile_config, i
         const double fill256 = (double)n256 / (double)(((n256 + kCUs - 1) / kCUs) * kCUs);
         const int64_t n64 = count(T64x64s2);
         if (n256 >= 208 && fill256 >= 0.8 && ksteps >= 8) t = T256x256;
+        // so few tiles that most CUs would idle and the contraction is too short to split:
+        // half the rows per tile, and half the columns too if that still fits one round
+        else if (layout == 0 && 4 * n64 <= kCUs && ksteps >= 16 && ksteps <= 40 && count(T32x32w) <= kCUs)
+            t = T32x32w;
+        else if (!(layout & 1) && 2 * n64 <= kCUs && ksteps >= 16 && ksteps <= 40 && count(T32x64w) <= kCUs)
+            t = T32x64w;
         else if (n64 <= kCUs && ksteps >= 16) t = T64x64w;  // one workgroup per CU, one round
         else if (tn && (n128 < 16 || (n128 < 192 && ksteps <= 64))) t = T64x64s2;
         else if (tn) t = ksteps >= 64 ? T128x128s4 : T128x128s2;
@@ -166,6 +183,8 @@ static Plan make_plan(int64_t rows, int64_t cols, int64_t kc, int tile_config, i
     int s = 1;
     if (kTiles[t].max_ksteps > 0) {
         s = 1;  // these kernels take the whole contraction at once
+    } else if (split_k == 0 && (t == T32x64w || t == T32x32w)) {
+        s = 1;
     } else if (split_k == 0 && t == T64x64w) {
         // one workgroup per CU and never more workgroups than CUs (a second round would double
         // the time); at least two stages for each of the four waves.  A split costs the finishing

@@ -17,14 +17,20 @@ namespace mp8 {
 // are added in wave order; each thread then owns sixteen consecutive columns of one row for
 // the epilogue.  Operand layouts and slab images as in the general kernel (ATN / BTN:
 // contraction-major).  CONV = 3: the weight gradient of the 3x3 convolution (tap shift per tile
-// row), else 0.
-template <int EPI, bool ATN, bool BTN, int CONV>
+// row), else 0.  BM = 32 / BN = 32 (row-major operand only): half the tile rows / columns, for
+// outputs with so few 64x64 tiles that most CUs would idle while the busy ones wait for their
+// own loads (a CU takes 64 bytes per clock however few of them work).
+template <int EPI, bool ATN, bool BTN, int CONV, int BM = 64, int BN = 64>
 __global__ __launch_bounds__(256, 1) void gemm_wavek_kernel(const GemmArgs p) {
     static_assert(CONV == 0 || (CONV == 3 && ATN && BTN), "plain or convolution weight gradient");
     static_assert(BTN || !ATN, "a alone contraction-major is not built");
-    constexpr int BM = 64, BN = 64;
-    constexpr int SLAB = 64 * BK;           // 64 rows of 128 bytes, or 128 contraction rows of 64
-    constexpr int STAGE = 2 * SLAB;         // a, then b
+    static_assert(BM == 64 || (BM == 32 && !ATN), "the 32-row tile takes a row-major a");
+    static_assert(BN == 64 || (BN == 32 && !BTN), "the 32-column tile takes a row-major b");
+    constexpr int MI = BM / 32, NJ = BN / 32;  // 32x32 accumulator tiles along rows and columns
+    constexpr int QA = BM / 8, QB = BN / 8;    // direct loads per stage and operand (eight rows each)
+    constexpr int SLAB_A = BM * BK;         // BM rows of 128 bytes, or 128 contraction rows of 64
+    constexpr int SLAB = BN * BK;           // b
+    constexpr int STAGE = SLAB_A + SLAB;    // a, then b
     constexpr int WAVE_LDS = 2 * STAGE;     // ring of two stages per wave
     constexpr int RED_LD = BN + 4;          // floats per row of a tile parked for the reduction
     static_assert(4 * BM * RED_LD * 4 <= 4 * WAVE_LDS, "reduction buffers fit in the rings");
@@ -87,21 +93,21 @@ __global__ __launch_bounds__(256, 1) void gemm_wavek_kernel(const GemmArgs p) {
     lane_offsets(BTN, col0, p.cols, p.ldb, ob);
     uint8_t *ring = lds + wave * WAVE_LDS;
     const uint32_t ring0 = lds_address(ring);
-    auto issue = [&](int j) {  // stage j of this wave into buffer j % 2: 16 loads
+    auto issue = [&](int j) {  // stage j of this wave into buffer j % 2: QA + QB loads
         const uint8_t *ak = a_tile + (int64_t)(4 * j) * a_kstep;
         const uint8_t *bk = b_tile + (int64_t)(4 * j) * b_kstep;
         const uint32_t sa = ring0 + (j & 1) * STAGE;
 #pragma unroll
-        for (int q = 0; q < 8; ++q) dma16(ak, oa[q], sa + q * 1024);
+        for (int q = 0; q < QA; ++q) dma16(ak, oa[q], sa + q * 1024);
 #pragma unroll
-        for (int q = 0; q < 8; ++q) dma16(bk, ob[q], sa + SLAB + q * 1024);
+        for (int q = 0; q < QB; ++q) dma16(bk, ob[q], sa + SLAB_A + q * 1024);
     };
 
-    f32x16 acc[2][2];
+    f32x16 acc[MI][NJ];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < NJ; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
     const int frow = lane & 31, fkb = lane >> 5, t16 = lane & 15;
@@ -110,7 +116,7 @@ __global__ __launch_bounds__(256, 1) void gemm_wavek_kernel(const GemmArgs p) {
     // 16-byte reads of a row-major slab, four transposing reads of eight contraction indices
     // each of a contraction-major one (see the general kernel)
     auto fragment = [&](const uint8_t *s, int sub, int f) -> i32x8 {
-        const uint8_t *slab = s + (f >> 1) * SLAB;
+        const uint8_t *slab = s + (f >> 1) * SLAB_A;
         if ((f < 2 && ATN) || (f >= 2 && BTN)) {
             const int m = (f & 1) * 32 + (frow & 16);
             const int mc = m >> 4;
@@ -138,18 +144,23 @@ __global__ __launch_bounds__(256, 1) void gemm_wavek_kernel(const GemmArgs p) {
     if (mine > 0) issue(0);
     if (mine > 1) issue(1);
     for (int j = 0; j < mine; ++j) {
-        if (j + 1 < mine) wait_vm_lds<16>();  // the sixteen loads of the next stage may fly
+        if (j + 1 < mine) wait_vm_lds<QA + QB>();  // the loads of the next stage may fly
         else wait_vm_lds<0>();
         const uint8_t *s = ring + (j & 1) * STAGE;
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
-            const i32x8 a0 = fragment(s, sub, 0), a1 = fragment(s, sub, 1);
-            const i32x8 b0 = fragment(s, sub, 2), b1 = fragment(s, sub, 3);
+            i32x8 af[MI];
+#pragma unroll
+            for (int i = 0; i < MI; ++i) af[i] = fragment(s, sub, i);
+            i32x8 bf[NJ];
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) bf[j] = fragment(s, sub, 2 + j);
             // bf8 x bf8, unscaled; b as the "row" matrix: a lane gets consecutive output columns
-            acc[0][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b0, a0, acc[0][0], 1, 1, 0, 0, 0, 0);
-            acc[0][1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b1, a0, acc[0][1], 1, 1, 0, 0, 0, 0);
-            acc[1][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b0, a1, acc[1][0], 1, 1, 0, 0, 0, 0);
-            acc[1][1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b1, a1, acc[1][1], 1, 1, 0, 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(bf[j], af[i], acc[i][j], 1, 1, 0, 0, 0, 0);
         }
         if (j + 2 < mine) {
             // the loads below are invisible to the compiler (it could sink the multiplications
@@ -165,9 +176,9 @@ __global__ __launch_bounds__(256, 1) void gemm_wavek_kernel(const GemmArgs p) {
     __syncthreads();  // every wave is done with its ring
     float *red = reinterpret_cast<float *>(lds);
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < NJ; ++j)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 f32x4 o = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
@@ -176,8 +187,9 @@ __global__ __launch_bounds__(256, 1) void gemm_wavek_kernel(const GemmArgs p) {
     __syncthreads();
     StatsAcc st;
     const bool fast_cols = (p.cols & 15) == 0;
-    {
-        const int rr = threadIdx.x >> 2, cg = threadIdx.x & 3;
+    if (BM * BN == 64 * 64 || threadIdx.x < BM * BN / 16) {  // whole waves either way
+        constexpr int CG = BN / 16;
+        const int rr = threadIdx.x / CG, cg = threadIdx.x % CG;
         const int64_t r = row0 + rr, c = col0 + 16 * cg;
         float v[16];
 #pragma unroll

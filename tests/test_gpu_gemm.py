@@ -117,8 +117,10 @@ def test_static_lds_of_every_kernel_is_what_its_tile_implies(mp8):
             got = mp8.gemm_tile_config_lds_bytes(i, epi)
             if name.endswith("k"):          # all stages in dynamic LDS; statistics need 1 KB
                 assert 0 <= got <= 1024, (name, epi, got)
-            elif name.endswith("w"):        # a two-stage ring of 16 KB stages per wave
-                assert 4 * 2 * 16384 <= got <= 4 * 2 * 16384 + 1024, (name, epi, got)
+            elif name.endswith("w"):        # a two-stage ring of (BM + BN) x 128 bytes per wave
+                bm, bn = (int(x) for x in name.split("x")[:2])
+                ring = 4 * 2 * (bm + bn) * 128
+                assert ring <= got <= ring + 1024, (name, epi, got)
             else:
                 bm, bn, rest = name.split("x")
                 stages = int(rest.split("s")[1])
@@ -437,6 +439,61 @@ def test_wave_split_kernel_all_epilogues_and_uneven_slices(mp8):
         torch.cuda.synchronize()
         ok, worst, _ = acc_tolerance_ok(host(acc2).reshape(rows, cols) / 2, ref, absref, kc)
         assert ok, worst
+
+
+def test_small_wave_split_tiles_every_epilogue_and_their_automatic_choice(mp8):
+    """The 32x64 and 32x32 tiles of the kernel that divides the contraction among the waves (for
+    outputs with so few 64x64 tiles that most CUs would idle, e.g. the per-timestep GEMMs of the
+    LSTM configuration): rows and columns ragged against the tile, 19 stages (uneven over four
+    waves and over slices), RNE and SR, saturation, statistics, FP32 output, row-major operands
+    and -- for the 32x64 tile -- b contraction-major; then the planner's own choice."""
+    names = mp8.gemm_tile_configs()
+    rows, cols, kc = 100, 208, 128 * 19
+    a8 = workloads.random_e5m2_codes(51, (rows, kc))
+    b8 = workloads.random_e5m2_codes(52, (cols, kc))
+    a8, b8 = (a8 & 0x83) | 0x38, (b8 & 0x83) | 0x38
+    ref, absref = oracle.gemm_ref(a8, b8)
+    for name in ("32x64x128w", "32x32x128w"):
+        tile = 1 + names.index(name)
+        for split in (1, 3):
+            assert mp8.gemm_fp8_plan(mp8.FWD, rows, cols, kc, 0, tile, split) == (name, split)
+            for mode, fl, alpha in ((oracle.RNE, 0, 1.0), (oracle.SR, 0, 0.01), (oracle.SR, oracle.FLAG_SATURATE, 40.0)):
+                acc, out8, out8_t, st = run_gemm(mp8, a8, b8, want_t=True, tile_config=tile, split_k=split,
+                                                 alpha=alpha, round=mode, flags=fl, seed=6, offset=2)
+                check_outputs(acc, out8, ref, absref, kc, mode=mode, seed=6, offset=2, alpha=alpha, flags=fl)
+                assert np.array_equal(out8_t, out8.T), (name, split, mode)
+                ost = oracle.Stats()
+                oracle.quantize_e5m2(acc, scale=alpha, mode=mode, seed=6, offset=2, flags=fl, stats=ost)
+                assert st == ost.as_tuple(), (name, split, mode, fl)
+    # b contraction-major (the forward GEMM from row-major weights) on the 32x64 tile
+    import torch
+    b_km = np.ascontiguousarray(b8.T)
+    tile = 1 + names.index("32x64x128w")
+    acc = torch.empty((rows, cols), dtype=torch.float32, device="cuda")
+    out = torch.empty((rows, cols), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(max(mp8.gemm_fp8_workspace_bytes(mp8.FWD, rows, cols, kc, tile, 1), 16), dtype=torch.uint8,
+                     device="cuda")
+    mp8.gemm_fp8(mp8.FWD, rows, cols, kc, gpu(a8), gpu(b_km), out8=out, acc=acc, acc_mode=1, round=oracle.SR, seed=6,
+                 offset=2, flags=mp8.FLAG_B_CONTRACTION_MAJOR, workspace=ws, tile_config=tile, split_k=1)
+    torch.cuda.synchronize()
+    check_outputs(host(acc), host(out), ref, absref, kc, mode=oracle.SR, seed=6, offset=2)
+    # no contraction-major b for the 32-column tile: no plan, and the call is refused
+    t32 = 1 + names.index("32x32x128w")
+    assert mp8.gemm_fp8_plan(mp8.FWD, rows, cols, kc, mp8.FLAG_B_CONTRACTION_MAJOR, t32)[0] is None
+    with pytest.raises(mp8.Mp8Error):
+        mp8.gemm_fp8(mp8.FWD, rows, cols, kc, gpu(a8), gpu(b_km), out8=out, flags=mp8.FLAG_B_CONTRACTION_MAJOR,
+                     workspace=ws, tile_config=t32)
+    # the per-timestep GEMMs of the LSTM configuration (128 rows): few tiles, contraction too
+    # short to split
+    assert mp8.gemm_fp8_plan(mp8.BWD_DATA, 128, 4096, 2048) == ("32x32x128w", 1)
+    assert mp8.gemm_fp8_plan(mp8.FWD, 128, 4096, 2048) == ("32x64x128w", 1)
+    assert mp8.gemm_fp8_plan(mp8.FWD, 128, 4096, 2048, mp8.FLAG_B_CONTRACTION_MAJOR) == ("32x64x128w", 1)
+    lay_a = workloads.random_e5m2_codes(53, (128, 4096))
+    lay_b = workloads.random_e5m2_codes(54, (2048, 4096))
+    lay_a, lay_b = (lay_a & 0x8F) | 0x30, (lay_b & 0x8F) | 0x30
+    r2, ar2 = oracle.gemm_ref(lay_a, lay_b)
+    acc, out8, _, _ = run_gemm(mp8, lay_a, lay_b, op=mp8.BWD_DATA, dims=(128, 4096, 2048))
+    check_outputs(acc, out8, r2, ar2, 4096)
 
 
 def test_weight_gradient_from_row_major_activations_and_errors(mp8):
