@@ -1,7 +1,8 @@
-"""GPU parity at sizes whose element indices do not fit 32 bits: tensors of more than 2^32
-elements through the Q node, the random stream and the update.  The tensors live on the GPU only
-(tens of GB); the oracle computes sampled elements one by one -- the head, the ragged tail, both
-sides of index 2^32 and random positions."""
+"""GPU parity at sizes whose element indices or byte offsets do not fit 32 bits: tensors of more
+than 2^32 elements through the Q node, the random stream and the update; GEMM operands, outputs
+and contractions beyond 2^32 bytes.  The tensors live on the GPU only (tens of GB); the oracle
+computes sampled elements or rows -- the head, the ragged tail, both sides of offset 2^32 and
+random positions."""
 import numpy as np
 import pytest
 
@@ -110,3 +111,139 @@ def test_update_beyond_2_32_elements(mp8):
     torch.cuda.synchronize()
     want, _ = oracle.sgd_update_fp16(ws, gs, 0.02, 1.0 / 1024, mode=oracle.RNE)
     assert np.array_equal(take(w.view(torch.int16), idx).view(np.uint16), want)
+
+
+def exact_codes_on_gpu(shape, exps, seed):
+    """Random E5M2 codes of +-{1, 1.25, 1.5, 1.75} * 2^e, e drawn from `exps` (biased exponent
+    fields), generated on the GPU: sums of products of such values stay exactly representable
+    in FP32, so accumulators must equal the double-precision reference bit for bit."""
+    import torch
+    g = torch.Generator(device="cuda").manual_seed(seed)
+    c = torch.randint(0, 256, shape, dtype=torch.uint8, device="cuda", generator=g)
+    e = torch.tensor(exps, dtype=torch.uint8, device="cuda")[((c >> 2) & 3).long() % len(exps)]
+    return (c & 0x83) | (e << 2)
+
+
+def row_samples(M, row_bytes, seed):
+    cross = TWO32 // row_bytes                  # the row in which byte offset 2^32 falls
+    rng = np.random.default_rng(seed)
+    return np.unique(np.concatenate([np.arange(0, 64), np.arange(M - 140, M), np.arange(cross - 40, cross + 40),
+                                     rng.integers(0, M, 64)]).astype(np.int64))
+
+
+def test_tall_layer_operands_beyond_2_32_bytes(mp8):
+    """A layer with so many rows (batch x pixels) that activations, their codes and the
+    backward-data output each exceed 2^32 bytes: the forward GEMM that quantises its
+    activations, the plain forward GEMM and the backward-data GEMM (fused epilogue, and the
+    two-pass path with an FP32 output), on sampled rows against the oracle."""
+    import torch
+    M, N, K = (1 << 22) + 77, 128, 1152
+    rng = np.random.default_rng(8)
+    w8 = ((rng.integers(0, 2, (K, N)) << 7) | (rng.integers(15, 19, (K, N)) << 2) | rng.integers(0, 4, (K, N))).astype(np.uint8)
+    w8t = np.ascontiguousarray(w8.T)
+    W8, W8t = torch.from_numpy(w8).cuda(), torch.from_numpy(w8t).cuda()
+    x8_codes = exact_codes_on_gpu((M, K), [15, 16, 17, 18], 11)
+    X = x8_codes.view(torch.float8_e5m2).to(torch.float32)     # the values of those codes, as FP32 activations
+    del x8_codes
+    rows = row_samples(M, K, 5)
+    rows_d = torch.from_numpy(rows).cuda()
+    ox8 = oracle.quantize_e5m2(X[rows_d].cpu().numpy())[0]
+    ref, _ = oracle.gemm_ref(ox8, w8t, want_abs=False)
+    want8 = oracle.round_ref_e5m2(ref)
+
+    def buf(n):
+        return torch.full((n + 64,), 0xAA, dtype=torch.uint8, device="cuda")
+
+    X8, Y8, Y8b = buf(M * K), buf(M * N), buf(M * N)
+    acc = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(mp8.gemm_fp8_workspace_bytes(mp8.FWD, M, N, K), 16), dtype=torch.uint8, device="cuda")
+    mp8.quantize_gemm_fwd_fp8(M, N, K, X, X8[: M * K].view(M, K), W8, out8=Y8[: M * N].view(M, N), workspace=ws)
+    mp8.quantize_gemm_fwd_fp8(M, N, K, X, X8[: M * K].view(M, K), W8, out8=Y8b[: M * N].view(M, N), acc=acc,
+                              acc_mode=1, workspace=ws)
+    torch.cuda.synchronize()
+    for b in (X8, Y8, Y8b):
+        assert bool((b[-64:] == 0xAA).all()), "write past the end"
+    assert np.array_equal(X8[: M * K].view(M, K)[rows_d].cpu().numpy(), ox8)
+    assert np.array_equal(acc[rows_d].cpu().numpy().astype(np.float64), ref)
+    assert np.array_equal(Y8[: M * N].view(M, N)[rows_d].cpu().numpy(), want8)
+    assert bool(torch.equal(Y8, Y8b))
+    del X
+    # the plain forward GEMM from the codes
+    Y8b.fill_(0xAA)
+    acc.zero_()
+    mp8.gemm_fp8(mp8.FWD, M, N, K, X8[: M * K].view(M, K), W8t, out8=Y8b[: M * N].view(M, N), acc=acc, acc_mode=1,
+                 workspace=ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(acc[rows_d].cpu().numpy().astype(np.float64), ref)
+    assert bool(torch.equal(Y8, Y8b))
+    del acc, Y8, Y8b
+    # backward data: errors [M, N] . weights [K, N] -> [M, K], more than 2^32 output bytes
+    E8 = exact_codes_on_gpu((M, N), [15, 16, 17, 18], 12)
+    ref2, _ = oracle.gemm_ref(E8[rows_d].cpu().numpy(), w8, want_abs=False)
+    want2 = oracle.round_ref_e5m2(ref2)
+    D8, D8b = X8, buf(M * K)                      # reuse the activations' buffer (canary intact)
+    mp8.gemm_fp8(mp8.BWD_DATA, M, N, K, E8, W8, out8=D8[: M * K].view(M, K))
+    acc2 = torch.empty((M, K), dtype=torch.float32, device="cuda")
+    mp8.gemm_fp8(mp8.BWD_DATA, M, N, K, E8, W8, out8=D8b[: M * K].view(M, K), acc=acc2, acc_mode=1)
+    torch.cuda.synchronize()
+    assert bool((D8[-64:] == 0xAA).all()) and bool((D8b[-64:] == 0xAA).all()), "write past the end"
+    assert np.array_equal(D8[: M * K].view(M, K)[rows_d].cpu().numpy(), want2)
+    assert np.array_equal(acc2[rows_d].cpu().numpy().astype(np.float64), ref2)
+    assert bool(torch.equal(D8, D8b))
+
+
+def test_weight_gradient_over_a_contraction_beyond_2_32_bytes(mp8):
+    """The weight gradient of the same tall layer: a contraction over 2^22 + 384 rows read from
+    the row-major activations (more than 2^32 bytes) and errors, split into slices and summed by
+    the finishing pass; sampled output rows against the oracle's exact sums."""
+    import torch
+    M, N, K = (1 << 22) + 384, 128, 1152
+    X8 = exact_codes_on_gpu((M, K), [15, 16], 21)
+    E8 = exact_codes_on_gpu((M, N), [15, 16], 22)
+    ks = np.array([0, 1, 63, 64, 577, 1150, 1151])
+    a_rows = np.ascontiguousarray(X8[:, torch.from_numpy(ks).cuda()].t().cpu().numpy())      # [7, M]
+    e8t = np.ascontiguousarray(E8.t().cpu().numpy())                                          # [N, M]
+    ref, _ = oracle.gemm_ref(a_rows, e8t, want_abs=False)
+    assert np.max(np.abs(ref)) < 2.0 ** 20          # every partial sum far inside FP32's exact range
+    g8 = torch.full((K * N + 64,), 0xAA, dtype=torch.uint8, device="cuda")
+    acc = torch.empty((K, N), dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(mp8.gemm_fp8_workspace_bytes(mp8.WGRAD, M, N, K), 16), dtype=torch.uint8, device="cuda")
+    alpha = 2.0 ** -6
+    mp8.gemm_fp8(mp8.WGRAD, M, N, K, X8, E8, out8=g8[: K * N].view(K, N), acc=acc, acc_mode=1, alpha=alpha,
+                 flags=mp8.FLAG_CONTRACTION_MAJOR, workspace=ws)
+    torch.cuda.synchronize()
+    assert bool((g8[-64:] == 0xAA).all()), "write past the end"
+    assert np.array_equal(acc.cpu().numpy()[ks].astype(np.float64), ref)
+    assert np.array_equal(g8[: K * N].view(K, N).cpu().numpy()[ks], oracle.round_ref_e5m2(ref, alpha=alpha))
+
+
+def test_output_beyond_2_32_elements_with_stochastic_rounding(mp8):
+    """An output of more than 2^32 elements (short contraction): the stochastic epilogue draws
+    the random halfword of each element's row-major index, also beyond 2^32; FP32 output and
+    fused epilogue; sampled rows against the oracle, element by element."""
+    import torch
+    R = 65536 + 64
+    kc = 128
+    assert R * R > TWO32
+    a8, b8 = exact_codes_on_gpu((R, kc), [15, 16, 17, 18], 31), exact_codes_on_gpu((R, kc), [15, 16, 17, 18], 32)
+    rows = np.array([0, 1, TWO32 // R, TWO32 // R + 1, R - 1])
+    rows_d = torch.from_numpy(rows).cuda()
+    ref, _ = oracle.gemm_ref(a8[rows_d].cpu().numpy(), b8.cpu().numpy(), want_abs=False)
+    seed, offset, alpha = 99, 5, 2.0 ** -7
+    want = np.array([[oracle.e5m2_encode(float(np.float32(v) * np.float32(alpha)), oracle.SR,
+                                         oracle.sr_bits(seed, offset, int(r) * R + c)) for c, v in enumerate(line)]
+                     for r, line in zip(rows, ref)], dtype=np.uint8)
+    out = torch.full((R * R + 64,), 0xAA, dtype=torch.uint8, device="cuda")
+    mp8.gemm_fp8(mp8.FWD, R, R, kc, a8, b8, out8=out[: R * R].view(R, R), alpha=alpha, round=mp8.SR, seed=seed,
+                 offset=offset)
+    torch.cuda.synchronize()
+    assert bool((out[-64:] == 0xAA).all()), "write past the end"
+    assert np.array_equal(out[: R * R].view(R, R)[rows_d].cpu().numpy(), want)
+    # the two-pass path (FP32 output, finishing kernel) gives the same codes everywhere
+    out2 = torch.full((R * R + 64,), 0xAA, dtype=torch.uint8, device="cuda")
+    acc = torch.empty((R, R), dtype=torch.float32, device="cuda")
+    mp8.gemm_fp8(mp8.FWD, R, R, kc, a8, b8, out8=out2[: R * R].view(R, R), acc=acc, acc_mode=1, alpha=alpha,
+                 round=mp8.SR, seed=seed, offset=offset)
+    torch.cuda.synchronize()
+    assert np.array_equal(acc[rows_d].cpu().numpy().astype(np.float64), ref)
+    assert bool(torch.equal(out, out2))
