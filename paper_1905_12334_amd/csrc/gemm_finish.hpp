@@ -95,9 +95,24 @@ __device__ __forceinline__ void update_element(const UpdateHook &u, int64_t i, u
     if (u.w8_out != nullptr) u.w8_out[i] = (uint8_t)e5m2_of_half(h);
 }
 
+// What update4 reads of elements i0 .. i0+3: fetched before the slices are summed, so that these
+// loads fly together with the slice loads instead of after them.
+struct UpdateOperands4 {
+    u32x2 w;
+    f32x4 s0, s1;
+};
+template <int STATES>
+__device__ __forceinline__ UpdateOperands4 load_update4(const UpdateHook &u, int64_t i0) {
+    UpdateOperands4 o{};
+    o.w = *reinterpret_cast<const u32x2 *>(u.w16 + i0);
+    if constexpr (STATES >= 1) o.s0 = *reinterpret_cast<const f32x4 *>(u.state0 + i0);
+    if constexpr (STATES == 2) o.s1 = *reinterpret_cast<const f32x4 *>(u.state1 + i0);
+    return o;
+}
+
 // Elements i0 .. i0+3 (i0 % 4 == 0) from their four packed gradient codes.
 template <int STATES>
-__device__ __forceinline__ void update4(const UpdateHook &u, int64_t i0, uint32_t pk) {
+__device__ __forceinline__ void update4(const UpdateHook &u, int64_t i0, uint32_t pk, const UpdateOperands4 &in) {
     uint32_t r01 = 0, r23 = 0;
     if (u.sr) {
         const Philox rng(u.seed, u.offset);
@@ -106,17 +121,17 @@ __device__ __forceinline__ void update4(const UpdateHook &u, int64_t i0, uint32_
         r23 = (i0 & 4) ? w.w : w.y;
     }
     u32x2 *wp = reinterpret_cast<u32x2 *>(u.w16 + i0);
-    const u32x2 wr = *wp;
+    const u32x2 wr = in.w;
     uint32_t h[4];
     const uint32_t w16v[4] = {wr.x & 0xFFFFu, wr.x >> 16, wr.y & 0xFFFFu, wr.y >> 16};
     const uint32_t r16[4] = {r01 & 0xFFFFu, r01 >> 16, r23 & 0xFFFFu, r23 >> 16};
     float st[4][2] = {{0.0f, 0.0f}, {0.0f, 0.0f}, {0.0f, 0.0f}, {0.0f, 0.0f}};
     if constexpr (STATES >= 1) {
-        const f32x4 x = *reinterpret_cast<const f32x4 *>(u.state0 + i0);
+        const f32x4 x = in.s0;
         st[0][0] = x.x; st[1][0] = x.y; st[2][0] = x.z; st[3][0] = x.w;
     }
     if constexpr (STATES == 2) {
-        const f32x4 x = *reinterpret_cast<const f32x4 *>(u.state1 + i0);
+        const f32x4 x = in.s1;
         st[0][1] = x.x; st[1][1] = x.y; st[2][1] = x.z; st[3][1] = x.w;
     }
 #pragma unroll
@@ -157,24 +172,37 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const float *__restr
         for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += stride) {
             const int64_t i0 = t << 2;
             const int64_t r = i0 / ep.cols, c = i0 - r * ep.cols;
+            UpdateOperands4 uo{};
+            if (upd.w16 != nullptr) uo = load_update4<STATES>(upd, i0);
+            // Up to eight slice loads in flight, added in slice order.  Slices beyond the last are
+            // read from the last one again and replaced by +0: the running sum starts from +0 and
+            // is therefore never -0, so adding +0 leaves every bit of it as it is.
             float v[4] = {0.f, 0.f, 0.f, 0.f};
-            int s = 0;
-            for (; s + 4 <= splits; s += 4) {  // four loads in flight, added in slice order
-                f32x4 x0 = *reinterpret_cast<const f32x4 *>(partial + (int64_t)s * slice + i0);
-                f32x4 x1 = *reinterpret_cast<const f32x4 *>(partial + (int64_t)(s + 1) * slice + i0);
-                f32x4 x2 = *reinterpret_cast<const f32x4 *>(partial + (int64_t)(s + 2) * slice + i0);
-                f32x4 x3 = *reinterpret_cast<const f32x4 *>(partial + (int64_t)(s + 3) * slice + i0);
-                v[0] += x0.x; v[1] += x0.y; v[2] += x0.z; v[3] += x0.w;
-                v[0] += x1.x; v[1] += x1.y; v[2] += x1.z; v[3] += x1.w;
-                v[0] += x2.x; v[1] += x2.y; v[2] += x2.z; v[3] += x2.w;
-                v[0] += x3.x; v[1] += x3.y; v[2] += x3.z; v[3] += x3.w;
-            }
-            for (; s < splits; ++s) {
-                f32x4 x = *reinterpret_cast<const f32x4 *>(partial + (int64_t)s * slice + i0);
-                v[0] += x.x; v[1] += x.y; v[2] += x.z; v[3] += x.w;
+            auto add_batch = [&](int s, auto nb) {
+                constexpr int NB = decltype(nb)::value;
+                f32x4 x[NB];
+#pragma unroll
+                for (int j = 0; j < NB; ++j) {
+                    const int sj = s + j < splits ? s + j : splits - 1;
+                    x[j] = *reinterpret_cast<const f32x4 *>(partial + (int64_t)sj * slice + i0);
+                }
+#pragma unroll
+                for (int j = 0; j < NB; ++j) {
+                    const bool on = s + j < splits;
+                    v[0] += on ? x[j].x : 0.f; v[1] += on ? x[j].y : 0.f;
+                    v[2] += on ? x[j].z : 0.f; v[3] += on ? x[j].w : 0.f;
+                }
+            };
+            if (splits == 1) {
+                add_batch(0, std::integral_constant<int, 1>{});
+            } else {
+                for (int s = 0; s < splits; s += 8) {
+                    if (splits - s > 4) add_batch(s, std::integral_constant<int, 8>{});
+                    else add_batch(s, std::integral_constant<int, 4>{});
+                }
             }
             const uint32_t pk = finish4(ep, r, c, v, st);
-            if (updating) update4<STATES>(upd, i0, pk);
+            if (updating) update4<STATES>(upd, i0, pk, uo);
         }
     } else {
         for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < slice; i += stride) {
