@@ -247,3 +247,30 @@ def test_output_beyond_2_32_elements_with_stochastic_rounding(mp8):
     torch.cuda.synchronize()
     assert np.array_equal(acc[rows_d].cpu().numpy().astype(np.float64), ref)
     assert bool(torch.equal(out, out2))
+
+
+def test_optimizers_with_state_beyond_2_32_elements(mp8):
+    """Momentum SGD and ADAM (FP32 state arrays of more than 2^34 bytes) on sampled elements."""
+    import torch
+    n = TWO32 + 8 * 321 + 3
+    idx = sample_indices(n, 6)
+    g = torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 256)
+    g = torch.where((g & 0x7C) == 0x7C, g & 0xBF, g)
+    gs = take(g, idx)
+    w = torch.empty(n, dtype=torch.float16, device="cuda").normal_(0, 0.05)
+    vel = torch.empty(n, dtype=torch.float32, device="cuda").normal_(0, 0.01)
+    ws, vs = take(w.view(torch.int16), idx).view(np.uint16), take(vel, idx)
+    mp8.sgd_momentum_fp16_sr(w.view(torch.int16), vel, g, 0.02, 1.0 / 1024, 0.9, weight_decay=1e-4, round=mp8.RNE)
+    torch.cuda.synchronize()
+    ow, ov, _ = oracle.sgd_momentum_fp16(ws, vs, gs, 0.02, 1.0 / 1024, 0.9, weight_decay=1e-4, mode=oracle.RNE)
+    assert np.array_equal(take(w.view(torch.int16), idx).view(np.uint16), ow)
+    assert np.array_equal(take(vel, idx).view(np.uint32), ov.view(np.uint32))
+    # ADAM, third step, on the weights as they are now; the velocity array serves as first moment
+    m, v = vel, torch.empty(n, dtype=torch.float32, device="cuda").uniform_(0.0, 1e-4)
+    ws, ms, vs = take(w.view(torch.int16), idx).view(np.uint16), take(m, idx), take(v, idx)
+    mp8.adam_fp16_sr(w.view(torch.int16), m, v, g, 1e-3, 1.0 / 1024, 3, round=mp8.RNE)
+    torch.cuda.synchronize()
+    ow, om, ov, _ = oracle.adam_fp16(ws, ms, vs, gs, 1e-3, 1.0 / 1024, 3, mode=oracle.RNE)
+    assert np.array_equal(take(w.view(torch.int16), idx).view(np.uint16), ow)
+    assert np.array_equal(take(m, idx).view(np.uint32), om.view(np.uint32))
+    assert np.array_equal(take(v, idx).view(np.uint32), ov.view(np.uint32))
