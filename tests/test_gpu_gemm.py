@@ -177,6 +177,30 @@ def test_short_contraction_automatic_choice_full_size(mp8):
     check_outputs(acc, out8, ref, absref, kc)
 
 
+@pytest.mark.parametrize("rows,cols,kc,alpha", [(160 * 128 + 37, 1152, 128, 1.0), (161 * 128, 384, 256, 0.25),
+                                                (25088, 1152, 128, 1.0), (160 * 128 + 1, 384, 128, 1.0)])
+def test_short_contraction_many_row_blocks(mp8, rows, cols, kc, alpha):
+    """Short contraction over many blocks of 128 rows and whole 128-column tiles (the
+    backward-data GEMM of configs[1] is the third case): exact-sum operands, every output byte
+    against the oracle, with a ragged and a full last row block; the fused RNE epilogue and the
+    path with an FP32 output (finishing pass) must give the same codes."""
+    import torch
+    rng = np.random.default_rng(rows + cols + kc)
+    a8, b8 = exact_sum_codes(rng, (rows, kc)), exact_sum_codes(rng, (cols, kc))
+    ref, _ = oracle.gemm_ref(a8, b8, want_abs=False)
+    want8 = oracle.round_ref_e5m2(ref, alpha=alpha)
+    a, b = gpu(a8), gpu(b8)
+    obuf = torch.full((rows * cols + 64,), 0xAA, dtype=torch.uint8, device="cuda")
+    for _ in range(2):          # twice: the second call finds the caches warm
+        mp8.gemm_fp8(mp8.FWD, rows, cols, kc, a, b, out8=obuf[: rows * cols].view(rows, cols), alpha=alpha)
+    torch.cuda.synchronize()
+    assert bool((obuf[rows * cols:] == 0xAA).all()), "write past the end of out8"
+    assert np.array_equal(host(obuf[: rows * cols]).reshape(rows, cols), want8)
+    acc, out8, _, _ = run_gemm(mp8, a8, b8, alpha=alpha)
+    assert np.array_equal(acc.astype(np.float64), ref)
+    assert np.array_equal(out8, want8)
+
+
 @pytest.mark.parametrize("shape", [(1, 1, 1), (3, 5, 7), (17, 33, 100), (64, 64, 128), (100, 36, 256),
                                    (257, 130, 384), (31, 515, 128), (130, 70, 130)])
 def test_ragged_shapes_identity_and_onehot(mp8, shape):
