@@ -77,6 +77,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-conv-step", action="store_true",
                     help="skip the implicit-GEMM convolution form of the same layer")
+    ap.add_argument("--vendor-gemm", action="store_true",
+                    help="also time the vendor library's GEMM (torch._scaled_mm, e5m2 in and out) beside every "
+                         "GEMM row of the all_configs table, for context")
     ap.add_argument("--no-all-configs", action="store_true",
                     help="skip the kernel-level table over the GEMM shapes of all configurations")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -378,7 +381,7 @@ def graph_time_us(torch, fn, reps=20):
     return s.elapsed_time(e) / (2 * reps) * 1e3
 
 
-def all_configs_report(mp8, torch):
+def all_configs_report(mp8, torch, vendor_gemm=False):
     """Kernel-level throughput on the GEMM shapes of every workload configuration (plus two large
     shapes that show what the main loop reaches when nothing else binds) and on the streaming
     kernels at a size far beyond the caches.  Operands are the codes of standard-normal values (the
@@ -426,7 +429,7 @@ def all_configs_report(mp8, torch):
         rows.append({"kernel": "gemm_fp8", "case": name, "us": us, "tflops": flops / us / 1e6,
                      "frac_mfma_peak": flops / us / 1e6 / FP8_PEAK_TFLOPS,
                      "alg_gbs": nbytes / us / 1e3, "flop_per_byte": flops / nbytes})
-        if hasattr(torch, "float8_e5m2") and hasattr(torch, "_scaled_mm"):
+        if vendor_gemm and hasattr(torch, "float8_e5m2") and hasattr(torch, "_scaled_mm"):
             # context, not a target: the vendor library's GEMM on the same codes, same box, same minute
             try:
                 one = torch.ones((), device=dev)
@@ -660,7 +663,7 @@ def main():
             out["conv_step"] = {"error": repr(exc)}
     if not args.no_all_configs:
         try:
-            out["all_configs"] = all_configs_report(mp8, torch)
+            out["all_configs"] = all_configs_report(mp8, torch, args.vendor_gemm)
         except Exception as exc:  # the table is extra evidence; the line above it stands on its own
             out["all_configs"] = {"error": repr(exc)}
     if not args.no_cpu_baseline:
