@@ -163,3 +163,19 @@ int main(void) {
     words = res.stdout.split()
     assert words[:4] == ["6627e8d5", "e169c58d", "bc57ac4c", "9b00dbd8"]     # Philox known answer
     assert int(words[4]) >= 1 and int(words[5]) >= 1
+
+
+def test_bench_refuses_more_than_one_gpu_and_knows_its_flags():
+    """bench.py is a one-GPU benchmark: --gpus N with N > 1 ends with a message and a non-zero
+    status before anything touches a GPU; the flags of the driver's contract parse."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2", "--steps", "3", "--warmup", "1"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in (r.stdout + r.stderr)
+    h = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--help"], capture_output=True, text=True,
+                       timeout=120)
+    assert h.returncode == 0
+    for flag in ("--gpus", "--steps", "--warmup", "--no-cpu-baseline", "--separate-quantize", "--vendor-gemm"):
+        assert flag in h.stdout
