@@ -115,7 +115,7 @@ __global__ __launch_bounds__(4 * BM + 256, BM == 64 ? 2 : 1) void gemm_qfwd_kern
             for (int u = 0; u < 8; ++u) {
                 float y[4] = {f[P][u].x * q.scale, f[P][u].y * q.scale, f[P][u].z * q.scale, f[P][u].w * q.scale};
                 if constexpr (QPLAIN) {
-                    codes[u] = e5m2_pack4<false>(y, 0u, 0u, false);
+                    codes[u] = e5m2_pack4<false, false>(y, 0u, 0u, false);
                 } else {
                     uint32_t r01 = 0, r23 = 0;
                     if (q.sr) {
@@ -126,7 +126,7 @@ __global__ __launch_bounds__(4 * BM + 256, BM == 64 ? 2 : 1) void gemm_qfwd_kern
                         r01 = (e0 & 4) ? w.z : w.x;
                         r23 = (e0 & 4) ? w.w : w.y;
                     }
-                    codes[u] = e5m2_pack4_rt(y, r01, r23, q.sr != 0, q.sat != 0);
+                    codes[u] = e5m2_pack4_rt<false>(y, r01, r23, q.sr != 0, q.sat != 0);
                     if (x_stats && valid[u]) stx.add4(y, codes[u]);
                 }
             }
