@@ -8,7 +8,10 @@
  *     allocates, frees or keeps them.  Tensors are row-major, last dimension contiguous.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  A call only
  *     enqueues work on that stream and returns; it never synchronises.
- *   - Errors are return codes.  On any error nothing has been enqueued.
+ *   - Errors are return codes.  Every check of a call, including those of the later launches of
+ *     a call made of several launches, is done before its first launch: on any error other
+ *     than MP8_ERR_HIP nothing has been enqueued.  (MP8_ERR_HIP reports that the runtime refused
+ *     a launch; for a call made of several launches the earlier ones may then be enqueued.)
  *   - `stats`, where present, is a nullable DEVICE pointer to an mp8_stats that the caller
  *     zeroes; calls accumulate into it (atomic max / atomic add), so one struct can collect
  *     a whole step.
@@ -174,7 +177,7 @@ int mp8_gemm_tile_config_lds_bytes(int tile_config, int epi);
 
 /*
  * The same primitive for a 3x3 convolution (stride 1, zero padding 1; Section 3 applies the
- * 8-bit format to "all convolution and GEMM kernels", Section 4 trains residual networks), as
+ * 8-bit format to every convolution and GEMM kernel, Section 4 trains residual networks), as
  * an implicit GEMM: no lowered (im2col) copy of the activations exists.
  *
  * Activations and errors are channels-last on the ZERO-PADDED pixel grid: a tensor with C
@@ -236,7 +239,7 @@ mp8_status mp8_sgd_momentum_fp16_sr(uint16_t *w16, float *velocity, const uint8_
                                     uint8_t *w8_out, mp8_stats *stats, void *stream);
 
 /*
- * The same path with the ADAM optimizer, which Section 4.2 names for the translation networks
+ * The same path with the ADAM optimizer, which Section 4 names for the translation networks
  * (the paper gives no formula: Kingma & Ba, Algorithm 1), with the regularisation gradient of
  * Eq. 1 as above.  Per element, every operation a separately rounded FP32 operation:
  *     g  = fmaf(weight_decay, w, fl32(value(g8[i]) * inv_loss_scale))
@@ -261,6 +264,13 @@ mp8_status mp8_adam_fp16_sr(uint16_t *w16, float *m, float *v, const uint8_t *g8
  * mp8_sgd_update_fp16_sr to the master weights w16 [K, N] with the codes it has just produced
  * (lr, inv_loss_scale, w_round / w_seed / w_offset, skip_if_nonzero, w8_out as there).  The
  * results are bit for bit those of the two separate calls.
+ *   skip_if_nonzero  as there.  The finishing pass reads the flag when it starts, so a flag that
+ *              earlier work on the stream has written (the overflow count of the error tensor's
+ *              Q node) is honoured as it is.  A flag that lies inside *stats would still be
+ *              counted by this very call (the gradient's own Inf/NaN codes) while the pass that
+ *              reads it runs: such a call runs the weight gradient and the update as two
+ *              launches, the update then sees the final count; it needs g8_out
+ *              (MP8_ERR_INVALID_ARG without it).
  *   g8_out     nullable [K, N]: the 8-bit weight gradient, if the caller wants to keep it
  *   workspace  at least mp8_gemm_fp8_workspace_bytes(MP8_WGRAD, M, N, K) bytes, always needed
  *              when that is non-zero
@@ -365,8 +375,11 @@ void mp8_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t ou
  * Host-side loss scaler of Section 3.1: back-off dynamic scaling with a minimum threshold
  * that the caller raises as training proceeds.  update(): nonfinite != 0 halves the scale
  * (not below `floor`), resets the clean-step count and returns 1 (skip the step);
- * otherwise counts a clean step, doubles the scale after growth_interval of them, returns 0.
+ * otherwise counts a clean step, doubles the scale after growth_interval of them (growth stops
+ * at MP8_SCALER_MAX = 2^32: the scale and its reciprocal stay exact FP32 numbers, and a run
+ * without overflows does not double without end), returns 0.
  */
+#define MP8_SCALER_MAX 4294967296.0
 typedef struct {
     double scale;
     double floor;

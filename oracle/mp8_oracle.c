@@ -313,8 +313,8 @@ void orc_gemm_ref(const uint8_t *a, int64_t lda, const uint8_t *b, int64_t ldb,
 }
 
 /* ------------------------------------------------------------------------- */
-/* 3x3 convolution reference (Section 3: "all convolution and GEMM kernels";   */
-/* Section 4: the ResNet layers)                                               */
+/* 3x3 convolution reference (Section 3 puts every convolution and GEMM        */
+/* kernel in the 8-bit format; Section 4: the ResNet layers)                   */
 /* ------------------------------------------------------------------------- */
 
 /*
@@ -536,7 +536,7 @@ void orc_sgd_update_fp16(uint16_t *w16, const uint8_t *g8, int64_t n, float lr,
  *   w'  = fmaf(-lr, v', w)
  *   w16 = half(w') rounded by `mode`
  * The paper does not give the precision of the velocity; FP32 is the reading
- * taken (every operation of this path is "a 32-bit operation").  With
+ * taken (Section 3 carries out the whole update path in 32 bits).  With
  * momentum = 0 and weight_decay = 0 this is orc_sgd_update_fp16 exactly.
  */
 void orc_sgd_momentum_fp16(uint16_t *w16, float *vel, const uint8_t *g8, int64_t n, float lr,
@@ -571,13 +571,13 @@ void orc_sgd_momentum_fp16(uint16_t *w16, float *vel, const uint8_t *g8, int64_t
 }
 
 /*
- * The same path with the ADAM optimizer, which Section 4.2 names for the
+ * The same path with the ADAM optimizer, which Section 4 names for the
  * translation networks (GNMT, Transformer).  The paper gives no formula; this
  * is the published algorithm (Kingma & Ba, Algorithm 1) with the L2
  * regularisation gradient of Eq. 1 added to the un-scaled gradient as in
  * orc_sgd_momentum_fp16.  Every operation is a separately rounded FP32
- * operation ("the weight update operation is performed as a 32-bit
- * operation", Section 3), the two moments are kept in FP32 (the paper is
+ * operation (Section 3 carries out the weight update in 32 bits), the two
+ * moments are kept in FP32 (the paper is
  * silent on the precision of optimizer state; same reading as the velocity):
  *   g    = fl32(value(g8) * inv_loss_scale);  w = value(w16)
  *   g    = fmaf(weight_decay, w, g)
@@ -648,9 +648,13 @@ typedef struct {
  * idea (halve on overflow, grow again after a while, and never go below a floor
  * that the user raises as training proceeds) but no constants; taken here:
  * overflow -> scale = max(scale/2, floor), step skipped, counter reset;
- * growth_interval clean steps in a row -> scale *= 2.  Returns 1 if the step must
- * be skipped.
+ * growth_interval clean steps in a row -> scale = min(2 * scale, 2^32): growth
+ * stops at 2^32 (an overflow-free run would otherwise double without end; up to
+ * there the scale and its reciprocal are exact single-precision numbers, and
+ * with the smallest 8-bit subnormal at 2^-16 a larger scale could only rescue
+ * errors below 2^-48).  Returns 1 if the step must be skipped.
  */
+#define ORC_SCALER_MAX 4294967296.0
 int orc_scaler_update(orc_scaler *s, uint32_t nonfinite)
 {
     if (nonfinite != 0u) {
@@ -662,7 +666,11 @@ int orc_scaler_update(orc_scaler *s, uint32_t nonfinite)
     }
     s->good_steps += 1;
     if (s->good_steps >= s->growth_interval) {
-        s->scale *= 2.0;
+        if (s->scale < ORC_SCALER_MAX) {   /* a floor above the limit is left alone */
+            s->scale *= 2.0;
+            if (s->scale > ORC_SCALER_MAX)
+                s->scale = ORC_SCALER_MAX;
+        }
         s->good_steps = 0;
     }
     return 0;

@@ -277,7 +277,8 @@ namespace mp8 {
 // epilogue fields are filled in here.
 static mp8_status launch_mfma(GemmArgs ga, const Epilogue &ep, const Plan &pl, int64_t kc,
                               void (*const pick[3])(const GemmArgs), void *workspace,
-                              size_t workspace_bytes, hipStream_t s, const UpdateHook *upd = nullptr) {
+                              size_t workspace_bytes, hipStream_t s, const UpdateHook *upd = nullptr,
+                              bool validate_only = false) {
     const int64_t rows = ep.rows, cols = ep.cols;
     const int acc_mode = ep.acc_mode;
     float *acc = ep.acc;
@@ -301,6 +302,7 @@ static mp8_status launch_mfma(GemmArgs ga, const Epilogue &ep, const Plan &pl, i
     }
     const int64_t nblocks = (int64_t)pl.tiles_m * pl.tiles_n * pl.splits;
     if (nblocks > 0x7FFFFFFFLL) return MP8_ERR_UNSUPPORTED;
+    if (validate_only) return MP8_OK;  // every check has passed; nothing is enqueued
 
     ga.rows = rows;
     ga.cols = cols;
@@ -349,7 +351,8 @@ static mp8_status gemm_impl(mp8_op op, int64_t M, int64_t N, int64_t K, const ui
                             const uint8_t *b, int64_t ldb, float alpha, float *acc, int acc_mode,
                             uint8_t *out8, uint8_t *out8_t, mp8_round round, int flags, uint64_t seed,
                             uint64_t offset, mp8_stats *stats, void *workspace, size_t workspace_bytes,
-                            void *stream, int tile_config, int split_k, const UpdateHook *upd) {
+                            void *stream, int tile_config, int split_k, const UpdateHook *upd,
+                            bool validate_only = false) {
     if ((int)op < 0 || (int)op > 2) return MP8_ERR_INVALID_ARG;
     if (M < 0 || N < 0 || K < 0) return MP8_ERR_INVALID_ARG;
     if (round != MP8_RNE && round != MP8_SR) return MP8_ERR_INVALID_ARG;
@@ -396,6 +399,7 @@ static mp8_status gemm_impl(mp8_op op, int64_t M, int64_t N, int64_t K, const ui
 
     if (!pl.mfma || kc == 0) {
         if (upd != nullptr) return MP8_ERR_UNSUPPORTED;
+        if (validate_only) return MP8_OK;
         int64_t blocks = std::min<int64_t>((rows * cols + 255) / 256, 1 << 20);
         hipLaunchKernelGGL(gemm_generic_kernel, dim3((unsigned)blocks), dim3(256), 0, s, a, lda, b,
                            ldb, kc, (atn ? 1 : 0) | (btn ? 2 : 0), ep);
@@ -409,7 +413,28 @@ static mp8_status gemm_impl(mp8_op op, int64_t M, int64_t N, int64_t K, const ui
     ga.ldb = ldb;
     const TileConfig &tc = kTiles[pl.tile];
     return launch_mfma(ga, ep, pl, kc, atn ? tc.kernel_tn : btn ? tc.kernel_bt : tc.kernel, workspace,
-                       workspace_bytes, s, upd);
+                       workspace_bytes, s, upd, validate_only);
+}
+
+// The checks of mp8_gemm_fp8 on these arguments without enqueuing anything: what a call made of
+// several launches runs first, so that it is rejected as a whole or not at all.
+static mp8_status gemm_validate(mp8_op op, int64_t M, int64_t N, int64_t K, const uint8_t *a, int64_t lda,
+                                const uint8_t *b, int64_t ldb, float *acc, int acc_mode, uint8_t *out8,
+                                uint8_t *out8_t, mp8_round round, int flags, void *workspace,
+                                size_t workspace_bytes) {
+    return gemm_impl(op, M, N, K, a, lda, b, ldb, 1.0f, acc, acc_mode, out8, out8_t, round, flags, 0, 0, nullptr,
+                     workspace, workspace_bytes, nullptr, 0, 0, nullptr, true);
+}
+
+// Does the skip flag of a fused weight-gradient update live inside the statistics the same call
+// accumulates into?  The finishing pass reads the flag when it starts and adds this gradient's
+// Inf/NaN count when it ends, so such a flag would change under the pass that reads it; those
+// calls run the weight gradient and the update as two launches instead, and the update then sees
+// the final count.
+static bool flag_inside_stats(const uint32_t *skip, const mp8_stats *stats) {
+    if (skip == nullptr || stats == nullptr) return false;
+    const uintptr_t f = (uintptr_t)skip, s0 = (uintptr_t)stats;
+    return f + sizeof(uint32_t) > s0 && f < s0 + sizeof(mp8_stats);
 }
 
 
@@ -464,6 +489,44 @@ extern "C" mp8_status mp8_gemm_fp8_tuned(mp8_op op, int64_t M, int64_t N, int64_
                           nullptr);
 }
 
+namespace mp8 {
+
+// Weight gradient, its rounding, and a master-weight update of the rounded codes (Figure 1b): the
+// body the three optimizer variants share.  `hook` is the rule as the finishing pass applies it,
+// `update_from(codes)` launches the same rule's stand-alone kernel on codes in memory.  Three ways,
+// all with the same results: the GEMM with its own epilogue followed by the update kernel (unsplit
+// contractions, any-shape kernel, and a skip flag that lives inside `stats` -- see
+// flag_inside_stats), or the update inside the finishing pass of a split contraction.  Whatever
+// can be checked is checked before the first launch.
+template <class UpdateFrom>
+static mp8_status wgrad_with_update(int64_t M, int64_t N, int64_t K, const uint8_t *a, int64_t lda,
+                                    const uint8_t *b, int64_t ldb, float alpha, uint8_t *g8_out,
+                                    mp8_round g_round, int flags, uint64_t g_seed, uint64_t g_offset,
+                                    mp8_stats *stats, const UpdateHook &hook, void *workspace,
+                                    size_t workspace_bytes, void *stream, UpdateFrom update_from) {
+    auto two_launches = [&](uint8_t *codes, void *ws, size_t ws_bytes) -> mp8_status {
+        const mp8_status sv = gemm_validate(MP8_WGRAD, M, N, K, a, lda, b, ldb, nullptr, 0, codes, nullptr,
+                                            g_round, flags, ws, ws_bytes);
+        if (sv != MP8_OK) return sv;
+        const mp8_status sg = mp8_gemm_fp8(MP8_WGRAD, M, N, K, a, lda, b, ldb, alpha, nullptr, 0, codes, nullptr,
+                                           g_round, flags, g_seed, g_offset, stats, ws, ws_bytes, stream);
+        if (sg != MP8_OK) return sg;
+        return update_from(codes);
+    };
+    if (uint8_t *codes = codes_for_separate_update(M, N, K, flags, g8_out, workspace, workspace_bytes))
+        return two_launches(codes, nullptr, 0);
+    if (flag_inside_stats(hook.skip, stats))
+        return g8_out != nullptr ? two_launches(g8_out, workspace, workspace_bytes) : MP8_ERR_INVALID_ARG;
+    const mp8_status st = gemm_impl(MP8_WGRAD, M, N, K, a, lda, b, ldb, alpha, nullptr, 0, g8_out, nullptr,
+                                    g_round, flags, g_seed, g_offset, stats, workspace, workspace_bytes,
+                                    stream, 0, 0, &hook);
+    if (st != MP8_ERR_UNSUPPORTED || g8_out == nullptr) return st;
+    // shapes that only the any-shape kernel takes: two launches through the 8-bit gradient
+    return two_launches(g8_out, workspace, workspace_bytes);
+}
+
+}  // namespace mp8
+
 extern "C" mp8_status mp8_wgrad_update_fp16_sr(int64_t M, int64_t N, int64_t K, const uint8_t *a,
                                                int64_t lda, const uint8_t *b, int64_t ldb, float alpha,
                                                uint8_t *g8_out, mp8_round g_round, int flags,
@@ -478,25 +541,12 @@ extern "C" mp8_status mp8_wgrad_update_fp16_sr(int64_t M, int64_t N, int64_t K, 
     if (K == 0 || N == 0) return MP8_OK;
     if (!w16) return MP8_ERR_INVALID_ARG;
     if (((uintptr_t)w16 | (uintptr_t)w8_out) & 15u) return MP8_ERR_ALIGNMENT;
-    if (uint8_t *codes = codes_for_separate_update(M, N, K, flags, g8_out, workspace, workspace_bytes)) {
-        const mp8_status sg = mp8_gemm_fp8(MP8_WGRAD, M, N, K, a, lda, b, ldb, alpha, nullptr, 0, codes, nullptr,
-                                           g_round, flags, g_seed, g_offset, stats, nullptr, 0, stream);
-        if (sg != MP8_OK) return sg;
+    const UpdateHook upd = make_update_hook(w16, w8_out, skip_if_nonzero, lr, inv_loss_scale, w_round, w_seed, w_offset);
+    return wgrad_with_update(M, N, K, a, lda, b, ldb, alpha, g8_out, g_round, flags, g_seed, g_offset, stats, upd,
+                             workspace, workspace_bytes, stream, [&](const uint8_t *codes) {
         return mp8_sgd_update_fp16_sr(w16, codes, K * N, lr, inv_loss_scale, w_round, w_seed, w_offset,
                                       skip_if_nonzero, w8_out, nullptr, stream);
-    }
-    UpdateHook upd = make_update_hook(w16, w8_out, skip_if_nonzero, lr, inv_loss_scale, w_round, w_seed, w_offset);
-    const mp8_status st = gemm_impl(MP8_WGRAD, M, N, K, a, lda, b, ldb, alpha, nullptr, 0, g8_out, nullptr,
-                                    g_round, flags, g_seed, g_offset, stats, workspace, workspace_bytes,
-                                    stream, 0, 0, &upd);
-    if (st != MP8_ERR_UNSUPPORTED || g8_out == nullptr) return st;
-    // shapes that only the any-shape kernel takes: two launches through the 8-bit gradient
-    const mp8_status sg = mp8_gemm_fp8(MP8_WGRAD, M, N, K, a, lda, b, ldb, alpha, nullptr, 0, g8_out, nullptr,
-                                       g_round, flags, g_seed, g_offset, stats, workspace, workspace_bytes,
-                                       stream);
-    if (sg != MP8_OK) return sg;
-    return mp8_sgd_update_fp16_sr(w16, g8_out, K * N, lr, inv_loss_scale, w_round, w_seed, w_offset,
-                                  skip_if_nonzero, w8_out, nullptr, stream);
+    });
 }
 
 extern "C" mp8_status mp8_wgrad_momentum_fp16_sr(int64_t M, int64_t N, int64_t K, const uint8_t *a, int64_t lda,
@@ -514,26 +564,13 @@ extern "C" mp8_status mp8_wgrad_momentum_fp16_sr(int64_t M, int64_t N, int64_t K
     if (K == 0 || N == 0) return MP8_OK;
     if (!w16 || !velocity) return MP8_ERR_INVALID_ARG;
     if (((uintptr_t)w16 | (uintptr_t)w8_out | (uintptr_t)velocity) & 15u) return MP8_ERR_ALIGNMENT;
-    if (uint8_t *codes = codes_for_separate_update(M, N, K, flags, g8_out, workspace, workspace_bytes)) {
-        const mp8_status sg = mp8_gemm_fp8(MP8_WGRAD, M, N, K, a, lda, b, ldb, alpha, nullptr, 0, codes, nullptr,
-                                           g_round, flags, g_seed, g_offset, stats, nullptr, 0, stream);
-        if (sg != MP8_OK) return sg;
+    const UpdateHook upd = make_update_hook(w16, w8_out, skip_if_nonzero, lr, inv_loss_scale, w_round, w_seed, w_offset,
+                                            velocity, momentum, weight_decay);
+    return wgrad_with_update(M, N, K, a, lda, b, ldb, alpha, g8_out, g_round, flags, g_seed, g_offset, stats, upd,
+                             workspace, workspace_bytes, stream, [&](const uint8_t *codes) {
         return mp8_sgd_momentum_fp16_sr(w16, velocity, codes, K * N, lr, inv_loss_scale, momentum, weight_decay,
                                         w_round, w_seed, w_offset, skip_if_nonzero, w8_out, nullptr, stream);
-    }
-    UpdateHook upd = make_update_hook(w16, w8_out, skip_if_nonzero, lr, inv_loss_scale, w_round, w_seed, w_offset,
-                                      velocity, momentum, weight_decay);
-    const mp8_status st = gemm_impl(MP8_WGRAD, M, N, K, a, lda, b, ldb, alpha, nullptr, 0, g8_out, nullptr,
-                                    g_round, flags, g_seed, g_offset, stats, workspace, workspace_bytes,
-                                    stream, 0, 0, &upd);
-    if (st != MP8_ERR_UNSUPPORTED || g8_out == nullptr) return st;
-    // shapes that only the any-shape kernel takes: two launches through the 8-bit gradient
-    const mp8_status sg = mp8_gemm_fp8(MP8_WGRAD, M, N, K, a, lda, b, ldb, alpha, nullptr, 0, g8_out, nullptr,
-                                       g_round, flags, g_seed, g_offset, stats, workspace, workspace_bytes,
-                                       stream);
-    if (sg != MP8_OK) return sg;
-    return mp8_sgd_momentum_fp16_sr(w16, velocity, g8_out, K * N, lr, inv_loss_scale, momentum, weight_decay,
-                                    w_round, w_seed, w_offset, skip_if_nonzero, w8_out, nullptr, stream);
+    });
 }
 
 extern "C" mp8_status mp8_wgrad_adam_fp16_sr(int64_t M, int64_t N, int64_t K, const uint8_t *a, int64_t lda,
@@ -551,13 +588,6 @@ extern "C" mp8_status mp8_wgrad_adam_fp16_sr(int64_t M, int64_t N, int64_t K, co
     if (K == 0 || N == 0) return MP8_OK;
     if (!w16 || !m || !v) return MP8_ERR_INVALID_ARG;
     if (((uintptr_t)w16 | (uintptr_t)w8_out | (uintptr_t)m | (uintptr_t)v) & 15u) return MP8_ERR_ALIGNMENT;
-    if (uint8_t *codes = codes_for_separate_update(M, N, K, flags, g8_out, workspace, workspace_bytes)) {
-        const mp8_status sg = mp8_gemm_fp8(MP8_WGRAD, M, N, K, a, lda, b, ldb, alpha, nullptr, 0, codes, nullptr,
-                                           g_round, flags, g_seed, g_offset, stats, nullptr, 0, stream);
-        if (sg != MP8_OK) return sg;
-        return mp8_adam_fp16_sr(w16, m, v, codes, K * N, lr, inv_loss_scale, beta1, beta2, eps, weight_decay, step,
-                                w_round, w_seed, w_offset, skip_if_nonzero, w8_out, nullptr, stream);
-    }
     UpdateHook upd = make_update_hook(w16, w8_out, skip_if_nonzero, lr, inv_loss_scale, w_round, w_seed, w_offset);
     upd.states = 2;
     upd.state0 = m;
@@ -571,17 +601,11 @@ extern "C" mp8_status mp8_wgrad_adam_fp16_sr(int64_t M, int64_t N, int64_t K, co
     upd.c1 = (float)(1.0 - std::pow((double)beta1, (double)step));
     upd.c2 = (float)(1.0 - std::pow((double)beta2, (double)step));
     upd.eps = eps;
-    const mp8_status st = gemm_impl(MP8_WGRAD, M, N, K, a, lda, b, ldb, alpha, nullptr, 0, g8_out, nullptr,
-                                    g_round, flags, g_seed, g_offset, stats, workspace, workspace_bytes,
-                                    stream, 0, 0, &upd);
-    if (st != MP8_ERR_UNSUPPORTED || g8_out == nullptr) return st;
-    // shapes that only the any-shape kernel takes: two launches through the 8-bit gradient
-    const mp8_status sg = mp8_gemm_fp8(MP8_WGRAD, M, N, K, a, lda, b, ldb, alpha, nullptr, 0, g8_out, nullptr,
-                                       g_round, flags, g_seed, g_offset, stats, workspace, workspace_bytes,
-                                       stream);
-    if (sg != MP8_OK) return sg;
-    return mp8_adam_fp16_sr(w16, m, v, g8_out, K * N, lr, inv_loss_scale, beta1, beta2, eps, weight_decay, step,
-                            w_round, w_seed, w_offset, skip_if_nonzero, w8_out, nullptr, stream);
+    return wgrad_with_update(M, N, K, a, lda, b, ldb, alpha, g8_out, g_round, flags, g_seed, g_offset, stats, upd,
+                             workspace, workspace_bytes, stream, [&](const uint8_t *codes) {
+        return mp8_adam_fp16_sr(w16, m, v, codes, K * N, lr, inv_loss_scale, beta1, beta2, eps, weight_decay, step,
+                                w_round, w_seed, w_offset, skip_if_nonzero, w8_out, nullptr, stream);
+    });
 }
 
 extern "C" mp8_status mp8_gemm_fp8(mp8_op op, int64_t M, int64_t N, int64_t K, const uint8_t *a,
@@ -621,13 +645,19 @@ extern "C" mp8_status mp8_quantize_gemm_fwd_fp8(int64_t M, int64_t N, int64_t K,
                        ((uintptr_t)w8 & 15u) == 0 && (ldw & 15) == 0 && ldw < (1 << 24) &&
                        M <= (INT64_MAX / 8) / K && (M + 63) / 64 <= 0x7FFFFFFFLL;
     if (!fused) {
-        // any other shape: the two calls this one stands for
+        // any other shape: the two calls this one stands for (the second one's checks first, so
+        // that a rejected call has enqueued nothing)
+        const int gflags = (flags & MP8_FLAG_SATURATE) | MP8_FLAG_B_CONTRACTION_MAJOR;
+        if (N > 0 && K > 0) {
+            const mp8_status sv = gemm_validate(MP8_FWD, M, N, K, x8_out, K, w8, ldw, acc, acc_mode, out8, out8_t,
+                                                round, gflags, workspace, workspace_bytes);
+            if (sv != MP8_OK) return sv;
+        }
         const mp8_status sq = mp8_quantize_e5m2(x, 0, x8_out, nullptr, M, K, x_scale, x_round, x_flags,
                                                 x_seed, x_offset, x_stats, stream);
         if (sq != MP8_OK) return sq;
         return mp8_gemm_fp8(MP8_FWD, M, N, K, x8_out, K, w8, ldw, alpha, acc, acc_mode, out8, out8_t,
-                            round, (flags & MP8_FLAG_SATURATE) | MP8_FLAG_B_CONTRACTION_MAJOR, seed,
-                            offset, stats, workspace, workspace_bytes, stream);
+                            round, gflags, seed, offset, stats, workspace, workspace_bytes, stream);
     }
     GemmArgs ga{};
     ga.b = w8;
@@ -801,6 +831,15 @@ extern "C" mp8_status mp8_conv3x3_wgrad_update_fp16_sr(
     if (B == 0 || H == 0 || W == 0 || Ci == 0 || Co == 0) return MP8_OK;
     if (!w16) return MP8_ERR_INVALID_ARG;
     if (((uintptr_t)w16 | (uintptr_t)w8_out) & 15u) return MP8_ERR_ALIGNMENT;
+    if (flag_inside_stats(skip_if_nonzero, stats)) {
+        // the flag is still being counted while the finishing pass would read it: two launches
+        if (g8_out == nullptr) return MP8_ERR_INVALID_ARG;
+        const mp8_status sg = conv_impl(MP8_WGRAD, B, H, W, Ci, Co, prows, x8, e8, alpha, nullptr, 0, g8_out, g_round,
+                                        flags, g_seed, g_offset, stats, workspace, workspace_bytes, stream, nullptr);
+        if (sg != MP8_OK) return sg;
+        return mp8_sgd_update_fp16_sr(w16, g8_out, 9 * Ci * Co, lr, inv_loss_scale, w_round, w_seed, w_offset,
+                                      skip_if_nonzero, w8_out, nullptr, stream);
+    }
     UpdateHook upd = make_update_hook(w16, w8_out, skip_if_nonzero, lr, inv_loss_scale, w_round, w_seed, w_offset);
     return conv_impl(MP8_WGRAD, B, H, W, Ci, Co, prows, x8, e8, alpha, nullptr, 0, g8_out, g_round, flags,
                      g_seed, g_offset, stats, workspace, workspace_bytes, stream, &upd);
@@ -818,17 +857,17 @@ extern "C" mp8_status mp8_conv3x3_wgrad_momentum_fp16_sr(
     if (B == 0 || H == 0 || W == 0 || Ci == 0 || Co == 0) return MP8_OK;
     if (!w16 || !velocity) return MP8_ERR_INVALID_ARG;
     if (((uintptr_t)w16 | (uintptr_t)w8_out | (uintptr_t)velocity) & 15u) return MP8_ERR_ALIGNMENT;
+    if (flag_inside_stats(skip_if_nonzero, stats)) {
+        if (g8_out == nullptr) return MP8_ERR_INVALID_ARG;
+        const mp8_status sg = conv_impl(MP8_WGRAD, B, H, W, Ci, Co, prows, x8, e8, alpha, nullptr, 0, g8_out, g_round,
+                                        flags, g_seed, g_offset, stats, workspace, workspace_bytes, stream, nullptr);
+        if (sg != MP8_OK) return sg;
+        return mp8_sgd_momentum_fp16_sr(w16, velocity, g8_out, 9 * Ci * Co, lr, inv_loss_scale, momentum,
+                                        weight_decay, w_round, w_seed, w_offset, skip_if_nonzero, w8_out, nullptr,
+                                        stream);
+    }
     UpdateHook upd = make_update_hook(w16, w8_out, skip_if_nonzero, lr, inv_loss_scale, w_round, w_seed, w_offset,
                                       velocity, momentum, weight_decay);
     return conv_impl(MP8_WGRAD, B, H, W, Ci, Co, prows, x8, e8, alpha, nullptr, 0, g8_out, g_round, flags,
                      g_seed, g_offset, stats, workspace, workspace_bytes, stream, &upd);
 }
-
-#ifdef MP8_TRACE
-extern "C" int mp8_debug_read_trace(unsigned long long *host, size_t bytes) {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(mp8::mp8_trace_buf), bytes);
-}
-extern "C" int mp8_debug_read_block_times(unsigned long long *host, size_t bytes) {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(mp8::mp8_block_times), bytes);
-}
-#endif

@@ -19,23 +19,6 @@ using f32x16 = float __attribute__((ext_vector_type(16)));
 
 constexpr int BK = 128;  // bytes (= elements) of contraction per pipeline stage
 
-#ifdef MP8_TRACE
-// Diagnostic build only: cycle stamps of one block, [wave][stage][point].
-#ifndef MP8_TRACE_BLOCK
-#define MP8_TRACE_BLOCK 0
-#endif
-__device__ unsigned long long mp8_trace_buf[4][160][8];
-#define MP8_STAMP(pt) do { if (blockIdx.x == MP8_TRACE_BLOCK && lane == 0 && t < 159) mp8_trace_buf[wave][t][pt] = __builtin_readcyclecounter(); } while (0)
-#define MP8_STAMP_PHASE(pt) do { if (blockIdx.x == MP8_TRACE_BLOCK && (threadIdx.x & 63) == 0) mp8_trace_buf[threadIdx.x >> 6][159][pt] = __builtin_readcyclecounter(); } while (0)
-// constant-rate (100 MHz) clock stamps of every workgroup: [block][point]
-__device__ unsigned long long mp8_block_times[16384][4];
-#define MP8_BLOCK_STAMP(pt) do { if (threadIdx.x == 0 && blockIdx.x < 16384) mp8_block_times[blockIdx.x][pt] = wall_clock64(); } while (0)
-#else
-#define MP8_BLOCK_STAMP(pt) do { } while (0)
-#define MP8_STAMP(pt) do { } while (0)
-#define MP8_STAMP_PHASE(pt) do { } while (0)
-#endif
-
 // Division of a 31-bit number by a fixed divisor with a precomputed reciprocal:
 // m = floor(2^32 / d) (all ones for d = 1) makes mulhi(x, m) the quotient or one less.
 struct FastDiv {
@@ -281,7 +264,7 @@ __device__ __forceinline__ void dma16(const uint8_t *gbase, uint32_t lane_off, u
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  :
                  : "v"(lane_off), "s"(gbase), "s"(lds_addr)
-                 : "memory");
+                 : "memory", "m0");
 }
 
 // Tell the compiler that a pointer is the same in every lane (keeps it in scalar registers).

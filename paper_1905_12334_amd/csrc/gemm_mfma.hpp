@@ -58,8 +58,6 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     constexpr int LDS_BYTES = NSTAGE * STAGE > EP_BYTES ? NSTAGE * STAGE : EP_BYTES;
     __shared__ __attribute__((aligned(1024))) uint8_t lds[LDS_BYTES];
 
-    MP8_STAMP_PHASE(0);
-    MP8_BLOCK_STAMP(0);
     int split, tm, tn;
     map_block(p, split, tm, tn);
     split = __builtin_amdgcn_readfirstlane(split);
@@ -268,7 +266,6 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     };
 
     Frags f0, f1;
-    MP8_STAMP_PHASE(1);
     // prologue: fill the ring, fetch the fragments of (0, 0)
 #pragma unroll
     for (int st = 0; st < NSTAGE; ++st)
@@ -277,8 +274,6 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     __syncthreads();
 #pragma unroll
     for (int n = 0; n < 2 * F; ++n) read_half(0, 0, frag_order(n / 2), n & 1, f0);
-    MP8_STAMP_PHASE(2);
-    MP8_BLOCK_STAMP(1);
 
     // One stage = 2*NM "slots", one MFMA each, fenced so that the order below is the issue
     // order.  Everything else a stage needs is spread over the slots so that it issues in the
@@ -312,7 +307,6 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
         else wait_vm_lds<0>();
     };
     for (int t = 0; t < ks_count; ++t) {
-        MP8_STAMP(0);
         const bool more = t + NSTAGE < ks_count;
         const bool next = t + 1 < ks_count;
 #pragma unroll
@@ -327,12 +321,9 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
             }
             if (k == S_BAR - 1) {
                 __builtin_amdgcn_sched_barrier(0);
-                MP8_STAMP(1);
                 if constexpr (SPLIT_BAR) wait_vm_lds<63>();  // own LDS reads only
                 else wait_stage(t);
-                MP8_STAMP(2);
                 __syncthreads();
-                MP8_STAMP(3);
             }
             if (k >= S_BAR) {
 #pragma unroll
@@ -355,11 +346,8 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        MP8_STAMP(5);
     }
     wait_vm_lds<0>();
-    MP8_STAMP_PHASE(3);
-    MP8_BLOCK_STAMP(2);
 
     // Epilogue.  acc[i][j][4g + e] is output row  wm*WTM + 32i + lane%32  and column
     // wn*WTN + 32j + 8g + 4*(lane/32) + e.  Each wave passes its tile through LDS one band
@@ -424,8 +412,6 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
                 *reinterpret_cast<u32x4 *>(p.ep.out8 + r * p.cols + c) = o;
             }
         }
-        MP8_STAMP_PHASE(4);
-        MP8_BLOCK_STAMP(3);
         return;
     }
     float *band = reinterpret_cast<float *>(lds) + wave * BANDS * 32 * EP_LD;
@@ -448,7 +434,6 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        MP8_STAMP_PHASE(5);
         // the RNE-only variant is small enough to unroll: the LDS reads of several items then
         // overlap instead of each item paying the full LDS latency
 #pragma unroll(EPI == EPI_RNE ? 4 : 1)
@@ -467,7 +452,6 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
                 emit16<EPI>(p, split, r, c, v, st, fast_cols);
             }
         }
-        MP8_STAMP_PHASE(6);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -475,8 +459,6 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     if constexpr (EPI == EPI_FULL) {
         if (p.ep.stats != nullptr) st.flush(p.ep.stats);
     }
-    MP8_STAMP_PHASE(4);
-    MP8_BLOCK_STAMP(3);
 }
 
 }  // namespace mp8

@@ -20,7 +20,6 @@ template <int EPI>
 __global__ __launch_bounds__(256, EPI == EPI_FULL ? 4 : 5) void gemm_shortk_kernel(const GemmArgs p) {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds_dyn[];
     constexpr int BM = 128, BN = 128, A_BYTES = BM * BK, STAGE = (BM + BN) * BK;
-    MP8_BLOCK_STAMP(0);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // consecutive workgroup ids sit on different XCDs: give each XCD a contiguous tile range
@@ -71,7 +70,6 @@ __global__ __launch_bounds__(256, EPI == EPI_FULL ? 4 : 5) void gemm_shortk_kern
             if (st + 1 < ksteps) wait_vm_lds<8>();  // the eight loads of the next stage may fly
             else wait_vm_lds<0>();
             __syncthreads();
-            if (st == 0) MP8_BLOCK_STAMP(1);
             const uint8_t *s = lds_dyn + st * STAGE;
 #pragma unroll
             for (int sub = 0; sub < 2; ++sub) {
@@ -94,7 +92,6 @@ __global__ __launch_bounds__(256, EPI == EPI_FULL ? 4 : 5) void gemm_shortk_kern
     }
 
     const int64_t r = row0 + 32 * wave + frow;
-    MP8_BLOCK_STAMP(2);
     if constexpr (EPI == EPI_RNE) {
         // Codes first, then the exchange: four codes are one register, so a 32x32 tile needs two
         // swaps.  After swap(pk[g], pk[g+2]) the lower half holds its own columns 8g .. 8g+3
@@ -138,7 +135,6 @@ __global__ __launch_bounds__(256, EPI == EPI_FULL ? 4 : 5) void gemm_shortk_kern
             const int64_t ro = row0 + 32 * wave + rr;
             if (ro < p.rows && c < p.cols) *reinterpret_cast<u32x4 *>(p.ep.out8 + ro * p.cols + c) = o;
         }
-        MP8_BLOCK_STAMP(3);
         return;
     }
     StatsAcc stt;

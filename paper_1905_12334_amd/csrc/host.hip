@@ -37,7 +37,11 @@ extern "C" int mp8_scaler_update(mp8_scaler *s, uint32_t nonfinite) {
         return 1;
     }
     if (++s->good_steps >= s->growth_interval) {
-        s->scale *= 2.0;
+        // growth stops at MP8_SCALER_MAX; a scale already beyond it (a floor the caller chose) stays
+        if (s->scale < MP8_SCALER_MAX) {
+            const double doubled = s->scale * 2.0;
+            s->scale = doubled > MP8_SCALER_MAX ? MP8_SCALER_MAX : doubled;
+        }
         s->good_steps = 0;
     }
     return 0;

@@ -266,6 +266,73 @@ def test_weight_gradient_and_update_in_one_call_against_the_oracle_chain(mp8, la
             assert torch.equal(wd2, wd)
 
 
+def test_fused_update_with_the_skip_flag_inside_the_statistics_of_the_same_call(mp8):
+    """Section 3.1's back-off skips a step whose gradients overflowed.  When the skip flag is the
+    Inf/NaN count of the statistics that the very same call accumulates into, the count is only
+    final once the whole gradient has been rounded: an overflowing gradient must leave every master
+    weight untouched (not a part of them), a clean one must update all of them -- on a split
+    contraction (whose finishing pass would otherwise carry the update) and on an unsplit one, for
+    the three optimizer rules.  Without g8_out there is nowhere to keep the codes between the two
+    launches: rejected."""
+    import torch
+    from test_gpu_gemm import exact_sum_codes
+    rng = np.random.default_rng(41)
+    for (M, N, K) in ((8192, 64, 64), (1024, 64, 256)):
+        xt, et = exact_sum_codes(rng, (K, M)), exact_sum_codes(rng, (N, M))
+        if M == 8192:
+            xt[:, rng.random(M) < 0.75] = 0
+            assert mp8.gemm_fp8_plan(mp8.WGRAD, M, N, K, 0)[1] > 1
+        ref, _ = oracle.gemm_ref(xt, et, want_abs=False)
+        a, b = gpu(xt), gpu(et)
+        ws = torch.empty(max(mp8.gemm_fp8_workspace_bytes(mp8.WGRAD, M, N, K), 16), dtype=torch.uint8, device="cuda")
+        w16 = (rng.standard_normal(K * N) * 0.05).astype(np.float16).view(np.uint16)
+        lr, inv = 0.05, 1.0 / 64
+        for alpha in (2.0 ** 20, 2.0 ** -9):          # every sum overflows / none does
+            want_g = oracle.quantize_e5m2(ref.astype(np.float32), scale=alpha)[0]
+            overflow = int(np.count_nonzero((want_g & 0x7C) == 0x7C))
+            assert (overflow > 0) == (alpha > 1)
+            want_w, want_w8 = oracle.sgd_update_fp16(w16, want_g.reshape(-1), lr, inv, mode=oracle.SR, seed=23, offset=24,
+                                                     skip=overflow or None, want_w8=True)
+            if overflow:
+                assert np.array_equal(want_w, w16)
+            for rule in ("sgd", "momentum", "adam"):
+                wd = gpu(w16.view(np.int16))
+                g8 = torch.full((K * N,), 0xAA, dtype=torch.uint8, device="cuda")
+                w8 = torch.full((K * N,), 0x55, dtype=torch.uint8, device="cuda")
+                st = mp8.new_stats()
+                flag = st[1:2]                                   # the nonfinite word of the same struct
+                common = dict(g8_out=g8, alpha=alpha, stats=st, w_round=oracle.SR, w_seed=23, w_offset=24,
+                              skip_if_nonzero=flag, w8_out=w8, workspace=ws)
+                if rule == "sgd":
+                    mp8.wgrad_update_fp16_sr(M, N, K, a, b, wd, lr, inv, **common)
+                elif rule == "momentum":
+                    vel = torch.zeros(K * N, dtype=torch.float32, device="cuda")
+                    mp8.wgrad_momentum_fp16_sr(M, N, K, a, b, wd, vel, lr, inv, 0.0, 0.0, **common)
+                else:
+                    m1 = torch.zeros(K * N, dtype=torch.float32, device="cuda")
+                    m2 = torch.zeros(K * N, dtype=torch.float32, device="cuda")
+                    mp8.wgrad_adam_fp16_sr(M, N, K, a, b, wd, m1, m2, lr, inv, 1, **common)
+                torch.cuda.synchronize()
+                assert np.array_equal(host(g8).reshape(K, N), want_g), (M, rule)
+                assert mp8.read_stats(st)[1] == overflow
+                got = host(wd).view(np.uint16)
+                if overflow:
+                    assert np.array_equal(got, w16), (M, rule, "an overflowed step must not touch any weight")
+                    assert bool((w8 == 0x55).all())
+                    if rule == "adam":
+                        assert not bool(m1.any()) and not bool(m2.any())
+                elif rule != "adam":                             # momentum 0, decay 0 = the plain update
+                    assert np.array_equal(got, want_w), (M, rule)
+                    assert np.array_equal(host(w8), want_w8)
+                else:
+                    assert not np.array_equal(got, w16)
+        if M == 8192:
+            st = mp8.new_stats()
+            with pytest.raises(mp8.Mp8Error):
+                mp8.wgrad_update_fp16_sr(M, N, K, a, b, gpu(w16.view(np.int16)), lr, inv, stats=st,
+                                         skip_if_nonzero=st[1:2], workspace=ws)
+
+
 @pytest.mark.parametrize("layout", ["row-major", "contraction-major"])
 def test_weight_gradient_and_momentum_update_in_one_call_against_the_oracle_chain(mp8, layout):
     """mp8_wgrad_momentum_fp16_sr over two consecutive steps (the velocity carries over) on exact-sum

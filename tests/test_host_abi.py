@@ -53,6 +53,14 @@ def test_scaler_matches_oracle_on_random_traces():
                 oracle.scaler_set_floor(b, nfloor)
             assert (a.scale, a.floor, a.good_steps) == (b.scale, b.floor, b.good_steps)
             assert a.scale >= a.floor
+    # around the growth limit of 2^32, and with floors beyond it
+    for scale, floor in ((2.0 ** 29, 1.0), (3.0 * 2.0 ** 30, 2.0), (2.0 ** 32, 2.0 ** 32), (2.0 ** 36, 2.0 ** 36)):
+        a, b = mp8.scaler_new(scale, floor, 2), oracle.scaler_new(scale, floor, 2)
+        for step in range(40):
+            nf = int(step % 11 == 10)
+            assert mp8.scaler_update(a, nf) == oracle.scaler_update(b, nf)
+            assert (a.scale, a.floor, a.good_steps) == (b.scale, b.floor, b.good_steps)
+            assert a.scale <= max(2.0 ** 32, a.floor)
 
 
 def test_status_strings_and_validation_without_gpu():

@@ -252,6 +252,20 @@ def test_scaler_traces():
     assert s.scale == 8192.0
     oracle.scaler_set_floor(s, 32768.0)
     assert s.scale == 32768.0 and s.floor == 32768.0
+    # growth stops at 2^32 (hand trace: 2^30 doubles twice, then stays); an overflow still halves;
+    # a floor above the limit is respected and not grown further
+    s = oracle.scaler_new(2.0 ** 30, 1.0, 1)
+    assert [oracle.scaler_update(s, 0) or s.scale for _ in range(4)] == [2.0 ** 31, 2.0 ** 32, 2.0 ** 32, 2.0 ** 32]
+    assert oracle.scaler_update(s, 5) == 1 and s.scale == 2.0 ** 31
+    s = oracle.scaler_new(3.0 * 2.0 ** 30, 1.0, 1)      # 1.5 * 2^31 doubles past the limit: clamped
+    oracle.scaler_update(s, 0)
+    assert s.scale == 2.0 ** 32
+    s = oracle.scaler_new(1.0, 1.0, 1)
+    oracle.scaler_set_floor(s, 2.0 ** 40)
+    oracle.scaler_update(s, 0)
+    assert s.scale == 2.0 ** 40
+    oracle.scaler_update(s, 1)
+    assert s.scale == 2.0 ** 40
 
 
 def test_overflow_injection_drives_scaler():
@@ -326,7 +340,7 @@ def test_momentum_update_against_float32_numpy():
     assert np.array_equal(got_w[same], wn.astype(np.float16).view(np.uint16)[same])
 
 
-# --- ADAM on the master weights (Section 4.2 names the optimizer; published algorithm) ----------
+# --- ADAM on the master weights (Section 4 names the optimizer; published algorithm) ----------
 
 def _half_grid_error(w16_codes, ref):
     """|value(code) - ref| in units of the half-precision spacing at ref."""
