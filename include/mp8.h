@@ -365,6 +365,18 @@ mp8_status mp8_wgrad_adam_fp16_sr(int64_t M, int64_t N, int64_t K, const uint8_t
                                   uint64_t w_offset, const uint32_t *skip_if_nonzero, uint8_t *w8_out,
                                   void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Diagnostic, for benchmarks: a kernel that only moves bytes, in the access pattern and with the
+ * read:write ratio of the streaming kernels above (Section 3 calls the weight update a
+ * bandwidth-bound operation; this is the stick that bound is measured with).  Reads read_bytes
+ * from src (device, 16-byte aligned, a multiple of 16) and writes read_bytes / reads_per_write
+ * bytes to dst: reads_per_write = 4 is the Q node's ratio (FP32 in, one byte out), 1 a plain copy
+ * (the optimizers with FP32 state).  The bytes written are a function of the bytes read, of no
+ * other use.
+ */
+mp8_status mp8_stream_probe(const void *src, void *dst, int64_t read_bytes, int reads_per_write,
+                            void *stream);
+
 /* out[i] = the 16 random bits element i would use (device array of n uint16), for tests. */
 mp8_status mp8_sr_bits(uint16_t *out, int64_t n, uint64_t seed, uint64_t offset, void *stream);
 

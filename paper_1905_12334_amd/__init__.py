@@ -30,7 +30,7 @@ EXPORTS = [
     "mp8_gemm_fp8_plan", "mp8_gemm_tile_config_lds_bytes", "mp8_adam_fp16_sr",
     "mp8_quantize_e5m2_batch", "mp8_wgrad_update_fp16_sr", "mp8_conv3x3_wgrad_update_fp16_sr",
     "mp8_quantize_gemm_fwd_fp8", "mp8_wgrad_momentum_fp16_sr", "mp8_conv3x3_wgrad_momentum_fp16_sr",
-    "mp8_wgrad_adam_fp16_sr",
+    "mp8_wgrad_adam_fp16_sr", "mp8_stream_probe",
 ]
 
 
@@ -108,6 +108,8 @@ def lib() -> C.CDLL:
     L.mp8_adam_fp16_sr.restype = ci
     L.mp8_adam_fp16_sr.argtypes = [vp, vp, vp, vp, i64, f32, f32, f32, f32, f32, f32, i64, ci, u64, u64,
                                    vp, vp, vp, vp]
+    L.mp8_stream_probe.restype = ci
+    L.mp8_stream_probe.argtypes = [vp, vp, i64, ci, vp]
     L.mp8_sr_bits.restype = ci
     L.mp8_sr_bits.argtypes = [vp, i64, u64, u64, vp]
     L.mp8_philox4x32_10.restype = None
@@ -153,6 +155,16 @@ def _dev(t, name, dtype=None):
         raise Mp8Error(f"{name} must be contiguous")
     if dtype is not None and t.dtype not in (dtype if isinstance(dtype, tuple) else (dtype,)):
         raise Mp8Error(f"{name} has dtype {t.dtype}, expected {dtype}")
+
+
+def stream_probe(src, dst, reads_per_write):
+    """mp8_stream_probe: read all of src, write 1/reads_per_write as many bytes to dst (diagnostic)."""
+    _dev(src, "src")
+    _dev(dst, "dst")
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() < nbytes // reads_per_write:
+        raise Mp8Error("dst is too small")
+    _check(lib().mp8_stream_probe(_ptr(src), _ptr(dst), nbytes, reads_per_write, _stream()), "mp8_stream_probe")
 
 
 def new_stats(device="cuda"):

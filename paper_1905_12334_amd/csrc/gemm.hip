@@ -25,6 +25,7 @@
 #include <cstring>
 #include <type_traits>
 
+#include "../../include/mp8.h"
 #include "gemm_common.hpp"
 #include "gemm_finish.hpp"
 #include "gemm_mfma.hpp"

@@ -599,3 +599,56 @@ extern "C" mp8_status mp8_sr_bits(uint16_t *out, int64_t n, uint64_t seed, uint6
                        (hipStream_t)stream, out, n, seed, offset);
     return hipGetLastError() == hipSuccess ? MP8_OK : MP8_ERR_HIP;
 }
+
+// ---------------------------------------------------------------------------------------
+// Measuring stick for the streaming kernels: a kernel that only moves bytes, in the access
+// pattern of the flat quantize and update kernels (wave-interleaved 16-byte non-temporal loads,
+// four in flight per thread) and with their read:write ratio.  What it reaches is what the
+// memory system gives a kernel of this shape; the quantize and update kernels are held against it.
+namespace mp8 {
+
+// kReadsPerWrite = 4: 16 bytes read per 4 bytes written (the Q node's 4:1; the plain update's
+// 3:2 sits between the two); 1: a plain copy (the optimizers with FP32 state, about 1:1).
+template <int kReadsPerWrite>
+__global__ __launch_bounds__(256) void stream_probe_kernel(const u32x4 *__restrict__ src, void *__restrict__ dst,
+                                                           int64_t n16) {
+    const int64_t stride = (int64_t)gridDim.x * 256 * kFlatUnroll;
+    for (int64_t base = (int64_t)blockIdx.x * 256 * kFlatUnroll + threadIdx.x; base < n16; base += stride) {
+        u32x4 v[kFlatUnroll];
+#pragma unroll
+        for (int u = 0; u < kFlatUnroll; ++u) {
+            const int64_t g = base + u * 256;
+            if (g < n16) v[u] = __builtin_nontemporal_load(src + g);
+        }
+#pragma unroll
+        for (int u = 0; u < kFlatUnroll; ++u) {
+            const int64_t g = base + u * 256;
+            if (g < n16) {
+                if constexpr (kReadsPerWrite == 4)
+                    __builtin_nontemporal_store(v[u].x ^ v[u].y ^ v[u].z ^ v[u].w, reinterpret_cast<uint32_t *>(dst) + g);
+                else
+                    __builtin_nontemporal_store(v[u], reinterpret_cast<u32x4 *>(dst) + g);
+            }
+        }
+    }
+}
+
+}  // namespace mp8
+
+extern "C" mp8_status mp8_stream_probe(const void *src, void *dst, int64_t read_bytes, int reads_per_write,
+                                       void *stream) {
+    if (read_bytes < 0 || (reads_per_write != 1 && reads_per_write != 4)) return MP8_ERR_INVALID_ARG;
+    if (read_bytes == 0) return MP8_OK;
+    if (!src || !dst) return MP8_ERR_INVALID_ARG;
+    if ((((uintptr_t)src | (uintptr_t)dst) & 15u) || (read_bytes & 15)) return MP8_ERR_ALIGNMENT;
+    const int64_t n16 = read_bytes >> 4, per_block = 256 * mp8::kFlatUnroll;
+    int64_t blocks = (n16 + per_block - 1) / per_block;
+    if (blocks > (1 << 22)) blocks = 1 << 22;
+    if (reads_per_write == 4)
+        hipLaunchKernelGGL(mp8::stream_probe_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
+                           (const mp8::u32x4 *)src, dst, n16);
+    else
+        hipLaunchKernelGGL(mp8::stream_probe_kernel<1>, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
+                           (const mp8::u32x4 *)src, dst, n16);
+    return hipGetLastError() == hipSuccess ? MP8_OK : MP8_ERR_HIP;
+}
