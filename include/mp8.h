@@ -148,6 +148,31 @@ mp8_status mp8_gemm_fp8(mp8_op op, int64_t M, int64_t N, int64_t K, const uint8_
 size_t mp8_gemm_fp8_workspace_bytes(mp8_op op, int64_t M, int64_t N, int64_t K);
 
 /*
+ * mp8_gemm_fp8 for callers that cannot allocate device memory and have no workspace at hand:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments and, bit for bit, the same results as mp8_gemm_fp8 (automatic kernel choice), but
+ * the scratch of the two-pass paths lives in a static device array inside the library instead of
+ * a caller's workspace.  The call allocates and frees nothing.
+ *   - Limit: shapes for which mp8_gemm_fp8_workspace_bytes(op, M, N, K) exceeds
+ *     MP8_STATIC_SCRATCH_BYTES (32 MiB, also returned by mp8_static_scratch_bytes()) are
+ *     rejected with MP8_ERR_WORKSPACE.  Each GPU the library runs on holds that array until the
+ *     process ends.
+ *   - The array is looked up once per device, on the first call with that device current (a
+ *     symbol look-up, no allocation); the call must be made with the device of the tensors and
+ *     of `stream` current.
+ *   - Every call on a GPU shares that GPU's array: two calls whose kernels may overlap on one
+ *     GPU (different streams, no dependency between them) race on it; calls on one stream, or
+ *     ordered by events, are safe.  Nothing in the array has to be cleared between calls.
+ */
+#define MP8_STATIC_SCRATCH_BYTES (32u << 20)
+mp8_status mp8_gemm_fp8_static(mp8_op op, int64_t M, int64_t N, int64_t K, const uint8_t *a,
+                               int64_t lda, const uint8_t *b, int64_t ldb, float alpha, float *acc,
+                               int acc_mode, uint8_t *out8, uint8_t *out8_t, mp8_round round,
+                               int flags, uint64_t seed, uint64_t offset, mp8_stats *stats,
+                               void *stream);
+size_t mp8_static_scratch_bytes(void);
+
+/*
  * As mp8_gemm_fp8 with the kernel choice made by the caller (for tuning and tests):
  * tile_config 0 = automatic, otherwise an index below mp8_gemm_num_tile_configs() + 1;
  * split_k 0 = automatic, otherwise the number of contraction slices.  Workspace need:

@@ -30,7 +30,8 @@ EXPORTS = [
     "mp8_gemm_fp8_plan", "mp8_gemm_tile_config_lds_bytes", "mp8_adam_fp16_sr",
     "mp8_quantize_e5m2_batch", "mp8_wgrad_update_fp16_sr", "mp8_conv3x3_wgrad_update_fp16_sr",
     "mp8_quantize_gemm_fwd_fp8", "mp8_wgrad_momentum_fp16_sr", "mp8_conv3x3_wgrad_momentum_fp16_sr",
-    "mp8_wgrad_adam_fp16_sr", "mp8_stream_probe",
+    "mp8_wgrad_adam_fp16_sr", "mp8_gemm_fp8_static", "mp8_static_scratch_bytes",
+    "mp8_stream_probe",
 ]
 
 
@@ -65,6 +66,10 @@ def lib() -> C.CDLL:
     L.mp8_gemm_fp8.argtypes = gemm_args
     L.mp8_gemm_fp8_tuned.restype = ci
     L.mp8_gemm_fp8_tuned.argtypes = gemm_args + [ci, ci]
+    L.mp8_gemm_fp8_static.restype = ci
+    L.mp8_gemm_fp8_static.argtypes = gemm_args[:-3] + [vp]
+    L.mp8_static_scratch_bytes.restype = C.c_size_t
+    L.mp8_static_scratch_bytes.argtypes = []
     L.mp8_gemm_fp8_workspace_bytes.restype = C.c_size_t
     L.mp8_gemm_fp8_workspace_bytes.argtypes = [ci, i64, i64, i64]
     L.mp8_gemm_fp8_workspace_bytes_tuned.restype = C.c_size_t
@@ -237,7 +242,7 @@ def gemm_fp8_workspace_bytes(op, M, N, K, tile_config=0, split_k=0) -> int:
 
 def gemm_fp8(op, M, N, K, a, b, out8=None, out8_t=None, acc=None, acc_mode=0, alpha=1.0,
              round=RNE, flags=0, seed=0, offset=0, stats=None, workspace=None, lda=None,
-             ldb=None, tile_config=0, split_k=0):
+             ldb=None, tile_config=0, split_k=0, static_scratch=False):
     """mp8_gemm_fp8(_tuned): out[r,c] = sum_j a[r,j]*b[c,j] with the operand orientation of
     include/mp8.h.  All tensors are caller-allocated GPU tensors; workspace is a uint8/any
     tensor of at least gemm_fp8_workspace_bytes(...) bytes when that is non-zero."""
@@ -262,6 +267,14 @@ def gemm_fp8(op, M, N, K, a, b, out8=None, out8_t=None, acc=None, acc_mode=0, al
     for t, name in ((out8, "out8"), (out8_t, "out8_t"), (acc, "acc")):
         if t is not None and t.numel() < rows * cols:
             raise Mp8Error(f"{name} is smaller than rows*cols")
+    if static_scratch:
+        if workspace is not None or tile_config or split_k:
+            raise Mp8Error("static_scratch takes no workspace, tile_config or split_k")
+        st = lib().mp8_gemm_fp8_static(op, M, N, K, _ptr(a), lda, _ptr(b), ldb, float(alpha), _ptr(acc),
+                                       acc_mode, _ptr(out8), _ptr(out8_t), round, flags, seed, offset,
+                                       _ptr(stats), _stream())
+        _check(st, "mp8_gemm_fp8_static")
+        return out8
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     st = lib().mp8_gemm_fp8_tuned(op, M, N, K, _ptr(a), lda, _ptr(b), ldb, float(alpha), _ptr(acc),
                                   acc_mode, _ptr(out8), _ptr(out8_t), round, flags, seed, offset,
@@ -269,6 +282,15 @@ def gemm_fp8(op, M, N, K, a, b, out8=None, out8_t=None, acc=None, acc_mode=0, al
                                   split_k)
     _check(st, "mp8_gemm_fp8")
     return out8
+
+
+def gemm_fp8_static(op, M, N, K, a, b, **kw):
+    """mp8_gemm_fp8_static: gemm_fp8 with the library's own static scratch (allocates nothing)."""
+    return gemm_fp8(op, M, N, K, a, b, static_scratch=True, **kw)
+
+
+def static_scratch_bytes() -> int:
+    return int(lib().mp8_static_scratch_bytes())
 
 
 def quantize_gemm_fwd_fp8(M, N, K, x, x8_out, w8, out8=None, out8_t=None, acc=None, acc_mode=0,

@@ -23,6 +23,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <type_traits>
 
 #include "../../include/mp8.h"
@@ -618,6 +619,61 @@ extern "C" mp8_status mp8_gemm_fp8(mp8_op op, int64_t M, int64_t N, int64_t K, c
     return mp8_gemm_fp8_tuned(op, M, N, K, a, lda, b, ldb, alpha, acc, acc_mode, out8, out8_t,
                               round, flags, seed, offset, stats, workspace, workspace_bytes,
                               stream, 0, 0);
+}
+
+// ---------------------------------------------------------------------------------------
+// mp8_gemm_fp8 for callers that cannot allocate: the scratch of the two-pass paths (FP32 tiles of
+// the contraction slices, unfused epilogues) lives in a static device array of this library.
+namespace mp8 {
+
+constexpr size_t kStaticScratchBytes = (size_t)MP8_STATIC_SCRATCH_BYTES;
+// Every GPU the library runs on holds its own copy of this array, at an address of its own, until
+// the process ends.  In host code the name is only a handle for hipGetSymbolAddress: kernels get
+// the device address looked up below, never the name.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];   // device address of `scratch` per device, once looked up
+static std::mutex g_scratch_mutex;
+
+// Device address of the current device's copy of `scratch` (looked up once per device).
+static mp8_status static_scratch(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MP8_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+            (void)hipGetLastError();
+            return MP8_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return MP8_OK;
+}
+
+}  // namespace mp8
+
+extern "C" size_t mp8_static_scratch_bytes(void) { return mp8::kStaticScratchBytes; }
+
+extern "C" mp8_status mp8_gemm_fp8_static(mp8_op op, int64_t M, int64_t N, int64_t K, const uint8_t *a,
+                                          int64_t lda, const uint8_t *b, int64_t ldb, float alpha,
+                                          float *acc, int acc_mode, uint8_t *out8, uint8_t *out8_t,
+                                          mp8_round round, int flags, uint64_t seed, uint64_t offset,
+                                          mp8_stats *stats, void *stream) {
+    using namespace mp8;
+    // the same bound the workspace query gives the callers of mp8_gemm_fp8
+    if (M > 0 && N > 0 && K > 0 && (int)op >= 0 && (int)op <= 2 &&
+        mp8_gemm_fp8_workspace_bytes(op, M, N, K) > kStaticScratchBytes)
+        return MP8_ERR_WORKSPACE;
+    void *ws = nullptr;
+    const mp8_status ss = static_scratch(&ws);
+    if (ss != MP8_OK) return ss;
+    // Nothing in the scratch has to start at zero: every FP32 tile element the finishing pass
+    // reads has been written by this call's first kernel.
+    return gemm_impl(op, M, N, K, a, lda, b, ldb, alpha, acc, acc_mode, out8, out8_t, round, flags, seed,
+                     offset, stats, ws, kStaticScratchBytes, stream, 0, 0, nullptr);
 }
 
 // ---------------------------------------------------------------------------------------
