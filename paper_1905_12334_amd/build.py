@@ -13,7 +13,9 @@ SOURCES = ["quantize.hip", "update.hip", "gemm.hip", "host.hip"]
 # the weight update, is an explicit fma).  Packed FP32 instructions are switched off.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall",
-         "-Wno-unused-command-line-argument"]
+         "-Wno-unused-command-line-argument",
+         # the direct-to-LDS load names M0 as clobbered; clang remarks that M0 is a reserved register
+         "-Wno-inline-asm"]
 
 
 def build(verbose: bool = False) -> str:
