@@ -11,6 +11,7 @@
 //                     contraction, slot-scheduled MFMA loop, every operand layout, 3x3 convolutions
 //   gemm_shortk.hpp   contractions of one or two stages (all start-up and epilogue)
 //   gemm_wavek.hpp    small outputs with long contractions (contraction divided among waves)
+//   gemm_wave128.hpp  about one 128x128 tile per CU and a long contraction (every wave the whole tile)
 //   gemm_finish.hpp   second pass for split contractions and unfused epilogues, optionally with
 //                     the master-weight update; the any-shape fallback kernel
 // Split contraction, FP32 / transposed outputs, ragged column counts: the MFMA kernels write
@@ -32,6 +33,7 @@
 #include "gemm_mfma.hpp"
 #include "gemm_shortk.hpp"
 #include "gemm_wavek.hpp"
+#include "gemm_wave128.hpp"
 #include "gemm_qfwd.hpp"
 
 namespace mp8 {
@@ -93,6 +95,12 @@ struct TileConfig {
     {gemm_wavek_kernel<EPI_PARTIAL, false, BTN, 0, 32, BN>, gemm_wavek_kernel<EPI_RNE, false, BTN, 0, 32, BN>, \
      gemm_wavek_kernel<EPI_FULL, false, BTN, 0, 32, BN>}
 #define MP8_NO_KERNELS {nullptr, nullptr, nullptr}
+#define MP8_WAVE128(ATN, BTN)                                                \
+    {gemm_wave128_kernel<EPI_PARTIAL, ATN, BTN>, gemm_wave128_kernel<EPI_RNE, ATN, BTN>, \
+     gemm_wave128_kernel<EPI_FULL, ATN, BTN>}
+#define MP8_TILE_WAVE128                                                     \
+    {128, 128, "128x128x128p", MP8_WAVE128(false, false), MP8_WAVE128(true, true), MP8_WAVE128(false, true), \
+     {MP8_NO_KERNELS, MP8_NO_KERNELS, MP8_NO_KERNELS}, 0, 0}
 #define MP8_TILE_WAVEK32x64                                                  \
     {32, 64, "32x64x128w", MP8_WAVEK32(false, 64), MP8_NO_KERNELS, MP8_WAVEK32(true, 64), \
      {MP8_NO_KERNELS, MP8_NO_KERNELS, MP8_NO_KERNELS}, 0, 0}
@@ -104,7 +112,7 @@ static const TileConfig kTiles[] = {
     MP8_TILE_TN(128, 128, 2, 2, 2, 2), MP8_TILE_TN(128, 128, 2, 2, 4, 1), MP8_TILE(64, 128, 1, 4, 3, 2),
     MP8_TILE(128, 64, 4, 1, 3, 2),  MP8_TILE_TN(64, 64, 2, 2, 4, 2), MP8_TILE(64, 128, 1, 4, 2, 3),
     MP8_TILE(128, 64, 4, 1, 2, 3),  MP8_TILE_TN(64, 64, 2, 2, 2, 4),   MP8_TILE_SHORTK,
-    MP8_TILE_WAVEK, MP8_TILE_WAVEK32x64, MP8_TILE_WAVEK32x32,
+    MP8_TILE_WAVEK, MP8_TILE_WAVEK32x64, MP8_TILE_WAVEK32x32, MP8_TILE_WAVE128,
 };
 constexpr int kNumTiles = (int)(sizeof(kTiles) / sizeof(kTiles[0]));
 constexpr int kCUs = 256;
@@ -133,9 +141,10 @@ static void op_dims(mp8_op op, int64_t M, int64_t N, int64_t K, int64_t &rows, i
 // outputs take 64x64 tiles and, if even those are too few, a split contraction -- kept to a
 // minimum because the second pass costs several microseconds.
 enum { T256x256 = 0, T128x128s2 = 3, T128x128s4 = 4, T128x64s2 = 9, T64x64s2 = 10, T128x128k = 11, T64x64w = 12,
-       T32x64w = 13, T32x32w = 14 };
+       T32x64w = 13, T32x32w = 14, T128x128p = 15 };
 static Plan make_plan(int64_t rows, int64_t cols, int64_t kc, int tile_config, int split_k,
-                      int layout = 0) {  // bit 0: a contraction-major, bit 1: b
+                      int layout = 0,      // bit 0: a contraction-major, bit 1: b
+                      bool conv = false) { // a convolution: only the tiles with convolution addressing
     Plan pl{};
     pl.mfma = (kc % BK) == 0 && kc > 0;
     // contraction-major operands are fetched in 16-row chunks, by the tiles built for them
@@ -164,6 +173,10 @@ static Plan make_plan(int64_t rows, int64_t cols, int64_t kc, int tile_config, i
         const int64_t n256 = count(T256x256), n128 = count(T128x128s2);
         const double fill256 = (double)n256 / (double)(((n256 + kCUs - 1) / kCUs) * kCUs);
         const int64_t n64 = count(T64x64s2);
+        // 128x128 tiles, one workgroup per CU, long contraction: every wave the whole tile on a
+        // quarter of the contraction (measured 6-17 % faster than the four-stage ring when no CU
+        // gets more than two tiles; with more tiles, or a split contraction, the ring kernels win)
+        const int long128 = (!conv && n128 >= kCUs / 2 && n128 <= 2 * kCUs) ? T128x128p : T128x128s4;
         if (n256 >= 208 && fill256 >= 0.8 && ksteps >= 8) t = T256x256;
         // so few tiles that most CUs would idle and the contraction is too short to split:
         // half the rows per tile, and half the columns too if that still fits one round
@@ -173,9 +186,9 @@ static Plan make_plan(int64_t rows, int64_t cols, int64_t kc, int tile_config, i
             t = T32x64w;
         else if (n64 <= kCUs && ksteps >= 16) t = T64x64w;  // one workgroup per CU, one round
         else if (tn && (n128 < 16 || (n128 < 192 && ksteps <= 64))) t = T64x64s2;
-        else if (tn) t = ksteps >= 64 ? T128x128s4 : T128x128s2;
+        else if (tn) t = ksteps >= 64 ? long128 : T128x128s2;
         else if (n128 >= 192 && ksteps <= 2) t = T128x128k;  // all prologue and epilogue
-        else if (n128 >= 192) t = (ksteps >= 64 && n128 <= 2 * kCUs) ? T128x128s4 : T128x128s2;
+        else if (n128 >= 192) t = (ksteps >= 64 && n128 <= 2 * kCUs) ? long128 : T128x128s2;
         else t = T64x64s2;
     }
     pl.tile = t;
@@ -784,14 +797,14 @@ static bool conv_dims(mp8_op op, int64_t prows, int64_t Ci, int64_t Co, ConvDims
 
 static Plan conv_plan(mp8_op op, const ConvDims &d, int64_t Ci) {
     // the tile shapes built for contraction-major operands are the ones built for convolutions
-    Plan pl = make_plan(d.rows, d.cols, d.kc, 0, 0, 3);
+    Plan pl = make_plan(d.rows, d.cols, d.kc, 0, 0, 3, true);
     // a tile row of the weight gradient must not straddle two taps
     if (pl.mfma && op == MP8_WGRAD && (Ci % kTiles[pl.tile].bm) != 0)
-        pl = make_plan(d.rows, d.cols, d.kc, T128x128s2 + 1, 0, 3);
+        pl = make_plan(d.rows, d.cols, d.kc, T128x128s2 + 1, 0, 3, true);
     // forward and backward data have one tile row per 128 pixels and few tile columns: the
     // 128-row tile keeps the re-reads of the weights low
     if (pl.mfma && op != MP8_WGRAD && kTiles[pl.tile].bm < 128)
-        pl = make_plan(d.rows, d.cols, d.kc, T128x128s2 + 1, 0, 3);
+        pl = make_plan(d.rows, d.cols, d.kc, T128x128s2 + 1, 0, 3, true);
     return pl;
 }
 

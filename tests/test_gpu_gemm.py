@@ -117,6 +117,8 @@ def test_static_lds_of_every_kernel_is_what_its_tile_implies(mp8):
             got = mp8.gemm_tile_config_lds_bytes(i, epi)
             if name.endswith("k"):          # all stages in dynamic LDS; statistics need 1 KB
                 assert 0 <= got <= 1024, (name, epi, got)
+            elif name.endswith("p"):        # one stage per wave, or four half tiles of FP32 for the reduction
+                assert 4 * 64 * 132 * 4 <= got <= 4 * 64 * 132 * 4 + 1024, (name, epi, got)
             elif name.endswith("w"):        # a two-stage ring of (BM + BN) x 128 bytes per wave
                 bm, bn = (int(x) for x in name.split("x")[:2])
                 ring = 4 * 2 * (bm + bn) * 128

@@ -109,7 +109,7 @@ ROW_MAJOR_KERNELS = [("256x256x128s2", 0, 128), ("256x128x128s3", 0, 128), ("128
                      ("128x128x128s2", 0, 128), ("128x128x128s4", 3, 1152), ("64x128x128s3", 0, 128),
                      ("128x64x128s3", 0, 128), ("64x64x128s4", 2, 256), ("64x64x128s2", 0, 128),
                      ("64x64x128w", 0, 128), ("64x64x128w", 5, 6400), ("32x64x128w", 0, 1152),
-                     ("32x32x128w", 0, 1152)]
+                     ("32x32x128w", 0, 1152), ("128x128x128p", 0, 128), ("128x128x128p", 3, 1152)]
 
 
 @pytest.mark.parametrize("kc", KCS)
@@ -155,7 +155,7 @@ def test_full_range_operands_contraction_major_kernels(mp8, kc, mode):
     alpha = alpha_for(kc)
     want = Reference.of(("contraction-major", kc), a8, b8)
     for name, split in (("256x256x128s2", 0), ("128x128x128s2", 0), ("128x128x128s4", 2), ("64x64x128s2", 0),
-                        ("64x64x128w", 0)):
+                        ("64x64x128w", 0), ("128x128x128p", 0), ("128x128x128p", 2)):
         if split and kc < 1152:
             continue
         t = tile_index(mp8, name)
