@@ -12,7 +12,8 @@ import ctypes as C
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libmp8.so")
+# MP8_LIB_PATH: another build of the same library (tuning experiments); default: the in-tree build
+LIB_PATH = os.environ.get("MP8_LIB_PATH") or os.path.join(_HERE, "libmp8.so")
 
 RNE, SR = 0, 1
 FWD, BWD_DATA, WGRAD = 0, 1, 2

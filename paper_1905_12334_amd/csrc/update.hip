@@ -76,7 +76,7 @@ __global__ __launch_bounds__(256) void sgd_update_kernel(uint16_t *__restrict__ 
             __builtin_nontemporal_store(o, reinterpret_cast<u32x4 *>(w16) + t);
             if constexpr (kW8) {
                 u32x2 o8 = {w8[0], w8[1]};
-                __builtin_nontemporal_store(o8, reinterpret_cast<u32x2 *>(w8_out) + t);
+                reinterpret_cast<u32x2 *>(w8_out)[t] = o8;  // the next step's GEMM operand: stays in the caches
             }
         }
     }
@@ -166,7 +166,7 @@ __global__ __launch_bounds__(256) void state_update_kernel(uint16_t *__restrict_
         }
         if constexpr (kW8) {
             u32x2 o8 = {w8[0], w8[1]};
-            __builtin_nontemporal_store(o8, reinterpret_cast<u32x2 *>(w8_out) + t);
+            reinterpret_cast<u32x2 *>(w8_out)[t] = o8;  // the next step's GEMM operand: stays in the caches
         }
     }
     if (blockIdx.x == 0 && threadIdx.x < 8) {  // ragged tail (< 8 elements)

@@ -266,6 +266,50 @@ def test_weight_gradient_and_update_in_one_call_against_the_oracle_chain(mp8, la
             assert torch.equal(wd2, wd)
 
 
+@pytest.mark.parametrize("layout", ["row-major", "contraction-major"])
+def test_weight_gradient_and_update_on_the_one_tile_per_cu_plan(mp8, layout):
+    """The weight gradient with its SGD step on the plan of the Transformer-big shape class (one
+    128x128 tile per CU, a long unsplit contraction, every wave a quarter of it).  Exact-sum operands (nine in ten contraction positions zero) make the chain the
+    oracle's: gradient codes (stochastic rounding), master weights (stochastic rounding), 8-bit
+    weights, bit for bit; a set skip flag leaves the weights alone; the statistics count the
+    gradient's Inf codes."""
+    import torch
+    from test_gpu_gemm import exact_sum_codes
+    rng = np.random.default_rng(53)
+    M, N, K = 8192, 3072, 1024
+    flags = 0 if layout == "row-major" else mp8.FLAG_CONTRACTION_MAJOR
+    assert mp8.gemm_fp8_plan(mp8.WGRAD, M, N, K, flags) == ("128x128x128p", 1)
+    xt, et = exact_sum_codes(rng, (K, M)), exact_sum_codes(rng, (N, M))
+    xt[:, rng.random(M) < 0.9] = 0
+    ref, _ = oracle.gemm_ref(xt, et, want_abs=False)
+    w16 = (rng.standard_normal(K * N) * 0.05).astype(np.float16).view(np.uint16)
+    lr, inv = 0.05, 1.0 / 64
+    a, b = (gpu(xt), gpu(et)) if layout == "row-major" else (gpu(np.ascontiguousarray(xt.T)), gpu(np.ascontiguousarray(et.T)))
+    for alpha, skip in ((2.0 ** -9, 0), (2.0 ** -9, 5), (2.0 ** 6, 0)):
+        want_g = oracle.quantize_e5m2(ref.astype(np.float32), scale=alpha, mode=oracle.SR, seed=21, offset=22)[0]
+        want_w, want_w8 = oracle.sgd_update_fp16(w16, want_g.reshape(-1), lr, inv, mode=oracle.SR, seed=23, offset=24,
+                                                 skip=skip or None, want_w8=True)
+        for keep_codes in (True, False):
+            wd = gpu(w16.view(np.int16))
+            g8 = torch.full((K * N + 64,), 0xAA, dtype=torch.uint8, device="cuda")
+            w8 = torch.full((K * N + 64,), 0x55, dtype=torch.uint8, device="cuda")
+            flag = torch.full((1,), skip, dtype=torch.int32, device="cuda")
+            st = mp8.new_stats()
+            mp8.wgrad_update_fp16_sr(M, N, K, a, b, wd, lr, inv, g8_out=g8[: K * N] if keep_codes else None, alpha=alpha,
+                                     g_round=oracle.SR, flags=flags, g_seed=21, g_offset=22, stats=st, w_round=oracle.SR,
+                                     w_seed=23, w_offset=24, skip_if_nonzero=flag, w8_out=w8[: K * N])
+            torch.cuda.synchronize()
+            if keep_codes:
+                assert np.array_equal(host(g8[: K * N]).reshape(K, N), want_g), (alpha, skip)
+            assert bool((g8[K * N:] == 0xAA).all()) and bool((w8[K * N:] == 0x55).all())
+            assert np.array_equal(host(wd).view(np.uint16), want_w), (alpha, skip)
+            assert mp8.read_stats(st)[1] == int(np.count_nonzero((want_g & 0x7C) == 0x7C))
+            if skip:
+                assert bool((w8[: K * N] == 0x55).all())
+            else:
+                assert np.array_equal(host(w8[: K * N]), want_w8), (alpha, skip)
+
+
 def test_fused_update_with_the_skip_flag_inside_the_statistics_of_the_same_call(mp8):
     """Section 3.1's back-off skips a step whose gradients overflowed.  When the skip flag is the
     Inf/NaN count of the statistics that the very same call accumulates into, the count is only
