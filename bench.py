@@ -342,9 +342,9 @@ class ConvWorkload:
     grid ([28800, 128] instead of the lowered [25088, 1152]); a filter tap is a row shift of the
     operand, so nothing is lowered and nothing is transposed."""
 
-    def __init__(self, mp8, torch, lay):
+    def __init__(self, mp8, torch, lay, shape=(32, 28, 28, 128)):
         self.mp8, self.torch = mp8, torch
-        B, H, W, C = 32, 28, 28, 128
+        B, H, W, C = shape
         self.dims = (B, H, W, C, C)
         dev, u8 = "cuda", torch.uint8
         P = mp8.conv_prows(B, H, W)
@@ -887,6 +887,20 @@ def main():
                                 "fwd + bwd_data + wgrad, FP16 SR update emitting the next 8-bit weights",
                     "ms_per_step": msc, "value": flops2 / (msc * 1e-3) / 1e12,
                     "unit": "TFLOP/s (useful flops of the unpadded layer, 3 * 2*M*N*K)",
+                    "overflow_count_last_step": mp8.read_stats(cw.stats)[1], "kernels": kc_}
+                del cw
+                torch.cuda.empty_cache()
+                # the first stage of the residual networks: 64 channels at four times the pixels (a stage
+                # of the contraction spans two filter taps, the last stage is half a stage)
+                cw = ConvWorkload(mp8, torch, lay2, shape=(32, 56, 56, 64))
+                msc, kc_ = timed_workload(torch, cw, args)
+                flops64 = 3 * 2.0 * 32 * 56 * 56 * 9 * 64 * 64
+                out["conv64_step"] = {
+                    "workload": "a 3x3 convolution of the 64-channel stage (batch 32, 56x56, 64 -> 64 channels) as an "
+                                "implicit GEMM: quantize X and dY, conv fwd + bwd_data + wgrad, FP16 SR update "
+                                "emitting the next 8-bit weights",
+                    "ms_per_step": msc, "value": flops64 / (msc * 1e-3) / 1e12,
+                    "unit": "TFLOP/s (useful flops of the unpadded layer, 3 * 2*B*H*W*9*Cin*Cout)",
                     "overflow_count_last_step": mp8.read_stats(cw.stats)[1], "kernels": kc_}
                 del cw
                 torch.cuda.empty_cache()

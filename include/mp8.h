@@ -218,7 +218,8 @@ int mp8_gemm_tile_config_lds_bytes(int tile_config, int epi);
  * Padding rows of y8 / dx8 are written as zero codes (so an output can be the next input) and
  * do not enter the statistics; acc, if requested, has the shape of out and its padding rows are
  * unspecified.  SR uses the row-major index of the output matrix.  Cin and Cout must be
- * multiples of 128, and prows a multiple of 128 for MP8_WGRAD (MP8_ERR_UNSUPPORTED otherwise).
+ * multiples of 64 (the residual networks of Section 4 start at 64 channels) below 32768, W below
+ * 32768, and prows a multiple of 128 for MP8_WGRAD (MP8_ERR_UNSUPPORTED otherwise).
  * Everything else (alpha, acc_mode, round, flags = MP8_FLAG_SATURATE or 0, stats, workspace)
  * as for mp8_gemm_fp8.
  */

@@ -795,18 +795,33 @@ static bool conv_dims(mp8_op op, int64_t prows, int64_t Ci, int64_t Co, ConvDims
     return false;
 }
 
+// Stages of the implicit GEMM's contraction: whole stages of 128, the last one starting 64 early
+// when forward / backward data contract over an odd number of 64-channel units.
+static int64_t conv_kc_stages(const ConvDims &d) { return (d.kc + BK - 1) / BK * BK; }
+
 static Plan conv_plan(mp8_op op, const ConvDims &d, int64_t Ci) {
     // the tile shapes built for contraction-major operands are the ones built for convolutions
-    Plan pl = make_plan(d.rows, d.cols, d.kc, 0, 0, 3, true);
+    const int64_t kc = conv_kc_stages(d);
+    Plan pl = make_plan(d.rows, d.cols, kc, 0, 0, 3, true);
     // a tile row of the weight gradient must not straddle two taps
     if (pl.mfma && op == MP8_WGRAD && (Ci % kTiles[pl.tile].bm) != 0)
-        pl = make_plan(d.rows, d.cols, d.kc, T128x128s2 + 1, 0, 3, true);
+        pl = make_plan(d.rows, d.cols, kc, ((Ci & 127) == 0 ? T128x128s2 : T64x64s2) + 1, 0, 3, true);
     // forward and backward data have one tile row per 128 pixels and few tile columns: the
-    // 128-row tile keeps the re-reads of the weights low
-    if (pl.mfma && op != MP8_WGRAD && kTiles[pl.tile].bm < 128)
-        pl = make_plan(d.rows, d.cols, d.kc, T128x128s2 + 1, 0, 3, true);
+    // 128-row tile keeps the re-reads of the weights low; it is also the tile whose kernels are
+    // built for stages that span two taps (contracted channels an odd multiple of 64)
+    if (pl.mfma && op != MP8_WGRAD && (kTiles[pl.tile].bm < 128 || (d.kc / 9 / 64) % 2 != 0))
+        pl = make_plan(d.rows, d.cols, kc, T128x128s2 + 1, 0, 3, true);
     return pl;
 }
+
+// Forward / backward data with the contracted channel count an odd multiple of 64: [op][EPI_*]
+static void (*const kConvHalves[2][3])(const GemmArgs) = {
+    {gemm_mfma_kernel<128, 128, 2, 2, 2, 2, EPI_PARTIAL, false, true, 4>,
+     gemm_mfma_kernel<128, 128, 2, 2, 2, 2, EPI_RNE, false, true, 4>,
+     gemm_mfma_kernel<128, 128, 2, 2, 2, 2, EPI_FULL, false, true, 4>},
+    {gemm_mfma_kernel<128, 128, 2, 2, 2, 2, EPI_PARTIAL, false, false, 5>,
+     gemm_mfma_kernel<128, 128, 2, 2, 2, 2, EPI_RNE, false, false, 5>,
+     gemm_mfma_kernel<128, 128, 2, 2, 2, 2, EPI_FULL, false, false, 5>}};
 
 }  // namespace mp8
 
@@ -838,8 +853,10 @@ static mp8_status conv_impl(mp8_op op, int64_t B, int64_t H, int64_t W, int64_t 
     const int64_t img = (H + 2) * (W + 2);
     if (B > (int64_t)0x7FFFFFFF / img || prows < B * img || prows > 0x7FFFFFFF) return MP8_ERR_INVALID_ARG;
     if (!a || !b || (acc_mode != 0 && !acc)) return MP8_ERR_INVALID_ARG;
-    // whole 128-byte stages per tap, whole tiles per tap of the weight gradient
-    if ((Ci & 127) != 0 || (Co & 127) != 0 || Ci >= (1 << 20) || Co >= (1 << 20)) return MP8_ERR_UNSUPPORTED;
+    // whole 64-byte halves of a stage per tap, whole tiles per tap of the weight gradient; lane
+    // offsets (a tile's rows, a filter row's shift, a tap's weight slab) stay within 32 bits
+    if ((Ci & 63) != 0 || (Co & 63) != 0 || Ci >= (1 << 15) || Co >= (1 << 15) || W >= (1 << 15))
+        return MP8_ERR_UNSUPPORTED;
     if (op == MP8_WGRAD && (prows & 127) != 0) return MP8_ERR_UNSUPPORTED;
     if (((uintptr_t)a | (uintptr_t)b | (uintptr_t)acc | (uintptr_t)out8 | (uintptr_t)workspace) & 15u)
         return MP8_ERR_ALIGNMENT;
@@ -871,10 +888,15 @@ static mp8_status conv_impl(mp8_op op, int64_t B, int64_t H, int64_t W, int64_t 
     ga.lda = d.lda;
     ga.ldb = d.ldb;
     ga.cv.w2 = (int)(W + 2);
-    ga.cv.div_cpb = make_fastdiv((uint32_t)((op == MP8_BWD_DATA ? Co : Ci) / 128));
+    ga.cv.units_per_tap = (int)((op == MP8_BWD_DATA ? Co : Ci) / 64);
+    ga.cv.div_cpb = make_fastdiv((uint32_t)ga.cv.units_per_tap);
+    ga.cv.odd_units = op != MP8_WGRAD && (d.kc % BK) != 0;
     ga.cv.b_tap_stride = Ci * Co;
     ga.cv.div_ci = make_fastdiv((uint32_t)Ci);
-    return launch_mfma(ga, ep, pl, d.kc, kTiles[pl.tile].kernel_conv[(int)op], workspace, workspace_bytes,
+    const bool halves = op != MP8_WGRAD && (ga.cv.units_per_tap & 1) != 0;
+    if (halves && pl.tile != T128x128s2) return MP8_ERR_UNSUPPORTED;
+    return launch_mfma(ga, ep, pl, conv_kc_stages(d), halves ? kConvHalves[(int)op] : kTiles[pl.tile].kernel_conv[(int)op],
+                       workspace, workspace_bytes,
                        (hipStream_t)stream, upd);
 }
 

@@ -73,7 +73,9 @@ __device__ __forceinline__ bool conv_padding_row(const Epilogue &ep, int64_t r) 
 // What a convolution adds to the operand addressing (conv = 0: plain GEMM).
 struct ConvArgs {
     int w2;               // W + 2: a tap (r, s) shifts the pixel row by (r-1)*w2 + (s-1)
-    FastDiv div_cpb;      // by the number of 128-byte stages per tap (channels / 128)
+    FastDiv div_cpb;      // by units_per_tap
+    int units_per_tap;    // 64-byte units of the contraction per tap (contracted channels / 64)
+    int odd_units;        // the contraction has an odd number of units: its last stage starts one early
     int64_t b_tap_stride; // backward data: bytes between the weight slabs of two taps
     FastDiv div_ci;       // weight gradient: by Cin (tile row -> tap, first channel)
 };

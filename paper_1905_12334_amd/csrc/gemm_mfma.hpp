@@ -39,8 +39,11 @@ namespace mp8 {
 //   3  a[(tap, ci), r] = x[r + shift(tap), ci]      both contraction-major, tap fixed per tile row
 // so only the base address of a stage (1, 2) or of a tile (3) differs from the plain GEMM.
 template <int BM, int BN, int WGM, int WGN, int NSTAGE, int MINBLOCKS, int EPI, bool ATN = false,
-          bool BTN = false, int CONV = 0>
+          bool BTN = false, int CONV_ = 0>
 __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArgs p) {
+    // CONV_ 4 / 5: forms 1 / 2 for channel counts that are odd multiples of 64 (HALVES below)
+    constexpr int CONV = CONV_ > 3 ? CONV_ - 3 : CONV_;
+    constexpr bool HALVES = CONV_ > 3;
     static_assert(CONV == 0 || (CONV == 1 && !ATN && BTN) || (CONV == 2 && !ATN && !BTN) ||
                       (CONV == 3 && ATN && BTN), "operand layouts of the convolution forms");
     static_assert((!ATN || BM % 128 == 0 || BM == 64) && (!BTN || BN % 128 == 0 || BN == 64),
@@ -117,24 +120,59 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     const uint8_t *a_tile = uniform_ptr(a_origin);
     const uint8_t *b_tile = uniform_ptr(b_origin);
     // base addresses of stage `kstage` of this workgroup's slice
-    auto a_stage = [&](int kstage) -> const uint8_t * {
+    // Convolution forms 1 and 2: stage `kstage` lies inside one tap when the contracted channel count
+    // is a multiple of 128.  Otherwise (HALVES; a multiple of 64) a stage is two halves of 64
+    // contraction indices ("units"), each inside one tap.  The lanes that fetch chunks 4 .. 7 of a
+    // row belong to the second half; their addresses differ from the first half's by a
+    // wave-uniform amount whenever the second half starts a new tap, so a stage is a uniform base
+    // plus one of two non-negative offsets (`lo` for chunks 0 .. 3, `hi` for 4 .. 7) added to the
+    // lane's own.  A contraction of an odd number of units ends with a stage that starts one unit
+    // early: its first half repeats the stage before and is not multiplied.
+    struct StageAddr {
+        const uint8_t *base;
+        uint32_t lo, hi;
+    };
+    auto first_unit = [&](int kstage, uint32_t &part) -> uint32_t {  // -> tap, part = unit within the tap
+        uint32_t u = 2u * (uint32_t)(ks_begin + kstage);
+        if (HALVES && p.cv.odd_units && ks_begin + kstage == p.ksteps - 1) u -= 1u;
+        return fastdiv(u, p.cv.div_cpb, part);
+    };
+    auto a_stage = [&](int kstage) -> StageAddr {
         if constexpr (CONV == 1 || CONV == 2) {
             uint32_t part;
-            const uint32_t tap = fastdiv((uint32_t)(ks_begin + kstage), p.cv.div_cpb, part);
-            const int sh = CONV == 1 ? tap_shift(tap) : -tap_shift(tap);
-            return a_tile + (int64_t)sh * p.lda + part * BK;
+            const uint32_t tap = first_unit(kstage, part);
+            const int s0 = CONV == 1 ? tap_shift(tap) : -tap_shift(tap);
+            const int64_t b0 = (int64_t)s0 * p.lda + part * 64;
+            if constexpr (!HALVES) return {a_tile + b0, 0u, 0u};
+            int64_t b1 = b0;
+            if ((int)part + 1 == p.cv.units_per_tap) {
+                const int s1 = CONV == 1 ? tap_shift(tap + 1) : -tap_shift(tap + 1);
+                b1 = (int64_t)s1 * p.lda - 64;
+            }
+            const int64_t least = b0 < b1 ? b0 : b1;
+            return {a_tile + least, (uint32_t)(b0 - least), (uint32_t)(b1 - least)};
         } else {
-            return a_tile + (int64_t)kstage * a_kstep;
+            return {a_tile + (int64_t)kstage * a_kstep, 0u, 0u};
         }
     };
-    auto b_stage = [&](int kstage) -> const uint8_t * {
+    auto b_stage = [&](int kstage) -> StageAddr {
         if constexpr (CONV == 2) {
             uint32_t part;
-            const uint32_t tap = fastdiv((uint32_t)(ks_begin + kstage), p.cv.div_cpb, part);
-            return b_tile + (int64_t)tap * p.cv.b_tap_stride + part * BK;
+            const uint32_t tap = first_unit(kstage, part);
+            const int64_t b0 = (int64_t)tap * p.cv.b_tap_stride + part * 64;
+            if constexpr (!HALVES) return {b_tile + b0, 0u, 0u};
+            const int64_t b1 = (int)part + 1 == p.cv.units_per_tap ? (int64_t)(tap + 1) * p.cv.b_tap_stride - 64 : b0;
+            return {b_tile + b0, 0u, (uint32_t)(b1 - b0)};
+        } else if constexpr (CONV == 1 && HALVES) {
+            const bool early = p.cv.odd_units && ks_begin + kstage == p.ksteps - 1;
+            return {b_tile + (int64_t)kstage * b_kstep - (early ? 64 * p.ldb : 0), 0u, 0u};
         } else {
-            return b_tile + (int64_t)kstage * b_kstep;
+            return {b_tile + (int64_t)kstage * b_kstep, 0u, 0u};
         }
+    };
+    const bool second_half = (lchunk & 4) != 0;   // row-major slabs: this lane fetches chunks 4 .. 7
+    auto lane_off = [&](const StageAddr &sa, uint32_t own, bool halves) -> uint32_t {
+        return halves ? own + (second_half ? sa.hi : sa.lo) : own;
     };
     uint32_t oa[A_DMA], ob[B_DMA];
 #pragma unroll
@@ -167,12 +205,12 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     auto issue_loads = [&](int kstage) {
         const uint32_t sa = lds0 + (kstage % NSTAGE) * STAGE + wave * 1024;
         const uint32_t sb = sa + A_BYTES;
-        const uint8_t *ak = a_stage(kstage);
-        const uint8_t *bk = b_stage(kstage);
+        const StageAddr ak = a_stage(kstage);
+        const StageAddr bk = b_stage(kstage);
 #pragma unroll
-        for (int q = 0; q < A_DMA; ++q) dma16(ak, oa[q], sa + q * 4096);
+        for (int q = 0; q < A_DMA; ++q) dma16(ak.base, lane_off(ak, oa[q], HALVES), sa + q * 4096);
 #pragma unroll
-        for (int q = 0; q < B_DMA; ++q) dma16(bk, ob[q], sb + q * 4096);
+        for (int q = 0; q < B_DMA; ++q) dma16(bk.base, lane_off(bk, ob[q], HALVES && CONV == 2), sb + q * 4096);
     };
 
     // Fragments: lane l supplies row (l % 32) of a 32-row tile and, for sub-step s, the 32
@@ -239,11 +277,14 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     };
     auto issue_one = [&](int kstage, int q) {  // load q (0 .. G-1) of a stage
         const uint32_t sa = lds0 + (kstage % NSTAGE) * STAGE + wave * 1024;
-        if (q < A_DMA)
-            dma16(a_stage(kstage), oa[q < A_DMA ? q : 0], sa + q * 4096);
-        else
-            dma16(b_stage(kstage), ob[q >= A_DMA ? q - A_DMA : 0],
+        if (q < A_DMA) {
+            const StageAddr ak = a_stage(kstage);
+            dma16(ak.base, lane_off(ak, oa[q < A_DMA ? q : 0], HALVES), sa + q * 4096);
+        } else {
+            const StageAddr bk = b_stage(kstage);
+            dma16(bk.base, lane_off(bk, ob[q >= A_DMA ? q - A_DMA : 0], HALVES && CONV == 2),
                   sa + A_BYTES + (q - A_DMA) * 4096);
+        }
     };
 
     // Wait for this wave's loads of stage t+1 (and for its own LDS reads).  Loads complete in
@@ -309,9 +350,15 @@ __global__ __launch_bounds__(256, MINBLOCKS) void gemm_mfma_kernel(const GemmArg
     for (int t = 0; t < ks_count; ++t) {
         const bool more = t + NSTAGE < ks_count;
         const bool next = t + 1 < ks_count;
+        // the early stage that ends a contraction of an odd number of units: second half only
+        const bool skip_first = HALVES && p.cv.odd_units && ks_begin + t == p.ksteps - 1;
 #pragma unroll
         for (int k = 0; k < 2 * NM; ++k) {
-            if (k < NM) mfma(f0, k); else mfma(f1, k - NM);
+            if (k < NM) {
+                if (!skip_first) mfma(f0, k);
+            } else {
+                mfma(f1, k - NM);
+            }
             if (k < S_RD) {
 #pragma unroll
                 for (int r = 0; r < R0; ++r) {

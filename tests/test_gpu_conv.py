@@ -63,10 +63,14 @@ def exact_codes(rng, shape):
     return ((s << 7) | (e << 2) | m).astype(np.uint8)
 
 
-@pytest.mark.parametrize("dims", [(2, 6, 5, 128, 128), (1, 9, 14, 128, 256), (3, 4, 4, 256, 128)])
+@pytest.mark.parametrize("dims", [(2, 6, 5, 128, 128), (1, 9, 14, 128, 256), (3, 4, 4, 256, 128),
+                                  (2, 6, 5, 64, 64), (1, 9, 14, 64, 128), (3, 4, 4, 128, 64), (2, 5, 7, 192, 64),
+                                  (1, 3, 3, 64, 320)])
 def test_conv_exact_sums_all_three_operations(mp8, dims):
     """Exactly representable sums: the FP32 accumulators must equal the direct convolution bit for
-    bit on every interior pixel, padding rows of the outputs must be zero codes."""
+    bit on every interior pixel, padding rows of the outputs must be zero codes.  Channel counts
+    that are odd multiples of 64 (the first stage of the residual networks of Section 4) make a
+    stage of the contraction span two taps, and its last stage half a stage."""
     B, H, W, Ci, Co = dims
     rng = np.random.default_rng(sum(dims))
     x, w, e = exact_codes(rng, (B, H, W, Ci)), exact_codes(rng, (3, 3, Ci, Co)), exact_codes(rng, (B, H, W, Co))
@@ -144,8 +148,9 @@ def test_conv_weight_gradient_and_momentum_update_in_one_call(mp8):
         assert np.array_equal(host(vdev).view(np.uint32), v_ref.view(np.uint32))
 
 
-def test_conv_random_operands_sr_epilogue_and_statistics(mp8):
-    B, H, W, Ci, Co = 2, 7, 9, 128, 128
+@pytest.mark.parametrize("channels", [(128, 128), (64, 64), (64, 192)])
+def test_conv_random_operands_sr_epilogue_and_statistics(mp8, channels):
+    B, H, W, (Ci, Co) = 2, 7, 9, channels
     dims = (B, H, W, Ci, Co)
     x = (workloads.random_e5m2_codes(1, (B, H, W, Ci)) & 0x83) | 0x38
     w = (workloads.random_e5m2_codes(2, (3, 3, Ci, Co)) & 0x83) | 0x34
@@ -200,7 +205,7 @@ def test_conv_config2_layer_full_size(mp8):
 def test_conv_argument_checks(mp8):
     import torch
     u8 = lambda *s: torch.zeros(s, dtype=torch.uint8, device="cuda")
-    with pytest.raises(mp8.Mp8Error):                      # channels not a multiple of 128
-        mp8.conv3x3_fp8(mp8.FWD, 1, 4, 4, 64, 128, mp8.conv_buffer(128, 64, 4), u8(3, 3, 64, 128), out8=u8(128, 128))
+    with pytest.raises(mp8.Mp8Error):                      # channels not a multiple of 64
+        mp8.conv3x3_fp8(mp8.FWD, 1, 4, 4, 32, 128, mp8.conv_buffer(128, 32, 4), u8(3, 3, 32, 128), out8=u8(128, 128))
     with pytest.raises(mp8.Mp8Error):                      # no guard rows around the shifted operand
         mp8.conv3x3_fp8(mp8.FWD, 1, 4, 4, 128, 128, u8(128, 128), u8(3, 3, 128, 128), out8=u8(128, 128))

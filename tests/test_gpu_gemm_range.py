@@ -214,14 +214,15 @@ def _lower(xp, taps_first_row, w2, n):
     return low
 
 
+@pytest.mark.parametrize("C", [128, 64])
 @pytest.mark.parametrize("mode", [oracle.RNE, oracle.SR])
-def test_full_range_operands_convolution_forms(mp8, mode):
+def test_full_range_operands_convolution_forms(mp8, mode, C):
     """The three implicit-GEMM forms of the 3x3 convolution on full-range codes.  The matrix-core
     bound needs the products in the order the kernel contracts them, so the test lowers the padded
     tensors itself (index bookkeeping only) and also holds the result against the oracle's direct
     convolution."""
     from test_gpu_conv import to_padded, interior, run_conv
-    B, H, W, C = 2, 10, 9, 128
+    B, H, W = 2, 10, 9
     dims = (B, H, W, C, C)
     x, e = codes(31, (B, H, W, C)), codes(32, (B, H, W, C))
     w = codes(33, (3, 3, C, C))
