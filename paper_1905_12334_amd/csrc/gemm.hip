@@ -811,6 +811,10 @@ static Plan conv_plan(mp8_op op, const ConvDims &d, int64_t Ci) {
     // built for stages that span two taps (contracted channels an odd multiple of 64)
     if (pl.mfma && op != MP8_WGRAD && (kTiles[pl.tile].bm < 128 || (d.kc / 9 / 64) % 2 != 0))
         pl = make_plan(d.rows, d.cols, kc, T128x128s2 + 1, 0, 3, true);
+    // ... and for 64 output columns a 128x64 tile of the same kind (tile geometry and slices as
+    // for the row-major kernel of that shape)
+    if (pl.mfma && op != MP8_WGRAD && (d.kc / 9 / 64) % 2 != 0 && d.cols == 64)
+        pl = make_plan(d.rows, d.cols, kc, T128x64s2 + 1, 0, 0, true);
     return pl;
 }
 
@@ -822,6 +826,14 @@ static void (*const kConvHalves[2][3])(const GemmArgs) = {
     {gemm_mfma_kernel<128, 128, 2, 2, 2, 2, EPI_PARTIAL, false, false, 5>,
      gemm_mfma_kernel<128, 128, 2, 2, 2, 2, EPI_RNE, false, false, 5>,
      gemm_mfma_kernel<128, 128, 2, 2, 2, 2, EPI_FULL, false, false, 5>}};
+// the same for 64 output columns
+static void (*const kConvHalves64[2][3])(const GemmArgs) = {
+    {gemm_mfma_kernel<128, 64, 4, 1, 2, 3, EPI_PARTIAL, false, true, 4>,
+     gemm_mfma_kernel<128, 64, 4, 1, 2, 3, EPI_RNE, false, true, 4>,
+     gemm_mfma_kernel<128, 64, 4, 1, 2, 3, EPI_FULL, false, true, 4>},
+    {gemm_mfma_kernel<128, 64, 4, 1, 2, 3, EPI_PARTIAL, false, false, 5>,
+     gemm_mfma_kernel<128, 64, 4, 1, 2, 3, EPI_RNE, false, false, 5>,
+     gemm_mfma_kernel<128, 64, 4, 1, 2, 3, EPI_FULL, false, false, 5>}};
 
 }  // namespace mp8
 
@@ -894,8 +906,10 @@ static mp8_status conv_impl(mp8_op op, int64_t B, int64_t H, int64_t W, int64_t 
     ga.cv.b_tap_stride = Ci * Co;
     ga.cv.div_ci = make_fastdiv((uint32_t)Ci);
     const bool halves = op != MP8_WGRAD && (ga.cv.units_per_tap & 1) != 0;
-    if (halves && pl.tile != T128x128s2) return MP8_ERR_UNSUPPORTED;
-    return launch_mfma(ga, ep, pl, conv_kc_stages(d), halves ? kConvHalves[(int)op] : kTiles[pl.tile].kernel_conv[(int)op],
+    if (halves && pl.tile != T128x128s2 && pl.tile != T128x64s2) return MP8_ERR_UNSUPPORTED;
+    return launch_mfma(ga, ep, pl, conv_kc_stages(d),
+                       !halves ? kTiles[pl.tile].kernel_conv[(int)op]
+                               : pl.tile == T128x64s2 ? kConvHalves64[(int)op] : kConvHalves[(int)op],
                        workspace, workspace_bytes,
                        (hipStream_t)stream, upd);
 }
