@@ -295,9 +295,11 @@ def test_weight_gradient_and_update_on_the_one_tile_per_cu_plan(mp8, layout):
             w8 = torch.full((K * N + 64,), 0x55, dtype=torch.uint8, device="cuda")
             flag = torch.full((1,), skip, dtype=torch.int32, device="cuda")
             st = mp8.new_stats()
+            ws = None if keep_codes else torch.empty(max(mp8.gemm_fp8_workspace_bytes(mp8.WGRAD, M, N, K), K * N),
+                                                     dtype=torch.uint8, device="cuda")
             mp8.wgrad_update_fp16_sr(M, N, K, a, b, wd, lr, inv, g8_out=g8[: K * N] if keep_codes else None, alpha=alpha,
                                      g_round=oracle.SR, flags=flags, g_seed=21, g_offset=22, stats=st, w_round=oracle.SR,
-                                     w_seed=23, w_offset=24, skip_if_nonzero=flag, w8_out=w8[: K * N])
+                                     w_seed=23, w_offset=24, skip_if_nonzero=flag, w8_out=w8[: K * N], workspace=ws)
             torch.cuda.synchronize()
             if keep_codes:
                 assert np.array_equal(host(g8[: K * N]).reshape(K, N), want_g), (alpha, skip)
