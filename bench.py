@@ -91,6 +91,10 @@ def parse_args():
                     help="configs[1] step: run its two Q nodes as one mp8_quantize_e5m2_batch launch")
     ap.add_argument("--kernel-reps", type=int, default=50,
                     help="back-to-back launches per graph in the per-kernel timing")
+    ap.add_argument("--steps-only", action="store_true",
+                    help="headline workload only, and of it only whole steps (the timed ones and the ones with an "
+                         "event pair around every kernel): no stand-alone per-kernel loops, no clock sampling -- the "
+                         "run to put under a tracer, whose per-kernel averages are then in-step durations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-conv-step", action="store_true",
                     help="skip the implicit-GEMM convolution form of the same layer")
@@ -402,11 +406,16 @@ class ConvWorkload:
             fn()
 
 
-def kernel_table(kernels, times_ms, traffic=None, cold_ms=None):
+def kernel_table(kernels, times_ms, traffic=None, cold_ms=None, in_step_ms=None):
     """One row per kernel.  `us` / `achieved` / `frac` come from back-to-back launches on the same
     buffers (warm); `us_cold` / `achieved_cold` / `frac_cold`, where measured, from launches that
-    rotate through buffer sets of more than twice the 256 MB cache."""
+    rotate through buffer sets of more than twice the 256 MB cache; `us_in_step` / `achieved_in_step`
+    / `frac_in_step`, where measured, from events around the kernel inside whole steps (each kernel
+    finds in the caches what the kernel before it left there, as in training).  Without the
+    stand-alone loops (`times_ms` None) the in-step figures stand in for `us` / `achieved` / `frac`."""
     out = []
+    if times_ms is None:
+        times_ms = in_step_ms
     for j, ((name, _, nbytes, flops, bound), ms) in enumerate(zip(kernels, times_ms)):
         def rate(t_ms):
             if bound == "mfma":
@@ -423,6 +432,9 @@ def kernel_table(kernels, times_ms, traffic=None, cold_ms=None):
             ac, _, _ = rate(cold_ms[j])
             row.update({"us_cold": cold_ms[j] * 1e3, "achieved_cold": ac, "frac_cold": ac / peak,
                         "hbm_gbs_cold": nbytes / (cold_ms[j] * 1e-3) / 1e9})
+        if in_step_ms is not None:
+            ai, _, _ = rate(in_step_ms[j])
+            row.update({"us_in_step": in_step_ms[j] * 1e3, "achieved_in_step": ai, "frac_in_step": ai / peak})
         out.append(row)
     return out
 
@@ -477,6 +489,29 @@ def time_kernels(torch, wl, reps, rotate=False):
         torch.cuda.synchronize()
         out.append(s.elapsed_time(e) / (2 * reps))
     return out
+
+
+def time_kernels_in_step(torch, wl, steps):
+    """Average duration of every kernel INSIDE the step: `steps` whole steps are launched one
+    call per kernel with an event before and after each (on the stream the kernels run on); the
+    host stays ahead of the device (a step is four launches and eight event records against
+    about 150 us of device time), so an event pair brackets the kernel and the gap before it.
+    The steps continue the workload's own sequence (input sets, statistics ring, Philox offsets).
+    Returns ms per launch, in the order of wl.kernels."""
+    n = len(wl.kernels)
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+          for _ in range(steps)]
+    torch.cuda.synchronize()
+    for t in range(steps):
+        wl.ring.advance()
+        i = wl.step_no
+        wl.step_no += 1
+        for j, (_, fn, _, _, _) in enumerate(wl.kernels):
+            ev[t][j][0].record()
+            fn(i)
+            ev[t][j][1].record()
+    torch.cuda.synchronize()
+    return [sum(ev[t][j][0].elapsed_time(ev[t][j][1]) for t in range(steps)) / steps for j in range(n)]
 
 
 def graph_time_us(torch, fn, reps=20):
@@ -778,14 +813,17 @@ def device_clock_sample(torch, fn, seconds=1.0):
             "power_w_mean": sum(pw) / len(pw) if pw else None}
 
 
-def timed_workload(torch, wl, args, traffic=None, rotate=False):
+def timed_workload(torch, wl, args, traffic=None, rotate=False, in_step=False):
     """Warm-up, the timed steps, and the per-kernel table of one workload."""
     for _ in range(args.warmup):
         wl.step()
     ms = time_steps(torch, wl, args.steps, args.launch)
+    inside = time_kernels_in_step(torch, wl, min(args.steps, 140)) if in_step else None
+    if args.steps_only and in_step:
+        return ms, kernel_table(wl.kernels, None, traffic, None, inside)
     warm = time_kernels(torch, wl, args.kernel_reps)
     cold = time_kernels(torch, wl, args.kernel_reps, rotate=True) if rotate else None
-    return ms, kernel_table(wl.kernels, warm, traffic, cold)
+    return ms, kernel_table(wl.kernels, warm, traffic, cold, inside)
 
 
 def main():
@@ -811,22 +849,30 @@ def main():
     lay = workloads.config5()
     traffic = profiled_traffic()
     wl = Cfg5Workload(mp8, torch, lay, cold=cold, fused_update=not args.separate_update)
-    ms_per_step, kernels = timed_workload(torch, wl, args, traffic, rotate=cold)
+    if args.steps_only:
+        args.no_configs1_step = args.no_all_configs = args.no_cpu_baseline = True
+    ms_per_step, kernels = timed_workload(torch, wl, args, traffic, rotate=cold, in_step=True)
     nonfinite = mp8.read_stats(wl.stats)[1]
     gemm_flops = 2.0 * lay.M * lay.N * lay.K
     value = gemm_flops / (ms_per_step * 1e-3) / 1e12
-    which = "us_cold" if cold else "us"
-    dom = max(kernels, key=lambda k: k[which])
+    # the dominant kernel and its rate are those of the timed region: durations inside the step
+    dom = max(kernels, key=lambda k: k["us_in_step"])
     sfx = "_cold" if cold else ""
-    roofline = {"kernel": dom["kernel"], "bound": dom["bound"], "achieved": dom["achieved" + sfx],
-                "peak": dom["peak"], "unit": dom["unit"], "frac": dom["frac" + sfx],
-                "us": dom[which], "timing": "launches rotate over operand sets (cold)" if cold else "same buffers (warm)",
+    roofline = {"kernel": dom["kernel"], "bound": dom["bound"], "achieved": dom["achieved_in_step"],
+                "peak": dom["peak"], "unit": dom["unit"], "frac": dom["frac_in_step"],
+                "us": dom["us_in_step"],
+                "timing": "events around the kernel inside whole steps whose FP32 inputs rotate over sets; its "
+                          "8-bit operands are what the two Q nodes of the same step have just written"
+                          if cold else "events around the kernel inside whole steps on one input set",
+                "us_alone_warm": dom.get("us") if not args.steps_only else None,
+                "us_alone_cold": dom.get("us_cold"),
+                "frac_alone_cold": dom.get("frac_cold"),
                 "plan": list(wl.plan),
                 "traffic": traffic.get(dom["kernel"]),
                 "traffic_source": "profiles/bench_step_cfg5_hbm_traffic.txt (counter runs of this command, not this run)"
                                   if traffic.get(dom["kernel"]) else None}
     gemm = next(k for k in kernels if k["kernel"] == "gemm_wgrad_sr")
-    clocks = device_clock_sample(torch, lambda: wl.kernels[2][1](0))
+    clocks = None if args.steps_only else device_clock_sample(torch, lambda: wl.kernels[2][1](0))
 
     out = {
         "metric": "FP8 GEMM TFLOP/s (E5M2 in, FP32 acc, FP8 out) and % of MFMA FP8 peak",
@@ -849,8 +895,8 @@ def main():
                    "inputs": "rotate over sets (no step finds its FP32 inputs in the 256 MB cache)" if cold
                              else "one set, replayed"},
         "pct_of_fp8_peak_whole_step": 100.0 * value / FP8_PEAK_TFLOPS,
-        "gemm_only_tflops": gemm["achieved" + sfx],
-        "gemm_only_pct_of_fp8_peak": 100.0 * gemm["frac" + sfx],
+        "gemm_only_tflops": gemm["achieved_in_step"],
+        "gemm_only_pct_of_fp8_peak": 100.0 * gemm["frac_in_step"],
         "overflow_count_last_step": nonfinite,
         "device": {"name": props.name, "compute_units": props.multi_processor_count,
                    "max_clock_mhz": getattr(props, "clock_rate", 0) / 1e3 or None,

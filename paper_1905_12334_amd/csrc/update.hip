@@ -120,9 +120,78 @@ __global__ __launch_bounds__(256) void state_update_kernel(uint16_t *__restrict_
     const bool skipping = (skip != nullptr) && (*skip != 0u);
     if (skipping && stats == nullptr) return;
     uint32_t nonfinite = 0;
+    // Whole units of 512 elements, one per wave and pass: the unit is 128 chunks of four elements
+    // and lane l owns chunks l and 64 + l, so that every load and store of the wave covers one
+    // contiguous run (1 KB of a state array, 512 B of weights, 256 B of gradient codes) -- with
+    // eight consecutive elements per lane the 16-byte accesses to the FP32 state would be strided
+    // by 32 bytes and every line would be touched by two instructions.  A chunk is half a Philox
+    // block; the two lanes of a pair need the same two blocks (one per chunk), each computes one
+    // and hands the other lane its half.
+    const int lane = threadIdx.x & 63;
+    const int64_t units = n >> 9;
+    const int64_t wave0 = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6), nwaves = (int64_t)gridDim.x * 4;
+    for (int64_t u = wave0; u < units; u += nwaves) {
+        const int64_t c[2] = {u * 128 + lane, u * 128 + 64 + lane};
+        uint32_t gw[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            gw[h] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(g8) + c[h]);
+            nonfinite += __builtin_popcount(((gw[h] & 0x7C7C7C7Cu) + 0x04040404u) & 0x80808080u);
+        }
+        if (skipping) continue;
+        u32x2 wr[2];
+        f32x4 sr[2][NS];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            wr[h] = __builtin_nontemporal_load(reinterpret_cast<u32x2 *>(w16) + c[h]);
+#pragma unroll
+            for (int k = 0; k < NS; ++k)
+                sr[h][k] = __builtin_nontemporal_load(reinterpret_cast<f32x4 *>(sp[k]) + c[h]);
+        }
+        uint32_t rw[2][2] = {{0, 0}, {0, 0}};   // [chunk][word]: 16 random bits per element
+        if constexpr (kSR) {
+            const bool odd = (lane & 1) != 0;
+            const uint4 mine = rng.block((uint64_t)(c[odd ? 1 : 0] >> 1));
+            // quad_perm [1,0,3,2]: the value of the other lane of the pair
+            const uint32_t got0 = (uint32_t)__builtin_amdgcn_mov_dpp((int)(odd ? mine.x : mine.z), 0xB1, 0xF, 0xF, true);
+            const uint32_t got1 = (uint32_t)__builtin_amdgcn_mov_dpp((int)(odd ? mine.y : mine.w), 0xB1, 0xF, 0xF, true);
+            rw[0][0] = odd ? got0 : mine.x;     // first chunk: this lane's half of the even lane's block
+            rw[0][1] = odd ? got1 : mine.y;
+            rw[1][0] = odd ? mine.z : got0;     // second chunk: this lane's half of the odd lane's block
+            rw[1][1] = odd ? mine.w : got1;
+        }
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            uint32_t ww[2] = {wr[h].x, wr[h].y};
+            float sv[4][NS];
+#pragma unroll
+            for (int k = 0; k < NS; ++k) {
+                sv[0][k] = sr[h][k].x; sv[1][k] = sr[h][k].y; sv[2][k] = sr[h][k].z; sv[3][k] = sr[h][k].w;
+            }
+            uint32_t w8 = 0;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {  // pair j = elements 2j, 2j+1 of the chunk
+                const uint32_t g_lo = (gw[h] >> (16 * j)) & 0xFFu;
+                const uint32_t g_hi = (gw[h] >> (16 * j + 8)) & 0xFFu;
+                const uint32_t h_lo = rule_one<kSR>(rule, ww[j] & 0xFFFFu, g_lo, sv[2 * j], inv_scale, rw[h][j] & 0xFFFFu);
+                const uint32_t h_hi = rule_one<kSR>(rule, ww[j] >> 16, g_hi, sv[2 * j + 1], inv_scale, rw[h][j] >> 16);
+                ww[j] = h_lo | (h_hi << 16);
+                if constexpr (kW8) w8 |= (e5m2_of_half(h_lo) | (e5m2_of_half(h_hi) << 8)) << (16 * j);
+            }
+            const u32x2 o = {ww[0], ww[1]};
+            __builtin_nontemporal_store(o, reinterpret_cast<u32x2 *>(w16) + c[h]);
+#pragma unroll
+            for (int k = 0; k < NS; ++k) {
+                const f32x4 a = {sv[0][k], sv[1][k], sv[2][k], sv[3][k]};
+                __builtin_nontemporal_store(a, reinterpret_cast<f32x4 *>(sp[k]) + c[h]);
+            }
+            if constexpr (kW8)
+                reinterpret_cast<uint32_t *>(w8_out)[c[h]] = w8;  // the next step's GEMM operand: stays in the caches
+        }
+    }
+    // what is left of whole items of eight elements (fewer than 64): block 0, one item per thread
     const int64_t n8 = n >> 3;
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < n8; t += stride) {
+    for (int64_t t = units * 64 + threadIdx.x; blockIdx.x == 0 && t < n8; t += 256) {
         const u32x2 gr = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(g8) + t);
         const uint32_t gw[2] = {gr.x, gr.y};
 #pragma unroll
@@ -166,7 +235,7 @@ __global__ __launch_bounds__(256) void state_update_kernel(uint16_t *__restrict_
         }
         if constexpr (kW8) {
             u32x2 o8 = {w8[0], w8[1]};
-            reinterpret_cast<u32x2 *>(w8_out)[t] = o8;  // the next step's GEMM operand: stays in the caches
+            reinterpret_cast<u32x2 *>(w8_out)[t] = o8;
         }
     }
     if (blockIdx.x == 0 && threadIdx.x < 8) {  // ragged tail (< 8 elements)
