@@ -93,7 +93,7 @@ def parse_args():
                     help="back-to-back launches per graph in the per-kernel timing")
     ap.add_argument("--steps-only", action="store_true",
                     help="headline workload only, and of it only whole steps (the timed ones and the ones with an "
-                         "event pair around every kernel): no stand-alone per-kernel loops, no clock sampling -- the "
+                         "event between consecutive kernels): no stand-alone per-kernel loops, no clock sampling -- the "
                          "run to put under a tracer, whose per-kernel averages are then in-step durations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-conv-step", action="store_true",
@@ -410,7 +410,7 @@ def kernel_table(kernels, times_ms, traffic=None, cold_ms=None, in_step_ms=None)
     """One row per kernel.  `us` / `achieved` / `frac` come from back-to-back launches on the same
     buffers (warm); `us_cold` / `achieved_cold` / `frac_cold`, where measured, from launches that
     rotate through buffer sets of more than twice the 256 MB cache; `us_in_step` / `achieved_in_step`
-    / `frac_in_step`, where measured, from events around the kernel inside whole steps (each kernel
+    / `frac_in_step`, where measured, from events between the kernels of whole steps (each kernel
     finds in the caches what the kernel before it left there, as in training).  Without the
     stand-alone loops (`times_ms` None) the in-step figures stand in for `us` / `achieved` / `frac`."""
     out = []
@@ -493,25 +493,26 @@ def time_kernels(torch, wl, reps, rotate=False):
 
 def time_kernels_in_step(torch, wl, steps):
     """Average duration of every kernel INSIDE the step: `steps` whole steps are launched one
-    call per kernel with an event before and after each (on the stream the kernels run on); the
-    host stays ahead of the device (a step is four launches and eight event records against
-    about 150 us of device time), so an event pair brackets the kernel and the gap before it.
+    call per kernel with ONE event between consecutive kernels (on the stream the kernels run on);
+    a kernel's figure is the time from the event before it to the event after it.  The host stays
+    ahead of the device (a step is four launches and five event records against about 150 us of
+    device time), so the interval is the kernel plus the gap in which the device picks up the next
+    command (1-2 us; a tracer's per-kernel average of the same launches is shorter by that much).
     The steps continue the workload's own sequence (input sets, statistics ring, Philox offsets).
     Returns ms per launch, in the order of wl.kernels."""
     n = len(wl.kernels)
-    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
-          for _ in range(steps)]
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(n + 1)] for _ in range(steps)]
     torch.cuda.synchronize()
     for t in range(steps):
         wl.ring.advance()
         i = wl.step_no
         wl.step_no += 1
+        ev[t][0].record()
         for j, (_, fn, _, _, _) in enumerate(wl.kernels):
-            ev[t][j][0].record()
             fn(i)
-            ev[t][j][1].record()
+            ev[t][j + 1].record()
     torch.cuda.synchronize()
-    return [sum(ev[t][j][0].elapsed_time(ev[t][j][1]) for t in range(steps)) / steps for j in range(n)]
+    return [sum(ev[t][j].elapsed_time(ev[t][j + 1]) for t in range(steps)) / steps for j in range(n)]
 
 
 def graph_time_us(torch, fn, reps=20):
@@ -861,9 +862,9 @@ def main():
     roofline = {"kernel": dom["kernel"], "bound": dom["bound"], "achieved": dom["achieved_in_step"],
                 "peak": dom["peak"], "unit": dom["unit"], "frac": dom["frac_in_step"],
                 "us": dom["us_in_step"],
-                "timing": "events around the kernel inside whole steps whose FP32 inputs rotate over sets; its "
-                          "8-bit operands are what the two Q nodes of the same step have just written"
-                          if cold else "events around the kernel inside whole steps on one input set",
+                "timing": "events before and after the kernel inside whole steps whose FP32 inputs rotate over sets; "
+                          "its 8-bit operands are what the two Q nodes of the same step have just written"
+                          if cold else "events before and after the kernel inside whole steps on one input set",
                 "us_alone_warm": dom.get("us") if not args.steps_only else None,
                 "us_alone_cold": dom.get("us_cold"),
                 "frac_alone_cold": dom.get("frac_cold"),

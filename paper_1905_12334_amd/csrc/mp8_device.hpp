@@ -131,7 +131,7 @@ __device__ __forceinline__ uint32_t canonical_nan_codes(uint32_t w) {
 
 // Bit-level conversion of four values (groups that contain a NaN).  Out of line on
 // purpose: it is rare, and keeping it out of the callers keeps their hot code small.
-static __device__ __noinline__ uint32_t e5m2_pack4_slow(float y0, float y1, float y2, float y3,
+static inline __device__ __noinline__ uint32_t e5m2_pack4_slow(float y0, float y1, float y2, float y3,
                                                         uint32_t r01, uint32_t r23, bool sr,
                                                         bool sat) {
     const float y[4] = {y0, y1, y2, y3};
