@@ -93,12 +93,13 @@ def test_conv_exact_sums_all_three_operations(mp8, dims):
     assert np.array_equal(out8.reshape(3, 3, Ci, Co), oracle.round_ref_e5m2(ref, alpha=alpha))
 
 
-def test_conv_weight_gradient_and_update_in_one_call(mp8):
+@pytest.mark.parametrize("channels", [(128, 128), (64, 64), (192, 64)])
+def test_conv_weight_gradient_and_update_in_one_call(mp8, channels):
     """mp8_conv3x3_wgrad_update_fp16_sr against the oracle's chain (direct convolution weight
     gradient -> one rounding -> FP16 update) on exact-sum operands: gradient codes, new master
     weights and their 8-bit copies bit for bit."""
     import torch
-    B, H, W, Ci, Co = 2, 6, 5, 128, 128
+    B, H, W, (Ci, Co) = 2, 6, 5, channels
     rng = np.random.default_rng(77)
     x, e = exact_codes(rng, (B, H, W, Ci)), exact_codes(rng, (B, H, W, Co))
     ref, _ = oracle.conv3x3_ref("wgrad", x, e, want_abs=False)
@@ -118,12 +119,13 @@ def test_conv_weight_gradient_and_update_in_one_call(mp8):
     assert np.array_equal(host(wd).view(np.uint16), want_w) and np.array_equal(host(w8), want_w8)
 
 
-def test_conv_weight_gradient_and_momentum_update_in_one_call(mp8):
+@pytest.mark.parametrize("channels", [(128, 128), (64, 128)])
+def test_conv_weight_gradient_and_momentum_update_in_one_call(mp8, channels):
     """mp8_conv3x3_wgrad_momentum_fp16_sr against the oracle's chain (direct convolution weight
     gradient -> one rounding -> momentum update with L2 regularisation) on exact-sum operands, two
     steps in a row: gradient codes, master weights, velocity and 8-bit weights bit for bit."""
     import torch
-    B, H, W, Ci, Co = 2, 6, 5, 128, 128
+    B, H, W, (Ci, Co) = 2, 6, 5, channels
     rng = np.random.default_rng(78)
     x, e = exact_codes(rng, (B, H, W, Ci)), exact_codes(rng, (B, H, W, Co))
     ref, _ = oracle.conv3x3_ref("wgrad", x, e, want_abs=False)
