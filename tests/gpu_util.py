@@ -28,16 +28,18 @@ def signed_rank(codes):
 # --- what was measured, for the record -------------------------------------------------------
 # Every accumulator check appends its worst error ratios to a JSON-lines file (one line per
 # check: label, contraction length, ratios), so that a test run leaves the figures behind and not
-# only a pass/fail.  GPU runs write under gpurun_out/ when that folder exists.
-_RECORD = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out",
-                       "gemm_accumulator_ratios.jsonl")
+# only a pass/fail: gemm_accumulator_ratios.jsonl in the directory that the environment variable
+# MP8_TEST_RECORD_DIR names (nothing is recorded when it is not set).
+_RECORD_DIR = os.environ.get("MP8_TEST_RECORD_DIR")
 
 
 def record_ratios(label, kc, **ratios):
+    if not _RECORD_DIR:
+        return
     try:
-        if os.path.isdir(os.path.dirname(_RECORD)):
-            with open(_RECORD, "a") as f:
-                f.write(json.dumps({"label": label, "kc": int(kc), **{k: float(v) for k, v in ratios.items()}}) + "\n")
+        os.makedirs(_RECORD_DIR, exist_ok=True)
+        with open(os.path.join(_RECORD_DIR, "gemm_accumulator_ratios.jsonl"), "a") as f:
+            f.write(json.dumps({"label": label, "kc": int(kc), **{k: float(v) for k, v in ratios.items()}}) + "\n")
     except OSError:
         pass
 

@@ -11,7 +11,8 @@ each result goes through gpu_util.check_outputs with the operands, i.e. against
     everywhere: on such operands short contractions miss it, see `STATED_HOLDS_FROM`),
   - the oracle's rounding of the GPU's own accumulator (bit for bit) and the rounding / bracket of
     the double reference.
-The worst ratios of every case are appended to gpurun_out/gemm_accumulator_ratios.jsonl."""
+The worst ratios of every case are appended to gemm_accumulator_ratios.jsonl in the directory
+that MP8_TEST_RECORD_DIR names (gpu_util.record_ratios)."""
 import numpy as np
 import pytest
 
