@@ -874,6 +874,13 @@ def main():
                                   if traffic.get(dom["kernel"]) else None}
     gemm = next(k for k in kernels if k["kernel"] == "gemm_wgrad_sr")
     clocks = None if args.steps_only else device_clock_sample(torch, lambda: wl.kernels[2][1](0))
+    if clocks and clocks.get("sclk_mhz_mean") and roofline["bound"] == "mfma":
+        # the same rate against the matrix-core peak at the clock the chip actually held under this
+        # kernel (256 CUs x 4 SIMDs x 2048 flop per clock x sampled clock) beside the datasheet's 2.4 GHz
+        at_clock = 256 * 4 * 2048 * clocks["sclk_mhz_mean"] * 1e6 / 1e12
+        roofline["peak_at_sampled_clock"] = at_clock
+        roofline["frac_at_sampled_clock"] = roofline["achieved"] / at_clock
+        roofline["sampled_clock_mhz"] = clocks["sclk_mhz_mean"]
 
     out = {
         "metric": "FP8 GEMM TFLOP/s (E5M2 in, FP32 acc, FP8 out) and % of MFMA FP8 peak",
