@@ -98,7 +98,7 @@ def test_update_transformer_big_magnitudes_and_skip(mp8):
     assert np.array_equal(ran, want)
 
 
-@pytest.mark.parametrize("n", [1, 7, 4099, 1 << 20])
+@pytest.mark.parametrize("n", [1, 7, 511, 1579, 4099, 1 << 20])
 @pytest.mark.parametrize("rnd", [oracle.RNE, oracle.SR])
 def test_momentum_update_matches_oracle_over_several_steps(mp8, n, rnd):
     """Momentum SGD with L2 regularisation: weights, FP32 velocity and the 8-bit weight copy
@@ -155,7 +155,7 @@ def _same_f32(got, want):
     return np.array_equal(np.isnan(got), ~ok) and np.array_equal(got[ok].view(np.uint32), want[ok].view(np.uint32))
 
 
-@pytest.mark.parametrize("n", [1, 7, 4099, 1 << 20])
+@pytest.mark.parametrize("n", [1, 7, 511, 1579, 4099, 1 << 20])
 @pytest.mark.parametrize("rnd", [oracle.RNE, oracle.SR])
 def test_adam_update_matches_oracle_over_several_steps(mp8, n, rnd):
     """ADAM with L2 regularisation: weights, both FP32 moments and the 8-bit weight copy bit-exact
