@@ -613,6 +613,34 @@ def all_configs_report(mp8, torch, vendor_gemm=False):
                  "alg_gbs": (K * M + N * M + 9 * K * N) / us / 1e3,
                  "flop_per_byte": 2.0 * M * N * K / (K * M + N * M + 9 * K * N)})
     del a, b, acc, out, ws
+    # configs[3] as the recurrence it is: 50 dependent forward GEMMs, the hidden state of step t+1
+    # being the cell's output of step t.  The cell itself is harness code (half-precision torch ops
+    # on two gate slices, then the library's Q node), timed with the chain and named as such.
+    M, N, K, H, T = 128, 4096, 2048, 1024, 50
+    w8 = codes(N, K)
+    a_t = [codes(M, K) for _ in range(2)]              # [x_t, h_{t-1}]; the h half is overwritten per step
+    y8 = torch.empty((M, N), dtype=torch.uint8, device=dev)
+    ws = torch.empty(max(mp8.gemm_fp8_workspace_bytes(mp8.FWD, M, N, K), 16), dtype=torch.uint8, device=dev)
+
+    def recurrence(with_cell):
+        def run():
+            for t in range(T):
+                cur, nxt = a_t[t & 1], a_t[(t + 1) & 1]
+                mp8.gemm_fp8(mp8.FWD, M, N, K, cur, w8, out8=y8, workspace=ws)
+                if with_cell:
+                    y = (y8.to(torch.int16) << 8).view(torch.float16)
+                    h = torch.tanh(y[:, 2 * H:3 * H]) * torch.sigmoid(y[:, 3 * H:])
+                    hq = torch.empty((M, H), dtype=torch.uint8, device=dev)
+                    mp8.quantize_e5m2(h.contiguous(), hq)
+                    nxt[:, H:].copy_(hq)
+        return run
+    for with_cell, label in ((False, "50 forward GEMMs back to back in one graph"),
+                             (True, "50 dependent steps in one graph: forward GEMM, cell stand-in (harness: half-precision "
+                                    "tanh * sigmoid in torch, 5 small kernels), Q node, copy into the next step's operand")):
+        us = graph_time_us(torch, recurrence(with_cell), 1) / T
+        rows.append({"kernel": "gemm_fp8 (recurrence)", "case": "configs[3] " + label + ", per timestep", "us": us,
+                     "tflops": 2.0 * M * N * K / us / 1e6, "frac_mfma_peak": 2.0 * M * N * K / us / 1e6 / FP8_PEAK_TFLOPS})
+    del w8, a_t, y8, ws
     # configs[4] as a whole: weight gradient from the row-major X8 [tokens, 1024] and E8 [tokens, 4096],
     # rounded stochastically to 8 bits, then the FP16 master-weight step with stochastic rounding
     # (mp8_wgrad_update_fp16_sr; lr 1e-3, loss scale 2^14)
